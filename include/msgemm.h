@@ -1,0 +1,169 @@
+/*
+ * msgemm.h -- C ABI of the msGeMM library for AMD MI355X (gfx950).
+ *
+ * msGeMM (arxiv 2310.06178) computes the GeMM  M x X = Y  (Section 1, Eq. 1;
+ * sizes m x k x b, Section 2) for a 4-bit weight matrix M without multiplying
+ * in the inner loop: for every group of d consecutive k-indices and every
+ * column of X a table L of all 16^d partial dot products is produced once
+ * (phase 1, Section 3.1), and every output row then adds up the table entries
+ * addressed by its packed d x 4-bit codes (phase 2, Section 3.2).  Weights
+ * that share a scale per block of a row are handled by multiplying the block's
+ * partial sum after the table has been consumed (Section 3.3).
+ *
+ * All pointers named "device" are HIP device pointers on the current device;
+ * "stream" is a hipStream_t passed as void* (NULL = the null stream).  Every
+ * call only enqueues work on that stream and never synchronises it, except
+ * msgemm_plan (which returns after its one-off weight repack has been
+ * enqueued; the caller may free W_codes / scales once the stream has been
+ * synchronised) and msgemm_destroy (which synchronises the device before it
+ * frees).  No exception or abort crosses this boundary: every entry point
+ * returns MSGEMM_OK (0) or a negative msgemm_status_t.
+ *
+ * Storage conventions (the paper fixes none; Section 4 only requires that the
+ * d codes of a group are adjacent in a row-major M):
+ *   W_codes  uint8 [m][k/2] row-major; byte t of row i holds column 2t in bits
+ *            3:0 and column 2t+1 in bits 7:4.  A code is the two's-complement
+ *            pattern of its value: b(0000)=0 .. b(0111)=7, b(1000)=-8 ..
+ *            b(1111)=-1 (Section 3.1).  k must be even.
+ *   scales   fp16 [m][k/scale_group], or NULL when scale_group == 0.
+ *   X        column c of the paper's k x b matrix is contiguous:
+ *            X(j,c) = X[c*ldx + j], ldx >= k, in x_dtype.
+ *   Y        Y(i,c) = Y[c*ldy + i], ldy >= m, in y_dtype.
+ *   L        [groups][16^d][b] in the LUT dtype (fp32 for floating-point X,
+ *            int32 for int8 X); the entry index of codes (i_0..i_{d-1}) is
+ *            sum_r i_r << 4r, so a packed code byte is itself the d = 2 index.
+ *            Groups restart at every scale-block boundary; a group cut short
+ *            by the end of its block (d does not divide the block length)
+ *            ignores the missing positions.
+ */
+#ifndef MSGEMM_H
+#define MSGEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct msgemm_plan_s msgemm_plan_t; /* opaque, owned by the library */
+
+typedef enum {
+    MSGEMM_F32 = 0,
+    MSGEMM_F16 = 1,
+    MSGEMM_BF16 = 2,
+    MSGEMM_I8 = 3,
+    MSGEMM_I32 = 4
+} msgemm_dtype_t;
+
+typedef enum {
+    MSGEMM_OK = 0,
+    MSGEMM_ERR_INVALID_ARG = -1, /* null pointer, bad size, bad d, bad dtype pair */
+    MSGEMM_ERR_ALLOC = -2,       /* host or device allocation failed */
+    MSGEMM_ERR_HIP = -3,         /* a HIP call failed; see msgemm_last_hip_error */
+    MSGEMM_ERR_UNSUPPORTED = -4  /* valid request that the chosen variant cannot serve */
+} msgemm_status_t;
+
+/* How phase 1 and phase 2 are scheduled on the GPU. */
+typedef enum {
+    MSGEMM_VARIANT_AUTO = 0,
+    /* Two launches: L is written to device memory once and shared by all rows
+     * (the paper's "L kept in cache", Section 4); any d in 1..4. */
+    MSGEMM_VARIANT_GLOBAL_LUT = 1,
+    /* One launch, d = 2: each workgroup builds the tables of its k-tile in LDS
+     * (phase 1 and 2 pipelined over the last dimension of L, Section 4), streams
+     * its repacked code tile and reduces over k-tiles inside the same launch. */
+    MSGEMM_VARIANT_FUSED_LDS = 2
+} msgemm_variant_t;
+
+typedef struct {
+    int64_t m, k, b;
+    int x_dtype, y_dtype, lut_dtype;
+    int d;
+    int scale_group;
+    int variant;         /* the variant actually chosen */
+    int64_t lut_groups;  /* last dimension of L */
+    int tile_rows;       /* rows per workgroup (fused variant), else 0 */
+    int tile_groups;     /* table groups resident in LDS per workgroup, else 0 */
+    int split_k;         /* k-tiles whose partial sums are reduced per output */
+    int col_chunk;       /* batch columns handled per pass over the codes */
+    int64_t workspace_bytes; /* device memory the plan owns besides the codes */
+} msgemm_plan_info_t;
+
+/*
+ * Validate an m x k x b problem (Section 2), choose the kernel variant and
+ * tile shape, and make the plan's own device copies of the weights: the
+ * row-major codes, the scales and, for the fused variant, the codes reordered
+ * into the order the kernel streams them.  M is a static model weight
+ * (Section 1), so this is one-off work outside the hot path.
+ *
+ *   d            1..4 (Section 5: larger d is never useful), or 0 = library's choice
+ *   scale_group  0 = no scales; else the number r of consecutive row elements
+ *                sharing a scale; needs r >= d and k % r == 0 (Section 3.3)
+ *   W_codes      device, m*k/2 bytes, read during this call's stream work
+ *   scales       device, fp16 [m][k/scale_group], or NULL
+ *   variant      a msgemm_variant_t
+ * Supported (x_dtype, y_dtype): (F32,F32) (F16,F16) (BF16,BF16) (I8,I32);
+ * the int8 pair takes no scales.  On failure *out is NULL.
+ */
+int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b,
+                int x_dtype, int y_dtype, int d, int scale_group,
+                const void* W_codes, const void* scales, int variant, void* stream);
+
+/* Fill *info with what the plan chose. */
+int msgemm_plan_get_info(const msgemm_plan_t* plan, msgemm_plan_info_t* info);
+
+/* Bytes the caller must provide for L_out: lut_groups * 16^d * b * 4. */
+size_t msgemm_lut_bytes(const msgemm_plan_t* plan);
+
+/*
+ * Phase 1 alone (Section 3.1): L(i_0..i_{d-1}, j, c) = sum_r b(i_r) X(j d + r, c)
+ * for every code combination, group j and column c, written to L_out (device,
+ * msgemm_lut_bytes bytes, layout above).  X: device, ldx >= k.
+ */
+int msgemm_build_lut(const msgemm_plan_t* plan, const void* X, int64_t ldx,
+                     void* L_out, void* stream);
+
+/*
+ * Phase 2 alone (Section 3.2, second line of the y(i) equation, and Section
+ * 3.3): Y(i,c) = sum_blocks q(i,block) * sum_{groups j of the block}
+ * L(codes of row i at group j, j, c).  L: device, as written by
+ * msgemm_build_lut for the same plan.  Y: device, ldy >= m.
+ */
+int msgemm_consume_lut(const msgemm_plan_t* plan, const void* L,
+                       void* Y, int64_t ldy, void* stream);
+
+/*
+ * The whole hot path, Y = M x X, by the plan's variant (both phases).
+ * X, Y: device.  Uses the plan's workspace: calls on the same plan must not
+ * overlap (use one stream, or one plan per stream).
+ */
+int msgemm_run(const msgemm_plan_t* plan, const void* X, int64_t ldx,
+               void* Y, int64_t ldy, void* stream);
+
+/*
+ * Comparison point only, not msGeMM: the same Y computed as a dense
+ * contraction on the matrix cores (codes dequantised to bf16/fp16 in
+ * registers, MFMA per scale block, fp32 accumulate).  Floating-point dtypes
+ * only.  Exists so the LUT path can be timed against it on equal inputs
+ * (Section 6 argues the matrix units are what a table-add has to compete with).
+ */
+int msgemm_dequant_mfma_run(const msgemm_plan_t* plan, const void* X, int64_t ldx,
+                            void* Y, int64_t ldy, void* stream);
+
+/* Synchronise the device, free everything the plan owns.  NULL is allowed. */
+void msgemm_destroy(msgemm_plan_t* plan);
+
+/* Static text for a status code. */
+const char* msgemm_status_string(int status);
+
+/* hipError_t (as int) of the most recent failing HIP call on this thread, 0 if none. */
+int msgemm_last_hip_error(void);
+
+/* Library version, "major.minor". */
+const char* msgemm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MSGEMM_H */

@@ -1,0 +1,220 @@
+// The C ABI of libmsgemm.so: argument checking, plan ownership, dispatch.
+// See include/msgemm.h for the contract of every entry point.
+#include <new>
+
+#include "msgemm_internal.h"
+
+namespace msgemm {
+
+static thread_local int g_last_hip_error = 0;
+void set_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+
+namespace {
+
+bool dtype_pair_ok(int x, int y)
+{
+    return (x == MSGEMM_F32 && y == MSGEMM_F32) || (x == MSGEMM_F16 && y == MSGEMM_F16) ||
+           (x == MSGEMM_BF16 && y == MSGEMM_BF16) || (x == MSGEMM_I8 && y == MSGEMM_I32);
+}
+
+void free_plan(Plan* p)
+{
+    if (!p) return;
+    if (p->codes) (void)hipFree(p->codes);
+    if (p->scales) (void)hipFree(p->scales);
+    if (p->lut_ws) (void)hipFree(p->lut_ws);
+    if (p->codes_tiled) (void)hipFree(p->codes_tiled);
+    if (p->partials) (void)hipFree(p->partials);
+    if (p->counters) (void)hipFree(p->counters);
+    delete p;
+}
+
+size_t lut_bytes_of(const Plan& p)
+{
+    return (size_t)p.lut_groups * ((size_t)1 << (4 * p.d)) * (size_t)p.b * 4u;
+}
+
+}  // namespace
+}  // namespace msgemm
+
+using msgemm::Plan;
+
+extern "C" {
+
+int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtype, int y_dtype, int d,
+                int scale_group, const void* W_codes, const void* scales, int variant, void* stream)
+{
+    if (!out) return MSGEMM_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (m <= 0 || k <= 0 || b <= 0 || (k & 1) || !W_codes) return MSGEMM_ERR_INVALID_ARG;
+    if (m > ((int64_t)1 << 31) || k > ((int64_t)1 << 31) || b > 65536) return MSGEMM_ERR_INVALID_ARG;
+    if (d < 0 || d > 4) return MSGEMM_ERR_INVALID_ARG;  // Section 5: d cannot usefully exceed 4
+    if (!msgemm::dtype_pair_ok(x_dtype, y_dtype)) return MSGEMM_ERR_INVALID_ARG;
+    if (variant < MSGEMM_VARIANT_AUTO || variant > MSGEMM_VARIANT_FUSED_LDS) return MSGEMM_ERR_INVALID_ARG;
+    if (scale_group < 0) return MSGEMM_ERR_INVALID_ARG;
+    if (scale_group > 0) {
+        if (!scales || x_dtype == MSGEMM_I8) return MSGEMM_ERR_INVALID_ARG;
+        if (k % scale_group) return MSGEMM_ERR_INVALID_ARG;
+    } else if (scales) {
+        return MSGEMM_ERR_INVALID_ARG;
+    }
+    const int d_eff = d == 0 ? 2 : d;
+    // Section 3.3: a scale must be shared by at least d row elements.
+    if (scale_group > 0 && scale_group < d_eff) return MSGEMM_ERR_INVALID_ARG;
+
+    Plan* p = new (std::nothrow) Plan();
+    if (!p) return MSGEMM_ERR_ALLOC;
+    p->m = m; p->k = k; p->b = b;
+    p->x_dtype = x_dtype; p->y_dtype = y_dtype;
+    p->lut_dtype = (x_dtype == MSGEMM_I8) ? MSGEMM_I32 : MSGEMM_F32;
+    p->d = d_eff;
+    p->scale_group = scale_group;
+    p->block = scale_group > 0 ? scale_group : k;
+    p->nblocks = k / p->block;
+    p->gpb = (p->block + p->d - 1) / p->d;
+    p->lut_groups = p->nblocks * p->gpb;
+
+    hipStream_t s = (hipStream_t)stream;
+    int rc = MSGEMM_OK;
+    auto fail = [&](int code) { msgemm::free_plan(p); return code; };
+    auto hip_fail = [&](hipError_t e) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_HIP); };
+
+    hipError_t e = hipGetDevice(&p->device);
+    if (e != hipSuccess) return hip_fail(e);
+
+    // variant
+    p->variant = MSGEMM_VARIANT_GLOBAL_LUT;
+    if (variant != MSGEMM_VARIANT_GLOBAL_LUT) {
+        rc = msgemm::fused_choose_shape(*p);
+        if (rc == MSGEMM_OK) {
+            p->variant = MSGEMM_VARIANT_FUSED_LDS;
+        } else if (variant == MSGEMM_VARIANT_FUSED_LDS || rc != MSGEMM_ERR_UNSUPPORTED) {
+            return fail(rc);
+        }
+    }
+
+    // the plan's own copies of the weights
+    const size_t code_bytes = (size_t)m * (size_t)(k / 2);
+    e = hipMalloc((void**)&p->codes, code_bytes);
+    if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
+    e = hipMemcpyAsync(p->codes, W_codes, code_bytes, hipMemcpyDeviceToDevice, s);
+    if (e != hipSuccess) return hip_fail(e);
+    if (scale_group > 0) {
+        const size_t sb = (size_t)m * (size_t)p->nblocks * 2u;
+        e = hipMalloc((void**)&p->scales, sb);
+        if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
+        e = hipMemcpyAsync(p->scales, scales, sb, hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+
+    if (p->variant == MSGEMM_VARIANT_GLOBAL_LUT) {
+        p->lut_ws_bytes = msgemm::lut_bytes_of(*p);
+        e = hipMalloc((void**)&p->lut_ws, p->lut_ws_bytes);
+        if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
+        p->workspace_bytes = p->lut_ws_bytes;
+    } else {
+        const size_t tiled = (size_t)p->ktiles * (size_t)p->m_pad * (size_t)(p->fs.groups);
+        const size_t b_pad = (size_t)p->col_passes * (size_t)p->fs.cols;
+        const size_t part = (size_t)p->ktiles * b_pad * (size_t)p->m_pad * 4u;
+        const size_t cnt = (size_t)p->row_blocks * (size_t)p->col_passes * sizeof(unsigned);
+        e = hipMalloc((void**)&p->codes_tiled, tiled);
+        if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
+        e = hipMalloc((void**)&p->partials, part);
+        if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
+        e = hipMalloc((void**)&p->counters, cnt);
+        if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
+        e = hipMemsetAsync(p->counters, 0, cnt, s);
+        if (e != hipSuccess) return hip_fail(e);
+        p->workspace_bytes = tiled + part + cnt;
+        rc = msgemm::launch_repack(*p, s);
+        if (rc != MSGEMM_OK) return fail(rc);
+    }
+    *out = reinterpret_cast<msgemm_plan_t*>(p);
+    return MSGEMM_OK;
+}
+
+int msgemm_plan_get_info(const msgemm_plan_t* plan, msgemm_plan_info_t* info)
+{
+    if (!plan || !info) return MSGEMM_ERR_INVALID_ARG;
+    const Plan& p = *reinterpret_cast<const Plan*>(plan);
+    info->m = p.m; info->k = p.k; info->b = p.b;
+    info->x_dtype = p.x_dtype; info->y_dtype = p.y_dtype; info->lut_dtype = p.lut_dtype;
+    info->d = p.d; info->scale_group = p.scale_group; info->variant = p.variant;
+    info->lut_groups = p.lut_groups;
+    const bool fused = p.variant == MSGEMM_VARIANT_FUSED_LDS;
+    info->tile_rows = fused ? p.fs.tile_rows : 0;
+    info->tile_groups = fused ? p.fs.groups : 0;
+    info->split_k = fused ? (int)p.ktiles : 1;
+    info->col_chunk = fused ? p.fs.cols : (int)p.b;
+    info->workspace_bytes = (int64_t)p.workspace_bytes;
+    return MSGEMM_OK;
+}
+
+size_t msgemm_lut_bytes(const msgemm_plan_t* plan)
+{
+    if (!plan) return 0;
+    return msgemm::lut_bytes_of(*reinterpret_cast<const Plan*>(plan));
+}
+
+int msgemm_build_lut(const msgemm_plan_t* plan, const void* X, int64_t ldx, void* L_out, void* stream)
+{
+    if (!plan || !X || !L_out) return MSGEMM_ERR_INVALID_ARG;
+    const Plan& p = *reinterpret_cast<const Plan*>(plan);
+    if (ldx < p.k) return MSGEMM_ERR_INVALID_ARG;
+    return msgemm::launch_build_lut(p, X, ldx, L_out, (hipStream_t)stream);
+}
+
+int msgemm_consume_lut(const msgemm_plan_t* plan, const void* L, void* Y, int64_t ldy, void* stream)
+{
+    if (!plan || !L || !Y) return MSGEMM_ERR_INVALID_ARG;
+    const Plan& p = *reinterpret_cast<const Plan*>(plan);
+    if (ldy < p.m) return MSGEMM_ERR_INVALID_ARG;
+    return msgemm::launch_consume_lut(p, L, Y, ldy, (hipStream_t)stream);
+}
+
+int msgemm_run(const msgemm_plan_t* plan, const void* X, int64_t ldx, void* Y, int64_t ldy, void* stream)
+{
+    if (!plan || !X || !Y) return MSGEMM_ERR_INVALID_ARG;
+    const Plan& p = *reinterpret_cast<const Plan*>(plan);
+    if (ldx < p.k || ldy < p.m) return MSGEMM_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (p.variant == MSGEMM_VARIANT_FUSED_LDS) return msgemm::launch_fused(p, X, ldx, Y, ldy, s);
+    int rc = msgemm::launch_build_lut(p, X, ldx, p.lut_ws, s);
+    if (rc != MSGEMM_OK) return rc;
+    return msgemm::launch_consume_lut(p, p.lut_ws, Y, ldy, s);
+}
+
+int msgemm_dequant_mfma_run(const msgemm_plan_t* plan, const void* X, int64_t ldx, void* Y, int64_t ldy,
+                            void* stream)
+{
+    if (!plan || !X || !Y) return MSGEMM_ERR_INVALID_ARG;
+    const Plan& p = *reinterpret_cast<const Plan*>(plan);
+    if (ldx < p.k || ldy < p.m) return MSGEMM_ERR_INVALID_ARG;
+    if (p.x_dtype == MSGEMM_I8) return MSGEMM_ERR_UNSUPPORTED;
+    return msgemm::launch_dequant_mfma(p, X, ldx, Y, ldy, (hipStream_t)stream);
+}
+
+void msgemm_destroy(msgemm_plan_t* plan)
+{
+    if (!plan) return;
+    (void)hipDeviceSynchronize();
+    msgemm::free_plan(reinterpret_cast<Plan*>(plan));
+}
+
+const char* msgemm_status_string(int status)
+{
+    switch (status) {
+    case MSGEMM_OK: return "ok";
+    case MSGEMM_ERR_INVALID_ARG: return "invalid argument";
+    case MSGEMM_ERR_ALLOC: return "allocation failed";
+    case MSGEMM_ERR_HIP: return "HIP runtime error";
+    case MSGEMM_ERR_UNSUPPORTED: return "not supported by the requested variant";
+    default: return "unknown status";
+    }
+}
+
+int msgemm_last_hip_error(void) { return msgemm::g_last_hip_error; }
+
+const char* msgemm_version(void) { return "0.1"; }
+
+}  // extern "C"

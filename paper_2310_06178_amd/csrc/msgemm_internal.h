@@ -1,0 +1,78 @@
+// Internal declarations shared by the translation units of libmsgemm.so.
+// Nothing here is part of the public ABI (see include/msgemm.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "msgemm.h"
+
+namespace msgemm {
+
+// How the 64 lanes of a wavefront share one streamed panel of codes in the
+// fused kernel.  A k-tile holds `groups` tables (d = 2: one per pair of
+// k-indices); a panel is `panel_rows` rows by `groups` groups and is read as
+// 16 loads of 64 lanes x `lane_bytes` bytes.
+struct FusedShape {
+    int groups;       // tables resident in LDS per workgroup: 16, 32 or 64
+    int lane_bytes;   // bytes (= rows) a lane takes per load: 4, 8 or 16
+    int cols;         // batch columns per table entry (one pass over the codes)
+    int entry_bytes;  // bytes per table value: 4 (fp32/int32) or 2 (fp16/int16)
+    int waves;        // wavefronts per workgroup
+    int panels;       // panels per workgroup
+    int panel_rows;   // 64 * 16 / groups * lane_bytes
+    int tile_rows;    // panels * panel_rows
+    size_t lds_bytes; // 256 * groups * cols * entry_bytes
+};
+
+struct Plan {
+    int64_t m, k, b;
+    int x_dtype, y_dtype, lut_dtype;
+    int d, scale_group, variant;
+    int64_t block;        // columns per scale block (k when there are no scales)
+    int64_t nblocks;      // k / block
+    int64_t gpb;          // LUT groups per block = ceil(block / d)
+    int64_t lut_groups;   // nblocks * gpb
+    int device;
+
+    uint8_t* codes;       // device, [m][k/2], plan-owned copy
+    uint16_t* scales;     // device fp16 [m][nblocks] or nullptr
+    float* lut_ws;        // device workspace for the two-launch variant
+    size_t lut_ws_bytes;
+
+    // fused variant
+    FusedShape fs;
+    int64_t ktiles;       // k-tiles (split-k factor)
+    int64_t row_blocks;   // workgroups along m
+    int64_t m_pad;        // row_blocks * tile_rows
+    int col_passes;       // ceil(b / cols)
+    uint8_t* codes_tiled; // device, [ktiles][m_pad / panel_rows][16][64][lane_bytes]
+    float* partials;      // device, [ktiles][b_pad][m_pad] fp32 / int32
+    unsigned* counters;   // device, [row_blocks * col_passes], zero between launches
+    size_t workspace_bytes;
+};
+
+void set_hip_error(hipError_t e);
+
+#define MSGEMM_HIP_TRY(expr)                         \
+    do {                                             \
+        hipError_t e__ = (expr);                     \
+        if (e__ != hipSuccess) {                     \
+            ::msgemm::set_hip_error(e__);            \
+            return MSGEMM_ERR_HIP;                   \
+        }                                            \
+    } while (0)
+
+// kernels_global_lut.hip
+int launch_build_lut(const Plan& p, const void* X, int64_t ldx, void* L, hipStream_t s);
+int launch_consume_lut(const Plan& p, const void* L, void* Y, int64_t ldy, hipStream_t s);
+
+// kernels_fused.hip
+int fused_choose_shape(Plan& p);  // fills p.fs, ktiles, row_blocks ...; MSGEMM_ERR_UNSUPPORTED if not applicable
+int launch_repack(const Plan& p, hipStream_t s);
+int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s);
+
+// kernels_mfma.hip
+int launch_dequant_mfma(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s);
+
+}  // namespace msgemm
