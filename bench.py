@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""msGeMM benchmark: one JSON line on stdout.
+
+A step is one pass of the whole hot path (table build, code stream, gather,
+scale, k-tile reduction, output conversion = one ``msgemm_run``) over one batch
+of synthetic activations.  The default workload is the b = 1 GEMV
+(m = 16384, k = 4096, int4 weights, fp16 activations).  Inputs are resident in
+HBM before the timed region.  To keep the code stream cold, successive steps
+rotate through enough independent weight copies (> 1 GiB in total) to defeat
+the 256 MB on-package cache, as a chain of layers would in a model.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg2] [--mode graph|eager]
+                    [--hot] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+# HBM bytes per launch of the fused kernel on cfg2, from rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE, scaled by a copy kernel of known size); None until
+# measured.  Source: profiles/fused_kernel_cfg2_pmc.txt
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes(cfg) -> int:
+    """What the method itself must move per GeMM (Section 4.2: k*b + m*k element
+    accesses, the same as a plain GeMM): the 4-bit codes once, the scales, X, Y."""
+    m, k, b = cfg["m"], cfg["k"], cfg["b"]
+    sx = {"f32": 4, "f16": 2, "bf16": 2, "i8": 1}[cfg["x"]]
+    sy = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4}[cfg["y"]]
+    total = m * k // 2 + k * b * sx + m * b * sy
+    if cfg["scale_group"]:
+        total += m * (k // cfg["scale_group"]) * 2
+    return total
+
+
+def cpu_baseline(cfg, codes, X, scales, budget_s=12.0):
+    """The oracle as it stands, on the host cores, on a bounded sample."""
+    import oracle
+    m, k, b = cfg["m"], cfg["k"], cfg["b"]
+    # rows sampled so that one oracle pass is ~<= 2e9 multiply-adds
+    rows = m if m * k * b <= 2e9 else max(256, int(2e9 // (k * b)))
+    c = codes[:rows]
+    s = None if scales is None else scales[:rows]
+    if cfg["x"] == "i8":
+        run = lambda: oracle.gemm_i32(c, X)
+    else:
+        Xd = oracle.bf16_bits_to_f64(X) if cfg["x"] == "bf16" else X.astype(np.float64)
+        run = lambda: oracle.gemm_f64(c, Xd, s, cfg["scale_group"])
+    run()  # warm-up
+    reps, t_total = 0, 0.0
+    best = float("inf")
+    while t_total < budget_s and reps < 50:
+        t0 = time.perf_counter()
+        run()
+        dt = time.perf_counter() - t0
+        best = min(best, dt)
+        t_total += dt
+        reps += 1
+    mean = t_total / reps
+    return {
+        "value": 2.0 * rows * k * b / mean / 1e12,
+        "unit": "TOPS",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": f"{rows} of {m} rows x all k x all b, {reps} passes, mean {mean * 1e3:.2f} ms, best {best * 1e3:.2f} ms",
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--mode", choices=["graph", "eager"], default="graph")
+    ap.add_argument("--hot", action="store_true", help="one weight copy (cache-resident), labelled as such")
+    ap.add_argument("--variant", type=int, default=0)
+    ap.add_argument("--d", type=int, default=None)
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the path has no multi-GPU part); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2310_06178_amd import binding as B
+    from paper_2310_06178_amd import inputs, torch_io
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    B.load()
+    torch.cuda.set_device(0)
+
+    cfg, codes, X, scales = inputs.make_config(args.config)
+    m, k, b = cfg["m"], cfg["k"], cfg["b"]
+    if args.steps is None:
+        args.steps = 2000 if b == 1 else 100
+    d = cfg["d"] if args.d is None else args.d
+    code_bytes = m * k // 2
+    n_copies = 1 if args.hot else (1 << 30) // code_bytes + 2
+    n_copies = max(1, min(n_copies, 64))
+
+    dX = torch_io.to_device(X, cfg["x"])
+    dS = torch_io.to_device(scales, "scales")
+    plans = []
+    rng = np.random.default_rng(1234)
+    for i in range(n_copies):
+        # independent weight bytes per copy (copy 0 is the seeded config itself)
+        ci = codes if i == 0 else rng.integers(0, 256, size=codes.shape, dtype=np.uint8)
+        dC = torch_io.to_device(ci, "codes")
+        plans.append(B.msgemm_plan(m, k, b, cfg["x"], cfg["y"], d, cfg["scale_group"], dC, dS, args.variant))
+        torch.cuda.synchronize()
+        del dC
+    info = B.msgemm_plan_get_info(plans[0])
+    Y = torch_io.empty_output(b, m, cfg["y"])
+
+    def step(i):
+        B.msgemm_run(plans[i % n_copies], dX, k, Y, m)
+
+    for i in range(max(args.warmup, 1)):
+        step(i)
+    torch.cuda.synchronize()
+
+    mode = args.mode
+    graph = None
+    stream = torch.cuda.Stream()
+    if mode == "graph":
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                for i in range(args.steps):
+                    step(i)
+            graph.replay()  # untimed replay: instantiation / upload costs stay outside
+            torch.cuda.synchronize()
+        except Exception as e:  # capture not possible: time the eager loop instead
+            print(f"bench.py: graph capture failed ({e}); timing eager launches", file=sys.stderr)
+            graph, mode = None, "eager"
+
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    with torch.cuda.stream(stream):
+        ev0.record(stream)
+        if graph is not None:
+            graph.replay()
+        else:
+            for i in range(args.steps):
+                step(i)
+        ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu_ms = ev0.elapsed_time(ev1)
+
+    # the last step ran on plan (steps-1) % n_copies; copy 0 has a known answer:
+    # run it once more eagerly for the parity spot check
+    step(0)
+    torch.cuda.synchronize()
+
+    ms_per_step = wall * 1e3 / args.steps
+    kernel_us = gpu_ms * 1e3 / args.steps  # HIP events on the launch stream
+    alg = algorithmic_bytes(cfg)
+    achieved = alg / (kernel_us * 1e-6) / 1e9
+    tops = 2.0 * m * k * b / (wall / args.steps) / 1e12
+
+    out = {
+        "metric": "effective TOPS (2mkb/t), int4-weight LUT GeMM (msGeMM)",
+        "value": tops,
+        "unit": "TOPS",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": {"f32": "f32", "f16": "f32", "bf16": "f32", "i8": "int32"}[cfg["x"]],
+        "data": "synthetic",
+        "config": {
+            "workload": f"{args.config}: m={m} k={k} b={b} int4 W, {cfg['x']} X, {cfg['y']} Y, "
+                        f"scale_group={cfg['scale_group']}, d={info['d']}",
+            "variant": {1: "global_lut", 2: "fused_lds"}[info["variant"]],
+            "tile_rows": info["tile_rows"], "tile_groups": info["tile_groups"],
+            "split_k": info["split_k"], "col_chunk": info["col_chunk"],
+            "weight_copies_rotated": n_copies,
+            "cache_state": "hot (single weight copy)" if args.hot else "cold (rotating copies > 1 GiB)",
+            "launch": mode,
+            "paper_op_ratio": m * k / (16 ** info["d"] * k + (k / info["d"] - 1) * m),
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
+            "algorithmic_bytes": alg,
+            "kernel_us": kernel_us,
+        },
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(cfg, codes, X, scales)
+
+    for p in plans:
+        B.msgemm_destroy(p)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

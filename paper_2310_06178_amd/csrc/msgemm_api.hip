@@ -116,7 +116,7 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtyp
         const size_t tiled = (size_t)p->ktiles * (size_t)p->m_pad * (size_t)(p->fs.groups);
         const size_t b_pad = (size_t)p->col_passes * (size_t)p->fs.cols;
         const size_t part = (size_t)p->ktiles * b_pad * (size_t)p->m_pad * 4u;
-        const size_t cnt = (size_t)p->row_blocks * (size_t)p->col_passes * sizeof(unsigned);
+        const size_t cnt = (size_t)(p->m_pad / p->fs.panel_rows) * (size_t)p->col_passes * sizeof(unsigned);
         e = hipMalloc((void**)&p->codes_tiled, tiled);
         if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
         e = hipMalloc((void**)&p->partials, part);

@@ -197,3 +197,94 @@ def test_plan_rejects_bad_arguments():
     finally:
         B.msgemm_destroy(plan)
     B.msgemm_destroy(None)  # allowed
+
+
+# ---------------------------------------------------------------------------
+# fused LDS variant (d = 2): tiles, ragged tails, k-tile reduction
+
+FUSED_SMALL = [
+    # m, k, b, xd, sg   -- k/2 = groups; 64 groups per k-tile, 256 rows per panel
+    (12, 4, 1, "f32", 0),        # far smaller than one tile
+    (300, 520, 3, "f32", 0),     # 2 panels (ragged), 5 k-tiles (ragged)
+    (2049, 1024, 1, "f16", 128),  # 9 panels, one row in the last
+    (513, 512, 2, "bf16", 256),  # scale block spans two k-tiles
+    (700, 768, 2, "i8", 0),
+    (4100, 256, 1, "f16", 0),    # more panels than wavefronts per workgroup
+]
+
+
+@pytest.mark.parametrize("m,k,b,xd,sg", FUSED_SMALL)
+def test_fused_variant_small(m, k, b, xd, sg):
+    codes = inputs.make_codes(m, k, seed=m + 3 * k)
+    X = inputs.make_x(k, b, xd, seed=k + b + 1)
+    scales = inputs.make_scales(m, k, sg, seed=6) if sg else None
+    ref = oracle_y(codes, X, xd, scales, sg)
+    out, info = run_gpu(codes, X, xd, scales, sg, 2, B.VARIANT_FUSED_LDS, ldx_pad=10, ldy_pad=5)
+    assert info["variant"] == B.VARIANT_FUSED_LDS and info["d"] == 2
+    assert info["split_k"] == -(-(k // 2) // info["tile_groups"])
+    check(out, ref, xd, "fused")
+    if xd == "i8":
+        out_g, _ = run_gpu(codes, X, xd, scales, sg, 2, B.VARIANT_GLOBAL_LUT)
+        assert np.array_equal(out, out_g)
+
+
+def test_fused_scale_group_not_tileable_falls_back():
+    m, k, b = 64, 256, 2
+    codes = inputs.make_codes(m, k, seed=1)
+    X = inputs.make_x(k, b, "f16", seed=2)
+    scales = inputs.make_scales(m, k, 32, seed=3)
+    out, info = run_gpu(codes, X, "f16", scales, 32, 0, B.VARIANT_AUTO)
+    assert info["variant"] == B.VARIANT_GLOBAL_LUT
+    check(out, oracle_y(codes, X, "f16", scales, 32), "f16", "fallback")
+
+
+def test_fused_repeated_calls_reuse_workspace():
+    """The k-tile counters must be back at zero after every launch."""
+    m, k, b = 1000, 1024, 2
+    codes = inputs.make_codes(m, k, seed=8)
+    dC = torch_io.to_device(codes, "codes")
+    plan = B.msgemm_plan(m, k, b, "i8", "i32", 2, 0, dC, None, B.VARIANT_FUSED_LDS)
+    try:
+        for rep in range(4):
+            X = inputs.make_x(k, b, "i8", seed=20 + rep)
+            dX = torch_io.to_device(X, "i8")
+            Y = torch_io.empty_output(b, m, "i32")
+            B.msgemm_run(plan, dX, k, Y, m)
+            torch.cuda.synchronize()
+            assert np.array_equal(torch_io.to_host(Y), oracle.gemm_i32(codes, X)), rep
+    finally:
+        B.msgemm_destroy(plan)
+
+
+# ---------------------------------------------------------------------------
+# the benchmark configurations at full size, library's own choice of variant
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3a", "cfg3b", "cfg4", "cfg5"])
+def test_config_full_size(name):
+    cfg, codes, X, scales = inputs.make_config(name)
+    m, k, b, xd, sg = cfg["m"], cfg["k"], cfg["b"], cfg["x"], cfg["scale_group"]
+    out, info = run_gpu(codes, X, xd, scales, sg, cfg["d"], B.VARIANT_AUTO)
+    assert info["variant"] == B.VARIANT_FUSED_LDS
+    # the oracle takes every row where that is quick, else a seeded sample of rows
+    budget = 1.2e9
+    if m * k * b <= budget:
+        rows = np.arange(m)
+    else:
+        n = max(256, int(budget // (k * b)))
+        rows = np.sort(np.random.default_rng(99).choice(m, size=n, replace=False))
+    ref = oracle_y(codes[rows], X, xd, None if scales is None else scales[rows], sg)
+    err = check(np.ascontiguousarray(out[:, rows]), ref, xd, name)
+    if xd != "i8":
+        # against the oracle's own rounding to the output type as well
+        ref_rounded = oracle.round_to(ref, cfg["y"])
+        err_r = oracle.rel_l2(torch_io.to_f64(np.ascontiguousarray(out[:, rows])), torch_io.to_f64(ref_rounded))
+        assert err_r <= TOL[xd]
+    print(f"{name}: rows checked {len(rows)}/{m}, rel L2 {err:.3e}")
+
+
+def test_config2_d3_sweep_point():
+    """Config 2 also asks for d = 3 (k = 4096 is not a multiple of 3: short last group)."""
+    cfg, codes, X, _ = inputs.make_config("cfg2", m=2048)
+    out, info = run_gpu(codes, X, "f16", None, 0, 3, B.VARIANT_AUTO)
+    assert info["d"] == 3 and info["lut_groups"] == 1366
+    check(out, oracle_y(codes, X, "f16", None, 0), "f16", "cfg2 d=3")
