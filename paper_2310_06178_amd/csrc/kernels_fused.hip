@@ -33,6 +33,7 @@ namespace {
 
 constexpr int kWaves = 8;           // wavefronts per workgroup
 constexpr int kLoadsPerPanel = 16;  // one load per group of a 16-group class
+constexpr int kAuxSc1 = 16;         // buffer-load cache policy: coherent at agent scope
 
 struct FusedArgs {
     const uint8_t* tiled;
@@ -46,6 +47,7 @@ struct FusedArgs {
     int64_t m, k, b, m_pad, b_pad;
     int ktiles, panels_total, panels_per_wg, row_blocks, col_passes;
     int64_t nblocks;        // scale blocks per row
+    int64_t partial_span;   // bytes of the partial buffer addressable from any panel base (< 2^31)
     int tiles_per_block;    // k-tiles per scale block
 };
 
@@ -55,18 +57,11 @@ template <> struct LaneLoad<8> { using type = uint2; };
 template <> struct LaneLoad<4> { using type = uint32_t; };
 
 template <int LB>
-__device__ __forceinline__ uint32_t load_byte(const typename LaneLoad<LB>::type& v, int s)
+__device__ __forceinline__ uint32_t load_word(const typename LaneLoad<LB>::type& v, int w)
 {
-    uint32_t w;
-    if constexpr (LB == 16) {
-        const int q = s >> 2;
-        w = q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w;
-    } else if constexpr (LB == 8) {
-        w = (s >> 2) == 0 ? v.x : v.y;
-    } else {
-        w = v;
-    }
-    return (w >> (8 * (s & 3))) & 0xffu;
+    if constexpr (LB == 16) return w == 0 ? v.x : w == 1 ? v.y : w == 2 ? v.z : v.w;
+    else if constexpr (LB == 8) return w == 0 ? v.x : v.y;
+    else return v;
 }
 
 template <typename ET> __device__ __forceinline__ ET make_entry(float v);
@@ -80,20 +75,45 @@ template <> struct EntryAcc<__half> { using type = float; static __device__ __fo
 template <> struct EntryAcc<int> { using type = int; static __device__ __forceinline__ int widen(int e) { return e; } };
 template <> struct EntryAcc<short> { using type = int; static __device__ __forceinline__ int widen(short e) { return (int)e; } };
 
-template <typename T> __device__ __forceinline__ T lane_xor(T v, int mask)
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ unsigned bits_of(float v) { return __float_as_uint(v); }
+__device__ __forceinline__ unsigned bits_of(int v) { return (unsigned)v; }
+__device__ __forceinline__ void set_bits(float& d, unsigned u) { d = __uint_as_float(u); }
+__device__ __forceinline__ void set_bits(int& d, unsigned u) { d = (int)u; }
+
+// a <- a + (a moved across the wave halves), two registers at a time: after the
+// call lanes 0..31 hold the full sum of `a` and lanes 32..63 the full sum of `b`.
+template <typename AT> __device__ __forceinline__ AT fold32(AT a, AT b)
 {
-    return __shfl_xor(v, mask, 64);
+    v2u r = __builtin_amdgcn_permlane32_swap(bits_of(a), bits_of(b), false, false);
+    AT x, y;
+    set_bits(x, r.x);
+    set_bits(y, r.y);
+    return x + y;
+}
+// Same across the two 16-lane rows of each half: even rows end up with `a`, odd rows with `b`.
+template <typename AT> __device__ __forceinline__ AT fold16(AT a, AT b)
+{
+    v2u r = __builtin_amdgcn_permlane16_swap(bits_of(a), bits_of(b), false, false);
+    AT x, y;
+    set_bits(x, r.x);
+    set_bits(y, r.y);
+    return x + y;
 }
 
-// Stores / loads that stay coherent across the chip's L2 slices (the partial
-// sums of one output are produced on different XCDs).
+// The partial sums of one output come from workgroups on different XCDs, whose
+// L2 slices are not coherent with each other: partials and counters are only
+// touched with agent-scope atomic accesses (they go to the coherence point), and
+// ordered by waiting for the stores to be acknowledged before the counter is
+// bumped.  No cache-wide write-back / invalidate is needed that way.
 __device__ __forceinline__ void store_agent(float* p, float v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float load_agent(const float* p)
+__device__ __forceinline__ void wait_vmem()
 {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 template <typename AT> __device__ __forceinline__ float as_stored(AT v);
@@ -103,27 +123,43 @@ template <typename AT> __device__ __forceinline__ AT from_stored(float v);
 template <> __device__ __forceinline__ float from_stored<float>(float v) { return v; }
 template <> __device__ __forceinline__ int from_stored<int>(float v) { return __float_as_int(v); }
 
+template <typename ET, int C> struct alignas(C * sizeof(ET) >= 16 ? 16 : C * sizeof(ET)) EntryVec { ET v[C]; };
+
+// Row of a panel that lane (q, j) keeps in accumulator slot s.  Chosen so that
+// after the cross-lane fold lane l holds the rows base + 64*i + l, i.e. the
+// epilogue's stores are contiguous across the wavefront.
+template <int NQ, int LB>
+__host__ __device__ __forceinline__ int panel_row(int q, int j, int s)
+{
+    constexpr int nfinal = LB / NQ;
+    const int qr = q / NQ;
+    return (s % nfinal) * 64 + (qr * NQ + s / nfinal) * 16 + j;
+}
+
 template <typename XT, typename YT, typename ET, int C, int G, int LB>
 __global__ void __launch_bounds__(kWaves * 64)
 fused_kernel(FusedArgs a)
 {
     using AT = typename EntryAcc<ET>::type;
     using LoadT = typename LaneLoad<LB>::type;
+    using Entry = EntryVec<ET, C>;
     constexpr int NQ = G / 16;                    // lanes sharing a row (one per 16-group class)
     constexpr int kEntryBytes = C * (int)sizeof(ET);
     constexpr int kCodeStride = G * kEntryBytes;  // bytes between consecutive codes
-    constexpr int kPanelRows = (4 / NQ) * LB * 16;
+    constexpr int kFinal = LB / NQ;               // outputs per lane and column after the fold
+    constexpr int kPanelRows = kFinal * 64;
     constexpr int kThreads = kWaves * 64;
     static_assert(G == 16 || G == 32 || G == 64, "G");
     static_assert(kThreads % G == 0, "threads per group");
+    static_assert(LB % NQ == 0, "rows per lane must split over the lanes sharing them");
 
-    extern __shared__ __align__(16) unsigned char lds[];
+    __shared__ __align__(16) unsigned char lds[256 * kCodeStride];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int q = lane >> 4, j = lane & 15;
-    const int qg = q % NQ, qr = q / NQ;
+    const int qg = q % NQ;
 
     int bid = blockIdx.x;
     const int kt = bid % a.ktiles; bid /= a.ktiles;
@@ -134,48 +170,46 @@ fused_kernel(FusedArgs a)
     const XT* __restrict__ X = (const XT*)a.X;
     YT* __restrict__ Y = (YT*)a.Y;
 
-    // ---- first panel's codes: issued before the tables are built so that the
-    // HBM latency overlaps phase 1
-    const int panel_first = rb * a.panels_per_wg;
-    int panels_here = a.panels_total - panel_first;
-    if (panels_here > a.panels_per_wg) panels_here = a.panels_per_wg;
-    const LoadT* __restrict__ tiled = (const LoadT*)a.tiled;
-    auto panel_ptr = [&](int p) {
-        return tiled + ((int64_t)kt * a.panels_total + (panel_first + p)) * (kLoadsPerPanel * 64) + lane;
-    };
-    LoadT data[kLoadsPerPanel];
-    int p = wave;
-    if (p < panels_here) {
-        const LoadT* src = panel_ptr(p);
-#pragma unroll
-        for (int t = 0; t < kLoadsPerPanel; ++t) data[t] = src[t * 64];
-    }
-
-    // ---- phase 1: L(code, g, c) = b(code & 15) X(2g', c) + b(code >> 4) X(2g'+1, c)
+    // ---- activations of this k-tile (fetched first: the wait for them must not
+    // also wait for the code loads issued next)
+    const int g = tid % G;
+    AT x0[C], x1[C];
     {
-        const int g = tid % G;
         const int64_t kk = ((int64_t)kt * G + g) * 2;
-        AT x0[C], x1[C];
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             const bool live = (col0 + c < a.b) && (kk < a.k);
             x0[c] = live ? (AT)XTraits<XT>::load(X + (col0 + c) * a.ldx + kk) : (AT)0;
             x1[c] = live ? (AT)XTraits<XT>::load(X + (col0 + c) * a.ldx + kk + 1) : (AT)0;
         }
-        for (int code = tid / G; code < 256; code += kThreads / G) {
-            const AT w0 = (AT)decode4(code & 15), w1 = (AT)decode4(code >> 4);
-            ET e[C];
+    }
+
+    // ---- first panel's codes: in flight while the tables are built
+    const int panel_first = rb * a.panels_per_wg;
+    int panels_here = a.panels_total - panel_first;
+    if (panels_here > a.panels_per_wg) panels_here = a.panels_per_wg;
+    const LoadT* __restrict__ tiled =
+        (const LoadT*)a.tiled + ((int64_t)kt * a.panels_total + panel_first) * (kLoadsPerPanel * 64) + lane;
+    LoadT data[kLoadsPerPanel];
+    int p = wave;
+    if (p < panels_here) {
+        const LoadT* src = tiled + (int64_t)p * (kLoadsPerPanel * 64);
 #pragma unroll
-            for (int c = 0; c < C; ++c) {
-                if constexpr (sizeof(AT) == 4 && __is_same(AT, float))
-                    e[c] = make_entry<ET>(fmaf(w0, x0[c], w1 * x1[c]));
-                else
-                    e[c] = make_entry_i<ET>(w0 * x0[c] + w1 * x1[c]);
-            }
-            ET* dst = (ET*)(lds + (size_t)code * kCodeStride + g * kEntryBytes);
+        for (int t = 0; t < kLoadsPerPanel; ++t) data[t] = src[t * 64];
+    }
+
+    // ---- phase 1: L(code, g, c) = b(code & 15) X(2g', c) + b(code >> 4) X(2g'+1, c)
+    for (int code = tid / G; code < 256; code += kThreads / G) {
+        const AT w0 = (AT)decode4(code & 15), w1 = (AT)decode4(code >> 4);
+        Entry e;
 #pragma unroll
-            for (int c = 0; c < C; ++c) dst[c] = e[c];
+        for (int c = 0; c < C; ++c) {
+            if constexpr (__is_same(AT, float))
+                e.v[c] = make_entry<ET>(fmaf(w0, x0[c], w1 * x1[c]));
+            else
+                e.v[c] = make_entry_i<ET>(w0 * x0[c] + w1 * x1[c]);
         }
+        *(Entry*)(lds + (size_t)code * kCodeStride + g * kEntryBytes) = e;
     }
     __syncthreads();
 
@@ -188,73 +222,129 @@ fused_kernel(FusedArgs a)
 #pragma unroll
             for (int c = 0; c < C; ++c) acc[s][c] = 0;
 
-#pragma unroll
-        for (int t = 0; t < kLoadsPerPanel; ++t) {
+        // One load's worth of look-ups is issued while the previous one's
+        // entries are being added: the LDS latency hides behind the adds
+        // without the scheduler hoisting all 16*LB reads at once.
+        auto issue = [&](int t, Entry (&dst)[LB]) {
             const uint32_t lane_off = class_base + (uint32_t)((j + t) & 15) * kEntryBytes;
 #pragma unroll
             for (int s = 0; s < LB; ++s) {
-                const uint32_t code = load_byte<LB>(data[t], s);
-                const ET* e = (const ET*)(lds + code * kCodeStride + lane_off);
-                ET v[C];
-#pragma unroll
-                for (int c = 0; c < C; ++c) v[c] = e[c];
-#pragma unroll
-                for (int c = 0; c < C; ++c) acc[s][c] += EntryAcc<ET>::widen(v[c]);
+                const uint32_t w = load_word<LB>(data[t], s >> 2);
+                uint32_t addr;
+                if constexpr (kCodeStride == 256)  // code byte drops straight into address bits 15:8
+                    addr = __builtin_amdgcn_perm(w, lane_off, 0x0c0c0000u | ((4u + (s & 3)) << 8));
+                else
+                    addr = ((w >> (8 * (s & 3))) & 0xffu) * kCodeStride + lane_off;
+                dst[s] = *(const Entry*)(lds + addr);
             }
-        }
-        // next panel's codes (if any) while this panel is being finished
-        const int pn = p + kWaves;
-        if (pn < panels_here) {
-            const LoadT* src = panel_ptr(pn);
-#pragma unroll
-            for (int t = 0; t < kLoadsPerPanel; ++t) data[t] = src[t * 64];
-        }
-
-        // lanes that share rows: add the NQ group classes
-        if constexpr (NQ >= 2) {
+        };
+        auto consume = [&](const Entry (&src)[LB]) {
 #pragma unroll
             for (int s = 0; s < LB; ++s)
 #pragma unroll
                 for (int c = 0; c < C; ++c) {
-                    acc[s][c] += lane_xor(acc[s][c], 16);
-                    if constexpr (NQ == 4) acc[s][c] += lane_xor(acc[s][c], 32);
+                    acc[s][c] += EntryAcc<ET>::widen(src[s].v[c]);
+                    // pin the add to this stage: otherwise the compiler sinks all
+                    // adds below the gather and keeps every table entry live
+                    asm volatile("" : "+v"(acc[s][c]));
                 }
+        };
+        Entry e0[LB], e1[LB];
+        issue(0, e0);
+#pragma unroll
+        for (int t = 0; t < kLoadsPerPanel; t += 2) {
+            issue(t + 1, e1);
+            consume(e0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + 2 < kLoadsPerPanel) issue(t + 2, e0);
+            consume(e1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // next panel's codes (if any) while this panel is being finished
+        const int pn = p + kWaves;
+        if (pn < panels_here) {
+            const LoadT* src = tiled + (int64_t)pn * (kLoadsPerPanel * 64);
+#pragma unroll
+            for (int t = 0; t < kLoadsPerPanel; ++t) data[t] = src[t * 64];
+        }
+
+        // lanes that share rows: fold the NQ group classes; each lane ends up
+        // with kFinal distinct rows (base + 64*i + lane)
+        AT fin[kFinal][C];
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            if constexpr (NQ == 4) {
+                AT half[LB / 2];
+#pragma unroll
+                for (int s = 0; s < LB / 2; ++s) half[s] = fold32(acc[s][c], acc[s + LB / 2][c]);
+#pragma unroll
+                for (int s = 0; s < kFinal; ++s) fin[s][c] = fold16(half[s], half[s + kFinal]);
+            } else if constexpr (NQ == 2) {
+#pragma unroll
+                for (int s = 0; s < kFinal; ++s) fin[s][c] = fold16(acc[s][c], acc[s + kFinal][c]);
+            } else {
+#pragma unroll
+                for (int s = 0; s < kFinal; ++s) fin[s][c] = acc[s][c];
+            }
         }
 
         // scale of this k-tile's block (Section 3.3), then hand the partial over
         const int panel_g = panel_first + p;
-        const int64_t row_base = (int64_t)panel_g * kPanelRows;
+        const int64_t row0 = (int64_t)panel_g * kPanelRows + lane;
+        float* part = a.partials + ((int64_t)kt * a.b_pad + col0) * a.m_pad + row0;
 #pragma unroll
-        for (int s = 0; s < LB; ++s) {
-            if ((s % NQ) != qg) continue;   // spread the stores over the NQ lanes holding the same sums
-            const int64_t row = row_base + (int64_t)(qr * LB + s) * 16 + j;
+        for (int i = 0; i < kFinal; ++i) {
             float qv = 1.0f;
-            if (a.scales && row < a.m) qv = __half2float(a.scales[row * a.nblocks + kt / a.tiles_per_block]);
+            if constexpr (__is_same(AT, float)) {
+                const int64_t row = row0 + 64 * i;
+                if (a.scales && row < a.m) qv = __half2float(a.scales[row * a.nblocks + kt / a.tiles_per_block]);
+            }
 #pragma unroll
             for (int c = 0; c < C; ++c) {
-                AT v = acc[s][c];
+                AT v = fin[i][c];
                 if constexpr (__is_same(AT, float)) v = v * qv;
-                store_agent(a.partials + ((int64_t)kt * a.b_pad + (col0 + c)) * a.m_pad + row, as_stored<AT>(v));
+                store_agent(part + (int64_t)c * a.m_pad + 64 * i, as_stored<AT>(v));
             }
         }
-        __threadfence();
+        wait_vmem();  // partials acknowledged before the counter moves
         unsigned prev = 0;
         unsigned* counter = a.counters + (int64_t)panel_g * a.col_passes + cp;
         if (lane == 0)
-            prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        prev = __shfl(prev, 0, 64);
+            prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        prev = __builtin_amdgcn_readfirstlane(prev);
         if (prev == (unsigned)a.ktiles - 1u) {
-            // every k-tile's partial for this panel has been published: reduce in k-tile order
-            __threadfence();
-            for (int idx = lane; idx < kPanelRows * C; idx += 64) {
-                const int c = idx / kPanelRows;
-                const int64_t row = row_base + (idx % kPanelRows);
-                if (row >= a.m || col0 + c >= a.b) continue;
-                const float* src = a.partials + (col0 + c) * a.m_pad + row;
-                AT sum = 0;
-                for (int t = 0; t < a.ktiles; ++t)
-                    sum += from_stored<AT>(load_agent(src + (int64_t)t * a.b_pad * a.m_pad));
-                Y[(col0 + c) * a.ldy + row] = to_output<YT, AT>(sum);
+            // every k-tile's partial for this panel has been published: add them
+            // in k-tile order.  Buffer loads with the agent-coherent policy bit:
+            // independent loads stay in flight together.
+            // (the descriptor is wave-uniform; the lane's rows go into the offset)
+            __amdgpu_buffer_rsrc_t rsrc =
+                __builtin_amdgcn_make_buffer_rsrc((void*)a.partials, 0, (int)a.partial_span, 0x00020000);
+            const uint32_t lane_base = (uint32_t)(col0 * a.m_pad + row0) * 4u;
+            const uint32_t tile_stride = (uint32_t)(a.b_pad * a.m_pad * 4);
+            AT sum[kFinal][C];
+#pragma unroll
+            for (int i = 0; i < kFinal; ++i)
+#pragma unroll
+                for (int c = 0; c < C; ++c) sum[i][c] = 0;
+#pragma unroll 4
+            for (int t = 0; t < a.ktiles; ++t) {
+#pragma unroll
+                for (int i = 0; i < kFinal; ++i)
+#pragma unroll
+                    for (int c = 0; c < C; ++c) {
+                        const uint32_t off = lane_base + (uint32_t)t * tile_stride + (uint32_t)(c * (uint32_t)a.m_pad + 64 * i) * 4u;
+                        const unsigned u = __builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)off, 0, kAuxSc1);
+                        AT v;
+                        set_bits(v, u);
+                        sum[i][c] += v;
+                    }
+            }
+#pragma unroll
+            for (int i = 0; i < kFinal; ++i) {
+                const int64_t row = row0 + 64 * i;
+#pragma unroll
+                for (int c = 0; c < C; ++c)
+                    if (row < a.m && col0 + c < a.b) Y[(col0 + c) * a.ldy + row] = to_output<YT, AT>(sum[i][c]);
             }
             if (lane == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
@@ -279,8 +369,8 @@ repack_kernel(const uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled, in
         const int64_t panel = r % panels_total;
         const int64_t kt = r / panels_total;
         const int q = lane >> 4, j = lane & 15;
-        const int qg = q % NQ, qr = q / NQ;
-        const int64_t row = panel * kPanelRows + (int64_t)(qr * LB + s) * 16 + j;
+        const int qg = q % NQ;
+        const int64_t row = panel * kPanelRows + panel_row<NQ, LB>(q, j, s);
         const int64_t byte = kt * G + 16 * qg + ((j + t) & 15);
         tiled[o] = (row < m && byte < kbytes) ? codes[row * kbytes + byte] : (uint8_t)0;
     }
@@ -298,14 +388,8 @@ template <typename XT, typename YT, typename ET, int C, int G, int LB>
 int launch_one(const Plan& p, const FusedArgs& a, hipStream_t s)
 {
     auto kern = fused_kernel<XT, YT, ET, C, G, LB>;
-    static thread_local bool attr_set = false;
-    if (!attr_set) {
-        MSGEMM_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)p.fs.lds_bytes));
-        attr_set = true;
-    }
     const unsigned grid = (unsigned)((int64_t)p.ktiles * p.row_blocks * p.col_passes);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kWaves * 64), p.fs.lds_bytes, s, a);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kWaves * 64), 0, s, a);
     MSGEMM_HIP_TRY(hipGetLastError());
     return MSGEMM_OK;
 }
@@ -344,6 +428,8 @@ int fused_choose_shape(Plan& p)
     p.row_blocks = (panels + ppw - 1) / ppw;
     p.m_pad = panels * fs.panel_rows;
     if ((int64_t)p.ktiles * p.row_blocks * p.col_passes > 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
+    // the k-tile reduction addresses the partial buffer with 32-bit byte offsets
+    if ((int64_t)p.ktiles * p.col_passes * sc.C * p.m_pad * 4 >= 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
     return MSGEMM_OK;
 }
 
@@ -379,6 +465,7 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     a.row_blocks = (int)p.row_blocks;
     a.col_passes = p.col_passes;
     a.nblocks = p.nblocks;
+    a.partial_span = (int64_t)p.ktiles * a.b_pad * p.m_pad * 4;
     a.tiles_per_block = p.scale_group > 0 ? (int)(p.scale_group / (2 * p.fs.groups)) : 1;
 
     if (p.fs.cols == 1 && p.fs.groups == 64 && p.fs.lane_bytes == 16) {

@@ -276,8 +276,10 @@ def test_config_full_size(name):
     err = check(np.ascontiguousarray(out[:, rows]), ref, xd, name)
     if xd != "i8":
         # against the oracle's own rounding to the output type as well
-        ref_rounded = oracle.round_to(ref, cfg["y"])
-        err_r = oracle.rel_l2(torch_io.to_f64(np.ascontiguousarray(out[:, rows])), torch_io.to_f64(ref_rounded))
+        widen = {"f32": lambda a: a.astype(np.float64), "f16": oracle.f16_bits_to_f64,
+                 "bf16": oracle.bf16_bits_to_f64}[cfg["y"]]
+        ref_rounded = widen(oracle.round_to(ref, cfg["y"]))
+        err_r = oracle.rel_l2(torch_io.to_f64(np.ascontiguousarray(out[:, rows])), ref_rounded)
         assert err_r <= TOL[xd]
     print(f"{name}: rows checked {len(rows)}/{m}, rel L2 {err:.3e}")
 
