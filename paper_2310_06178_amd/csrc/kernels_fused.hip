@@ -9,31 +9,64 @@
 //   A workgroup owns one k-tile and `panels` row panels; each wavefront
 //   streams whole panels.  Outputs are reduced over k-tiles through a
 //   partial-sum buffer: the wavefront that delivers the last partial of a
-//   panel adds them up in k-tile order and writes Y.
+//   panel adds them up in k-tile order and writes Y (one launch, and the sum
+//   order is fixed, so results are reproducible).
 //
 // LDS layout and the gather
 //   entry(code, g) sits at byte (code*G + g) * C * sizeof(ET).  Lane l = 16q+j
 //   of a wavefront looks up group 16*(q % NQ) + (j + t) % 16 in its t-th load
-//   (NQ = G/16), so the G/NQ... lanes that are served together always address
-//   different groups, hence different banks, whatever the codes are: the
-//   gather is bank-conflict free by construction.  A lane keeps the same rows
-//   for all 16 loads of a panel, so its accumulators never move between lanes;
-//   only the NQ lanes that share rows are added at the end of the panel.
+//   (NQ = G/16): lanes that are served together always address different
+//   groups, hence different banks, whatever the codes are -- the gather is
+//   bank-conflict free by construction.  A lane keeps the same rows for all 16
+//   loads of a panel, so its accumulators never move between lanes; only the
+//   NQ lanes that share rows are folded together at the end of the panel.
 //
 // Code stream
 //   The plan stores the codes in the order the lanes consume them
 //   ([k-tile][panel][load][lane][byte]), so every load instruction of a
-//   wavefront reads one contiguous 64*LB-byte segment with full-width
-//   per-lane loads.
+//   wavefront reads one contiguous 64*LB-byte segment with full-width per-lane
+//   loads.  A wavefront keeps a ring of kRing loads in flight and refills a
+//   slot as soon as its bytes have been turned into LDS addresses.
+#include <stdlib.h>
+
 #include "device_types.h"
 #include "msgemm_internal.h"
+
+// Optional phase timestamps for kernel tuning (compiled out unless requested).
+#ifdef MSGEMM_PHASE_TRACE
+__device__ unsigned long long* g_msgemm_trace = nullptr;
+extern "C" int msgemm_debug_set_trace(unsigned long long* buf)
+{
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_msgemm_trace), &buf, sizeof(buf));
+}
+#define MSGEMM_TRACE(id)                                                                         \
+    do {                                                                                         \
+        if (g_msgemm_trace && (threadIdx.x & 63) == 0)                                           \
+            g_msgemm_trace[((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + (id)] = wall_clock64(); \
+    } while (0)
+#else
+#define MSGEMM_TRACE(id) do { } while (0)
+#endif
 
 namespace msgemm {
 namespace {
 
 constexpr int kWaves = 8;           // wavefronts per workgroup
 constexpr int kLoadsPerPanel = 16;  // one load per group of a 16-group class
-constexpr int kAuxSc1 = 16;         // buffer-load cache policy: coherent at agent scope
+#ifndef MSGEMM_RING
+#define MSGEMM_RING 8
+#endif
+#ifndef MSGEMM_EARLY
+#define MSGEMM_EARLY 8
+#endif
+constexpr int kRing = MSGEMM_RING;    // code loads a wavefront keeps in flight (a whole panel)
+constexpr int kEarly = MSGEMM_EARLY;  // of which requested before the tables are ready
+#ifndef MSGEMM_BUILDERS
+#define MSGEMM_BUILDERS 4
+#endif
+constexpr int kBuilders = MSGEMM_BUILDERS;  // wavefronts that build the tables (phase 1)
+constexpr int kAuxSc1 = 16;         // buffer cache policy bit: coherent at agent scope
+constexpr int kXcds = 8;            // L2 slices (XCDs); workgroups are dealt to them round-robin
 
 struct FusedArgs {
     const uint8_t* tiled;
@@ -42,13 +75,22 @@ struct FusedArgs {
     void* Y;
     int64_t ldy;
     const __half* scales;   // [m][nblocks] or nullptr
-    float* partials;        // [ktiles][b_pad][m_pad]
+    float* partials;        // [ktiles][b_pad][panels_total][64][outputs per lane]
     unsigned* counters;     // [panels_total][col_passes]
     int64_t m, k, b, m_pad, b_pad;
     int ktiles, panels_total, panels_per_wg, row_blocks, col_passes;
+    int row_groups;         // row_blocks * col_passes
+    int xcd_map;            // 1: workgroups that share outputs get ids congruent modulo kXcds
     int64_t nblocks;        // scale blocks per row
-    int64_t partial_span;   // bytes of the partial buffer addressable from any panel base (< 2^31)
+    int64_t partial_span;   // bytes of the partial buffer (< 2^31)
     int tiles_per_block;    // k-tiles per scale block
+    int reduce_mode;        // how partial sums over k-tiles become Y, see ReduceMode
+};
+
+enum ReduceMode {
+    kReduceDirect = 0,    // a single k-tile: the fused kernel writes Y itself
+    kReduceSecondPass = 1,  // partials to memory, a second small kernel adds them
+    kReduceLastArriver = 2  // partials to memory, the wavefront delivering the last one adds them
 };
 
 template <int LB> struct LaneLoad;
@@ -64,26 +106,41 @@ __device__ __forceinline__ uint32_t load_word(const typename LaneLoad<LB>::type&
     else return v;
 }
 
-template <typename ET> __device__ __forceinline__ ET make_entry(float v);
-template <> __device__ __forceinline__ float make_entry<float>(float v) { return v; }
-template <> __device__ __forceinline__ __half make_entry<__half>(float v) { return __float2half_rn(v); }
-template <typename ET> __device__ __forceinline__ ET make_entry_i(int v) { return (ET)v; }
-
 template <typename ET> struct EntryAcc;
-template <> struct EntryAcc<float> { using type = float; static __device__ __forceinline__ float widen(float e) { return e; } };
-template <> struct EntryAcc<__half> { using type = float; static __device__ __forceinline__ float widen(__half e) { return __half2float(e); } };
-template <> struct EntryAcc<int> { using type = int; static __device__ __forceinline__ int widen(int e) { return e; } };
-template <> struct EntryAcc<short> { using type = int; static __device__ __forceinline__ int widen(short e) { return (int)e; } };
+template <> struct EntryAcc<float> {
+    using type = float;
+    static __device__ __forceinline__ float widen(float e) { return e; }
+    static __device__ __forceinline__ float make(float v) { return v; }
+};
+template <> struct EntryAcc<__half> {
+    using type = float;
+    static __device__ __forceinline__ float widen(__half e) { return __half2float(e); }
+    static __device__ __forceinline__ __half make(float v) { return __float2half_rn(v); }
+};
+template <> struct EntryAcc<int> {
+    using type = int;
+    static __device__ __forceinline__ int widen(int e) { return e; }
+    static __device__ __forceinline__ int make(int v) { return v; }
+};
+template <> struct EntryAcc<short> {
+    using type = int;
+    static __device__ __forceinline__ int widen(short e) { return (int)e; }
+    static __device__ __forceinline__ short make(int v) { return (short)v; }
+};
 
 typedef unsigned v2u __attribute__((ext_vector_type(2)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ unsigned bits_of(float v) { return __float_as_uint(v); }
 __device__ __forceinline__ unsigned bits_of(int v) { return (unsigned)v; }
 __device__ __forceinline__ void set_bits(float& d, unsigned u) { d = __uint_as_float(u); }
 __device__ __forceinline__ void set_bits(int& d, unsigned u) { d = (int)u; }
 
-// a <- a + (a moved across the wave halves), two registers at a time: after the
-// call lanes 0..31 hold the full sum of `a` and lanes 32..63 the full sum of `b`.
+__device__ __forceinline__ float mul_add(float w, float x, float acc) { return fmaf(w, x, acc); }
+__device__ __forceinline__ int mul_add(int w, int x, int acc) { return w * x + acc; }
+
+// Sum across the wave halves, two registers at a time: afterwards lanes 0..31
+// hold the full sum of `a` and lanes 32..63 the full sum of `b`.
 template <typename AT> __device__ __forceinline__ AT fold32(AT a, AT b)
 {
     v2u r = __builtin_amdgcn_permlane32_swap(bits_of(a), bits_of(b), false, false);
@@ -102,32 +159,62 @@ template <typename AT> __device__ __forceinline__ AT fold16(AT a, AT b)
     return x + y;
 }
 
-// The partial sums of one output come from workgroups on different XCDs, whose
-// L2 slices are not coherent with each other: partials and counters are only
-// touched with agent-scope atomic accesses (they go to the coherence point), and
-// ordered by waiting for the stores to be acknowledged before the counter is
-// bumped.  No cache-wide write-back / invalidate is needed that way.
-__device__ __forceinline__ void store_agent(float* p, float v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
+// The partial sums of one output come from workgroups that may sit on different
+// XCDs, whose L2 slices are not coherent with each other.  Partials and counters
+// are therefore only touched with agent-coherent accesses (they go to the point
+// of coherence) and ordered by waiting for the stores to be acknowledged before
+// the counter is bumped.  No cache-wide write-back / invalidate is needed.
 __device__ __forceinline__ void wait_vmem()
 {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
-template <typename AT> __device__ __forceinline__ float as_stored(AT v);
-template <> __device__ __forceinline__ float as_stored<float>(float v) { return v; }
-template <> __device__ __forceinline__ float as_stored<int>(int v) { return __int_as_float(v); }
-template <typename AT> __device__ __forceinline__ AT from_stored(float v);
-template <> __device__ __forceinline__ float from_stored<float>(float v) { return v; }
-template <> __device__ __forceinline__ int from_stored<int>(float v) { return __float_as_int(v); }
+template <int N, int AUX>
+__device__ __forceinline__ void store_partials(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, const unsigned (&v)[N])
+{
+    if constexpr (N % 4 == 0) {
+#pragma unroll
+        for (int i = 0; i < N; i += 4) {
+            v4u q = {v[i], v[i + 1], v[i + 2], v[i + 3]};
+            __builtin_amdgcn_raw_buffer_store_b128(q, rsrc, (int)(off + 4 * i), 0, AUX);
+        }
+    } else if constexpr (N % 2 == 0) {
+#pragma unroll
+        for (int i = 0; i < N; i += 2) {
+            v2u q = {v[i], v[i + 1]};
+            __builtin_amdgcn_raw_buffer_store_b64(q, rsrc, (int)(off + 4 * i), 0, AUX);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) __builtin_amdgcn_raw_buffer_store_b32(v[i], rsrc, (int)(off + 4 * i), 0, AUX);
+    }
+}
+
+template <int N, int AUX>
+__device__ __forceinline__ void load_partials(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, unsigned (&v)[N])
+{
+    if constexpr (N % 4 == 0) {
+#pragma unroll
+        for (int i = 0; i < N; i += 4) {
+            v4u q = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(off + 4 * i), 0, AUX);
+            v[i] = q.x; v[i + 1] = q.y; v[i + 2] = q.z; v[i + 3] = q.w;
+        }
+    } else if constexpr (N % 2 == 0) {
+#pragma unroll
+        for (int i = 0; i < N; i += 2) {
+            v2u q = __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)(off + 4 * i), 0, AUX);
+            v[i] = q.x; v[i + 1] = q.y;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)(off + 4 * i), 0, AUX);
+    }
+}
 
 template <typename ET, int C> struct alignas(C * sizeof(ET) >= 16 ? 16 : C * sizeof(ET)) EntryVec { ET v[C]; };
 
 // Row of a panel that lane (q, j) keeps in accumulator slot s.  Chosen so that
-// after the cross-lane fold lane l holds the rows base + 64*i + l, i.e. the
-// epilogue's stores are contiguous across the wavefront.
+// after the cross-lane fold lane l holds the rows 64*i + l of the panel.
 template <int NQ, int LB>
 __host__ __device__ __forceinline__ int panel_row(int q, int j, int s)
 {
@@ -148,10 +235,12 @@ fused_kernel(FusedArgs a)
     constexpr int kCodeStride = G * kEntryBytes;  // bytes between consecutive codes
     constexpr int kFinal = LB / NQ;               // outputs per lane and column after the fold
     constexpr int kPanelRows = kFinal * 64;
-    constexpr int kThreads = kWaves * 64;
+    constexpr int kBuildParts = kBuilders * 64 / G;  // builder threads per group
+    static_assert(kBuildParts >= 1 && kBuilders * 64 % G == 0, "builders must cover whole groups");
+    constexpr int kPanelLoads = kLoadsPerPanel * 64;  // LoadT elements per panel
     static_assert(G == 16 || G == 32 || G == 64, "G");
-    static_assert(kThreads % G == 0, "threads per group");
     static_assert(LB % NQ == 0, "rows per lane must split over the lanes sharing them");
+    static_assert(kLoadsPerPanel % kRing == 0, "ring slots are reused with a period dividing the panel");
 
     __shared__ __align__(16) unsigned char lds[256 * kCodeStride];
 
@@ -161,81 +250,147 @@ fused_kernel(FusedArgs a)
     const int q = lane >> 4, j = lane & 15;
     const int qg = q % NQ;
 
-    int bid = blockIdx.x;
-    const int kt = bid % a.ktiles; bid /= a.ktiles;
-    const int rb = bid % a.row_blocks;
-    const int cp = bid / a.row_blocks;
+    // ---- which k-tile / row block / column pass
+    int kt, rg;
+    {
+        const int bid = blockIdx.x;
+        if (a.xcd_map) {
+            const int n = bid / kXcds;
+            rg = (bid % kXcds) + kXcds * (n / a.ktiles);
+            kt = n % a.ktiles;
+            if (rg >= a.row_groups) return;
+        } else {
+            kt = bid % a.ktiles;
+            rg = bid / a.ktiles;
+        }
+    }
+    const int rb = rg % a.row_blocks;
+    const int cp = rg / a.row_blocks;
     const int64_t col0 = (int64_t)cp * C;
 
     const XT* __restrict__ X = (const XT*)a.X;
     YT* __restrict__ Y = (YT*)a.Y;
+    MSGEMM_TRACE(0);
+#ifdef MSGEMM_PHASE_TRACE
+    if (g_msgemm_trace && lane == 0)  // hardware XCC_ID register, bits 3:0
+        g_msgemm_trace[((size_t)blockIdx.x * 8 + wave) * 16 + 9] = 1 + __builtin_amdgcn_s_getreg((3 << 11) | 20);
+#endif
 
-    // ---- activations of this k-tile (fetched first: the wait for them must not
-    // also wait for the code loads issued next)
-    const int g = tid % G;
-    AT x0[C], x1[C];
-    {
-        const int64_t kk = ((int64_t)kt * G + g) * 2;
-#pragma unroll
-        for (int c = 0; c < C; ++c) {
-            const bool live = (col0 + c < a.b) && (kk < a.k);
-            x0[c] = live ? (AT)XTraits<XT>::load(X + (col0 + c) * a.ldx + kk) : (AT)0;
-            x1[c] = live ? (AT)XTraits<XT>::load(X + (col0 + c) * a.ldx + kk + 1) : (AT)0;
-        }
-    }
-
-    // ---- first panel's codes: in flight while the tables are built
+    // ---- this wavefront's stream of panels: wave, wave + kWaves, ...
     const int panel_first = rb * a.panels_per_wg;
     int panels_here = a.panels_total - panel_first;
     if (panels_here > a.panels_per_wg) panels_here = a.panels_per_wg;
-    const LoadT* __restrict__ tiled =
-        (const LoadT*)a.tiled + ((int64_t)kt * a.panels_total + panel_first) * (kLoadsPerPanel * 64) + lane;
-    LoadT data[kLoadsPerPanel];
-    int p = wave;
-    if (p < panels_here) {
-        const LoadT* src = tiled + (int64_t)p * (kLoadsPerPanel * 64);
+    const int npan = wave < panels_here ? (panels_here - wave + kWaves - 1) / kWaves : 0;
+    const LoadT* __restrict__ stream =
+        (const LoadT*)a.tiled + ((int64_t)kt * a.panels_total + panel_first + wave) * kPanelLoads + lane;
+    // (idle wavefronts re-read the tile's first panel, which keeps the code below branch-free)
+    const LoadT* first = npan > 0 ? stream : (const LoadT*)a.tiled + lane;
+    LoadT ring[kRing];
+    auto fill_ring = [&](int from, int to) {
 #pragma unroll
-        for (int t = 0; t < kLoadsPerPanel; ++t) data[t] = src[t * 64];
-    }
+        for (int u = from; u < to; ++u) {
+            ring[u] = first[u * 64];
+            __builtin_amdgcn_sched_barrier(0);  // loads return in issue order: keep slot 0 first
+        }
+    };
 
     // ---- phase 1: L(code, g, c) = b(code & 15) X(2g', c) + b(code >> 4) X(2g'+1, c)
-    for (int code = tid / G; code < 256; code += kThreads / G) {
-        const AT w0 = (AT)decode4(code & 15), w1 = (AT)decode4(code >> 4);
-        Entry e;
+    // The first kBuilders wavefronts fetch the activations of the k-tile and
+    // build the tables before they touch the code stream; the others start the
+    // code stream at once.  Were every wavefront to queue its code loads first,
+    // the activation fetch would sit behind them in the memory pipeline and
+    // phase 1 -- and with it the start of the gather -- would come microseconds late.
+    // Only a few code loads go out before the barrier (a load instruction stalls
+    // its wavefront when the memory queue is full, and the barrier must not wait
+    // for that); all others follow right after it.
+    if (wave < kBuilders) {
+        const int g = tid % G;
+        const int64_t kk = ((int64_t)kt * G + g) * 2;
+        AT x0[C], x1[C];
 #pragma unroll
         for (int c = 0; c < C; ++c) {
-            if constexpr (__is_same(AT, float))
-                e.v[c] = make_entry<ET>(fmaf(w0, x0[c], w1 * x1[c]));
-            else
-                e.v[c] = make_entry_i<ET>(w0 * x0[c] + w1 * x1[c]);
+            const bool live = (col0 + c < a.b) && (kk < a.k);
+            const XT* px = X + (live ? (col0 + c) * a.ldx + kk : 0);
+            x0[c] = live ? (AT)XTraits<XT>::load(px) : (AT)0;
+            x1[c] = live ? (AT)XTraits<XT>::load(px + 1) : (AT)0;
         }
-        *(Entry*)(lds + (size_t)code * kCodeStride + g * kEntryBytes) = e;
+        MSGEMM_TRACE(1);
+        for (int c1 = tid / G; c1 < 16; c1 += kBuildParts) {
+            AT hi[C];
+            const AT w1 = (AT)decode4(c1);
+#pragma unroll
+            for (int c = 0; c < C; ++c) hi[c] = w1 * x1[c];
+            unsigned char* dst = lds + (size_t)(c1 * 16) * kCodeStride + g * kEntryBytes;
+#pragma unroll
+            for (int c0 = 0; c0 < 16; ++c0) {
+                Entry e;
+#pragma unroll
+                for (int c = 0; c < C; ++c) e.v[c] = EntryAcc<ET>::make(mul_add((AT)decode4(c0), x0[c], hi[c]));
+                *(Entry*)(dst + c0 * kCodeStride) = e;
+            }
+        }
+    } else {
+        fill_ring(0, kEarly);
+        MSGEMM_TRACE(1);
     }
+    MSGEMM_TRACE(2);
     __syncthreads();
+    MSGEMM_TRACE(3);
+    // the rest of the first panel: everything is requested before the gather starts
+    if (wave < kBuilders) fill_ring(0, kRing);
+    else fill_ring(kEarly, kRing);
 
     // ---- phase 2: stream panels, gather, accumulate
     const uint32_t class_base = (uint32_t)(16 * qg) * kEntryBytes;
-    for (; p < panels_here; p += kWaves) {
+    __amdgpu_buffer_rsrc_t part_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)a.partials, 0, (int)a.partial_span, 0x00020000);
+    const uint32_t col_stride = (uint32_t)(a.m_pad * 4);            // bytes between columns of the partials
+    const uint32_t tile_stride = (uint32_t)(a.b_pad * a.m_pad * 4); // bytes between k-tiles
+
+    for (int pi = 0; pi < npan; ++pi) {
+        const int panel_g = panel_first + wave + pi * kWaves;
+        const int64_t row0 = (int64_t)panel_g * kPanelRows + lane;
+
+        // scales of this k-tile's block for the rows this lane will own after the fold
+        float qv[kFinal];
+#pragma unroll
+        for (int i = 0; i < kFinal; ++i) {
+            qv[i] = 1.0f;
+            if constexpr (__is_same(AT, float)) {
+                const int64_t row = row0 + 64 * i;
+                if (a.scales && row < a.m) qv[i] = __half2float(a.scales[row * a.nblocks + kt / a.tiles_per_block]);
+            }
+        }
+
         AT acc[LB][C];
 #pragma unroll
         for (int s = 0; s < LB; ++s)
 #pragma unroll
             for (int c = 0; c < C; ++c) acc[s][c] = 0;
 
-        // One load's worth of look-ups is issued while the previous one's
-        // entries are being added: the LDS latency hides behind the adds
-        // without the scheduler hoisting all 16*LB reads at once.
+        // One load's worth of look-ups is issued while the previous one's entries
+        // are being added, so the LDS latency hides behind the adds without the
+        // scheduler hoisting all 16*LB reads at once.
+        const bool more = pi + 1 < npan;
+        const LoadT* cur = stream + (int64_t)pi * kWaves * kPanelLoads;
         auto issue = [&](int t, Entry (&dst)[LB]) {
             const uint32_t lane_off = class_base + (uint32_t)((j + t) & 15) * kEntryBytes;
+            const LoadT d = ring[t % kRing];
 #pragma unroll
             for (int s = 0; s < LB; ++s) {
-                const uint32_t w = load_word<LB>(data[t], s >> 2);
+                const uint32_t w = load_word<LB>(d, s >> 2);
                 uint32_t addr;
                 if constexpr (kCodeStride == 256)  // code byte drops straight into address bits 15:8
                     addr = __builtin_amdgcn_perm(w, lane_off, 0x0c0c0000u | ((4u + (s & 3)) << 8));
                 else
                     addr = ((w >> (8 * (s & 3))) & 0xffu) * kCodeStride + lane_off;
                 dst[s] = *(const Entry*)(lds + addr);
+            }
+            // the slot's bytes are now addresses: refill it with the load kRing ahead
+            if (t + kRing < kLoadsPerPanel) {
+                ring[t % kRing] = cur[(t + kRing) * 64];
+            } else if (more) {
+                ring[t % kRing] = cur[kWaves * kPanelLoads + (t + kRing - kLoadsPerPanel) * 64];
             }
         };
         auto consume = [&](const Entry (&src)[LB]) {
@@ -260,94 +415,148 @@ fused_kernel(FusedArgs a)
             consume(e1);
             __builtin_amdgcn_sched_barrier(0);
         }
-        // next panel's codes (if any) while this panel is being finished
-        const int pn = p + kWaves;
-        if (pn < panels_here) {
-            const LoadT* src = tiled + (int64_t)pn * (kLoadsPerPanel * 64);
-#pragma unroll
-            for (int t = 0; t < kLoadsPerPanel; ++t) data[t] = src[t * 64];
-        }
+        MSGEMM_TRACE(4);
 
-        // lanes that share rows: fold the NQ group classes; each lane ends up
-        // with kFinal distinct rows (base + 64*i + lane)
-        AT fin[kFinal][C];
+        // ---- lanes that share rows: fold the NQ group classes; each lane ends
+        // up with kFinal distinct rows (64*i + lane); then the block scale (Section 3.3)
+        const uint32_t part_off = (uint32_t)col0 * col_stride + (uint32_t)(panel_g * kPanelRows + lane * kFinal) * 4u;
 #pragma unroll
         for (int c = 0; c < C; ++c) {
+            AT fin[kFinal];
             if constexpr (NQ == 4) {
                 AT half[LB / 2];
 #pragma unroll
                 for (int s = 0; s < LB / 2; ++s) half[s] = fold32(acc[s][c], acc[s + LB / 2][c]);
 #pragma unroll
-                for (int s = 0; s < kFinal; ++s) fin[s][c] = fold16(half[s], half[s + kFinal]);
+                for (int s = 0; s < kFinal; ++s) fin[s] = fold16(half[s], half[s + kFinal]);
             } else if constexpr (NQ == 2) {
 #pragma unroll
-                for (int s = 0; s < kFinal; ++s) fin[s][c] = fold16(acc[s][c], acc[s + kFinal][c]);
+                for (int s = 0; s < kFinal; ++s) fin[s] = fold16(acc[s][c], acc[s + kFinal][c]);
             } else {
 #pragma unroll
-                for (int s = 0; s < kFinal; ++s) fin[s][c] = acc[s][c];
+                for (int s = 0; s < kFinal; ++s) fin[s] = acc[s][c];
+            }
+            unsigned out[kFinal];
+#pragma unroll
+            for (int i = 0; i < kFinal; ++i) {
+                if constexpr (__is_same(AT, float)) out[i] = bits_of(fin[i] * qv[i]);
+                else out[i] = bits_of(fin[i]);
+            }
+            if (a.reduce_mode == kReduceDirect) {
+#pragma unroll
+                for (int i = 0; i < kFinal; ++i) {
+                    const int64_t row = row0 + 64 * i;
+                    AT v;
+                    set_bits(v, out[i]);
+                    if (row < a.m && col0 + c < a.b) Y[(col0 + c) * a.ldy + row] = to_output<YT, AT>(v);
+                }
+            } else {
+                const uint32_t off = (uint32_t)kt * tile_stride + part_off + (uint32_t)c * col_stride;
+                if (a.reduce_mode == kReduceLastArriver) store_partials<kFinal, kAuxSc1>(part_rsrc, off, out);
+                else store_partials<kFinal, 0>(part_rsrc, off, out);
             }
         }
-
-        // scale of this k-tile's block (Section 3.3), then hand the partial over
-        const int panel_g = panel_first + p;
-        const int64_t row0 = (int64_t)panel_g * kPanelRows + lane;
-        float* part = a.partials + ((int64_t)kt * a.b_pad + col0) * a.m_pad + row0;
-#pragma unroll
-        for (int i = 0; i < kFinal; ++i) {
-            float qv = 1.0f;
-            if constexpr (__is_same(AT, float)) {
-                const int64_t row = row0 + 64 * i;
-                if (a.scales && row < a.m) qv = __half2float(a.scales[row * a.nblocks + kt / a.tiles_per_block]);
-            }
-#pragma unroll
-            for (int c = 0; c < C; ++c) {
-                AT v = fin[i][c];
-                if constexpr (__is_same(AT, float)) v = v * qv;
-                store_agent(part + (int64_t)c * a.m_pad + 64 * i, as_stored<AT>(v));
-            }
-        }
+        MSGEMM_TRACE(5);
+        if (a.reduce_mode != kReduceLastArriver) continue;
         wait_vmem();  // partials acknowledged before the counter moves
+        MSGEMM_TRACE(6);
         unsigned prev = 0;
         unsigned* counter = a.counters + (int64_t)panel_g * a.col_passes + cp;
         if (lane == 0)
             prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         prev = __builtin_amdgcn_readfirstlane(prev);
+        MSGEMM_TRACE(7);
         if (prev == (unsigned)a.ktiles - 1u) {
-            // every k-tile's partial for this panel has been published: add them
-            // in k-tile order.  Buffer loads with the agent-coherent policy bit:
-            // independent loads stay in flight together.
-            // (the descriptor is wave-uniform; the lane's rows go into the offset)
-            __amdgpu_buffer_rsrc_t rsrc =
-                __builtin_amdgcn_make_buffer_rsrc((void*)a.partials, 0, (int)a.partial_span, 0x00020000);
-            const uint32_t lane_base = (uint32_t)(col0 * a.m_pad + row0) * 4u;
-            const uint32_t tile_stride = (uint32_t)(a.b_pad * a.m_pad * 4);
-            AT sum[kFinal][C];
+            // Every k-tile's partial for this panel has been published: add them in
+            // k-tile order.  Independent agent-coherent loads stay in flight together.
 #pragma unroll
-            for (int i = 0; i < kFinal; ++i)
+            for (int c = 0; c < C; ++c) {
+                AT sum[kFinal];
 #pragma unroll
-                for (int c = 0; c < C; ++c) sum[i][c] = 0;
-#pragma unroll 4
-            for (int t = 0; t < a.ktiles; ++t) {
+                for (int i = 0; i < kFinal; ++i) sum[i] = 0;
+                const uint32_t off0 = part_off + (uint32_t)c * col_stride;
+                // kBatch k-tiles' partials are requested together, then added in order;
+                // k-tiles past the end get an out-of-range offset, which reads as zero
+                constexpr int kBatch = (kFinal * C <= 4) ? 16 : (kFinal * C <= 8 ? 8 : 4);
+                for (int t0 = 0; t0 < a.ktiles; t0 += kBatch) {
+                    unsigned v[kBatch][kFinal];
 #pragma unroll
-                for (int i = 0; i < kFinal; ++i)
-#pragma unroll
-                    for (int c = 0; c < C; ++c) {
-                        const uint32_t off = lane_base + (uint32_t)t * tile_stride + (uint32_t)(c * (uint32_t)a.m_pad + 64 * i) * 4u;
-                        const unsigned u = __builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)off, 0, kAuxSc1);
-                        AT v;
-                        set_bits(v, u);
-                        sum[i][c] += v;
+                    for (int u = 0; u < kBatch; ++u) {
+                        const uint32_t off = (t0 + u < a.ktiles) ? off0 + (uint32_t)(t0 + u) * tile_stride : 0x7ffffff0u;
+                        load_partials<kFinal, kAuxSc1>(part_rsrc, off, v[u]);
                     }
-            }
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < kFinal; ++i) {
-                const int64_t row = row0 + 64 * i;
+                    for (int u = 0; u < kBatch; ++u)
 #pragma unroll
-                for (int c = 0; c < C; ++c)
-                    if (row < a.m && col0 + c < a.b) Y[(col0 + c) * a.ldy + row] = to_output<YT, AT>(sum[i][c]);
+                        for (int i = 0; i < kFinal; ++i) {
+                            AT x;
+                            set_bits(x, v[u][i]);
+                            sum[i] += x;
+                        }
+                }
+#pragma unroll
+                for (int i = 0; i < kFinal; ++i) {
+                    const int64_t row = row0 + 64 * i;
+                    if (row < a.m && col0 + c < a.b) Y[(col0 + c) * a.ldy + row] = to_output<YT, AT>(sum[i]);
+                }
             }
             if (lane == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            MSGEMM_TRACE(8);
         }
+    }
+}
+
+// Second pass of the k-tile reduction.  A workgroup of kReduceWaves wavefronts
+// owns 64 consecutive partial sums of one column; wavefront w adds the k-tiles
+// t = w, w + kReduceWaves, ... in increasing order, the wavefront sums are then
+// added in wavefront order: a fixed order, so the result is reproducible.
+// Many small workgroups keep the loads of the whole pass in flight at once.
+constexpr int kReduceWaves = 4;
+
+template <typename YT, typename AT, int F>
+__global__ void __launch_bounds__(kReduceWaves * 64)
+reduce_kernel(const float* __restrict__ partials, YT* __restrict__ Y, int64_t ldy, int64_t m, int64_t b,
+              int64_t m_pad, int64_t b_pad, int ktiles, int64_t span)
+{
+    __shared__ AT wave_sum[kReduceWaves][64];
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    const int64_t chunks_per_col = m_pad / 64;
+    const int64_t chunk = blockIdx.x % chunks_per_col;  // 64 consecutive floats of the column
+    const int64_t col = blockIdx.x / chunks_per_col;
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)partials, 0, (int)span, 0x00020000);
+    const uint32_t tile_stride = (uint32_t)(b_pad * m_pad * 4);
+    const uint32_t off0 = (uint32_t)(col * m_pad + chunk * 64 + lane) * 4u;
+    AT sum = 0;
+    constexpr int kBatch = 8;
+    for (int t0 = w; t0 < ktiles; t0 += kBatch * kReduceWaves) {
+        unsigned v[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int t = t0 + u * kReduceWaves;
+            v[u] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, t < ktiles ? (int)(off0 + (uint32_t)t * tile_stride) : 0x7ffffff0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            AT x;
+            set_bits(x, v[u]);
+            sum += x;
+        }
+    }
+    wave_sum[w][lane] = sum;
+    __syncthreads();
+    if (w == 0) {
+        AT total = wave_sum[0][lane];
+#pragma unroll
+        for (int i = 1; i < kReduceWaves; ++i) total += wave_sum[i][lane];
+        // float f of a panel belongs to lane f / F, output i = f % F, i.e. row 64*i + lane
+        const int64_t f = chunk * 64 + lane;
+        const int64_t panel = f / (64 * F);
+        const int in_panel = (int)(f % (64 * F));
+        const int64_t row = panel * (64 * F) + 64 * (in_panel % F) + in_panel / F;
+        if (row < m) Y[col * ldy + row] = to_output<YT, AT>(total);
     }
 }
 
@@ -358,7 +567,7 @@ repack_kernel(const uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled, in
               int ktiles, int panels_total)
 {
     constexpr int NQ = G / 16;
-    constexpr int kPanelRows = (4 / NQ) * LB * 16;
+    constexpr int kPanelRows = (LB / NQ) * 64;
     const int64_t total = (int64_t)ktiles * panels_total * kLoadsPerPanel * 64 * LB;
     for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < total;
          o += (int64_t)gridDim.x * blockDim.x) {
@@ -378,19 +587,36 @@ repack_kernel(const uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled, in
 
 struct ShapeChoice { int C, G, LB, entry_bytes; };
 
+int env_int(const char* name, int fallback)
+{
+    const char* v = getenv(name);
+    return (v && *v) ? atoi(v) : fallback;
+}
+
 ShapeChoice pick_shape(const Plan& p)
 {
     (void)p;
-    return ShapeChoice{1, 64, 16, 4};
+    // MSGEMM_TUNE_LB = 8 halves the rows per panel (tuning aid)
+    const int lb = env_int("MSGEMM_TUNE_LB", 16) == 8 ? 8 : 16;
+    return ShapeChoice{1, 64, lb, 4};
 }
 
 template <typename XT, typename YT, typename ET, int C, int G, int LB>
 int launch_one(const Plan& p, const FusedArgs& a, hipStream_t s)
 {
+    using AT = typename EntryAcc<ET>::type;
+    constexpr int kFinal = LB / (G / 16);
     auto kern = fused_kernel<XT, YT, ET, C, G, LB>;
-    const unsigned grid = (unsigned)((int64_t)p.ktiles * p.row_blocks * p.col_passes);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kWaves * 64), 0, s, a);
+    int64_t grid = (int64_t)p.ktiles * a.row_groups;
+    if (a.xcd_map) grid = (int64_t)p.ktiles * kXcds * ((a.row_groups + kXcds - 1) / kXcds);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kWaves * 64), 0, s, a);
     MSGEMM_HIP_TRY(hipGetLastError());
+    if (a.reduce_mode == kReduceSecondPass) {
+        const int64_t blocks = (a.m_pad / 64) * a.b;
+        hipLaunchKernelGGL((reduce_kernel<YT, AT, kFinal>), dim3((unsigned)blocks), dim3(kReduceWaves * 64), 0, s,
+                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.ktiles, a.partial_span);
+        MSGEMM_HIP_TRY(hipGetLastError());
+    }
     return MSGEMM_OK;
 }
 
@@ -408,7 +634,7 @@ int fused_choose_shape(Plan& p)
     fs.cols = sc.C;
     fs.entry_bytes = sc.entry_bytes;
     fs.waves = kWaves;
-    fs.panel_rows = (4 / (sc.G / 16)) * sc.LB * 16;
+    fs.panel_rows = (sc.LB / (sc.G / 16)) * 64;
     fs.lds_bytes = (size_t)256 * sc.G * sc.C * sc.entry_bytes;
     p.ktiles = (p.k / 2 + sc.G - 1) / sc.G;
     p.col_passes = (int)((p.b + sc.C - 1) / sc.C);
@@ -421,13 +647,17 @@ int fused_choose_shape(Plan& p)
         cus = prop.multiProcessorCount;
     // Rows per table build: as many panels per workgroup as still leave one
     // workgroup per compute unit (each build costs 256 entries per group).
+    // MSGEMM_TUNE_PPW overrides the choice (tuning aid).
     int ppw = 16;
     while (ppw > 1 && (int64_t)p.ktiles * p.col_passes * ((panels + ppw - 1) / ppw) < cus) ppw >>= 1;
+    const int forced = env_int("MSGEMM_TUNE_PPW", 0);
+    if (forced >= 1 && forced <= 64) ppw = forced;
     fs.panels = ppw;
     fs.tile_rows = ppw * fs.panel_rows;
     p.row_blocks = (panels + ppw - 1) / ppw;
     p.m_pad = panels * fs.panel_rows;
-    if ((int64_t)p.ktiles * p.row_blocks * p.col_passes > 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
+    const int64_t row_groups = p.row_blocks * p.col_passes;
+    if ((int64_t)p.ktiles * (row_groups + kXcds) > 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
     // the k-tile reduction addresses the partial buffer with 32-bit byte offsets
     if ((int64_t)p.ktiles * p.col_passes * sc.C * p.m_pad * 4 >= 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
     return MSGEMM_OK;
@@ -441,6 +671,9 @@ int launch_repack(const Plan& p, hipStream_t s)
     if (blocks > 65536) blocks = 65536;
     if (p.fs.groups == 64 && p.fs.lane_bytes == 16) {
         hipLaunchKernelGGL((repack_kernel<64, 16>), dim3((unsigned)blocks), dim3(256), 0, s, p.codes,
+                           p.codes_tiled, p.m, p.k / 2, (int)p.ktiles, (int)panels);
+    } else if (p.fs.groups == 64 && p.fs.lane_bytes == 8) {
+        hipLaunchKernelGGL((repack_kernel<64, 8>), dim3((unsigned)blocks), dim3(256), 0, s, p.codes,
                            p.codes_tiled, p.m, p.k / 2, (int)p.ktiles, (int)panels);
     } else {
         return MSGEMM_ERR_UNSUPPORTED;
@@ -464,9 +697,21 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     a.panels_per_wg = p.fs.panels;
     a.row_blocks = (int)p.row_blocks;
     a.col_passes = p.col_passes;
+    a.row_groups = (int)(p.row_blocks * p.col_passes);
+    // Workgroups are dealt to the XCDs round-robin by id.  Giving the k-tiles of
+    // one row block ids that are congruent modulo the XCD count keeps the traffic
+    // on their shared counter and partials on one L2 slice.  Purely a locality
+    // choice: the accesses are agent-coherent wherever the workgroups land.
+    a.xcd_map = (a.row_groups >= kXcds && env_int("MSGEMM_TUNE_XCD_MAP", 1)) ? 1 : 0;
     a.nblocks = p.nblocks;
     a.partial_span = (int64_t)p.ktiles * a.b_pad * p.m_pad * 4;
     a.tiles_per_block = p.scale_group > 0 ? (int)(p.scale_group / (2 * p.fs.groups)) : 1;
+    // MSGEMM_TUNE_REDUCE = 1 (second pass) or 2 (last arriver) overrides the default (tuning aid)
+    a.reduce_mode = p.ktiles == 1 ? kReduceDirect : kReduceSecondPass;
+    if (p.ktiles > 1) {
+        const int forced = env_int("MSGEMM_TUNE_REDUCE", 0);
+        if (forced == kReduceSecondPass || forced == kReduceLastArriver) a.reduce_mode = forced;
+    }
 
     if (p.fs.cols == 1 && p.fs.groups == 64 && p.fs.lane_bytes == 16) {
         switch (p.x_dtype) {
@@ -474,6 +719,15 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
         case MSGEMM_F16: return launch_one<__half, __half, float, 1, 64, 16>(p, a, s);
         case MSGEMM_BF16: return launch_one<bf16_t, bf16_t, float, 1, 64, 16>(p, a, s);
         case MSGEMM_I8: return launch_one<int8_t, int, int, 1, 64, 16>(p, a, s);
+        default: break;
+        }
+    }
+    if (p.fs.cols == 1 && p.fs.groups == 64 && p.fs.lane_bytes == 8) {
+        switch (p.x_dtype) {
+        case MSGEMM_F32: return launch_one<float, float, float, 1, 64, 8>(p, a, s);
+        case MSGEMM_F16: return launch_one<__half, __half, float, 1, 64, 8>(p, a, s);
+        case MSGEMM_BF16: return launch_one<bf16_t, bf16_t, float, 1, 64, 8>(p, a, s);
+        case MSGEMM_I8: return launch_one<int8_t, int, int, 1, 64, 8>(p, a, s);
         default: break;
         }
     }
