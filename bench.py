@@ -195,7 +195,7 @@ def main() -> int:
         "config": {
             "workload": f"{args.config}: m={m} k={k} b={b} int4 W, {cfg['x']} X, {cfg['y']} Y, "
                         f"scale_group={cfg['scale_group']}, d={info['d']}",
-            "variant": {1: "global_lut", 2: "fused_lds"}[info["variant"]],
+            "variant": {1: "global_lut", 2: "fused_lds", 3: "fused_lds16"}[info["variant"]],
             "tile_rows": info["tile_rows"], "tile_groups": info["tile_groups"],
             "split_k": info["split_k"], "col_chunk": info["col_chunk"],
             "weight_copies_rotated": n_copies,

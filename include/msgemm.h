@@ -72,8 +72,14 @@ typedef enum {
     MSGEMM_VARIANT_GLOBAL_LUT = 1,
     /* One launch, d = 2: each workgroup builds the tables of its k-tile in LDS
      * (phase 1 and 2 pipelined over the last dimension of L, Section 4), streams
-     * its repacked code tile and reduces over k-tiles inside the same launch. */
-    MSGEMM_VARIANT_FUSED_LDS = 2
+     * its repacked code tile; partial sums over k-tiles are added by a small
+     * second kernel.  Table entries are fp32 (int32 for int8 X). */
+    MSGEMM_VARIANT_FUSED_LDS = 2,
+    /* Same schedule with 16-bit table entries, 8 batch columns per entry: int16
+     * for int8 X (exact), fp16 for fp16 / bf16 X (each entry rounded to fp16,
+     * which needs |16 x| inside the fp16 range; accumulation stays fp32).
+     * Not available for fp32 X.  AUTO picks it for b > 2. */
+    MSGEMM_VARIANT_FUSED_LDS16 = 3
 } msgemm_variant_t;
 
 typedef struct {

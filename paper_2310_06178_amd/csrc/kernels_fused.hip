@@ -42,7 +42,7 @@ extern "C" int msgemm_debug_set_trace(unsigned long long* buf)
 #define MSGEMM_TRACE(id)                                                                         \
     do {                                                                                         \
         if (g_msgemm_trace && (threadIdx.x & 63) == 0)                                           \
-            g_msgemm_trace[((size_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + (id)] = wall_clock64(); \
+            g_msgemm_trace[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 16 + (id)] = wall_clock64(); \
     } while (0)
 #else
 #define MSGEMM_TRACE(id) do { } while (0)
@@ -51,20 +51,17 @@ extern "C" int msgemm_debug_set_trace(unsigned long long* buf)
 namespace msgemm {
 namespace {
 
-constexpr int kWaves = 8;           // wavefronts per workgroup
 constexpr int kLoadsPerPanel = 16;  // one load per group of a 16-group class
-#ifndef MSGEMM_RING
-#define MSGEMM_RING 8
+#ifndef MSGEMM_BUILDERS_1COL
+#define MSGEMM_BUILDERS_1COL(waves) ((waves) / 2)
 #endif
-#ifndef MSGEMM_EARLY
-#define MSGEMM_EARLY 8
+#ifndef MSGEMM_EARLY_BUILDER
+#define MSGEMM_EARLY_BUILDER 0
 #endif
-constexpr int kRing = MSGEMM_RING;    // code loads a wavefront keeps in flight (a whole panel)
-constexpr int kEarly = MSGEMM_EARLY;  // of which requested before the tables are ready
-#ifndef MSGEMM_BUILDERS
-#define MSGEMM_BUILDERS 4
+#ifndef MSGEMM_RING_BYTES
+#define MSGEMM_RING_BYTES 128
 #endif
-constexpr int kBuilders = MSGEMM_BUILDERS;  // wavefronts that build the tables (phase 1)
+constexpr int kRingBytes = MSGEMM_RING_BYTES;  // code bytes per lane a wavefront keeps in flight (x64 lanes)
 constexpr int kAuxSc1 = 16;         // buffer cache policy bit: coherent at agent scope
 constexpr int kXcds = 8;            // L2 slices (XCDs); workgroups are dealt to them round-robin
 
@@ -223,7 +220,7 @@ __host__ __device__ __forceinline__ int panel_row(int q, int j, int s)
     return (s % nfinal) * 64 + (qr * NQ + s / nfinal) * 16 + j;
 }
 
-template <typename XT, typename YT, typename ET, int C, int G, int LB>
+template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves>
 __global__ void __launch_bounds__(kWaves * 64)
 fused_kernel(FusedArgs a)
 {
@@ -235,6 +232,12 @@ fused_kernel(FusedArgs a)
     constexpr int kCodeStride = G * kEntryBytes;  // bytes between consecutive codes
     constexpr int kFinal = LB / NQ;               // outputs per lane and column after the fold
     constexpr int kPanelRows = kFinal * 64;
+    // wavefronts that build the tables (phase 1): half of them when one column
+    // is built (the others start the code stream at once), all of them for the
+    // wide tables of a batch
+    constexpr int kBuilders = C == 1 ? MSGEMM_BUILDERS_1COL(kWaves) : kWaves;
+    constexpr int kRing = kRingBytes / LB < kLoadsPerPanel ? kRingBytes / LB : kLoadsPerPanel;  // loads in flight
+    constexpr int kEarlyBuilder = C == 1 ? MSGEMM_EARLY_BUILDER : 2;  // code loads a builder requests before it waits for the activations
     constexpr int kBuildParts = kBuilders * 64 / G;  // builder threads per group
     static_assert(kBuildParts >= 1 && kBuilders * 64 % G == 0, "builders must cover whole groups");
     constexpr int kPanelLoads = kLoadsPerPanel * 64;  // LoadT elements per panel
@@ -243,6 +246,7 @@ fused_kernel(FusedArgs a)
     static_assert(kLoadsPerPanel % kRing == 0, "ring slots are reused with a period dividing the panel");
 
     __shared__ __align__(16) unsigned char lds[256 * kCodeStride];
+    __shared__ unsigned tables_built;  // builder wavefronts that have finished phase 1
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -264,16 +268,18 @@ fused_kernel(FusedArgs a)
             rg = bid / a.ktiles;
         }
     }
-    const int rb = rg % a.row_blocks;
-    const int cp = rg / a.row_blocks;
+    const int cp = rg % a.col_passes;  // column passes of one row block are neighbours: the codes stay cached
+    const int rb = rg / a.col_passes;
     const int64_t col0 = (int64_t)cp * C;
 
     const XT* __restrict__ X = (const XT*)a.X;
     YT* __restrict__ Y = (YT*)a.Y;
+    if (tid == 0) tables_built = 0;
+    __syncthreads();  // nothing is in flight yet: this costs a few cycles
     MSGEMM_TRACE(0);
 #ifdef MSGEMM_PHASE_TRACE
     if (g_msgemm_trace && lane == 0)  // hardware XCC_ID register, bits 3:0
-        g_msgemm_trace[((size_t)blockIdx.x * 8 + wave) * 16 + 9] = 1 + __builtin_amdgcn_s_getreg((3 << 11) | 20);
+        g_msgemm_trace[((size_t)blockIdx.x * 16 + wave) * 16 + 9] = 1 + __builtin_amdgcn_s_getreg((3 << 11) | 20);
 #endif
 
     // ---- this wavefront's stream of panels: wave, wave + kWaves, ...
@@ -296,25 +302,34 @@ fused_kernel(FusedArgs a)
 
     // ---- phase 1: L(code, g, c) = b(code & 15) X(2g', c) + b(code >> 4) X(2g'+1, c)
     // The first kBuilders wavefronts fetch the activations of the k-tile and
-    // build the tables before they touch the code stream; the others start the
-    // code stream at once.  Were every wavefront to queue its code loads first,
-    // the activation fetch would sit behind them in the memory pipeline and
-    // phase 1 -- and with it the start of the gather -- would come microseconds late.
-    // Only a few code loads go out before the barrier (a load instruction stalls
-    // its wavefront when the memory queue is full, and the barrier must not wait
-    // for that); all others follow right after it.
+    // build the tables before they join the code stream; the others request
+    // their codes at once.  (Were every wavefront to queue its code loads first,
+    // the activation fetch would sit behind them in the memory pipeline.)
+    // Readiness of the tables is a counter in LDS rather than a barrier: a load
+    // instruction stalls its wavefront while the memory queue is full, and a
+    // barrier would make the builders -- and so the tables -- wait for that.
     if (wave < kBuilders) {
         const int g = tid % G;
         const int64_t kk = ((int64_t)kt * G + g) * 2;
+        // raw values from clamped (always valid) addresses first, conversion after
+        // the early code loads: nothing waits for the activations before those are out
+        XT xr0[C], xr1[C];
+        bool live[C];
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            live[c] = (col0 + c < a.b) && (kk < a.k);
+            const XT* px = X + (live[c] ? (col0 + c) * a.ldx + kk : 0);
+            xr0[c] = px[0];
+            xr1[c] = px[1];
+        }
+        fill_ring(0, kEarlyBuilder);
+        MSGEMM_TRACE(1);
         AT x0[C], x1[C];
 #pragma unroll
         for (int c = 0; c < C; ++c) {
-            const bool live = (col0 + c < a.b) && (kk < a.k);
-            const XT* px = X + (live ? (col0 + c) * a.ldx + kk : 0);
-            x0[c] = live ? (AT)XTraits<XT>::load(px) : (AT)0;
-            x1[c] = live ? (AT)XTraits<XT>::load(px + 1) : (AT)0;
+            x0[c] = live[c] ? (AT)XTraits<XT>::load(&xr0[c]) : (AT)0;
+            x1[c] = live[c] ? (AT)XTraits<XT>::load(&xr1[c]) : (AT)0;
         }
-        MSGEMM_TRACE(1);
         for (int c1 = tid / G; c1 < 16; c1 += kBuildParts) {
             AT hi[C];
             const AT w1 = (AT)decode4(c1);
@@ -329,16 +344,21 @@ fused_kernel(FusedArgs a)
                 *(Entry*)(dst + c0 * kCodeStride) = e;
             }
         }
+        // this wavefront's LDS writes have landed; then count it
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        if (lane == 0) __hip_atomic_fetch_add(&tables_built, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        MSGEMM_TRACE(2);
+        fill_ring(kEarlyBuilder, kRing);
     } else {
-        fill_ring(0, kEarly);
+        fill_ring(0, kRing);
         MSGEMM_TRACE(1);
+        MSGEMM_TRACE(2);
     }
-    MSGEMM_TRACE(2);
-    __syncthreads();
+    // every builder runs to its increment without waiting on anyone, so this ends
+    while (__hip_atomic_load(&tables_built, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) != (unsigned)kBuilders)
+        __builtin_amdgcn_s_sleep(1);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     MSGEMM_TRACE(3);
-    // the rest of the first panel: everything is requested before the gather starts
-    if (wave < kBuilders) fill_ring(0, kRing);
-    else fill_ring(kEarly, kRing);
 
     // ---- phase 2: stream panels, gather, accumulate
     const uint32_t class_base = (uint32_t)(16 * qg) * kEntryBytes;
@@ -395,14 +415,28 @@ fused_kernel(FusedArgs a)
         };
         auto consume = [&](const Entry (&src)[LB]) {
 #pragma unroll
-            for (int s = 0; s < LB; ++s)
+            for (int s = 0; s < LB; ++s) {
+                if constexpr (__is_same(ET, __half) && C % 2 == 0) {
+                    // fp16 entries, fp32 accumulators: one mixed-precision FMA per
+                    // column (acc = half * 1.0 + acc) instead of a convert and an add
+                    const uint32_t* w = (const uint32_t*)&src[s];
 #pragma unroll
-                for (int c = 0; c < C; ++c) {
-                    acc[s][c] += EntryAcc<ET>::widen(src[s].v[c]);
-                    // pin the add to this stage: otherwise the compiler sinks all
-                    // adds below the gather and keeps every table entry live
-                    asm volatile("" : "+v"(acc[s][c]));
+                    for (int c = 0; c < C; c += 2) {
+                        asm volatile("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel_hi:[1,0,0]"
+                                     : "+v"(acc[s][c]) : "v"(w[c / 2]));
+                        asm volatile("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel:[1,0,0] op_sel_hi:[1,0,0]"
+                                     : "+v"(acc[s][c + 1]) : "v"(w[c / 2]));
+                    }
+                } else {
+#pragma unroll
+                    for (int c = 0; c < C; ++c) {
+                        acc[s][c] += EntryAcc<ET>::widen(src[s].v[c]);
+                        // pin the add to this stage: otherwise the compiler sinks all
+                        // adds below the gather and keeps every table entry live
+                        asm volatile("" : "+v"(acc[s][c]));
+                    }
                 }
+            }
         };
         Entry e0[LB], e1[LB];
         issue(0, e0);
@@ -585,7 +619,7 @@ repack_kernel(const uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled, in
     }
 }
 
-struct ShapeChoice { int C, G, LB, entry_bytes; };
+struct ShapeChoice { int C, G, LB, entry_bytes, waves; };
 
 int env_int(const char* name, int fallback)
 {
@@ -593,20 +627,30 @@ int env_int(const char* name, int fallback)
     return (v && *v) ? atoi(v) : fallback;
 }
 
-ShapeChoice pick_shape(const Plan& p)
+// Which instantiation serves a problem.  Entries are full width (fp32 / int32)
+// for one or two columns (the b = 1 GEMV streams from HBM and the table traffic
+// is small) and 16 bits wide (fp16 / int16) with 8 columns per entry for wider
+// batches, where the gather is bound by LDS bytes and VALU adds.  int16 holds
+// the int8 table values exactly (|entry| <= 2048); fp16 entries round.
+ShapeChoice pick_shape(const Plan& p, int requested_variant)
 {
-    (void)p;
-    // MSGEMM_TUNE_LB = 8 halves the rows per panel (tuning aid)
-    const int lb = env_int("MSGEMM_TUNE_LB", 16) == 8 ? 8 : 16;
-    return ShapeChoice{1, 64, lb, 4};
+    // MSGEMM_TUNE_LB = 16 selects the 8-wavefront, 256-row-panel form of the single-column kernel (tuning aid)
+    const int lb1 = env_int("MSGEMM_TUNE_LB", 8) == 16 ? 16 : 8;
+    const bool narrow_ok = p.x_dtype != MSGEMM_F32;
+    const bool narrow = requested_variant == MSGEMM_VARIANT_FUSED_LDS16 ||
+                        (requested_variant == MSGEMM_VARIANT_AUTO && p.b > 2);
+    if (narrow && narrow_ok) return ShapeChoice{8, 32, 8, 2, 8};
+    if (p.b > 2 && p.x_dtype == MSGEMM_F32) return ShapeChoice{4, 32, 8, 4, 8};
+    // one column: 16 wavefronts of 128-row panels keep the LDS and VALU pipes busier than 8 of 256 rows
+    return lb1 == 8 ? ShapeChoice{1, 64, 8, 4, 16} : ShapeChoice{1, 64, 16, 4, 8};
 }
 
-template <typename XT, typename YT, typename ET, int C, int G, int LB>
+template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves>
 int launch_one(const Plan& p, const FusedArgs& a, hipStream_t s)
 {
     using AT = typename EntryAcc<ET>::type;
     constexpr int kFinal = LB / (G / 16);
-    auto kern = fused_kernel<XT, YT, ET, C, G, LB>;
+    auto kern = fused_kernel<XT, YT, ET, C, G, LB, kWaves>;
     int64_t grid = (int64_t)p.ktiles * a.row_groups;
     if (a.xcd_map) grid = (int64_t)p.ktiles * kXcds * ((a.row_groups + kXcds - 1) / kXcds);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kWaves * 64), 0, s, a);
@@ -622,10 +666,11 @@ int launch_one(const Plan& p, const FusedArgs& a, hipStream_t s)
 
 }  // namespace
 
-int fused_choose_shape(Plan& p)
+int fused_choose_shape(Plan& p, int requested_variant)
 {
     if (p.d != 2) return MSGEMM_ERR_UNSUPPORTED;
-    const ShapeChoice sc = pick_shape(p);
+    if (requested_variant == MSGEMM_VARIANT_FUSED_LDS16 && p.x_dtype == MSGEMM_F32) return MSGEMM_ERR_UNSUPPORTED;
+    const ShapeChoice sc = pick_shape(p, requested_variant);
     const int cols_per_tile = 2 * sc.G;
     if (p.scale_group > 0 && (p.scale_group % cols_per_tile) != 0) return MSGEMM_ERR_UNSUPPORTED;
     FusedShape& fs = p.fs;
@@ -633,7 +678,7 @@ int fused_choose_shape(Plan& p)
     fs.lane_bytes = sc.LB;
     fs.cols = sc.C;
     fs.entry_bytes = sc.entry_bytes;
-    fs.waves = kWaves;
+    fs.waves = sc.waves;
     fs.panel_rows = (sc.LB / (sc.G / 16)) * 64;
     fs.lds_bytes = (size_t)256 * sc.G * sc.C * sc.entry_bytes;
     p.ktiles = (p.k / 2 + sc.G - 1) / sc.G;
@@ -648,7 +693,7 @@ int fused_choose_shape(Plan& p)
     // Rows per table build: as many panels per workgroup as still leave one
     // workgroup per compute unit (each build costs 256 entries per group).
     // MSGEMM_TUNE_PPW overrides the choice (tuning aid).
-    int ppw = 16;
+    int ppw = 2 * sc.waves;
     while (ppw > 1 && (int64_t)p.ktiles * p.col_passes * ((panels + ppw - 1) / ppw) < cus) ppw >>= 1;
     const int forced = env_int("MSGEMM_TUNE_PPW", 0);
     if (forced >= 1 && forced <= 64) ppw = forced;
@@ -669,17 +714,18 @@ int launch_repack(const Plan& p, hipStream_t s)
     const int64_t total = (int64_t)p.ktiles * p.m_pad * p.fs.groups;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
-    if (p.fs.groups == 64 && p.fs.lane_bytes == 16) {
-        hipLaunchKernelGGL((repack_kernel<64, 16>), dim3((unsigned)blocks), dim3(256), 0, s, p.codes,
-                           p.codes_tiled, p.m, p.k / 2, (int)p.ktiles, (int)panels);
-    } else if (p.fs.groups == 64 && p.fs.lane_bytes == 8) {
-        hipLaunchKernelGGL((repack_kernel<64, 8>), dim3((unsigned)blocks), dim3(256), 0, s, p.codes,
-                           p.codes_tiled, p.m, p.k / 2, (int)p.ktiles, (int)panels);
-    } else {
-        return MSGEMM_ERR_UNSUPPORTED;
+#define MSGEMM_REPACK(GG, LL)                                                                          \
+    if (p.fs.groups == GG && p.fs.lane_bytes == LL) {                                                  \
+        hipLaunchKernelGGL((repack_kernel<GG, LL>), dim3((unsigned)blocks), dim3(256), 0, s, p.codes, \
+                           p.codes_tiled, p.m, p.k / 2, (int)p.ktiles, (int)panels);                   \
+        MSGEMM_HIP_TRY(hipGetLastError());                                                             \
+        return MSGEMM_OK;                                                                              \
     }
-    MSGEMM_HIP_TRY(hipGetLastError());
-    return MSGEMM_OK;
+    MSGEMM_REPACK(64, 16)
+    MSGEMM_REPACK(64, 8)
+    MSGEMM_REPACK(32, 8)
+#undef MSGEMM_REPACK
+    return MSGEMM_ERR_UNSUPPORTED;
 }
 
 int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s)
@@ -713,24 +759,25 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
         if (forced == kReduceSecondPass || forced == kReduceLastArriver) a.reduce_mode = forced;
     }
 
-    if (p.fs.cols == 1 && p.fs.groups == 64 && p.fs.lane_bytes == 16) {
-        switch (p.x_dtype) {
-        case MSGEMM_F32: return launch_one<float, float, float, 1, 64, 16>(p, a, s);
-        case MSGEMM_F16: return launch_one<__half, __half, float, 1, 64, 16>(p, a, s);
-        case MSGEMM_BF16: return launch_one<bf16_t, bf16_t, float, 1, 64, 16>(p, a, s);
-        case MSGEMM_I8: return launch_one<int8_t, int, int, 1, 64, 16>(p, a, s);
-        default: break;
-        }
-    }
-    if (p.fs.cols == 1 && p.fs.groups == 64 && p.fs.lane_bytes == 8) {
-        switch (p.x_dtype) {
-        case MSGEMM_F32: return launch_one<float, float, float, 1, 64, 8>(p, a, s);
-        case MSGEMM_F16: return launch_one<__half, __half, float, 1, 64, 8>(p, a, s);
-        case MSGEMM_BF16: return launch_one<bf16_t, bf16_t, float, 1, 64, 8>(p, a, s);
-        case MSGEMM_I8: return launch_one<int8_t, int, int, 1, 64, 8>(p, a, s);
-        default: break;
-        }
-    }
+    const int C = p.fs.cols, G = p.fs.groups, LB = p.fs.lane_bytes, EB = p.fs.entry_bytes;
+#define MSGEMM_CASE(CC, GG, LL, EE, XD, XT, YT, ET)                                   \
+    if (C == CC && G == GG && LB == LL && EB == EE && p.x_dtype == XD)               \
+        return launch_one<XT, YT, ET, CC, GG, LL, (CC == 1 && LL == 8) ? 16 : 8>(p, a, s);
+    // single column, full-width entries
+    MSGEMM_CASE(1, 64, 16, 4, MSGEMM_F32, float, float, float)
+    MSGEMM_CASE(1, 64, 16, 4, MSGEMM_F16, __half, __half, float)
+    MSGEMM_CASE(1, 64, 16, 4, MSGEMM_BF16, bf16_t, bf16_t, float)
+    MSGEMM_CASE(1, 64, 16, 4, MSGEMM_I8, int8_t, int, int)
+    MSGEMM_CASE(1, 64, 8, 4, MSGEMM_F32, float, float, float)
+    MSGEMM_CASE(1, 64, 8, 4, MSGEMM_F16, __half, __half, float)
+    MSGEMM_CASE(1, 64, 8, 4, MSGEMM_BF16, bf16_t, bf16_t, float)
+    MSGEMM_CASE(1, 64, 8, 4, MSGEMM_I8, int8_t, int, int)
+    // batched: 4 columns of fp32 entries, or 8 columns of 16-bit entries
+    MSGEMM_CASE(4, 32, 8, 4, MSGEMM_F32, float, float, float)
+    MSGEMM_CASE(8, 32, 8, 2, MSGEMM_F16, __half, __half, __half)
+    MSGEMM_CASE(8, 32, 8, 2, MSGEMM_BF16, bf16_t, bf16_t, __half)
+    MSGEMM_CASE(8, 32, 8, 2, MSGEMM_I8, int8_t, int, short)
+#undef MSGEMM_CASE
     return MSGEMM_ERR_UNSUPPORTED;
 }
 

@@ -50,7 +50,7 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtyp
     if (m > ((int64_t)1 << 31) || k > ((int64_t)1 << 31) || b > 65536) return MSGEMM_ERR_INVALID_ARG;
     if (d < 0 || d > 4) return MSGEMM_ERR_INVALID_ARG;  // Section 5: d cannot usefully exceed 4
     if (!msgemm::dtype_pair_ok(x_dtype, y_dtype)) return MSGEMM_ERR_INVALID_ARG;
-    if (variant < MSGEMM_VARIANT_AUTO || variant > MSGEMM_VARIANT_FUSED_LDS) return MSGEMM_ERR_INVALID_ARG;
+    if (variant < MSGEMM_VARIANT_AUTO || variant > MSGEMM_VARIANT_FUSED_LDS16) return MSGEMM_ERR_INVALID_ARG;
     if (scale_group < 0) return MSGEMM_ERR_INVALID_ARG;
     if (scale_group > 0) {
         if (!scales || x_dtype == MSGEMM_I8) return MSGEMM_ERR_INVALID_ARG;
@@ -85,10 +85,10 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtyp
     // variant
     p->variant = MSGEMM_VARIANT_GLOBAL_LUT;
     if (variant != MSGEMM_VARIANT_GLOBAL_LUT) {
-        rc = msgemm::fused_choose_shape(*p);
+        rc = msgemm::fused_choose_shape(*p, variant);
         if (rc == MSGEMM_OK) {
-            p->variant = MSGEMM_VARIANT_FUSED_LDS;
-        } else if (variant == MSGEMM_VARIANT_FUSED_LDS || rc != MSGEMM_ERR_UNSUPPORTED) {
+            p->variant = p->fs.entry_bytes == 2 ? MSGEMM_VARIANT_FUSED_LDS16 : MSGEMM_VARIANT_FUSED_LDS;
+        } else if (variant != MSGEMM_VARIANT_AUTO || rc != MSGEMM_ERR_UNSUPPORTED) {
             return fail(rc);
         }
     }
@@ -141,7 +141,7 @@ int msgemm_plan_get_info(const msgemm_plan_t* plan, msgemm_plan_info_t* info)
     info->x_dtype = p.x_dtype; info->y_dtype = p.y_dtype; info->lut_dtype = p.lut_dtype;
     info->d = p.d; info->scale_group = p.scale_group; info->variant = p.variant;
     info->lut_groups = p.lut_groups;
-    const bool fused = p.variant == MSGEMM_VARIANT_FUSED_LDS;
+    const bool fused = p.variant != MSGEMM_VARIANT_GLOBAL_LUT;
     info->tile_rows = fused ? p.fs.tile_rows : 0;
     info->tile_groups = fused ? p.fs.groups : 0;
     info->split_k = fused ? (int)p.ktiles : 1;
@@ -178,7 +178,7 @@ int msgemm_run(const msgemm_plan_t* plan, const void* X, int64_t ldx, void* Y, i
     const Plan& p = *reinterpret_cast<const Plan*>(plan);
     if (ldx < p.k || ldy < p.m) return MSGEMM_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
-    if (p.variant == MSGEMM_VARIANT_FUSED_LDS) return msgemm::launch_fused(p, X, ldx, Y, ldy, s);
+    if (p.variant != MSGEMM_VARIANT_GLOBAL_LUT) return msgemm::launch_fused(p, X, ldx, Y, ldy, s);
     int rc = msgemm::launch_build_lut(p, X, ldx, p.lut_ws, s);
     if (rc != MSGEMM_OK) return rc;
     return msgemm::launch_consume_lut(p, p.lut_ws, Y, ldy, s);

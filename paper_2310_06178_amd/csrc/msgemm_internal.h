@@ -68,7 +68,7 @@ int launch_build_lut(const Plan& p, const void* X, int64_t ldx, void* L, hipStre
 int launch_consume_lut(const Plan& p, const void* L, void* Y, int64_t ldy, hipStream_t s);
 
 // kernels_fused.hip
-int fused_choose_shape(Plan& p);  // fills p.fs, ktiles, row_blocks ...; MSGEMM_ERR_UNSUPPORTED if not applicable
+int fused_choose_shape(Plan& p, int requested_variant);  // fills p.fs, ktiles, ...; MSGEMM_ERR_UNSUPPORTED if not applicable
 int launch_repack(const Plan& p, hipStream_t s);
 int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s);
 

@@ -228,11 +228,46 @@ def test_fused_variant_small(m, k, b, xd, sg):
         assert np.array_equal(out, out_g)
 
 
+BATCHED = [
+    # m, k, b, xd, sg, variant   -- 32 groups per k-tile, 8 (16-bit entries) or 4 (fp32) columns per pass
+    (300, 520, 5, "f16", 0, B.VARIANT_FUSED_LDS16),     # ragged everything, one partial column pass
+    (1025, 1024, 8, "f16", 128, B.VARIANT_FUSED_LDS16),  # scale block = two k-tiles
+    (513, 512, 11, "bf16", 64, B.VARIANT_FUSED_LDS16),   # scale block = one k-tile, two column passes
+    (700, 768, 16, "i8", 0, B.VARIANT_FUSED_LDS16),
+    (260, 130, 3, "i8", 0, B.VARIANT_FUSED_LDS16),
+    (300, 520, 6, "f32", 0, B.VARIANT_FUSED_LDS),        # fp32 entries, 4 columns per pass
+    (515, 256, 4, "f32", 128, B.VARIANT_FUSED_LDS),
+    (300, 520, 5, "f16", 0, B.VARIANT_FUSED_LDS),        # full-width entries on request: column at a time
+]
+
+
+@pytest.mark.parametrize("m,k,b,xd,sg,variant", BATCHED)
+def test_fused_variant_batched(m, k, b, xd, sg, variant):
+    codes = inputs.make_codes(m, k, seed=2 * m + k)
+    X = inputs.make_x(k, b, xd, seed=k + 7 * b)
+    scales = inputs.make_scales(m, k, sg, seed=9) if sg else None
+    ref = oracle_y(codes, X, xd, scales, sg)
+    out, info = run_gpu(codes, X, xd, scales, sg, 2, variant, ldx_pad=4, ldy_pad=7)
+    assert info["variant"] == variant
+    check(out, ref, xd, "fused batched")
+    if variant == B.VARIANT_FUSED_LDS16:
+        assert info["col_chunk"] == 8
+        out_auto, info_auto = run_gpu(codes, X, xd, scales, sg, 2, B.VARIANT_AUTO)
+        assert info_auto["variant"] == B.VARIANT_FUSED_LDS16  # the library's own choice for b > 2
+        assert np.array_equal(out_auto, out)
+
+
+def test_fused_lds16_not_for_fp32():
+    dC = torch.zeros(64 * 32, dtype=torch.uint8, device="cuda:0")
+    status, handle = B.msgemm_plan(64, 64, 4, "f32", "f32", 2, 0, dC, None, B.VARIANT_FUSED_LDS16, check=False)
+    assert status == B.ERR_UNSUPPORTED and handle is None
+
+
 def test_fused_scale_group_not_tileable_falls_back():
     m, k, b = 64, 256, 2
     codes = inputs.make_codes(m, k, seed=1)
     X = inputs.make_x(k, b, "f16", seed=2)
-    scales = inputs.make_scales(m, k, 32, seed=3)
+    scales = inputs.make_scales(m, k, 32, seed=3)  # a k-tile covers at least 64 columns
     out, info = run_gpu(codes, X, "f16", scales, 32, 0, B.VARIANT_AUTO)
     assert info["variant"] == B.VARIANT_GLOBAL_LUT
     check(out, oracle_y(codes, X, "f16", scales, 32), "f16", "fallback")
@@ -264,7 +299,7 @@ def test_config_full_size(name):
     cfg, codes, X, scales = inputs.make_config(name)
     m, k, b, xd, sg = cfg["m"], cfg["k"], cfg["b"], cfg["x"], cfg["scale_group"]
     out, info = run_gpu(codes, X, xd, scales, sg, cfg["d"], B.VARIANT_AUTO)
-    assert info["variant"] == B.VARIANT_FUSED_LDS
+    assert info["variant"] in (B.VARIANT_FUSED_LDS, B.VARIANT_FUSED_LDS16)
     # the oracle takes every row where that is quick, else a seeded sample of rows
     budget = 1.2e9
     if m * k * b <= budget:
