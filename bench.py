@@ -90,6 +90,8 @@ def main() -> int:
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--d", type=int, default=None)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 64 MiB elementwise copy (untimed): gives hardware-counter runs a kernel of known traffic")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -136,6 +138,12 @@ def main() -> int:
     for i in range(max(args.warmup, 1)):
         step(i)
     torch.cuda.synchronize()
+    if args.calib_copy:
+        src = torch.ones(64 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)  # an elementwise kernel: reads 64 MiB, writes 64 MiB
+        torch.cuda.synchronize()
 
     mode = args.mode
     graph = None

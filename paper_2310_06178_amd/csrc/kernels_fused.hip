@@ -23,10 +23,11 @@
 //
 // Code stream
 //   The plan stores the codes in the order the lanes consume them
-//   ([k-tile][panel][load][lane][byte]), so every load instruction of a
+//   ([load][k-tile][panel][lane][byte]), so every load instruction of a
 //   wavefront reads one contiguous 64*LB-byte segment with full-width per-lane
-//   loads.  A wavefront keeps a ring of kRing loads in flight and refills a
-//   slot as soon as its bytes have been turned into LDS addresses.
+//   loads, and the t-th loads of all wavefronts are neighbours in memory.  A
+//   wavefront keeps a ring of kRing loads in flight and refills a slot as soon
+//   as its bytes have been turned into LDS addresses.
 #include <stdlib.h>
 
 #include "device_types.h"
@@ -240,7 +241,6 @@ fused_kernel(FusedArgs a)
     constexpr int kEarlyBuilder = C == 1 ? MSGEMM_EARLY_BUILDER : 2;  // code loads a builder requests before it waits for the activations
     constexpr int kBuildParts = kBuilders * 64 / G;  // builder threads per group
     static_assert(kBuildParts >= 1 && kBuilders * 64 % G == 0, "builders must cover whole groups");
-    constexpr int kPanelLoads = kLoadsPerPanel * 64;  // LoadT elements per panel
     static_assert(G == 16 || G == 32 || G == 64, "G");
     static_assert(LB % NQ == 0, "rows per lane must split over the lanes sharing them");
     static_assert(kLoadsPerPanel % kRing == 0, "ring slots are reused with a period dividing the panel");
@@ -287,15 +287,19 @@ fused_kernel(FusedArgs a)
     int panels_here = a.panels_total - panel_first;
     if (panels_here > a.panels_per_wg) panels_here = a.panels_per_wg;
     const int npan = wave < panels_here ? (panels_here - wave + kWaves - 1) / kWaves : 0;
+    // load t of every panel of every k-tile is stored together ([load][k-tile][panel][lane]):
+    // wavefronts advance through their panels roughly in step, so what the chip has
+    // in flight at any time falls into a narrow address window (DRAM page locality)
+    const int64_t step_stride = (int64_t)a.ktiles * a.panels_total * 64;  // LoadT elements between loads
     const LoadT* __restrict__ stream =
-        (const LoadT*)a.tiled + ((int64_t)kt * a.panels_total + panel_first + wave) * kPanelLoads + lane;
+        (const LoadT*)a.tiled + ((int64_t)kt * a.panels_total + panel_first + wave) * 64 + lane;
     // (idle wavefronts re-read the tile's first panel, which keeps the code below branch-free)
     const LoadT* first = npan > 0 ? stream : (const LoadT*)a.tiled + lane;
     LoadT ring[kRing];
     auto fill_ring = [&](int from, int to) {
 #pragma unroll
         for (int u = from; u < to; ++u) {
-            ring[u] = first[u * 64];
+            ring[u] = first[u * step_stride];
             __builtin_amdgcn_sched_barrier(0);  // loads return in issue order: keep slot 0 first
         }
     };
@@ -392,7 +396,7 @@ fused_kernel(FusedArgs a)
         // are being added, so the LDS latency hides behind the adds without the
         // scheduler hoisting all 16*LB reads at once.
         const bool more = pi + 1 < npan;
-        const LoadT* cur = stream + (int64_t)pi * kWaves * kPanelLoads;
+        const LoadT* cur = stream + (int64_t)pi * kWaves * 64;
         auto issue = [&](int t, Entry (&dst)[LB]) {
             const uint32_t lane_off = class_base + (uint32_t)((j + t) & 15) * kEntryBytes;
             const LoadT d = ring[t % kRing];
@@ -408,9 +412,9 @@ fused_kernel(FusedArgs a)
             }
             // the slot's bytes are now addresses: refill it with the load kRing ahead
             if (t + kRing < kLoadsPerPanel) {
-                ring[t % kRing] = cur[(t + kRing) * 64];
+                ring[t % kRing] = cur[(t + kRing) * step_stride];
             } else if (more) {
-                ring[t % kRing] = cur[kWaves * kPanelLoads + (t + kRing - kLoadsPerPanel) * 64];
+                ring[t % kRing] = cur[kWaves * 64 + (t + kRing - kLoadsPerPanel) * step_stride];
             }
         };
         auto consume = [&](const Entry (&src)[LB]) {
@@ -608,9 +612,9 @@ repack_kernel(const uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled, in
         int64_t r = o;
         const int s = (int)(r % LB); r /= LB;
         const int lane = (int)(r % 64); r /= 64;
-        const int t = (int)(r % kLoadsPerPanel); r /= kLoadsPerPanel;
-        const int64_t panel = r % panels_total;
-        const int64_t kt = r / panels_total;
+        const int64_t panel = r % panels_total; r /= panels_total;
+        const int64_t kt = r % ktiles;
+        const int t = (int)(r / ktiles);
         const int q = lane >> 4, j = lane & 15;
         const int qg = q % NQ;
         const int64_t row = panel * kPanelRows + panel_row<NQ, LB>(q, j, s);
