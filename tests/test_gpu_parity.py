@@ -325,3 +325,43 @@ def test_config2_d3_sweep_point():
     out, info = run_gpu(codes, X, "f16", None, 0, 3, B.VARIANT_AUTO)
     assert info["d"] == 3 and info["lut_groups"] == 1366
     check(out, oracle_y(codes, X, "f16", None, 0), "f16", "cfg2 d=3")
+
+
+# ---------------------------------------------------------------------------
+# the dense matrix-core comparison kernel (not msGeMM) computes the same Y
+
+@pytest.mark.parametrize("m,k,b,xd,sg", [
+    (300, 256, 5, "f16", 0),
+    (257, 512, 64, "f16", 128),
+    (513, 384, 70, "bf16", 128),     # two column tiles, ragged rows
+    (64, 1024, 16, "bf16", 256),
+])
+def test_dequant_mfma_comparison_kernel(m, k, b, xd, sg):
+    codes = inputs.make_codes(m, k, seed=m + k)
+    X = inputs.make_x(k, b, xd, seed=b)
+    scales = inputs.make_scales(m, k, sg, seed=4) if sg else None
+    ref = oracle_y(codes, X, xd, scales, sg)
+    dC, dS, dX = torch_io.to_device(codes, "codes"), torch_io.to_device(scales, "scales"), torch_io.to_device(X, xd)
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS)
+    try:
+        Y = torch_io.empty_output(b, m, Y_OF_X[xd], ldy=m + 3)
+        Y.fill_(-3)
+        B.msgemm_dequant_mfma_run(plan, dX, k, Y, m + 3)
+        torch.cuda.synchronize()
+        out = torch_io.to_host(Y)
+    finally:
+        B.msgemm_destroy(plan)
+    check(np.ascontiguousarray(out[:, :m]), ref, xd, "dequant+MFMA")
+
+
+def test_dequant_mfma_unsupported_dtypes():
+    dC = torch.zeros(64 * 32, dtype=torch.uint8, device="cuda:0")
+    X = torch.zeros(64, dtype=torch.int8, device="cuda:0")
+    Y = torch.zeros(64, dtype=torch.int32, device="cuda:0")
+    plan = B.msgemm_plan(64, 64, 1, "i8", "i32", 2, 0, dC)
+    try:
+        with pytest.raises(B.MsgemmError) as e:
+            B.msgemm_dequant_mfma_run(plan, X, 64, Y, 64)
+        assert e.value.status == B.ERR_UNSUPPORTED
+    finally:
+        B.msgemm_destroy(plan)
