@@ -237,7 +237,9 @@ fused_kernel(FusedArgs a)
     // is built (the others start the code stream at once), all of them for the
     // wide tables of a batch
     constexpr int kBuilders = C == 1 ? MSGEMM_BUILDERS_1COL(kWaves) : kWaves;
-    constexpr int kRing = kRingBytes / LB < kLoadsPerPanel ? kRingBytes / LB : kLoadsPerPanel;  // loads in flight
+    // loads in flight: the batched kernels are bound by VALU work, half the depth is enough there
+    constexpr int kRingWant = (C == 1 ? kRingBytes : kRingBytes / 2) / LB;
+    constexpr int kRing = kRingWant < kLoadsPerPanel ? kRingWant : kLoadsPerPanel;
     constexpr int kEarlyBuilder = C == 1 ? MSGEMM_EARLY_BUILDER : 2;  // code loads a builder requests before it waits for the activations
     constexpr int kBuildParts = kBuilders * 64 / G;  // builder threads per group
     static_assert(kBuildParts >= 1 && kBuilders * 64 % G == 0, "builders must cover whole groups");
@@ -417,19 +419,42 @@ fused_kernel(FusedArgs a)
                 ring[t % kRing] = cur[kWaves * 64 + (t + kRing - kLoadsPerPanel) * step_stride];
             }
         };
-        auto consume = [&](const Entry (&src)[LB]) {
+        // 16-bit entries are first added up in packed 16-bit registers, two columns
+        // per instruction, over kChain look-ups, and only then widened into the
+        // 32-bit accumulators: int16 sums of 8 entries (|entry| <= 2048) are exact;
+        // fp16 sums of 4 entries round three times more (the error stays well
+        // inside the fp16 output tolerance, the entries themselves are fp16 already).
+        constexpr bool kPacked = sizeof(ET) == 2 && C % 2 == 0;
+        constexpr int kChain = __is_same(ET, short) ? 8 : 4;
+        uint32_t acc16[kPacked ? LB : 1][kPacked ? C / 2 : 1];
+        auto consume = [&](int t, const Entry (&src)[LB]) {
 #pragma unroll
             for (int s = 0; s < LB; ++s) {
-                if constexpr (__is_same(ET, __half) && C % 2 == 0) {
-                    // fp16 entries, fp32 accumulators: one mixed-precision FMA per
-                    // column (acc = half * 1.0 + acc) instead of a convert and an add
+                if constexpr (kPacked) {
                     const uint32_t* w = (const uint32_t*)&src[s];
 #pragma unroll
-                    for (int c = 0; c < C; c += 2) {
-                        asm volatile("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel_hi:[1,0,0]"
-                                     : "+v"(acc[s][c]) : "v"(w[c / 2]));
-                        asm volatile("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel:[1,0,0] op_sel_hi:[1,0,0]"
-                                     : "+v"(acc[s][c + 1]) : "v"(w[c / 2]));
+                    for (int c2 = 0; c2 < C / 2; ++c2) {
+                        if (t % kChain == 0) {
+                            acc16[s][c2] = w[c2];
+                            asm volatile("" : "+v"(acc16[s][c2]));
+                        } else if constexpr (__is_same(ET, __half)) {
+                            asm volatile("v_pk_add_f16 %0, %1, %0" : "+v"(acc16[s][c2]) : "v"(w[c2]));
+                        } else {
+                            asm volatile("v_pk_add_i16 %0, %1, %0" : "+v"(acc16[s][c2]) : "v"(w[c2]));
+                        }
+                        if (t % kChain == kChain - 1) {
+                            if constexpr (__is_same(ET, __half)) {
+                                // acc = half * 1.0 + acc, one mixed-precision FMA per column
+                                asm volatile("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel_hi:[1,0,0]"
+                                             : "+v"(acc[s][2 * c2]) : "v"(acc16[s][c2]));
+                                asm volatile("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel:[1,0,0] op_sel_hi:[1,0,0]"
+                                             : "+v"(acc[s][2 * c2 + 1]) : "v"(acc16[s][c2]));
+                            } else {
+                                acc[s][2 * c2] += (int)(short)(acc16[s][c2] & 0xffffu);
+                                acc[s][2 * c2 + 1] += (int)(short)(acc16[s][c2] >> 16);
+                                asm volatile("" : "+v"(acc[s][2 * c2]), "+v"(acc[s][2 * c2 + 1]));
+                            }
+                        }
                     }
                 } else {
 #pragma unroll
@@ -442,15 +467,16 @@ fused_kernel(FusedArgs a)
                 }
             }
         };
+        static_assert(kLoadsPerPanel % kChain == 0, "chains end with the panel");
         Entry e0[LB], e1[LB];
         issue(0, e0);
 #pragma unroll
         for (int t = 0; t < kLoadsPerPanel; t += 2) {
             issue(t + 1, e1);
-            consume(e0);
+            consume(t, e0);
             __builtin_amdgcn_sched_barrier(0);
             if (t + 2 < kLoadsPerPanel) issue(t + 2, e0);
-            consume(e1);
+            consume(t + 1, e1);
             __builtin_amdgcn_sched_barrier(0);
         }
         MSGEMM_TRACE(4);
