@@ -28,10 +28,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch of the fused kernel on cfg2, from rocprofv3 --pmc runs
-# (FETCH_SIZE, WRITE_SIZE, scaled by a copy kernel of known size); None until
-# measured.  Source: profiles/fused_kernel_cfg2_pmc.txt
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch of the dominant (fused) kernel, reads + writes, from two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same
+# counter reads for a 64 MiB elementwise kernel in the same run.
+# Source: profiles/fused_kernel_cfg2_hbm_traffic.txt
+MEASURED_TRAFFIC_BYTES = {"cfg2": 35866789}
 
 
 def algorithmic_bytes(cfg) -> int:
