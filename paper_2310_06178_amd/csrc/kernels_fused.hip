@@ -8,9 +8,10 @@
 //   once (Section 4, "pipeline phase 1 and 2 by partially computing L").
 //   A workgroup owns one k-tile and `panels` row panels; each wavefront
 //   streams whole panels.  Outputs are reduced over k-tiles through a
-//   partial-sum buffer: the wavefront that delivers the last partial of a
-//   panel adds them up in k-tile order and writes Y (one launch, and the sum
-//   order is fixed, so results are reproducible).
+//   partial-sum buffer, in k-tile order (a fixed order: results are
+//   reproducible): by trailing workgroups of the same launch that wait for the
+//   partials of their panels (single-column kernels), or by a second small
+//   launch (batched kernels).
 //
 // LDS layout and the gather
 //   entry(code, g) sits at byte (code*G + g) * C * sizeof(ET).  Lane l = 16q+j
@@ -36,15 +37,21 @@
 // Optional phase timestamps for kernel tuning (compiled out unless requested).
 #ifdef MSGEMM_PHASE_TRACE
 __device__ unsigned long long* g_msgemm_trace = nullptr;
-extern "C" int msgemm_debug_set_trace(unsigned long long* buf)
+__device__ unsigned long long g_msgemm_trace_slots = 0;  // capacity of the buffer in 64-bit slots
+extern "C" int msgemm_debug_set_trace(unsigned long long* buf, unsigned long long slots)
 {
+    hipError_t e = hipMemcpyToSymbol(HIP_SYMBOL(g_msgemm_trace_slots), &slots, sizeof(slots));
+    if (e != hipSuccess) return (int)e;
     return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_msgemm_trace), &buf, sizeof(buf));
 }
-#define MSGEMM_TRACE(id)                                                                         \
-    do {                                                                                         \
-        if (g_msgemm_trace && (threadIdx.x & 63) == 0)                                           \
-            g_msgemm_trace[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 16 + (id)] = wall_clock64(); \
-    } while (0)
+// slot (workgroup, wavefront, id); writes past the capacity are dropped
+__device__ __forceinline__ void msgemm_trace_put(int id, unsigned long long v)
+{
+    const unsigned long long slot = ((unsigned long long)blockIdx.x * 16 + (threadIdx.x >> 6)) * 16 + (unsigned)id;
+    if (g_msgemm_trace && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) < 16 && slot < g_msgemm_trace_slots)
+        g_msgemm_trace[slot] = v;
+}
+#define MSGEMM_TRACE(id) msgemm_trace_put((id), wall_clock64())
 #else
 #define MSGEMM_TRACE(id) do { } while (0)
 #endif
@@ -59,12 +66,38 @@ constexpr int kLoadsPerPanel = 16;  // one load per group of a 16-group class
 #ifndef MSGEMM_EARLY_BUILDER
 #define MSGEMM_EARLY_BUILDER 0
 #endif
+#ifndef MSGEMM_DEDICATED_1COL
+#define MSGEMM_DEDICATED_1COL 4
+#endif
 #ifndef MSGEMM_RING_BYTES
 #define MSGEMM_RING_BYTES 128
 #endif
 constexpr int kRingBytes = MSGEMM_RING_BYTES;  // code bytes per lane a wavefront keeps in flight (x64 lanes)
 constexpr int kAuxSc1 = 16;         // buffer cache policy bit: coherent at agent scope
+constexpr unsigned kMaxFlagPolls = 1u << 22;  // safety bound of the in-launch reduction's wait (seconds)
 constexpr int kXcds = 8;            // L2 slices (XCDs); workgroups are dealt to them round-robin
+
+// n / d for a divisor fixed at launch, without the hardware-less division
+// sequence (round-up multiplier of Granlund and Montgomery; exact for every
+// 32-bit n): q = (t + ((n - t) >> s1)) >> s2 with t = high word of n * magic.
+struct FastDiv { uint32_t magic, s1, s2; };
+
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    uint32_t l = 0;
+    while (l < 32 && ((uint64_t)1 << l) < d) ++l;
+    FastDiv f;
+    f.magic = (uint32_t)((((uint64_t)1 << 32) * (((uint64_t)1 << l) - d)) / d + 1);
+    f.s1 = l < 1 ? l : 1;
+    f.s2 = l - f.s1;
+    return f;
+}
+
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, const FastDiv& f)
+{
+    const uint32_t t = __umulhi(n, f.magic);
+    return (t + ((n - t) >> f.s1)) >> f.s2;
+}
 
 struct FusedArgs {
     const uint8_t* tiled;
@@ -72,9 +105,9 @@ struct FusedArgs {
     int64_t ldx;
     void* Y;
     int64_t ldy;
-    const __half* scales;   // [m][nblocks] or nullptr
+    const __half* scales;   // in output order, [nblocks][panels_total][64][outputs per lane], or nullptr
     float* partials;        // [ktiles][b_pad][panels_total][64][outputs per lane]
-    unsigned* counters;     // [panels_total][col_passes]
+    unsigned* flags;        // [panels_total][col_passes][ktiles], zero between launches
     int64_t m, k, b, m_pad, b_pad;
     int ktiles, panels_total, panels_per_wg, row_blocks, col_passes;
     int row_groups;         // row_blocks * col_passes
@@ -83,12 +116,16 @@ struct FusedArgs {
     int64_t partial_span;   // bytes of the partial buffer (< 2^31)
     int tiles_per_block;    // k-tiles per scale block
     int reduce_mode;        // how partial sums over k-tiles become Y, see ReduceMode
+    FastDiv div_ktiles, div_col_passes, div_tiles_per_block;
+    int fused_wgs;          // workgroups of the grid that do the fused work; the rest reduce (in-launch mode)
+    int red_waves;          // wavefronts of a reducing workgroup that take a unit
+    int red_units;          // (panel, column pass) pairs to reduce
 };
 
 enum ReduceMode {
     kReduceDirect = 0,    // a single k-tile: the fused kernel writes Y itself
     kReduceSecondPass = 1,  // partials to memory, a second small kernel adds them
-    kReduceLastArriver = 2  // partials to memory, the wavefront delivering the last one adds them
+    kReduceInLaunch = 2   // partials to memory, the workgroup of the last k-tile adds them in the same launch
 };
 
 template <int LB> struct LaneLoad;
@@ -158,10 +195,11 @@ template <typename AT> __device__ __forceinline__ AT fold16(AT a, AT b)
 }
 
 // The partial sums of one output come from workgroups that may sit on different
-// XCDs, whose L2 slices are not coherent with each other.  Partials and counters
-// are therefore only touched with agent-coherent accesses (they go to the point
-// of coherence) and ordered by waiting for the stores to be acknowledged before
-// the counter is bumped.  No cache-wide write-back / invalidate is needed.
+// XCDs, whose L2 slices are not coherent with each other.  When they are reduced
+// inside the launch, partials and flags are therefore only touched with
+// agent-coherent accesses (they go to the point of coherence) and ordered by
+// waiting for the stores to be acknowledged before the flag is raised.  No
+// cache-wide write-back / invalidate is needed.
 __device__ __forceinline__ void wait_vmem()
 {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -221,8 +259,89 @@ __host__ __device__ __forceinline__ int panel_row(int q, int j, int s)
     return (s % nfinal) * 64 + (qr * NQ + s / nfinal) * 16 + j;
 }
 
+// The single-column kernels can reduce inside the launch; the batched ones are
+// bound by the gather, not by launches, and have no registers to spare for it.
+template <int C> constexpr bool kInLaunchReduce = C == 1;
+
+// Reduction over the k-tiles inside the launch.  The workgroups that follow the
+// fused ones in the grid each take a few (panel, column pass) units: a wavefront
+// waits for the flags of its panel's k-tiles, adds their partial sums in k-tile
+// order and writes Y.  Workgroups are dispatched in id order, so everything a
+// reducer waits for is already resident and runs to its flag without waiting
+// on anyone: the wait ends (it is bounded all the same).  The sum order is
+// fixed: results are reproducible.
+template <typename YT, typename AT, int C, int kFinal>
+__device__ __forceinline__ void reduce_in_launch(const FusedArgs& a, int unit, int lane)
+{
+    constexpr int kPanelRows = kFinal * 64;
+    const int panel_g = (int)fast_div((uint32_t)unit, a.div_col_passes);
+    const int cp = unit - panel_g * a.col_passes;
+    const int64_t col0 = (int64_t)cp * C;
+    const int64_t row0 = (int64_t)panel_g * kPanelRows + lane;
+    YT* __restrict__ Y = (YT*)a.Y;
+    unsigned* flags = a.flags + (int64_t)unit * a.ktiles;
+    for (int base = 0; base < a.ktiles; base += 64) {
+        const int idx = base + lane;
+        const bool need = idx < a.ktiles;
+        for (unsigned spins = 0; spins < kMaxFlagPolls; ++spins) {
+            asm volatile("" ::: "memory");
+            const unsigned f = need ? __hip_atomic_load(flags + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1u;
+            if (__builtin_amdgcn_ballot_w64(f != 1u) == 0) break;
+            __builtin_amdgcn_s_sleep(2);
+        }
+        // lowered again for the next launch (kernel boundaries order launches)
+        if (need) __hip_atomic_store(flags + idx, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    asm volatile("" ::: "memory");
+    MSGEMM_TRACE(7);
+    __amdgpu_buffer_rsrc_t part_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)a.partials, 0, (int)a.partial_span, 0x00020000);
+    const uint32_t col_stride = (uint32_t)(a.m_pad * 4);
+    const uint32_t tile_stride = (uint32_t)(a.b_pad * a.m_pad * 4);
+    const uint32_t part_off = (uint32_t)col0 * col_stride + (uint32_t)(panel_g * kPanelRows + lane * kFinal) * 4u;
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        AT sum[kFinal];
+#pragma unroll
+        for (int i = 0; i < kFinal; ++i) sum[i] = 0;
+        const uint32_t off0 = part_off + (uint32_t)c * col_stride;
+        // kBatch k-tiles' partials are requested together, then added in order;
+        // k-tiles past the end get an out-of-range offset, which reads as zero
+        constexpr int kBatch = kFinal <= 4 ? 32 : 8;
+        for (int t0 = 0; t0 < a.ktiles; t0 += kBatch) {
+            unsigned v[kBatch][kFinal];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const uint32_t off = (t0 + u < a.ktiles) ? off0 + (uint32_t)(t0 + u) * tile_stride : 0x7ffffff0u;
+                load_partials<kFinal, kAuxSc1>(part_rsrc, off, v[u]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u)
+#pragma unroll
+                for (int i = 0; i < kFinal; ++i) {
+                    AT x;
+                    set_bits(x, v[u][i]);
+                    sum[i] += x;
+                }
+        }
+#pragma unroll
+        for (int i = 0; i < kFinal; ++i) {
+            const int64_t row = row0 + 64 * i;
+            if (row < a.m && col0 + c < a.b) Y[(col0 + c) * a.ldy + row] = to_output<YT, AT>(sum[i]);
+        }
+    }
+    MSGEMM_TRACE(8);
+}
+
+// Wavefronts that only build the tables and then retire.  The single-column
+// kernel with 8 streaming wavefronts has them: a wavefront that both builds and
+// streams requests its codes late, after the activations have arrived.  (The
+// 16-wavefront form has no room for more wavefronts in a workgroup.)
+template <int C, int kWaves> constexpr int dedicated_builders() { return (C == 1 && kWaves <= 8) ? MSGEMM_DEDICATED_1COL : 0; }
+
 template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves>
-__global__ void __launch_bounds__(kWaves * 64)
+__global__ void __launch_bounds__((kWaves + dedicated_builders<C, kWaves>()) * 64)
 fused_kernel(FusedArgs a)
 {
     using AT = typename EntryAcc<ET>::type;
@@ -236,7 +355,8 @@ fused_kernel(FusedArgs a)
     // wavefronts that build the tables (phase 1): half of them when one column
     // is built (the others start the code stream at once), all of them for the
     // wide tables of a batch
-    constexpr int kBuilders = C == 1 ? MSGEMM_BUILDERS_1COL(kWaves) : kWaves;
+    constexpr int kDedicated = dedicated_builders<C, kWaves>();
+    constexpr int kBuilders = kDedicated ? kDedicated : (C == 1 ? MSGEMM_BUILDERS_1COL(kWaves) : kWaves);
     // loads in flight: the batched kernels are bound by VALU work, half the depth is enough there
     constexpr int kRingWant = (C == 1 ? kRingBytes : kRingBytes / 2) / LB;
     constexpr int kRing = kRingWant < kLoadsPerPanel ? kRingWant : kLoadsPerPanel;
@@ -250,28 +370,49 @@ fused_kernel(FusedArgs a)
     __shared__ __align__(16) unsigned char lds[256 * kCodeStride];
     __shared__ unsigned tables_built;  // builder wavefronts that have finished phase 1
 
+    // Fetch every launch argument in one batch of scalar loads.  Left alone the
+    // compiler loads each where it is first used, and the kernel then starts with
+    // a chain of dependent round trips to the argument buffer -- each a cache miss.
+#define MSGEMM_ARG_NOW(x) asm volatile("" ::"s"(x))
+    MSGEMM_ARG_NOW((uint64_t)a.tiled); MSGEMM_ARG_NOW((uint64_t)a.X); MSGEMM_ARG_NOW(a.ldx);
+    MSGEMM_ARG_NOW((uint64_t)a.Y); MSGEMM_ARG_NOW(a.ldy); MSGEMM_ARG_NOW((uint64_t)a.scales);
+    MSGEMM_ARG_NOW((uint64_t)a.partials); MSGEMM_ARG_NOW(a.m); MSGEMM_ARG_NOW(a.k); MSGEMM_ARG_NOW(a.b);
+    MSGEMM_ARG_NOW(a.m_pad); MSGEMM_ARG_NOW(a.b_pad); MSGEMM_ARG_NOW(a.ktiles); MSGEMM_ARG_NOW(a.panels_total);
+    MSGEMM_ARG_NOW(a.panels_per_wg); MSGEMM_ARG_NOW(a.col_passes); MSGEMM_ARG_NOW(a.row_groups);
+    MSGEMM_ARG_NOW(a.xcd_map); MSGEMM_ARG_NOW(a.partial_span); MSGEMM_ARG_NOW(a.reduce_mode);
+    MSGEMM_ARG_NOW(a.div_ktiles.magic); MSGEMM_ARG_NOW(a.div_ktiles.s1); MSGEMM_ARG_NOW(a.div_ktiles.s2);
+    MSGEMM_ARG_NOW(a.div_col_passes.magic); MSGEMM_ARG_NOW(a.div_col_passes.s1); MSGEMM_ARG_NOW(a.div_col_passes.s2);
+    MSGEMM_ARG_NOW(a.div_tiles_per_block.magic); MSGEMM_ARG_NOW(a.div_tiles_per_block.s1);
+    MSGEMM_ARG_NOW(a.div_tiles_per_block.s2); MSGEMM_ARG_NOW(a.fused_wgs);
+#undef MSGEMM_ARG_NOW
+
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = (tid >> 6) - kDedicated;  // streaming wavefront index; negative: dedicated builder
     const int q = lane >> 4, j = lane & 15;
     const int qg = q % NQ;
 
     // ---- which k-tile / row block / column pass
+    if ((int)blockIdx.x >= a.fused_wgs) {  // trailing workgroups: the k-tile reduction (in-launch mode only)
+        if constexpr (kInLaunchReduce<C>) {
+            const int w = tid >> 6;
+            const int unit = ((int)blockIdx.x - a.fused_wgs) * a.red_waves + w;
+            if (w < a.red_waves && unit < a.red_units) reduce_in_launch<YT, AT, C, kFinal>(a, unit, lane);
+        }
+        return;
+    }
     int kt, rg;
     {
-        const int bid = blockIdx.x;
-        if (a.xcd_map) {
-            const int n = bid / kXcds;
-            rg = (bid % kXcds) + kXcds * (n / a.ktiles);
-            kt = n % a.ktiles;
-            if (rg >= a.row_groups) return;
-        } else {
-            kt = bid % a.ktiles;
-            rg = bid / a.ktiles;
-        }
+        const uint32_t bid = blockIdx.x;
+        const uint32_t n = a.xcd_map ? bid / kXcds : bid;
+        const uint32_t nq = fast_div(n, a.div_ktiles);
+        kt = (int)(n - nq * (uint32_t)a.ktiles);
+        rg = a.xcd_map ? (int)((bid % kXcds) + kXcds * nq) : (int)nq;
+        if (rg >= a.row_groups) return;
     }
-    const int cp = rg % a.col_passes;  // column passes of one row block are neighbours: the codes stay cached
-    const int rb = rg / a.col_passes;
+    const int rb = (int)fast_div((uint32_t)rg, a.div_col_passes);
+    const int cp = rg - rb * a.col_passes;  // column passes of one row block are neighbours: the codes stay cached
+    const int scale_block = (int)fast_div((uint32_t)kt, a.div_tiles_per_block);
     const int64_t col0 = (int64_t)cp * C;
 
     const XT* __restrict__ X = (const XT*)a.X;
@@ -280,15 +421,14 @@ fused_kernel(FusedArgs a)
     __syncthreads();  // nothing is in flight yet: this costs a few cycles
     MSGEMM_TRACE(0);
 #ifdef MSGEMM_PHASE_TRACE
-    if (g_msgemm_trace && lane == 0)  // hardware XCC_ID register, bits 3:0
-        g_msgemm_trace[((size_t)blockIdx.x * 16 + wave) * 16 + 9] = 1 + __builtin_amdgcn_s_getreg((3 << 11) | 20);
+    msgemm_trace_put(9, 1 + __builtin_amdgcn_s_getreg((3 << 11) | 20));  // hardware XCC_ID register, bits 3:0
 #endif
 
     // ---- this wavefront's stream of panels: wave, wave + kWaves, ...
     const int panel_first = rb * a.panels_per_wg;
     int panels_here = a.panels_total - panel_first;
     if (panels_here > a.panels_per_wg) panels_here = a.panels_per_wg;
-    const int npan = wave < panels_here ? (panels_here - wave + kWaves - 1) / kWaves : 0;
+    const int npan = (wave >= 0 && wave < panels_here) ? (panels_here - wave + kWaves - 1) / kWaves : 0;
     // load t of every panel of every k-tile is stored together ([load][k-tile][panel][lane]):
     // wavefronts advance through their panels roughly in step, so what the chip has
     // in flight at any time falls into a narrow address window (DRAM page locality)
@@ -314,7 +454,7 @@ fused_kernel(FusedArgs a)
     // Readiness of the tables is a counter in LDS rather than a barrier: a load
     // instruction stalls its wavefront while the memory queue is full, and a
     // barrier would make the builders -- and so the tables -- wait for that.
-    if (wave < kBuilders) {
+    if (kDedicated ? wave < 0 : wave < kBuilders) {
         const int g = tid % G;
         const int64_t kk = ((int64_t)kt * G + g) * 2;
         // raw values from clamped (always valid) addresses first, conversion after
@@ -328,7 +468,7 @@ fused_kernel(FusedArgs a)
             xr0[c] = px[0];
             xr1[c] = px[1];
         }
-        fill_ring(0, kEarlyBuilder);
+        if constexpr (!kDedicated) fill_ring(0, kEarlyBuilder);
         MSGEMM_TRACE(1);
         AT x0[C], x1[C];
 #pragma unroll
@@ -354,6 +494,7 @@ fused_kernel(FusedArgs a)
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         if (lane == 0) __hip_atomic_fetch_add(&tables_built, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         MSGEMM_TRACE(2);
+        if constexpr (kDedicated) return;
         fill_ring(kEarlyBuilder, kRing);
     } else {
         fill_ring(0, kRing);
@@ -378,13 +519,22 @@ fused_kernel(FusedArgs a)
         const int64_t row0 = (int64_t)panel_g * kPanelRows + lane;
 
         // scales of this k-tile's block for the rows this lane will own after the fold
-        float qv[kFinal];
+        // (one contiguous load per wavefront: the plan keeps them in the order of the
+        // outputs).  The load is unconditional -- without scales it reads the first
+        // code bytes instead -- and its value is first looked at after the gather, so
+        // no wait for it sits in front of the code stream.
+        struct alignas(2 * kFinal) PackedScales { __half h[kFinal]; };
+        PackedScales qraw;
+        if constexpr (__is_same(AT, float)) {
+            const PackedScales* qp = (const PackedScales*)(a.scales + ((int64_t)scale_block * a.m_pad +
+                                                                      (int64_t)panel_g * kPanelRows + lane * kFinal));
+            if constexpr (C == 1) {
+                qraw = *(a.scales ? qp : (const PackedScales*)a.tiled);
+            } else {
+                // (the batched kernels have no registers to spare: a conditional load, waited for at once)
 #pragma unroll
-        for (int i = 0; i < kFinal; ++i) {
-            qv[i] = 1.0f;
-            if constexpr (__is_same(AT, float)) {
-                const int64_t row = row0 + 64 * i;
-                if (a.scales && row < a.m) qv[i] = __half2float(a.scales[row * a.nblocks + kt / a.tiles_per_block]);
+                for (int i = 0; i < kFinal; ++i) qraw.h[i] = __float2half(1.0f);
+                if (a.scales) qraw = *qp;
             }
         }
 
@@ -484,6 +634,7 @@ fused_kernel(FusedArgs a)
         // ---- lanes that share rows: fold the NQ group classes; each lane ends
         // up with kFinal distinct rows (64*i + lane); then the block scale (Section 3.3)
         const uint32_t part_off = (uint32_t)col0 * col_stride + (uint32_t)(panel_g * kPanelRows + lane * kFinal) * 4u;
+        const bool in_launch = kInLaunchReduce<C> && a.reduce_mode == kReduceInLaunch;
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             AT fin[kFinal];
@@ -503,71 +654,29 @@ fused_kernel(FusedArgs a)
             unsigned out[kFinal];
 #pragma unroll
             for (int i = 0; i < kFinal; ++i) {
-                if constexpr (__is_same(AT, float)) out[i] = bits_of(fin[i] * qv[i]);
-                else out[i] = bits_of(fin[i]);
+                if constexpr (__is_same(AT, float)) fin[i] *= (a.scales ? __half2float(qraw.h[i]) : 1.0f);
+                out[i] = bits_of(fin[i]);
             }
             if (a.reduce_mode == kReduceDirect) {
 #pragma unroll
                 for (int i = 0; i < kFinal; ++i) {
                     const int64_t row = row0 + 64 * i;
-                    AT v;
-                    set_bits(v, out[i]);
-                    if (row < a.m && col0 + c < a.b) Y[(col0 + c) * a.ldy + row] = to_output<YT, AT>(v);
+                    if (row < a.m && col0 + c < a.b) Y[(col0 + c) * a.ldy + row] = to_output<YT, AT>(fin[i]);
                 }
             } else {
                 const uint32_t off = (uint32_t)kt * tile_stride + part_off + (uint32_t)c * col_stride;
-                if (a.reduce_mode == kReduceLastArriver) store_partials<kFinal, kAuxSc1>(part_rsrc, off, out);
+                if (in_launch) store_partials<kFinal, kAuxSc1>(part_rsrc, off, out);
                 else store_partials<kFinal, 0>(part_rsrc, off, out);
             }
         }
         MSGEMM_TRACE(5);
-        if (a.reduce_mode != kReduceLastArriver) continue;
-        wait_vmem();  // partials acknowledged before the counter moves
-        MSGEMM_TRACE(6);
-        unsigned prev = 0;
-        unsigned* counter = a.counters + (int64_t)panel_g * a.col_passes + cp;
+        if (!in_launch) continue;
+        // publish: partials acknowledged at the point of coherence, then the flag goes up
+        wait_vmem();
         if (lane == 0)
-            prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        prev = __builtin_amdgcn_readfirstlane(prev);
-        MSGEMM_TRACE(7);
-        if (prev == (unsigned)a.ktiles - 1u) {
-            // Every k-tile's partial for this panel has been published: add them in
-            // k-tile order.  Independent agent-coherent loads stay in flight together.
-#pragma unroll
-            for (int c = 0; c < C; ++c) {
-                AT sum[kFinal];
-#pragma unroll
-                for (int i = 0; i < kFinal; ++i) sum[i] = 0;
-                const uint32_t off0 = part_off + (uint32_t)c * col_stride;
-                // kBatch k-tiles' partials are requested together, then added in order;
-                // k-tiles past the end get an out-of-range offset, which reads as zero
-                constexpr int kBatch = (kFinal * C <= 4) ? 16 : (kFinal * C <= 8 ? 8 : 4);
-                for (int t0 = 0; t0 < a.ktiles; t0 += kBatch) {
-                    unsigned v[kBatch][kFinal];
-#pragma unroll
-                    for (int u = 0; u < kBatch; ++u) {
-                        const uint32_t off = (t0 + u < a.ktiles) ? off0 + (uint32_t)(t0 + u) * tile_stride : 0x7ffffff0u;
-                        load_partials<kFinal, kAuxSc1>(part_rsrc, off, v[u]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int u = 0; u < kBatch; ++u)
-#pragma unroll
-                        for (int i = 0; i < kFinal; ++i) {
-                            AT x;
-                            set_bits(x, v[u][i]);
-                            sum[i] += x;
-                        }
-                }
-#pragma unroll
-                for (int i = 0; i < kFinal; ++i) {
-                    const int64_t row = row0 + 64 * i;
-                    if (row < a.m && col0 + c < a.b) Y[(col0 + c) * a.ldy + row] = to_output<YT, AT>(sum[i]);
-                }
-            }
-            if (lane == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            MSGEMM_TRACE(8);
-        }
+            __hip_atomic_store(a.flags + ((int64_t)panel_g * a.col_passes + cp) * a.ktiles + kt, 1u, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        MSGEMM_TRACE(6);
     }
 }
 
@@ -649,6 +758,26 @@ repack_kernel(const uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled, in
     }
 }
 
+// One-off reorder of the block scales ([m][nblocks]) into the order in which the
+// lanes of the fused kernel hold their outputs: [block][panel][lane][output i],
+// output i of lane l being row 64*i + l of the panel.  Rows past m get 1.
+__global__ void __launch_bounds__(256)
+repack_scales_kernel(const __half* __restrict__ scales, __half* __restrict__ ordered, int64_t m, int64_t m_pad,
+                     int64_t nblocks, int panel_rows)
+{
+    const int64_t total = nblocks * m_pad;
+    const int nfinal = panel_rows / 64;
+    for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < total;
+         o += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t blk = o / m_pad;
+        const int64_t f = o % m_pad;
+        const int64_t panel = f / panel_rows;
+        const int in_panel = (int)(f % panel_rows);
+        const int64_t row = panel * panel_rows + 64 * (in_panel % nfinal) + in_panel / nfinal;
+        ordered[o] = row < m ? scales[row * nblocks + blk] : __float2half(1.0f);
+    }
+}
+
 struct ShapeChoice { int C, G, LB, entry_bytes, waves; };
 
 int env_int(const char* name, int fallback)
@@ -676,14 +805,21 @@ ShapeChoice pick_shape(const Plan& p, int requested_variant)
 }
 
 template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves>
-int launch_one(const Plan& p, const FusedArgs& a, hipStream_t s)
+int launch_one(const Plan& p, FusedArgs& a, hipStream_t s)
 {
     using AT = typename EntryAcc<ET>::type;
     constexpr int kFinal = LB / (G / 16);
     auto kern = fused_kernel<XT, YT, ET, C, G, LB, kWaves>;
-    int64_t grid = (int64_t)p.ktiles * a.row_groups;
-    if (a.xcd_map) grid = (int64_t)p.ktiles * kXcds * ((a.row_groups + kXcds - 1) / kXcds);
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kWaves * 64), 0, s, a);
+    a.fused_wgs = a.xcd_map ? (int)(p.ktiles * kXcds * ((a.row_groups + kXcds - 1) / kXcds)) : (int)(p.ktiles * a.row_groups);
+    // reducing workgroups: one unit per wavefront, and no more wavefronts per
+    // workgroup than it takes to give every compute unit one workgroup -- a unit's
+    // loads are latency-bound, a compute unit serves few of them at a time
+    a.red_units = a.panels_total * a.col_passes;
+    a.red_waves = (a.red_units + p.cus - 1) / p.cus;
+    if (a.red_waves > kWaves) a.red_waves = kWaves;
+    int64_t grid = a.fused_wgs;
+    if (a.reduce_mode == kReduceInLaunch) grid += (a.red_units + a.red_waves - 1) / a.red_waves;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3((kWaves + dedicated_builders<C, kWaves>()) * 64), 0, s, a);
     MSGEMM_HIP_TRY(hipGetLastError());
     if (a.reduce_mode == kReduceSecondPass) {
         const int64_t blocks = (a.m_pad / 64) * a.b;
@@ -720,6 +856,7 @@ int fused_choose_shape(Plan& p, int requested_variant)
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, p.device) == hipSuccess && prop.multiProcessorCount > 0)
         cus = prop.multiProcessorCount;
+    p.cus = cus;
     // Rows per table build: as many panels per workgroup as still leave one
     // workgroup per compute unit (each build costs 256 entries per group).
     // MSGEMM_TUNE_PPW overrides the choice (tuning aid).
@@ -732,7 +869,7 @@ int fused_choose_shape(Plan& p, int requested_variant)
     p.row_blocks = (panels + ppw - 1) / ppw;
     p.m_pad = panels * fs.panel_rows;
     const int64_t row_groups = p.row_blocks * p.col_passes;
-    if ((int64_t)p.ktiles * (row_groups + kXcds) > 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
+    if ((int64_t)p.ktiles * (row_groups + kXcds) + panels * p.col_passes > 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
     // the k-tile reduction addresses the partial buffer with 32-bit byte offsets
     if ((int64_t)p.ktiles * p.col_passes * sc.C * p.m_pad * 4 >= 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
     return MSGEMM_OK;
@@ -744,6 +881,13 @@ int launch_repack(const Plan& p, hipStream_t s)
     const int64_t total = (int64_t)p.ktiles * p.m_pad * p.fs.groups;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
+    if (p.scales) {
+        int64_t sblocks = (p.nblocks * p.m_pad + 255) / 256;
+        if (sblocks > 65536) sblocks = 65536;
+        hipLaunchKernelGGL(repack_scales_kernel, dim3((unsigned)sblocks), dim3(256), 0, s, (const __half*)p.scales,
+                           (__half*)p.scales_ordered, p.m, p.m_pad, p.nblocks, p.fs.panel_rows);
+        MSGEMM_HIP_TRY(hipGetLastError());
+    }
 #define MSGEMM_REPACK(GG, LL)                                                                          \
     if (p.fs.groups == GG && p.fs.lane_bytes == LL) {                                                  \
         hipLaunchKernelGGL((repack_kernel<GG, LL>), dim3((unsigned)blocks), dim3(256), 0, s, p.codes, \
@@ -763,9 +907,9 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     FusedArgs a;
     a.tiled = p.codes_tiled;
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy;
-    a.scales = (const __half*)p.scales;
+    a.scales = (const __half*)p.scales_ordered;
     a.partials = p.partials;
-    a.counters = p.counters;
+    a.flags = p.flags;
     a.m = p.m; a.k = p.k; a.b = p.b; a.m_pad = p.m_pad;
     a.b_pad = (int64_t)p.col_passes * p.fs.cols;
     a.ktiles = (int)p.ktiles;
@@ -782,11 +926,18 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     a.nblocks = p.nblocks;
     a.partial_span = (int64_t)p.ktiles * a.b_pad * p.m_pad * 4;
     a.tiles_per_block = p.scale_group > 0 ? (int)(p.scale_group / (2 * p.fs.groups)) : 1;
-    // MSGEMM_TUNE_REDUCE = 1 (second pass) or 2 (last arriver) overrides the default (tuning aid)
-    a.reduce_mode = p.ktiles == 1 ? kReduceDirect : kReduceSecondPass;
+    a.div_ktiles = make_fastdiv((uint32_t)a.ktiles);
+    a.div_col_passes = make_fastdiv((uint32_t)a.col_passes);
+    a.div_tiles_per_block = make_fastdiv((uint32_t)a.tiles_per_block);
+    // Several k-tiles: the single-column kernels reduce inside the launch (a second
+    // launch costs more than the reduction itself), the batched ones in a second
+    // pass.  MSGEMM_TUNE_REDUCE = 1 (second pass) or 2 (in launch) overrides the
+    // choice for the single-column kernels (tuning aid).
+    a.reduce_mode = kReduceDirect;
     if (p.ktiles > 1) {
+        a.reduce_mode = p.fs.cols == 1 ? kReduceInLaunch : kReduceSecondPass;
         const int forced = env_int("MSGEMM_TUNE_REDUCE", 0);
-        if (forced == kReduceSecondPass || forced == kReduceLastArriver) a.reduce_mode = forced;
+        if (p.fs.cols == 1 && (forced == kReduceSecondPass || forced == kReduceInLaunch)) a.reduce_mode = forced;
     }
 
     const int C = p.fs.cols, G = p.fs.groups, LB = p.fs.lane_bytes, EB = p.fs.entry_bytes;

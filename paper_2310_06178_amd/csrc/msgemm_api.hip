@@ -24,8 +24,9 @@ void free_plan(Plan* p)
     if (p->scales) (void)hipFree(p->scales);
     if (p->lut_ws) (void)hipFree(p->lut_ws);
     if (p->codes_tiled) (void)hipFree(p->codes_tiled);
+    if (p->scales_ordered) (void)hipFree(p->scales_ordered);
     if (p->partials) (void)hipFree(p->partials);
-    if (p->counters) (void)hipFree(p->counters);
+    if (p->flags) (void)hipFree(p->flags);
     delete p;
 }
 
@@ -116,16 +117,22 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtyp
         const size_t tiled = (size_t)p->ktiles * (size_t)p->m_pad * (size_t)(p->fs.groups);
         const size_t b_pad = (size_t)p->col_passes * (size_t)p->fs.cols;
         const size_t part = (size_t)p->ktiles * b_pad * (size_t)p->m_pad * 4u;
-        const size_t cnt = (size_t)(p->m_pad / p->fs.panel_rows) * (size_t)p->col_passes * sizeof(unsigned);
+        const size_t cnt = (size_t)(p->m_pad / p->fs.panel_rows) * (size_t)p->col_passes * (size_t)p->ktiles * sizeof(unsigned);
         e = hipMalloc((void**)&p->codes_tiled, tiled);
         if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
         e = hipMalloc((void**)&p->partials, part);
         if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
-        e = hipMalloc((void**)&p->counters, cnt);
+        e = hipMalloc((void**)&p->flags, cnt);
         if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
-        e = hipMemsetAsync(p->counters, 0, cnt, s);
+        e = hipMemsetAsync(p->flags, 0, cnt, s);
         if (e != hipSuccess) return hip_fail(e);
         p->workspace_bytes = tiled + part + cnt;
+        if (p->scales) {
+            const size_t so = (size_t)p->nblocks * (size_t)p->m_pad * 2u;
+            e = hipMalloc((void**)&p->scales_ordered, so);
+            if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
+            p->workspace_bytes += so;
+        }
         rc = msgemm::launch_repack(*p, s);
         if (rc != MSGEMM_OK) return fail(rc);
     }

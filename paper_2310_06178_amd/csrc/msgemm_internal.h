@@ -46,9 +46,11 @@ struct Plan {
     int64_t row_blocks;   // workgroups along m
     int64_t m_pad;        // row_blocks * tile_rows
     int col_passes;       // ceil(b / cols)
+    int cus;              // compute units of the device
+    uint16_t* scales_ordered;  // device fp16 [nblocks][m_pad], rows in the order the lanes own outputs; nullptr without scales
     uint8_t* codes_tiled; // device, [ktiles][m_pad / panel_rows][16][64][lane_bytes]
     float* partials;      // device, [ktiles][b_pad][m_pad] fp32 / int32
-    unsigned* counters;   // device, [row_blocks * col_passes], zero between launches
+    unsigned* flags;      // device, [panels][col_passes][ktiles] arrival flags of the in-launch reduction, zero between launches
     size_t workspace_bytes;
 };
 

@@ -273,8 +273,43 @@ def test_fused_scale_group_not_tileable_falls_back():
     check(out, oracle_y(codes, X, "f16", scales, 32), "f16", "fallback")
 
 
+REDUCE_CASES = [
+    # m, k, b, xd, sg
+    (2049, 1024, 1, "f16", 128),   # 8 k-tiles, 9 panels
+    (300, 8320, 1, "f32", 0),      # 65 k-tiles: more flags per panel than lanes in a wavefront
+    (700, 768, 2, "i8", 0),        # two column passes share the row blocks
+    (4100, 512, 1, "bf16", 256),   # more panels than wavefronts per workgroup, scale block = two k-tiles
+]
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("m,k,b,xd,sg", REDUCE_CASES)
+def test_fused_k_tile_reduction_modes(monkeypatch, m, k, b, xd, sg, mode):
+    """Both ways of adding the k-tile partial sums (1: second launch, 2: trailing
+    workgroups of the same launch) against the oracle, twice on the same plan:
+    the arrival flags of the in-launch reduction must be down again after a launch."""
+    monkeypatch.setenv("MSGEMM_TUNE_REDUCE", str(mode))
+    codes = inputs.make_codes(m, k, seed=m + k)
+    scales = inputs.make_scales(m, k, sg, seed=4) if sg else None
+    dC = torch_io.to_device(codes, "codes")
+    dS = torch_io.to_device(scales, "scales")
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS, B.VARIANT_FUSED_LDS)
+    try:
+        assert B.msgemm_plan_get_info(plan)["split_k"] == -(-(k // 2) // 64)
+        for rep in range(2):
+            X = inputs.make_x(k, b, xd, seed=31 + rep)
+            dX = torch_io.to_device(X, xd)
+            Y = torch_io.empty_output(b, m, Y_OF_X[xd])
+            Y.fill_(-3)
+            B.msgemm_run(plan, dX, k, Y, m)
+            torch.cuda.synchronize()
+            check(torch_io.to_host(Y), oracle_y(codes, X, xd, scales, sg), xd, f"reduce mode {mode} call {rep}")
+    finally:
+        B.msgemm_destroy(plan)
+
+
 def test_fused_repeated_calls_reuse_workspace():
-    """The k-tile counters must be back at zero after every launch."""
+    """Partial sums and arrival flags of one launch must not leak into the next."""
     m, k, b = 1000, 1024, 2
     codes = inputs.make_codes(m, k, seed=8)
     dC = torch_io.to_device(codes, "codes")
