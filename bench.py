@@ -80,6 +80,33 @@ def cpu_baseline(cfg, codes, X, scales, budget_s=12.0):
     }
 
 
+def stream_read_ceiling(B, torch, stream, nbytes, n_copies, steps):
+    """The same timing protocol (HIP graph, rotating cold buffers, events on the
+    launch stream) around a kernel that only reads `nbytes`: what this device
+    gives a single launch that streams that many cold bytes and does nothing else."""
+    unit = 256 * 8 * 1024  # bytes one load of every wavefront covers on a 256-CU device
+    nbytes = max(unit, nbytes // unit * unit)
+    bufs = [torch.randint(0, 255, (nbytes,), dtype=torch.uint8, device="cuda:0") for _ in range(n_copies)]
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
+    for i in range(10):
+        B.msgemm_calib_stream_read(bufs[i % n_copies], nbytes, sink)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        for i in range(steps):
+            B.msgemm_calib_stream_read(bufs[i % n_copies], nbytes, sink)
+    graph.replay()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(stream):
+        ev0.record(stream)
+        graph.replay()
+        ev1.record(stream)
+    torch.cuda.synchronize()
+    us = ev0.elapsed_time(ev1) * 1e3 / steps
+    return {"bytes": nbytes, "us": us, "GB/s": nbytes / (us * 1e-6) / 1e9}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -91,6 +118,8 @@ def main() -> int:
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--d", type=int, default=None)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-ceiling", action="store_true",
+                    help="skip the plain stream-read kernel that measures the practical HBM ceiling")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 64 MiB elementwise copy (untimed): gives hardware-counter runs a kernel of known traffic")
     args = ap.parse_args()
@@ -223,6 +252,11 @@ def main() -> int:
             "kernel_us": kernel_us,
         },
     }
+    if graph is not None and not args.no_ceiling and not args.hot:
+        try:
+            out["roofline"]["stream_read_kernel"] = stream_read_ceiling(B, torch, stream, code_bytes, n_copies, args.steps)
+        except Exception as e:  # a device with another CU count: the figure is optional
+            print(f"bench.py: stream-read ceiling not measured ({e})", file=sys.stderr)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, codes, X, scales)
 

@@ -157,6 +157,17 @@ int msgemm_run(const msgemm_plan_t* plan, const void* X, int64_t ldx,
 int msgemm_dequant_mfma_run(const msgemm_plan_t* plan, const void* X, int64_t ldx,
                             void* Y, int64_t ldy, void* stream);
 
+/*
+ * Measurement aid, not msGeMM: reads `bytes` bytes at `src` (device, 16-byte
+ * aligned, bytes a multiple of 128 KiB) once, with the load shape of the fused
+ * kernel's code stream (128 bits per lane, one workgroup per compute unit) and
+ * nothing else.  Timed like msgemm_run it gives the rate at which this device
+ * delivers a cold stream of that size to a single launch: the practical
+ * ceiling beside the nominal HBM peak.  `sink` (device, >= 4 bytes) is only
+ * written if the data sums to a magic value.
+ */
+int msgemm_calib_stream_read(const void* src, size_t bytes, void* sink, void* stream);
+
 /* Synchronise the device, free everything the plan owns.  NULL is allowed. */
 void msgemm_destroy(msgemm_plan_t* plan);
 

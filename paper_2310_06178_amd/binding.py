@@ -21,7 +21,7 @@ OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, -1, -2, -3, -4
 
 EXPORTS = (
     "msgemm_plan", "msgemm_plan_get_info", "msgemm_lut_bytes", "msgemm_build_lut",
-    "msgemm_consume_lut", "msgemm_run", "msgemm_dequant_mfma_run", "msgemm_destroy",
+    "msgemm_consume_lut", "msgemm_run", "msgemm_dequant_mfma_run", "msgemm_calib_stream_read", "msgemm_destroy",
     "msgemm_status_string", "msgemm_last_hip_error", "msgemm_version",
 )
 
@@ -77,6 +77,8 @@ def load():
     lib.msgemm_run.restype = ci
     lib.msgemm_dequant_mfma_run.argtypes = [vp, vp, i64, vp, i64, vp]
     lib.msgemm_dequant_mfma_run.restype = ci
+    lib.msgemm_calib_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.msgemm_calib_stream_read.restype = ci
     lib.msgemm_destroy.argtypes = [vp]
     lib.msgemm_destroy.restype = None
     lib.msgemm_status_string.argtypes = [ci]
@@ -174,6 +176,12 @@ def msgemm_dequant_mfma_run(plan, X, ldx, Y, ldy, stream=None):
                                         _stream(stream))
     if rc != OK:
         raise MsgemmError(rc, "msgemm_dequant_mfma_run")
+
+
+def msgemm_calib_stream_read(src, nbytes, sink, stream=None):
+    rc = load().msgemm_calib_stream_read(_ptr(src), int(nbytes), _ptr(sink), _stream(stream))
+    if rc != OK:
+        raise MsgemmError(rc, "msgemm_calib_stream_read")
 
 
 def msgemm_destroy(plan) -> None:

@@ -114,12 +114,12 @@ struct FusedArgs {
     int xcd_map;            // 1: workgroups that share outputs get ids congruent modulo kXcds
     int64_t nblocks;        // scale blocks per row
     int64_t partial_span;   // bytes of the partial buffer (< 2^31)
+    int64_t scale_span;     // bytes of the ordered scales (< 2^31)
     int tiles_per_block;    // k-tiles per scale block
     int reduce_mode;        // how partial sums over k-tiles become Y, see ReduceMode
     FastDiv div_ktiles, div_col_passes, div_tiles_per_block;
     int fused_wgs;          // workgroups of the grid that do the fused work; the rest reduce (in-launch mode)
-    int red_waves;          // wavefronts of a reducing workgroup that take a unit
-    int red_units;          // (panel, column pass) pairs to reduce
+    int red_units;          // (panel, column pass) pairs to reduce, one trailing workgroup each
 };
 
 enum ReduceMode {
@@ -263,56 +263,59 @@ __host__ __device__ __forceinline__ int panel_row(int q, int j, int s)
 // bound by the gather, not by launches, and have no registers to spare for it.
 template <int C> constexpr bool kInLaunchReduce = C == 1;
 
-// Reduction over the k-tiles inside the launch.  The workgroups that follow the
-// fused ones in the grid each take a few (panel, column pass) units: a wavefront
-// waits for the flags of its panel's k-tiles, adds their partial sums in k-tile
-// order and writes Y.  Workgroups are dispatched in id order, so everything a
-// reducer waits for is already resident and runs to its flag without waiting
-// on anyone: the wait ends (it is bounded all the same).  The sum order is
-// fixed: results are reproducible.
-template <typename YT, typename AT, int C, int kFinal>
-__device__ __forceinline__ void reduce_in_launch(const FusedArgs& a, int unit, int lane)
+// Reduction over the k-tiles inside the launch.  Each workgroup that follows
+// the fused ones in the grid takes one (panel, column pass) unit.  Its first
+// kRedSplit wavefronts share the k-tiles (wavefront w takes w, w + kRedSplit,
+// ...): each waits for the flags of its k-tiles, adds their partial sums in
+// increasing order and leaves its sum in LDS; wavefront 0 then adds the
+// wavefront sums in wavefront order and writes Y.  The association is fixed:
+// results are reproducible.  Workgroups are dispatched in id order, so everything
+// a reducer waits for is already resident and runs to its flag without waiting
+// on anyone: the wait ends (it is bounded all the same).
+constexpr int kRedSplit = 8;
+
+template <typename YT, typename AT, int kFinal>
+__device__ __forceinline__ void reduce_in_launch(const FusedArgs& a, int unit, int w, int lane, unsigned char* lds)
 {
     constexpr int kPanelRows = kFinal * 64;
     const int panel_g = (int)fast_div((uint32_t)unit, a.div_col_passes);
-    const int cp = unit - panel_g * a.col_passes;
-    const int64_t col0 = (int64_t)cp * C;
-    const int64_t row0 = (int64_t)panel_g * kPanelRows + lane;
-    YT* __restrict__ Y = (YT*)a.Y;
-    unsigned* flags = a.flags + (int64_t)unit * a.ktiles;
-    for (int base = 0; base < a.ktiles; base += 64) {
-        const int idx = base + lane;
-        const bool need = idx < a.ktiles;
-        for (unsigned spins = 0; spins < kMaxFlagPolls; ++spins) {
-            asm volatile("" ::: "memory");
-            const unsigned f = need ? __hip_atomic_load(flags + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1u;
-            if (__builtin_amdgcn_ballot_w64(f != 1u) == 0) break;
-            __builtin_amdgcn_s_sleep(2);
+    const int col = unit - panel_g * a.col_passes;  // single-column kernels: a column pass is a column
+    AT sum[kFinal];
+#pragma unroll
+    for (int i = 0; i < kFinal; ++i) sum[i] = 0;
+    AT* wave_sums = (AT*)lds;  // [kRedSplit][64][kFinal]
+    if (w < kRedSplit) {
+        const int mine = w < a.ktiles ? (a.ktiles - w + kRedSplit - 1) / kRedSplit : 0;  // k-tiles of this wavefront
+        unsigned* flags = a.flags + (int64_t)unit * a.ktiles;
+        for (int base = 0; base < mine; base += 64) {
+            const int idx = base + lane;
+            const bool need = idx < mine;
+            unsigned* flag = flags + w + (int64_t)idx * kRedSplit;
+            for (unsigned spins = 0; spins < kMaxFlagPolls; ++spins) {
+                asm volatile("" ::: "memory");
+                const unsigned f = need ? __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1u;
+                if (__builtin_amdgcn_ballot_w64(f != 1u) == 0) break;
+                __builtin_amdgcn_s_sleep(2);
+            }
+            // lowered again for the next launch (kernel boundaries order launches)
+            if (need) __hip_atomic_store(flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        // lowered again for the next launch (kernel boundaries order launches)
-        if (need) __hip_atomic_store(flags + idx, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    asm volatile("" ::: "memory");
-    MSGEMM_TRACE(7);
-    __amdgpu_buffer_rsrc_t part_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void*)a.partials, 0, (int)a.partial_span, 0x00020000);
-    const uint32_t col_stride = (uint32_t)(a.m_pad * 4);
-    const uint32_t tile_stride = (uint32_t)(a.b_pad * a.m_pad * 4);
-    const uint32_t part_off = (uint32_t)col0 * col_stride + (uint32_t)(panel_g * kPanelRows + lane * kFinal) * 4u;
-#pragma unroll
-    for (int c = 0; c < C; ++c) {
-        AT sum[kFinal];
-#pragma unroll
-        for (int i = 0; i < kFinal; ++i) sum[i] = 0;
-        const uint32_t off0 = part_off + (uint32_t)c * col_stride;
+        asm volatile("" ::: "memory");
+        MSGEMM_TRACE(7);
+        __amdgpu_buffer_rsrc_t part_rsrc =
+            __builtin_amdgcn_make_buffer_rsrc((void*)a.partials, 0, (int)a.partial_span, 0x00020000);
+        const uint32_t col_stride = (uint32_t)(a.m_pad * 4);
+        const uint32_t tile_stride = (uint32_t)(a.b_pad * a.m_pad * 4);
+        const uint32_t off0 = (uint32_t)col * col_stride + (uint32_t)(panel_g * kPanelRows + lane * kFinal) * 4u;
         // kBatch k-tiles' partials are requested together, then added in order;
         // k-tiles past the end get an out-of-range offset, which reads as zero
-        constexpr int kBatch = kFinal <= 4 ? 32 : 8;
-        for (int t0 = 0; t0 < a.ktiles; t0 += kBatch) {
+        constexpr int kBatch = 8;
+        for (int t0 = 0; t0 < mine; t0 += kBatch) {
             unsigned v[kBatch][kFinal];
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
-                const uint32_t off = (t0 + u < a.ktiles) ? off0 + (uint32_t)(t0 + u) * tile_stride : 0x7ffffff0u;
+                const uint32_t off =
+                    (t0 + u < mine) ? off0 + (uint32_t)(w + (t0 + u) * kRedSplit) * tile_stride : 0x7ffffff0u;
                 load_partials<kFinal, kAuxSc1>(part_rsrc, off, v[u]);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -326,10 +329,20 @@ __device__ __forceinline__ void reduce_in_launch(const FusedArgs& a, int unit, i
                 }
         }
 #pragma unroll
-        for (int i = 0; i < kFinal; ++i) {
-            const int64_t row = row0 + 64 * i;
-            if (row < a.m && col0 + c < a.b) Y[(col0 + c) * a.ldy + row] = to_output<YT, AT>(sum[i]);
-        }
+        for (int i = 0; i < kFinal; ++i) wave_sums[(w * 64 + lane) * kFinal + i] = sum[i];
+    }
+    __syncthreads();  // every wavefront of the workgroup gets here
+    if (w != 0) return;
+#pragma unroll
+    for (int j = 1; j < kRedSplit; ++j)
+#pragma unroll
+        for (int i = 0; i < kFinal; ++i) sum[i] += wave_sums[(j * 64 + lane) * kFinal + i];
+    YT* __restrict__ Y = (YT*)a.Y;
+    const int64_t row0 = (int64_t)panel_g * kPanelRows + lane;
+#pragma unroll
+    for (int i = 0; i < kFinal; ++i) {
+        const int64_t row = row0 + 64 * i;
+        if (row < a.m && col < a.b) Y[(int64_t)col * a.ldy + row] = to_output<YT, AT>(sum[i]);
     }
     MSGEMM_TRACE(8);
 }
@@ -394,11 +407,8 @@ fused_kernel(FusedArgs a)
 
     // ---- which k-tile / row block / column pass
     if ((int)blockIdx.x >= a.fused_wgs) {  // trailing workgroups: the k-tile reduction (in-launch mode only)
-        if constexpr (kInLaunchReduce<C>) {
-            const int w = tid >> 6;
-            const int unit = ((int)blockIdx.x - a.fused_wgs) * a.red_waves + w;
-            if (w < a.red_waves && unit < a.red_units) reduce_in_launch<YT, AT, C, kFinal>(a, unit, lane);
-        }
+        if constexpr (kInLaunchReduce<C>)
+            reduce_in_launch<YT, AT, kFinal>(a, (int)blockIdx.x - a.fused_wgs, tid >> 6, lane, lds);
         return;
     }
     int kt, rg;
@@ -511,6 +521,8 @@ fused_kernel(FusedArgs a)
     const uint32_t class_base = (uint32_t)(16 * qg) * kEntryBytes;
     __amdgpu_buffer_rsrc_t part_rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void*)a.partials, 0, (int)a.partial_span, 0x00020000);
+    __amdgpu_buffer_rsrc_t scale_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(a.scales ? (const void*)a.scales : (const void*)a.tiled), 0, a.scales ? (int)a.scale_span : 0, 0x00020000);
     const uint32_t col_stride = (uint32_t)(a.m_pad * 4);            // bytes between columns of the partials
     const uint32_t tile_stride = (uint32_t)(a.b_pad * a.m_pad * 4); // bytes between k-tiles
 
@@ -520,16 +532,24 @@ fused_kernel(FusedArgs a)
 
         // scales of this k-tile's block for the rows this lane will own after the fold
         // (one contiguous load per wavefront: the plan keeps them in the order of the
-        // outputs).  The load is unconditional -- without scales it reads the first
-        // code bytes instead -- and its value is first looked at after the gather, so
-        // no wait for it sits in front of the code stream.
+        // outputs).  In the single-column kernels the load is an unconditional,
+        // bounds-checked buffer load -- without scales the buffer is empty and it
+        // returns at once, without a memory access -- and its value is first looked
+        // at after the gather, so no wait for it sits in front of the code stream.
         struct alignas(2 * kFinal) PackedScales { __half h[kFinal]; };
         PackedScales qraw;
         if constexpr (__is_same(AT, float)) {
-            const PackedScales* qp = (const PackedScales*)(a.scales + ((int64_t)scale_block * a.m_pad +
-                                                                      (int64_t)panel_g * kPanelRows + lane * kFinal));
+            const int64_t qat = (int64_t)scale_block * a.m_pad + (int64_t)panel_g * kPanelRows + lane * kFinal;
+            const PackedScales* qp = (const PackedScales*)(a.scales + qat);
             if constexpr (C == 1) {
-                qraw = *(a.scales ? qp : (const PackedScales*)a.tiled);
+                static_assert(kFinal == 2 || kFinal == 4, "scales of a lane fit one 4- or 8-byte load");
+                if constexpr (kFinal == 4) {
+                    const v2u q = __builtin_amdgcn_raw_buffer_load_b64(scale_rsrc, (int)(qat * 2), 0, 0);
+                    __builtin_memcpy(&qraw, &q, sizeof(qraw));
+                } else {
+                    const unsigned q = __builtin_amdgcn_raw_buffer_load_b32(scale_rsrc, (int)(qat * 2), 0, 0);
+                    __builtin_memcpy(&qraw, &q, sizeof(qraw));
+                }
             } else {
                 // (the batched kernels have no registers to spare: a conditional load, waited for at once)
 #pragma unroll
@@ -811,14 +831,9 @@ int launch_one(const Plan& p, FusedArgs& a, hipStream_t s)
     constexpr int kFinal = LB / (G / 16);
     auto kern = fused_kernel<XT, YT, ET, C, G, LB, kWaves>;
     a.fused_wgs = a.xcd_map ? (int)(p.ktiles * kXcds * ((a.row_groups + kXcds - 1) / kXcds)) : (int)(p.ktiles * a.row_groups);
-    // reducing workgroups: one unit per wavefront, and no more wavefronts per
-    // workgroup than it takes to give every compute unit one workgroup -- a unit's
-    // loads are latency-bound, a compute unit serves few of them at a time
     a.red_units = a.panels_total * a.col_passes;
-    a.red_waves = (a.red_units + p.cus - 1) / p.cus;
-    if (a.red_waves > kWaves) a.red_waves = kWaves;
     int64_t grid = a.fused_wgs;
-    if (a.reduce_mode == kReduceInLaunch) grid += (a.red_units + a.red_waves - 1) / a.red_waves;
+    if (a.reduce_mode == kReduceInLaunch) grid += a.red_units;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3((kWaves + dedicated_builders<C, kWaves>()) * 64), 0, s, a);
     MSGEMM_HIP_TRY(hipGetLastError());
     if (a.reduce_mode == kReduceSecondPass) {
@@ -925,6 +940,7 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     a.xcd_map = (a.row_groups >= kXcds && env_int("MSGEMM_TUNE_XCD_MAP", 1)) ? 1 : 0;
     a.nblocks = p.nblocks;
     a.partial_span = (int64_t)p.ktiles * a.b_pad * p.m_pad * 4;
+    a.scale_span = p.nblocks * p.m_pad * 2;  // nblocks <= ktiles: within the bound checked for the partials
     a.tiles_per_block = p.scale_group > 0 ? (int)(p.scale_group / (2 * p.fs.groups)) : 1;
     a.div_ktiles = make_fastdiv((uint32_t)a.ktiles);
     a.div_col_passes = make_fastdiv((uint32_t)a.col_passes);

@@ -201,6 +201,12 @@ int msgemm_dequant_mfma_run(const msgemm_plan_t* plan, const void* X, int64_t ld
     return msgemm::launch_dequant_mfma(p, X, ldx, Y, ldy, (hipStream_t)stream);
 }
 
+int msgemm_calib_stream_read(const void* src, size_t bytes, void* sink, void* stream)
+{
+    if (!src || !sink || ((uintptr_t)src & 15)) return MSGEMM_ERR_INVALID_ARG;
+    return msgemm::launch_calib_stream_read(src, bytes, sink, (hipStream_t)stream);
+}
+
 void msgemm_destroy(msgemm_plan_t* plan)
 {
     if (!plan) return;

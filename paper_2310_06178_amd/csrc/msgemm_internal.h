@@ -74,6 +74,9 @@ int fused_choose_shape(Plan& p, int requested_variant);  // fills p.fs, ktiles, 
 int launch_repack(const Plan& p, hipStream_t s);
 int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s);
 
+// calibration.hip
+int launch_calib_stream_read(const void* src, size_t bytes, void* sink, hipStream_t s);
+
 // kernels_mfma.hip
 int launch_dequant_mfma(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s);
 

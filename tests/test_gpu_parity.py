@@ -400,3 +400,20 @@ def test_dequant_mfma_unsupported_dtypes():
         assert e.value.status == B.ERR_UNSUPPORTED
     finally:
         B.msgemm_destroy(plan)
+
+
+def test_calibration_stream_read_entry_point():
+    """The measurement aid accepts whole multiples of its launch footprint only and leaves the sink alone."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    unit = cus * 8 * 1024
+    buf = torch.zeros(3 * unit, dtype=torch.uint8, device="cuda:0")
+    sink = torch.full((4,), 7, dtype=torch.int32, device="cuda:0")
+    B.msgemm_calib_stream_read(buf, 3 * unit, sink)
+    B.msgemm_calib_stream_read(buf, unit, sink)
+    torch.cuda.synchronize()
+    assert sink.cpu().tolist() == [7, 7, 7, 7]
+    for bad in (0, unit - 1024, unit + 16):
+        with pytest.raises(B.MsgemmError):
+            B.msgemm_calib_stream_read(buf, bad, sink)
+    with pytest.raises(B.MsgemmError):
+        B.msgemm_calib_stream_read(buf.data_ptr() + 4, unit, sink)
