@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same
 # counter reads for a 64 MiB elementwise kernel in the same run.
 # Source: profiles/fused_kernel_cfg2_hbm_traffic.txt
-MEASURED_TRAFFIC_BYTES = {"cfg2": 35866789}
+MEASURED_TRAFFIC_BYTES = {"cfg2": 38158911}
 
 
 def algorithmic_bytes(cfg) -> int:
@@ -118,6 +118,8 @@ def main() -> int:
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--d", type=int, default=None)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--mfma", action="store_true",
+                    help="time the dequantise + MFMA comparison kernel instead of the msGeMM path (labelled as such)")
     ap.add_argument("--no-ceiling", action="store_true",
                     help="skip the plain stream-read kernel that measures the practical HBM ceiling")
     ap.add_argument("--calib-copy", action="store_true",
@@ -162,8 +164,10 @@ def main() -> int:
     info = B.msgemm_plan_get_info(plans[0])
     Y = torch_io.empty_output(b, m, cfg["y"])
 
+    run = B.msgemm_dequant_mfma_run if args.mfma else B.msgemm_run
+
     def step(i):
-        B.msgemm_run(plans[i % n_copies], dX, k, Y, m)
+        run(plans[i % n_copies], dX, k, Y, m)
 
     for i in range(max(args.warmup, 1)):
         step(i)
@@ -218,7 +222,8 @@ def main() -> int:
     tops = 2.0 * m * k * b / (wall / args.steps) / 1e12
 
     out = {
-        "metric": "effective TOPS (2mkb/t), int4-weight LUT GeMM (msGeMM)",
+        "metric": "effective TOPS (2mkb/t), int4-weight LUT GeMM (msGeMM)" if not args.mfma
+                  else "effective TOPS (2mkb/t), int4 dequantise + MFMA comparison kernel (not msGeMM)",
         "value": tops,
         "unit": "TOPS",
         "n_gpus": 1,
@@ -233,7 +238,8 @@ def main() -> int:
         "config": {
             "workload": f"{args.config}: m={m} k={k} b={b} int4 W, {cfg['x']} X, {cfg['y']} Y, "
                         f"scale_group={cfg['scale_group']}, d={info['d']}",
-            "variant": {1: "global_lut", 2: "fused_lds", 3: "fused_lds16"}[info["variant"]],
+            "variant": "dequant_mfma_comparison" if args.mfma else
+                       {1: "global_lut", 2: "fused_lds", 3: "fused_lds16"}[info["variant"]],
             "tile_rows": info["tile_rows"], "tile_groups": info["tile_groups"],
             "split_k": info["split_k"], "col_chunk": info["col_chunk"],
             "weight_copies_rotated": n_copies,

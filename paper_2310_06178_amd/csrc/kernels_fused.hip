@@ -283,7 +283,7 @@ __device__ __forceinline__ void reduce_in_launch(const FusedArgs& a, int unit, i
     AT sum[kFinal];
 #pragma unroll
     for (int i = 0; i < kFinal; ++i) sum[i] = 0;
-    AT* wave_sums = (AT*)lds;  // [kRedSplit][64][kFinal]
+    AT* wave_sums = (AT*)lds;  // [kRedSplit][kFinal][64]: consecutive lanes, consecutive banks
     if (w < kRedSplit) {
         const int mine = w < a.ktiles ? (a.ktiles - w + kRedSplit - 1) / kRedSplit : 0;  // k-tiles of this wavefront
         unsigned* flags = a.flags + (int64_t)unit * a.ktiles;
@@ -329,14 +329,14 @@ __device__ __forceinline__ void reduce_in_launch(const FusedArgs& a, int unit, i
                 }
         }
 #pragma unroll
-        for (int i = 0; i < kFinal; ++i) wave_sums[(w * 64 + lane) * kFinal + i] = sum[i];
+        for (int i = 0; i < kFinal; ++i) wave_sums[(w * kFinal + i) * 64 + lane] = sum[i];
     }
     __syncthreads();  // every wavefront of the workgroup gets here
     if (w != 0) return;
 #pragma unroll
     for (int j = 1; j < kRedSplit; ++j)
 #pragma unroll
-        for (int i = 0; i < kFinal; ++i) sum[i] += wave_sums[(j * 64 + lane) * kFinal + i];
+        for (int i = 0; i < kFinal; ++i) sum[i] += wave_sums[(j * kFinal + i) * 64 + lane];
     YT* __restrict__ Y = (YT*)a.Y;
     const int64_t row0 = (int64_t)panel_g * kPanelRows + lane;
 #pragma unroll
