@@ -1,0 +1,426 @@
+// Fused msGeMM for batches (b > 2, d = 2) on gfx950: tables of 8 batch columns
+// per entry in LDS, the table-adds of phase 2 done by the matrix cores.
+//
+// Work decomposition
+//   A k-tile is 32 table groups (64 k-columns); its table -- 256 entries per
+//   group, 8 fp16 batch columns (16 bytes) per entry, 128 KiB -- is built in LDS
+//   by the workgroup that consumes it (Section 4: the table is produced
+//   piecewise along its last dimension and consumed at once).  A workgroup owns
+//   up to 8 row panels of 256 rows (one per wavefront), one pass of 8 batch
+//   columns and a *segment* of consecutive k-tiles: it rebuilds the table for
+//   every k-tile of the segment and keeps the outputs in registers across
+//   them, so one partial sum per segment -- not per k-tile -- leaves the
+//   workgroup.  Segments are as long as the problem allows while every
+//   compute unit still gets a workgroup.
+//
+// Phase 2 on the matrix cores
+//   A look-up returns the 8 columns of one row as two 4 x fp16 operands.
+//   v_mfma_f32_4x4x4_16B_f16 computes, for each group of four lanes,
+//   D[i][j] += sum_k A[i][k] B[k][j] with lane (quad, i) supplying row i of A
+//   and lane (quad, j) column j of B and receiving column j of D.  With B the
+//   identity this is D[i][j] += A[i][j]: the instruction adds a fp16 entry to
+//   an fp32 accumulator, four columns at a time, without using the vector ALU
+//   -- which is what bounds a gather that adds with v_pk_add_f16 / v_fma_mix.
+//   The accumulators come out transposed within each quad of lanes: lane
+//   (quad, j), register i holds column j of the row that lane (quad, i) looked
+//   up.  Everything downstream (block scales, fold, stores) works on that
+//   layout directly.  Accumulation is in fp32 throughout; int8 activations use
+//   the same path (their table entries, |entry| <= 2048, are exact in fp16 and
+//   every sum stays below 2^24, so the fp32 sums are exact integers).
+//
+// Shared scales (Section 3.3) are applied when a scale block of k-columns has
+// been consumed: y += q(row, block) * (sum over the block's tables).
+#include "device_types.h"
+#include "fused_common.h"
+#include "msgemm_internal.h"
+
+namespace msgemm {
+namespace {
+
+constexpr int kBC = 8;                   // batch columns per table entry and per pass
+constexpr int kBG = 32;                  // table groups per k-tile
+// LB = rows (code bytes) a lane takes per load: 8 (8 wavefronts of 256-row panels)
+// or 4 (16 wavefronts of 128-row panels: half the registers per wavefront, twice
+// the wavefronts to hide the LDS latency behind).  A workgroup covers 2048 rows either way.
+template <int LB> constexpr int batched_waves() { return 64 / LB; }
+constexpr int kBCodeStride = kBG * 16;   // bytes between the entries of consecutive codes
+constexpr int kBRing = 8;                // code loads a wavefront keeps in flight
+static_assert(kLoadsPerPanel % kBRing == 0, "ring slots are reused with a period dividing the panel");
+
+template <int LB> struct LaneLoad;
+template <> struct LaneLoad<8> { using type = uint2; };
+template <> struct LaneLoad<4> { using type = uint32_t; };
+template <int LB> __device__ __forceinline__ uint32_t load_word(const typename LaneLoad<LB>::type& v, int w)
+{
+    if constexpr (LB == 8) return w == 0 ? v.x : v.y;
+    else return v;
+}
+
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+struct BatchedArgs {
+    const uint8_t* tiled;    // codes in streaming order [load][k-tile][panel][lane][8]
+    const void* X;
+    int64_t ldx;
+    void* Y;
+    int64_t ldy;
+    const __half* scales;    // [block][panel][lane][LB]: scale of the row behind each of a lane's look-ups; or nullptr
+    float* partials;         // [segment][column][panel][lane][LB / 2]
+    int64_t m, k, b, m_pad, b_pad;
+    int ktiles, panels_total, panels_per_wg, row_blocks, col_passes;
+    int segments;            // k-segments (partial sums per output)
+    int tiles_per_segment;
+    int tiles_per_block;     // k-tiles per scale block
+    int units;               // segments * row_blocks
+    int direct;              // 1: a single segment, the kernel writes Y itself
+    int64_t partial_span;    // bytes of the partial buffer (< 2^31)
+    FastDiv div_col_passes, div_segments, div_tiles_per_block;
+};
+
+template <typename XT> __device__ __forceinline__ _Float16 to_half(XT v);
+template <> __device__ __forceinline__ _Float16 to_half<__half>(__half v) { return (_Float16)__half2float(v); }
+template <> __device__ __forceinline__ _Float16 to_half<bf16_t>(bf16_t v) { return (_Float16)XTraits<bf16_t>::load(&v); }
+template <> __device__ __forceinline__ _Float16 to_half<int8_t>(int8_t v) { return (_Float16)(float)v; }
+
+// all of this wavefront's LDS traffic has landed / returned, then the workgroup meets.
+// (Not __syncthreads(): its fence would also wait for the code loads in flight.)
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// value of `v` in lane i of the caller's quad
+template <int I> __device__ __forceinline__ float quad_broadcast(float v)
+{
+    return __uint_as_float((unsigned)__builtin_amdgcn_mov_dpp((int)__float_as_uint(v), I * 0x55, 0xf, 0xf, true));
+}
+
+template <typename XT, typename YT, typename AT, bool kScaled, int kBLB>
+__global__ void __launch_bounds__(batched_waves<kBLB>() * 64)
+batched_kernel(BatchedArgs a)
+{
+    constexpr int kBWaves = batched_waves<kBLB>();  // wavefronts per workgroup, one row panel each
+    constexpr int kBPanelRows = 32 * kBLB;          // 64 lanes x LB rows / 2 lanes per row
+    constexpr int kBFinal = kBLB / 2;               // rows a lane owns after the fold
+    constexpr int kThreads = kBWaves * 64;
+    using LoadT = typename LaneLoad<kBLB>::type;
+    __shared__ __align__(16) unsigned char lds[256 * kBCodeStride];  // entry (code, g) at (code * 32 + g) * 16
+    __shared__ __align__(16) _Float16 xs[2][2 * kBG][kBC];            // activations of a k-tile: [k-column][batch column]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int q = lane >> 4, j = lane & 15, qg = q & 1;
+
+    // ---- block id -> (k-segment, row block, column pass).  The column passes of a
+    // unit (same codes) get ids that are congruent modulo the XCD count and close
+    // together: they run on one XCD around the same time and share its L2.
+    const uint32_t bid = blockIdx.x;
+    const uint32_t n = bid / kXcds;
+    const uint32_t hi = fast_div(n, a.div_col_passes);
+    const int cp = (int)(n - hi * (uint32_t)a.col_passes);
+    const int unit = (int)((bid % kXcds) + kXcds * hi);
+    if (unit >= a.units) return;
+    const int rb = (int)fast_div((uint32_t)unit, a.div_segments);
+    const int seg = unit - rb * a.segments;
+    const int kt_begin = seg * a.tiles_per_segment;
+    const int kt_end = min(kt_begin + a.tiles_per_segment, a.ktiles);
+    const int64_t col0 = (int64_t)cp * kBC;
+    const int panel = rb * a.panels_per_wg + wave;
+    const bool active = wave < a.panels_per_wg && panel < a.panels_total;
+
+    const XT* __restrict__ X = (const XT*)a.X;
+
+    // ---- activations of a k-tile: thread (c, kc) of the first 512 fetches X(64 kt + kc, col0 + c)
+    const int xc = (tid >> 6) & (kBC - 1), xkc = tid & 63;
+    auto x_fetch = [&](int kt) -> XT {
+        const int64_t kk = (int64_t)kt * (2 * kBG) + xkc;
+        const bool live = (col0 + xc < a.b) && (kk < a.k);
+        return X[live ? (col0 + xc) * a.ldx + kk : 0];  // (a clamped, always valid address; masked below)
+    };
+    auto x_store = [&](int buf, int kt, XT raw) {
+        const int64_t kk = (int64_t)kt * (2 * kBG) + xkc;
+        const bool live = (col0 + xc < a.b) && (kk < a.k);
+        if (tid < 2 * kBG * kBC) xs[buf][xkc][xc] = live ? to_half<XT>(raw) : (_Float16)0.0f;
+    };
+
+    // ---- phase 1: L(c0 | c1 << 4, g, c) = b(c0) X(2g, c) + b(c1) X(2g + 1, c), in packed fp16
+    // thread (g, c1, part) writes 16 / parts entries of its c1 for group g
+    constexpr int kBuildParts = kThreads / (kBG * 16);
+    constexpr int kBuildEach = 16 / kBuildParts;
+    auto build_tables = [&](int buf) {
+        const int g = tid & (kBG - 1), c1 = (tid >> 5) & 15, part = tid >> 9;
+        h2 x0[4], x1[4], top[4];
+        __builtin_memcpy(x0, &xs[buf][2 * g][0], 16);
+        __builtin_memcpy(x1, &xs[buf][2 * g + 1][0], 16);
+        const _Float16 w1 = (_Float16)(float)decode4((unsigned)c1);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) top[p] = x1[p] * h2{w1, w1};
+        unsigned char* dst = lds + (size_t)(c1 * 16) * kBCodeStride + g * 16;
+#pragma unroll
+        for (int cc = 0; cc < kBuildEach; ++cc) {
+            const int c0 = part * kBuildEach + cc;
+            const _Float16 w0 = (_Float16)(float)decode4((unsigned)c0);
+            h2 e[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) e[p] = __builtin_elementwise_fma(h2{w0, w0}, x0[p], top[p]);
+            __builtin_memcpy(dst + c0 * kBCodeStride, e, 16);
+        }
+    };
+
+    // ---- the code stream of this wavefront: load t of k-tile kt
+    const LoadT* __restrict__ tiled = (const LoadT*)a.tiled;
+    auto code_at = [&](int kt, int t) -> const LoadT* {
+        return tiled + (((int64_t)t * a.ktiles + kt) * a.panels_total + panel) * 64 + lane;
+    };
+    LoadT ring[kBRing];
+
+    XT xraw = x_fetch(kt_begin);
+    if (active) {
+#pragma unroll
+        for (int u = 0; u < kBRing; ++u) {
+            ring[u] = *code_at(kt_begin, u);
+            __builtin_amdgcn_sched_barrier(0);  // loads return in issue order: keep slot 0 first
+        }
+    }
+    x_store(0, kt_begin, xraw);
+    lds_barrier();
+    build_tables(0);
+    lds_barrier();
+
+    h4 onehot;  // column (lane % 4) of the 4 x 4 identity
+#pragma unroll
+    for (int e = 0; e < 4; ++e) onehot[e] = (_Float16)((lane & 3) == e ? 1.0f : 0.0f);
+    f4 dlo[kBLB], dhi[kBLB];  // sums of the current scale block (of everything, without scales)
+    f4 ylo[kScaled ? kBLB : 1], yhi[kScaled ? kBLB : 1];
+#pragma unroll
+    for (int s = 0; s < kBLB; ++s) {
+        dlo[s] = f4{0, 0, 0, 0};
+        dhi[s] = f4{0, 0, 0, 0};
+        if constexpr (kScaled) {
+            ylo[s] = f4{0, 0, 0, 0};
+            yhi[s] = f4{0, 0, 0, 0};
+        }
+    }
+
+    for (int kt = kt_begin; kt < kt_end; ++kt) {
+        const bool more = kt + 1 < kt_end;
+        if (more) xraw = x_fetch(kt + 1);
+        if (active) {
+            // scales of the rows behind this lane's 8 look-ups, for the block this k-tile belongs to
+            struct alignas(2 * kBLB) LaneScales { __half h[kBLB]; };
+            LaneScales qraw;
+            if constexpr (kScaled) {
+                const int blk = (int)fast_div((uint32_t)kt, a.div_tiles_per_block);
+                qraw = *(const LaneScales*)(a.scales + (((int64_t)blk * a.panels_total + panel) * 64 + lane) * kBLB);
+            }
+            const int kt_next = more ? kt + 1 : kt;  // (the last tile re-requests its own tail: harmless, and branch-free)
+#pragma unroll
+            for (int t = 0; t < kLoadsPerPanel; ++t) {
+                const uint32_t lane_off = (uint32_t)(16 * qg + ((j + t) & 15)) * 16u;
+                const LoadT d = ring[t % kBRing];
+#pragma unroll
+                for (int s = 0; s < kBLB; ++s) {
+                    const uint32_t w = load_word<kBLB>(d, s >> 2);
+                    const uint32_t code = (w >> (8 * (s & 3))) & 0xffu;
+                    const uint4 e = *(const uint4*)(lds + code * kBCodeStride + lane_off);
+                    h4 lo, up;
+                    __builtin_memcpy(&lo, &e.x, 8);
+                    __builtin_memcpy(&up, &e.z, 8);
+                    dlo[s] = __builtin_amdgcn_mfma_f32_4x4x4f16(lo, onehot, dlo[s], 0, 0, 0);
+                    dhi[s] = __builtin_amdgcn_mfma_f32_4x4x4f16(up, onehot, dhi[s], 0, 0, 0);
+                }
+                // the slot's bytes are now addresses: refill it with the load kBRing ahead
+                ring[t % kBRing] = (t + kBRing < kLoadsPerPanel) ? *code_at(kt, t + kBRing)
+                                                                   : *code_at(kt_next, t + kBRing - kLoadsPerPanel);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (kScaled) {
+                // a scale block ends with this k-tile: y += q(row) * block sum (Section 3.3).
+                // Register i of the accumulators belongs to the row of quad lane i.
+                const int blk = (int)fast_div((uint32_t)kt, a.div_tiles_per_block);
+                if (kt + 1 == kt_end || (kt + 1) == (blk + 1) * a.tiles_per_block) {
+#pragma unroll
+                    for (int s = 0; s < kBLB; ++s) {
+                        const float qf = __half2float(qraw.h[s]);
+                        const float q0 = quad_broadcast<0>(qf), q1 = quad_broadcast<1>(qf);
+                        const float q2 = quad_broadcast<2>(qf), q3 = quad_broadcast<3>(qf);
+                        ylo[s][0] = fmaf(q0, dlo[s][0], ylo[s][0]); yhi[s][0] = fmaf(q0, dhi[s][0], yhi[s][0]);
+                        ylo[s][1] = fmaf(q1, dlo[s][1], ylo[s][1]); yhi[s][1] = fmaf(q1, dhi[s][1], yhi[s][1]);
+                        ylo[s][2] = fmaf(q2, dlo[s][2], ylo[s][2]); yhi[s][2] = fmaf(q2, dhi[s][2], yhi[s][2]);
+                        ylo[s][3] = fmaf(q3, dlo[s][3], ylo[s][3]); yhi[s][3] = fmaf(q3, dhi[s][3], yhi[s][3]);
+                        dlo[s] = f4{0, 0, 0, 0};
+                        dhi[s] = f4{0, 0, 0, 0};
+                    }
+                }
+            }
+        }
+        if (more) {
+            const int buf = (kt + 1 - kt_begin) & 1;
+            x_store(buf, kt + 1, xraw);
+            lds_barrier();  // every wavefront is done with the old tables; the new activations are in place
+            build_tables(buf);
+            lds_barrier();
+        }
+    }
+    if (!active) return;
+
+    // ---- lanes 16 apart looked up the same rows (in different groups): fold them.
+    // Afterwards lane (quad b, j'), register (s, i) holds row 64 s + 4 b + i of the
+    // panel, column 4 h + j' of the pass.
+    const int quad = lane >> 2, jq = lane & 3;
+    YT* __restrict__ Y = (YT*)a.Y;
+    __amdgpu_buffer_rsrc_t part_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)a.partials, 0, (int)a.partial_span, 0x00020000);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int64_t col = col0 + 4 * h + jq;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float fin[kBFinal];
+#pragma unroll
+            for (int s = 0; s < kBFinal; ++s) {
+                float lo_s, hi_s;
+                if constexpr (kScaled) {
+                    lo_s = h ? yhi[s][i] : ylo[s][i];
+                    hi_s = h ? yhi[s + kBFinal][i] : ylo[s + kBFinal][i];
+                } else {
+                    lo_s = h ? dhi[s][i] : dlo[s][i];
+                    hi_s = h ? dhi[s + kBFinal][i] : dlo[s + kBFinal][i];
+                }
+                fin[s] = fold16(lo_s, hi_s);
+            }
+            const int owner = 4 * quad + i;  // the lane whose look-ups these sums come from
+            if (a.direct) {
+#pragma unroll
+                for (int s = 0; s < kBFinal; ++s) {
+                    const int64_t row = (int64_t)panel * kBPanelRows + 64 * s + owner;
+                    if (row < a.m && col < a.b) {
+                        if constexpr (__is_same(AT, int)) Y[col * a.ldy + row] = (YT)__float2int_rn(fin[s]);
+                        else Y[col * a.ldy + row] = to_output<YT, float>(fin[s]);
+                    }
+                }
+            } else {
+                unsigned out[kBFinal];
+#pragma unroll
+                for (int s = 0; s < kBFinal; ++s) {
+                    if constexpr (__is_same(AT, int)) out[s] = (unsigned)__float2int_rn(fin[s]);
+                    else out[s] = __float_as_uint(fin[s]);
+                }
+                const uint32_t off =
+                    (uint32_t)((((int64_t)seg * a.b_pad + col) * a.m_pad + (int64_t)panel * kBPanelRows + owner * kBFinal) * 4);
+                store_partials<kBFinal, 0>(part_rsrc, off, out);
+            }
+        }
+    }
+}
+
+// One-off reorder of the block scales ([m][nblocks]) for the batched kernel:
+// [block][panel][lane][s] = scale of the row behind look-up s of that lane.
+template <int kBLB>
+__global__ void __launch_bounds__(256)
+repack_scales_batched_kernel(const __half* __restrict__ scales, __half* __restrict__ ordered, int64_t m,
+                             int64_t nblocks, int64_t panels)
+{
+    constexpr int kBPanelRows = 32 * kBLB;
+    const int64_t total = nblocks * panels * 64 * kBLB;
+    for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < total;
+         o += (int64_t)gridDim.x * blockDim.x) {
+        int64_t r = o;
+        const int s = (int)(r % kBLB); r /= kBLB;
+        const int lane = (int)(r % 64); r /= 64;
+        const int64_t panel = r % panels;
+        const int64_t blk = r / panels;
+        const int64_t row = panel * kBPanelRows + panel_row<2, kBLB>(lane >> 4, lane & 15, s);
+        ordered[o] = row < m ? scales[row * nblocks + blk] : __float2half(1.0f);
+    }
+}
+
+}  // namespace
+
+// Segment length: the longest (a multiple of the scale block) that still gives
+// every compute unit a workgroup, preferring grids that fill whole rounds.
+void batched_choose_segments(Plan& p)
+{
+    const int tpb = p.scale_group > 0 ? (int)(p.scale_group / (2 * kBG)) : 1;
+    const int64_t blocks = (p.ktiles + tpb - 1) / tpb;  // indivisible runs of k-tiles
+    const int64_t units_per_seg = p.row_blocks * p.col_passes;
+    int64_t best_s = blocks;
+    double best_eff = -1.0;
+    for (int64_t per = blocks; per >= 1; --per) {  // scale blocks per segment, longest first
+        const int64_t segs = (blocks + per - 1) / per;
+        const int64_t wgs = segs * units_per_seg;
+        if (4 * wgs < 3 * (int64_t)p.cus && per > 1) continue;  // too few workgroups: shorter segments
+        const double eff = (double)wgs / (double)(((wgs + p.cus - 1) / p.cus) * p.cus);
+        if (eff > best_eff + 0.05) { best_eff = eff; best_s = segs; }  // shorter only if clearly better balanced
+        if (wgs >= 8 * (int64_t)p.cus) break;  // enough rounds to balance: stop shortening
+    }
+    const int forced = env_int("MSGEMM_TUNE_SEGMENTS", 0);
+    if (forced >= 1 && forced <= blocks) best_s = forced;
+    const int64_t per = (blocks + best_s - 1) / best_s;
+    p.tiles_per_segment = (int)(per * tpb);
+    p.segments = (int)((p.ktiles + p.tiles_per_segment - 1) / p.tiles_per_segment);
+}
+
+int launch_repack_scales_batched(const Plan& p, hipStream_t s)
+{
+    const int64_t panels = p.m_pad / p.fs.panel_rows;
+    int64_t blocks = (p.nblocks * panels * 64 * p.fs.lane_bytes + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    if (p.fs.lane_bytes == 8)
+        hipLaunchKernelGGL(repack_scales_batched_kernel<8>, dim3((unsigned)blocks), dim3(256), 0, s,
+                           (const __half*)p.scales, (__half*)p.scales_ordered, p.m, p.nblocks, panels);
+    else
+        hipLaunchKernelGGL(repack_scales_batched_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, s,
+                           (const __half*)p.scales, (__half*)p.scales_ordered, p.m, p.nblocks, panels);
+    MSGEMM_HIP_TRY(hipGetLastError());
+    return MSGEMM_OK;
+}
+
+int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s)
+{
+    BatchedArgs a;
+    a.tiled = p.codes_tiled;
+    a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy;
+    a.scales = (const __half*)p.scales_ordered;
+    a.partials = p.partials;
+    a.m = p.m; a.k = p.k; a.b = p.b; a.m_pad = p.m_pad;
+    a.b_pad = (int64_t)p.col_passes * kBC;
+    a.ktiles = (int)p.ktiles;
+    a.panels_total = (int)(p.m_pad / p.fs.panel_rows);
+    a.panels_per_wg = p.fs.panels;
+    a.row_blocks = (int)p.row_blocks;
+    a.col_passes = p.col_passes;
+    a.segments = p.segments;
+    a.tiles_per_segment = p.tiles_per_segment;
+    a.tiles_per_block = p.scale_group > 0 ? (int)(p.scale_group / (2 * kBG)) : 1;
+    a.units = (int)(p.segments * p.row_blocks);
+    a.direct = p.segments == 1;
+    a.partial_span = (int64_t)p.segments * a.b_pad * p.m_pad * 4;
+    a.div_col_passes = make_fastdiv((uint32_t)a.col_passes);
+    a.div_segments = make_fastdiv((uint32_t)a.segments);
+    a.div_tiles_per_block = make_fastdiv((uint32_t)a.tiles_per_block);
+    const int64_t grid = (int64_t)kXcds * a.col_passes * ((a.units + kXcds - 1) / kXcds);
+    const int lb = p.fs.lane_bytes;
+    const dim3 g((unsigned)grid), blk((unsigned)(64 / lb) * 64);
+    const bool scaled = p.scales != nullptr;
+#define MSGEMM_BATCHED(XD, XT, YT, AT)                                                              \
+    if (p.x_dtype == XD) {                                                                          \
+        if (scaled && lb == 8) hipLaunchKernelGGL((batched_kernel<XT, YT, AT, true, 8>), g, blk, 0, s, a);        \
+        else if (scaled) hipLaunchKernelGGL((batched_kernel<XT, YT, AT, true, 4>), g, blk, 0, s, a);              \
+        else if (lb == 8) hipLaunchKernelGGL((batched_kernel<XT, YT, AT, false, 8>), g, blk, 0, s, a);            \
+        else hipLaunchKernelGGL((batched_kernel<XT, YT, AT, false, 4>), g, blk, 0, s, a);                         \
+        MSGEMM_HIP_TRY(hipGetLastError());                                                          \
+        if (!a.direct) return launch_reduce_second_pass(p, a.partials, Y, ldy, a.segments, a.partial_span, s); \
+        return MSGEMM_OK;                                                                           \
+    }
+    MSGEMM_BATCHED(MSGEMM_F16, __half, __half, float)
+    MSGEMM_BATCHED(MSGEMM_BF16, bf16_t, bf16_t, float)
+    MSGEMM_BATCHED(MSGEMM_I8, int8_t, int, int)
+#undef MSGEMM_BATCHED
+    return MSGEMM_ERR_UNSUPPORTED;
+}
+
+}  // namespace msgemm

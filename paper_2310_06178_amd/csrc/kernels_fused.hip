@@ -1,4 +1,7 @@
-// Fused msGeMM for d = 2 on gfx950: phase 1 and phase 2 in one launch.
+// Fused msGeMM for d = 2 on gfx950: phase 1 and phase 2 in one launch, with
+// full-width (fp32 / int32) table entries: the single-column kernels (b <= 2,
+// every dtype) and the 4-column kernel for fp32 activations.  Batches of 16-bit
+// activations run through kernels_batched.hip.
 //
 // Work decomposition
 //   A k-tile is G consecutive table groups (a group = one pair of k-indices =
@@ -11,7 +14,7 @@
 //   partial-sum buffer, in k-tile order (a fixed order: results are
 //   reproducible): by trailing workgroups of the same launch that wait for the
 //   partials of their panels (single-column kernels), or by a second small
-//   launch (batched kernels).
+//   launch (4-column kernel).
 //
 // LDS layout and the gather
 //   entry(code, g) sits at byte (code*G + g) * C * sizeof(ET).  Lane l = 16q+j
@@ -32,6 +35,7 @@
 #include <stdlib.h>
 
 #include "device_types.h"
+#include "fused_common.h"
 #include "msgemm_internal.h"
 
 // Optional phase timestamps for kernel tuning (compiled out unless requested).
@@ -59,7 +63,6 @@ __device__ __forceinline__ void msgemm_trace_put(int id, unsigned long long v)
 namespace msgemm {
 namespace {
 
-constexpr int kLoadsPerPanel = 16;  // one load per group of a 16-group class
 #ifndef MSGEMM_BUILDERS_1COL
 #define MSGEMM_BUILDERS_1COL(waves) ((waves) / 2)
 #endif
@@ -73,31 +76,7 @@ constexpr int kLoadsPerPanel = 16;  // one load per group of a 16-group class
 #define MSGEMM_RING_BYTES 128
 #endif
 constexpr int kRingBytes = MSGEMM_RING_BYTES;  // code bytes per lane a wavefront keeps in flight (x64 lanes)
-constexpr int kAuxSc1 = 16;         // buffer cache policy bit: coherent at agent scope
 constexpr unsigned kMaxFlagPolls = 1u << 22;  // safety bound of the in-launch reduction's wait (seconds)
-constexpr int kXcds = 8;            // L2 slices (XCDs); workgroups are dealt to them round-robin
-
-// n / d for a divisor fixed at launch, without the hardware-less division
-// sequence (round-up multiplier of Granlund and Montgomery; exact for every
-// 32-bit n): q = (t + ((n - t) >> s1)) >> s2 with t = high word of n * magic.
-struct FastDiv { uint32_t magic, s1, s2; };
-
-inline FastDiv make_fastdiv(uint32_t d)
-{
-    uint32_t l = 0;
-    while (l < 32 && ((uint64_t)1 << l) < d) ++l;
-    FastDiv f;
-    f.magic = (uint32_t)((((uint64_t)1 << 32) * (((uint64_t)1 << l) - d)) / d + 1);
-    f.s1 = l < 1 ? l : 1;
-    f.s2 = l - f.s1;
-    return f;
-}
-
-__device__ __forceinline__ uint32_t fast_div(uint32_t n, const FastDiv& f)
-{
-    const uint32_t t = __umulhi(n, f.magic);
-    return (t + ((n - t) >> f.s1)) >> f.s2;
-}
 
 struct FusedArgs {
     const uint8_t* tiled;
@@ -147,117 +126,16 @@ template <> struct EntryAcc<float> {
     static __device__ __forceinline__ float widen(float e) { return e; }
     static __device__ __forceinline__ float make(float v) { return v; }
 };
-template <> struct EntryAcc<__half> {
-    using type = float;
-    static __device__ __forceinline__ float widen(__half e) { return __half2float(e); }
-    static __device__ __forceinline__ __half make(float v) { return __float2half_rn(v); }
-};
 template <> struct EntryAcc<int> {
     using type = int;
     static __device__ __forceinline__ int widen(int e) { return e; }
     static __device__ __forceinline__ int make(int v) { return v; }
 };
-template <> struct EntryAcc<short> {
-    using type = int;
-    static __device__ __forceinline__ int widen(short e) { return (int)e; }
-    static __device__ __forceinline__ short make(int v) { return (short)v; }
-};
-
-typedef unsigned v2u __attribute__((ext_vector_type(2)));
-typedef unsigned v4u __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ unsigned bits_of(float v) { return __float_as_uint(v); }
-__device__ __forceinline__ unsigned bits_of(int v) { return (unsigned)v; }
-__device__ __forceinline__ void set_bits(float& d, unsigned u) { d = __uint_as_float(u); }
-__device__ __forceinline__ void set_bits(int& d, unsigned u) { d = (int)u; }
 
 __device__ __forceinline__ float mul_add(float w, float x, float acc) { return fmaf(w, x, acc); }
 __device__ __forceinline__ int mul_add(int w, int x, int acc) { return w * x + acc; }
 
-// Sum across the wave halves, two registers at a time: afterwards lanes 0..31
-// hold the full sum of `a` and lanes 32..63 the full sum of `b`.
-template <typename AT> __device__ __forceinline__ AT fold32(AT a, AT b)
-{
-    v2u r = __builtin_amdgcn_permlane32_swap(bits_of(a), bits_of(b), false, false);
-    AT x, y;
-    set_bits(x, r.x);
-    set_bits(y, r.y);
-    return x + y;
-}
-// Same across the two 16-lane rows of each half: even rows end up with `a`, odd rows with `b`.
-template <typename AT> __device__ __forceinline__ AT fold16(AT a, AT b)
-{
-    v2u r = __builtin_amdgcn_permlane16_swap(bits_of(a), bits_of(b), false, false);
-    AT x, y;
-    set_bits(x, r.x);
-    set_bits(y, r.y);
-    return x + y;
-}
-
-// The partial sums of one output come from workgroups that may sit on different
-// XCDs, whose L2 slices are not coherent with each other.  When they are reduced
-// inside the launch, partials and flags are therefore only touched with
-// agent-coherent accesses (they go to the point of coherence) and ordered by
-// waiting for the stores to be acknowledged before the flag is raised.  No
-// cache-wide write-back / invalidate is needed.
-__device__ __forceinline__ void wait_vmem()
-{
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-}
-
-template <int N, int AUX>
-__device__ __forceinline__ void store_partials(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, const unsigned (&v)[N])
-{
-    if constexpr (N % 4 == 0) {
-#pragma unroll
-        for (int i = 0; i < N; i += 4) {
-            v4u q = {v[i], v[i + 1], v[i + 2], v[i + 3]};
-            __builtin_amdgcn_raw_buffer_store_b128(q, rsrc, (int)(off + 4 * i), 0, AUX);
-        }
-    } else if constexpr (N % 2 == 0) {
-#pragma unroll
-        for (int i = 0; i < N; i += 2) {
-            v2u q = {v[i], v[i + 1]};
-            __builtin_amdgcn_raw_buffer_store_b64(q, rsrc, (int)(off + 4 * i), 0, AUX);
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < N; ++i) __builtin_amdgcn_raw_buffer_store_b32(v[i], rsrc, (int)(off + 4 * i), 0, AUX);
-    }
-}
-
-template <int N, int AUX>
-__device__ __forceinline__ void load_partials(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, unsigned (&v)[N])
-{
-    if constexpr (N % 4 == 0) {
-#pragma unroll
-        for (int i = 0; i < N; i += 4) {
-            v4u q = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(off + 4 * i), 0, AUX);
-            v[i] = q.x; v[i + 1] = q.y; v[i + 2] = q.z; v[i + 3] = q.w;
-        }
-    } else if constexpr (N % 2 == 0) {
-#pragma unroll
-        for (int i = 0; i < N; i += 2) {
-            v2u q = __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)(off + 4 * i), 0, AUX);
-            v[i] = q.x; v[i + 1] = q.y;
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < N; ++i) v[i] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)(off + 4 * i), 0, AUX);
-    }
-}
-
 template <typename ET, int C> struct alignas(C * sizeof(ET) >= 16 ? 16 : C * sizeof(ET)) EntryVec { ET v[C]; };
-
-// Row of a panel that lane (q, j) keeps in accumulator slot s.  Chosen so that
-// after the cross-lane fold lane l holds the rows 64*i + l of the panel.
-template <int NQ, int LB>
-__host__ __device__ __forceinline__ int panel_row(int q, int j, int s)
-{
-    constexpr int nfinal = LB / NQ;
-    const int qr = q / NQ;
-    return (s % nfinal) * 64 + (qr * NQ + s / nfinal) * 16 + j;
-}
 
 // The single-column kernels can reduce inside the launch; the batched ones are
 // bound by the gather, not by launches, and have no registers to spare for it.
@@ -589,55 +467,18 @@ fused_kernel(FusedArgs a)
                 ring[t % kRing] = cur[kWaves * 64 + (t + kRing - kLoadsPerPanel) * step_stride];
             }
         };
-        // 16-bit entries are first added up in packed 16-bit registers, two columns
-        // per instruction, over kChain look-ups, and only then widened into the
-        // 32-bit accumulators: int16 sums of 8 entries (|entry| <= 2048) are exact;
-        // fp16 sums of 4 entries round three times more (the error stays well
-        // inside the fp16 output tolerance, the entries themselves are fp16 already).
-        constexpr bool kPacked = sizeof(ET) == 2 && C % 2 == 0;
-        constexpr int kChain = __is_same(ET, short) ? 8 : 4;
-        uint32_t acc16[kPacked ? LB : 1][kPacked ? C / 2 : 1];
         auto consume = [&](int t, const Entry (&src)[LB]) {
 #pragma unroll
             for (int s = 0; s < LB; ++s) {
-                if constexpr (kPacked) {
-                    const uint32_t* w = (const uint32_t*)&src[s];
 #pragma unroll
-                    for (int c2 = 0; c2 < C / 2; ++c2) {
-                        if (t % kChain == 0) {
-                            acc16[s][c2] = w[c2];
-                            asm volatile("" : "+v"(acc16[s][c2]));
-                        } else if constexpr (__is_same(ET, __half)) {
-                            asm volatile("v_pk_add_f16 %0, %1, %0" : "+v"(acc16[s][c2]) : "v"(w[c2]));
-                        } else {
-                            asm volatile("v_pk_add_i16 %0, %1, %0" : "+v"(acc16[s][c2]) : "v"(w[c2]));
-                        }
-                        if (t % kChain == kChain - 1) {
-                            if constexpr (__is_same(ET, __half)) {
-                                // acc = half * 1.0 + acc, one mixed-precision FMA per column
-                                asm volatile("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel_hi:[1,0,0]"
-                                             : "+v"(acc[s][2 * c2]) : "v"(acc16[s][c2]));
-                                asm volatile("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel:[1,0,0] op_sel_hi:[1,0,0]"
-                                             : "+v"(acc[s][2 * c2 + 1]) : "v"(acc16[s][c2]));
-                            } else {
-                                acc[s][2 * c2] += (int)(short)(acc16[s][c2] & 0xffffu);
-                                acc[s][2 * c2 + 1] += (int)(short)(acc16[s][c2] >> 16);
-                                asm volatile("" : "+v"(acc[s][2 * c2]), "+v"(acc[s][2 * c2 + 1]));
-                            }
-                        }
-                    }
-                } else {
-#pragma unroll
-                    for (int c = 0; c < C; ++c) {
-                        acc[s][c] += EntryAcc<ET>::widen(src[s].v[c]);
-                        // pin the add to this stage: otherwise the compiler sinks all
-                        // adds below the gather and keeps every table entry live
-                        asm volatile("" : "+v"(acc[s][c]));
-                    }
+                for (int c = 0; c < C; ++c) {
+                    acc[s][c] += EntryAcc<ET>::widen(src[s].v[c]);
+                    // pin the add to this stage: otherwise the compiler sinks all
+                    // adds below the gather and keeps every table entry live
+                    asm volatile("" : "+v"(acc[s][c]));
                 }
             }
         };
-        static_assert(kLoadsPerPanel % kChain == 0, "chains end with the panel");
         Entry e0[LB], e1[LB];
         issue(0, e0);
 #pragma unroll
@@ -800,12 +641,6 @@ repack_scales_kernel(const __half* __restrict__ scales, __half* __restrict__ ord
 
 struct ShapeChoice { int C, G, LB, entry_bytes, waves; };
 
-int env_int(const char* name, int fallback)
-{
-    const char* v = getenv(name);
-    return (v && *v) ? atoi(v) : fallback;
-}
-
 // Which instantiation serves a problem.  Entries are full width (fp32 / int32)
 // for one or two columns (the b = 1 GEMV streams from HBM and the table traffic
 // is small) and 16 bits wide (fp16 / int16) with 8 columns per entry for wider
@@ -819,7 +654,9 @@ ShapeChoice pick_shape(const Plan& p, int requested_variant)
     const bool narrow_ok = p.x_dtype != MSGEMM_F32;
     const bool narrow = requested_variant == MSGEMM_VARIANT_FUSED_LDS16 ||
                         (requested_variant == MSGEMM_VARIANT_AUTO && p.b > 2);
-    if (narrow && narrow_ok) return ShapeChoice{8, 32, 8, 2, 8};
+    // (MSGEMM_TUNE_BATCH_LB = 4: the 16-wavefront form of the batched kernel, tuning aid)
+    if (narrow && narrow_ok)
+        return env_int("MSGEMM_TUNE_BATCH_LB", 8) == 4 ? ShapeChoice{8, 32, 4, 2, 16} : ShapeChoice{8, 32, 8, 2, 8};
     if (p.b > 2 && p.x_dtype == MSGEMM_F32) return ShapeChoice{4, 32, 8, 4, 8};
     return lb1 == 8 ? ShapeChoice{1, 64, 8, 4, 16} : ShapeChoice{1, 64, 16, 4, 8};
 }
@@ -875,7 +712,10 @@ int fused_choose_shape(Plan& p, int requested_variant)
     // Rows per table build: as many panels per workgroup as still leave one
     // workgroup per compute unit (each build costs 256 entries per group).
     // MSGEMM_TUNE_PPW overrides the choice (tuning aid).
-    int ppw = 2 * sc.waves;
+    // (The batched 16-bit kernel keeps one panel per wavefront and runs through
+    // several k-tiles instead; its split over k is chosen below.)
+    const bool batched16 = sc.entry_bytes == 2;
+    int ppw = batched16 ? sc.waves : 2 * sc.waves;
     while (ppw > 1 && (int64_t)p.ktiles * p.col_passes * ((panels + ppw - 1) / ppw) < cus) ppw >>= 1;
     const int forced = env_int("MSGEMM_TUNE_PPW", 0);
     if (forced >= 1 && forced <= 64) ppw = forced;
@@ -886,7 +726,12 @@ int fused_choose_shape(Plan& p, int requested_variant)
     const int64_t row_groups = p.row_blocks * p.col_passes;
     if ((int64_t)p.ktiles * (row_groups + kXcds) + panels * p.col_passes > 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
     // the k-tile reduction addresses the partial buffer with 32-bit byte offsets
-    if ((int64_t)p.ktiles * p.col_passes * sc.C * p.m_pad * 4 >= 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
+    p.segments = 0;
+    p.tiles_per_segment = 0;
+    if (batched16) batched_choose_segments(p);
+    const int64_t slices = batched16 ? p.segments : p.ktiles;
+    if (slices * p.col_passes * sc.C * p.m_pad * 4 >= 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
+    if (p.nblocks * p.m_pad * 4 >= 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
     return MSGEMM_OK;
 }
 
@@ -896,7 +741,10 @@ int launch_repack(const Plan& p, hipStream_t s)
     const int64_t total = (int64_t)p.ktiles * p.m_pad * p.fs.groups;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
-    if (p.scales) {
+    if (p.scales && p.fs.entry_bytes == 2) {
+        const int rc = launch_repack_scales_batched(p, s);
+        if (rc != MSGEMM_OK) return rc;
+    } else if (p.scales) {
         int64_t sblocks = (p.nblocks * p.m_pad + 255) / 256;
         if (sblocks > 65536) sblocks = 65536;
         hipLaunchKernelGGL(repack_scales_kernel, dim3((unsigned)sblocks), dim3(256), 0, s, (const __half*)p.scales,
@@ -913,12 +761,40 @@ int launch_repack(const Plan& p, hipStream_t s)
     MSGEMM_REPACK(64, 16)
     MSGEMM_REPACK(64, 8)
     MSGEMM_REPACK(32, 8)
+    MSGEMM_REPACK(32, 4)
 #undef MSGEMM_REPACK
     return MSGEMM_ERR_UNSUPPORTED;
 }
 
+int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int64_t ldy, int slices,
+                              int64_t span, hipStream_t s)
+{
+    const int64_t b_pad = (int64_t)p.col_passes * p.fs.cols;
+    const dim3 grid((unsigned)((p.m_pad / 64) * p.b)), blk(kReduceWaves * 64);
+    const int f = p.fs.panel_rows / 64;  // outputs per lane of the producing kernel: 4 or 2
+#define MSGEMM_REDUCE(YT, AT)                                                                                   \
+    if (f == 4)                                                                                                 \
+        hipLaunchKernelGGL((reduce_kernel<YT, AT, 4>), grid, blk, 0, s, partials, (YT*)Y, ldy, p.m, p.b, p.m_pad, \
+                           b_pad, slices, span);                                                                \
+    else                                                                                                        \
+        hipLaunchKernelGGL((reduce_kernel<YT, AT, 2>), grid, blk, 0, s, partials, (YT*)Y, ldy, p.m, p.b, p.m_pad, \
+                           b_pad, slices, span);
+    switch (p.y_dtype) {
+    case MSGEMM_F32: MSGEMM_REDUCE(float, float) break;
+    case MSGEMM_F16: MSGEMM_REDUCE(__half, float) break;
+    case MSGEMM_BF16: MSGEMM_REDUCE(bf16_t, float) break;
+    case MSGEMM_I32: MSGEMM_REDUCE(int, int) break;
+    default:
+        return MSGEMM_ERR_INVALID_ARG;
+    }
+#undef MSGEMM_REDUCE
+    MSGEMM_HIP_TRY(hipGetLastError());
+    return MSGEMM_OK;
+}
+
 int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s)
 {
+    if (p.fs.entry_bytes == 2) return launch_batched(p, X, ldx, Y, ldy, s);
     FusedArgs a;
     a.tiled = p.codes_tiled;
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy;
@@ -969,11 +845,8 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     MSGEMM_CASE(1, 64, 8, 4, MSGEMM_F16, __half, __half, float)
     MSGEMM_CASE(1, 64, 8, 4, MSGEMM_BF16, bf16_t, bf16_t, float)
     MSGEMM_CASE(1, 64, 8, 4, MSGEMM_I8, int8_t, int, int)
-    // batched: 4 columns of fp32 entries, or 8 columns of 16-bit entries
+    // batched fp32 activations: 4 columns of fp32 entries (16-bit entries: the batched kernel)
     MSGEMM_CASE(4, 32, 8, 4, MSGEMM_F32, float, float, float)
-    MSGEMM_CASE(8, 32, 8, 2, MSGEMM_F16, __half, __half, __half)
-    MSGEMM_CASE(8, 32, 8, 2, MSGEMM_BF16, bf16_t, bf16_t, __half)
-    MSGEMM_CASE(8, 32, 8, 2, MSGEMM_I8, int8_t, int, short)
 #undef MSGEMM_CASE
     return MSGEMM_ERR_UNSUPPORTED;
 }

@@ -116,7 +116,8 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtyp
     } else {
         const size_t tiled = (size_t)p->ktiles * (size_t)p->m_pad * (size_t)(p->fs.groups);
         const size_t b_pad = (size_t)p->col_passes * (size_t)p->fs.cols;
-        const size_t part = (size_t)p->ktiles * b_pad * (size_t)p->m_pad * 4u;
+        const size_t slices = p->segments > 0 ? (size_t)p->segments : (size_t)p->ktiles;
+        const size_t part = slices * b_pad * (size_t)p->m_pad * 4u;
         const size_t cnt = (size_t)(p->m_pad / p->fs.panel_rows) * (size_t)p->col_passes * (size_t)p->ktiles * sizeof(unsigned);
         e = hipMalloc((void**)&p->codes_tiled, tiled);
         if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
@@ -128,7 +129,8 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtyp
         if (e != hipSuccess) return hip_fail(e);
         p->workspace_bytes = tiled + part + cnt;
         if (p->scales) {
-            const size_t so = (size_t)p->nblocks * (size_t)p->m_pad * 2u;
+            // (the batched kernel keeps one scale per look-up slot: twice the rows)
+            const size_t so = (size_t)p->nblocks * (size_t)p->m_pad * (p->fs.entry_bytes == 2 ? 4u : 2u);
             e = hipMalloc((void**)&p->scales_ordered, so);
             if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
             p->workspace_bytes += so;
@@ -151,7 +153,7 @@ int msgemm_plan_get_info(const msgemm_plan_t* plan, msgemm_plan_info_t* info)
     const bool fused = p.variant != MSGEMM_VARIANT_GLOBAL_LUT;
     info->tile_rows = fused ? p.fs.tile_rows : 0;
     info->tile_groups = fused ? p.fs.groups : 0;
-    info->split_k = fused ? (int)p.ktiles : 1;
+    info->split_k = fused ? (p.segments > 0 ? p.segments : (int)p.ktiles) : 1;
     info->col_chunk = fused ? p.fs.cols : (int)p.b;
     info->workspace_bytes = (int64_t)p.workspace_bytes;
     return MSGEMM_OK;

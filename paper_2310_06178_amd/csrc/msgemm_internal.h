@@ -47,9 +47,11 @@ struct Plan {
     int64_t m_pad;        // row_blocks * tile_rows
     int col_passes;       // ceil(b / cols)
     int cus;              // compute units of the device
+    int segments;         // batched kernel: k-segments (partial sums per output); 0 otherwise
+    int tiles_per_segment; // batched kernel: k-tiles a workgroup runs through
     uint16_t* scales_ordered;  // device fp16 [nblocks][m_pad], rows in the order the lanes own outputs; nullptr without scales
     uint8_t* codes_tiled; // device, [ktiles][m_pad / panel_rows][16][64][lane_bytes]
-    float* partials;      // device, [ktiles][b_pad][m_pad] fp32 / int32
+    float* partials;      // device, [ktiles or segments][b_pad][m_pad] fp32 / int32
     unsigned* flags;      // device, [panels][col_passes][ktiles] arrival flags of the in-launch reduction, zero between launches
     size_t workspace_bytes;
 };
@@ -73,6 +75,14 @@ int launch_consume_lut(const Plan& p, const void* L, void* Y, int64_t ldy, hipSt
 int fused_choose_shape(Plan& p, int requested_variant);  // fills p.fs, ktiles, ...; MSGEMM_ERR_UNSUPPORTED if not applicable
 int launch_repack(const Plan& p, hipStream_t s);
 int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s);
+// adds `slices` partial-sum slices ([slice][b_pad][m_pad], output order) and writes Y in the plan's output type
+int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int64_t ldy, int slices,
+                              int64_t span, hipStream_t s);
+
+// kernels_batched.hip (16-bit table entries, 8 batch columns per pass)
+void batched_choose_segments(Plan& p);  // needs ktiles, row_blocks, col_passes, cus; fills segments, tiles_per_segment
+int launch_repack_scales_batched(const Plan& p, hipStream_t s);
+int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s);
 
 // calibration.hip
 int launch_calib_stream_read(const void* src, size_t bytes, void* sink, hipStream_t s);
