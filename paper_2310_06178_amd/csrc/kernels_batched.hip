@@ -40,10 +40,15 @@ namespace {
 constexpr int kBC = 8;                   // batch columns per table entry and per pass
 constexpr int kBG = 32;                  // table groups per k-tile
 // LB = rows (code bytes) a lane takes per load: 8 (8 wavefronts of 256-row panels)
-// or 4 (16 wavefronts of 128-row panels: half the registers per wavefront, twice
-// the wavefronts to hide the LDS latency behind).  A workgroup covers 2048 rows either way.
-template <int LB> constexpr int batched_waves() { return 64 / LB; }
-constexpr int kBCodeStride = kBG * 16;   // bytes between the entries of consecutive codes
+// or 4 (12 wavefronts of 128-row panels: half the registers per wavefront, three
+// wavefronts per SIMD to hide the LDS latency behind).
+template <int LB> constexpr int batched_waves() { return LB == 8 ? 8 : 12; }
+// LDS layout of the table: two halves of 16 groups; entry (code, g) at
+// (g / 16) * 64 KiB + code * 256 + (g % 16) * 16.  The code byte is then byte 1
+// of the address and the half byte 2: one v_perm_b32 turns a packed code into
+// an address.  Lanes served together hold different g % 16, i.e. different banks.
+constexpr int kBCodeStride = 256;        // bytes between the entries of consecutive codes within a half
+constexpr int kBHalfBytes = 256 * kBCodeStride;
 constexpr int kBRing = 8;                // code loads a wavefront keeps in flight
 static_assert(kLoadsPerPanel % kBRing == 0, "ring slots are reused with a period dividing the panel");
 
@@ -106,7 +111,7 @@ batched_kernel(BatchedArgs a)
     constexpr int kBFinal = kBLB / 2;               // rows a lane owns after the fold
     constexpr int kThreads = kBWaves * 64;
     using LoadT = typename LaneLoad<kBLB>::type;
-    __shared__ __align__(16) unsigned char lds[256 * kBCodeStride];  // entry (code, g) at (code * 32 + g) * 16
+    __shared__ __align__(16) unsigned char lds[2 * kBHalfBytes];
     __shared__ __align__(16) _Float16 xs[2][2 * kBG][kBC];            // activations of a k-tile: [k-column][batch column]
 
     const int tid = threadIdx.x;
@@ -148,17 +153,18 @@ batched_kernel(BatchedArgs a)
 
     // ---- phase 1: L(c0 | c1 << 4, g, c) = b(c0) X(2g, c) + b(c1) X(2g + 1, c), in packed fp16
     // thread (g, c1, part) writes 16 / parts entries of its c1 for group g
-    constexpr int kBuildParts = kThreads / (kBG * 16);
+    constexpr int kBuildParts = kThreads % (kBG * 16) == 0 ? kThreads / (kBG * 16) : 1;
     constexpr int kBuildEach = 16 / kBuildParts;
     auto build_tables = [&](int buf) {
         const int g = tid & (kBG - 1), c1 = (tid >> 5) & 15, part = tid >> 9;
+        if (part >= kBuildParts) return;  // (a thread count that is no multiple of 512: the rest sits the build out)
         h2 x0[4], x1[4], top[4];
         __builtin_memcpy(x0, &xs[buf][2 * g][0], 16);
         __builtin_memcpy(x1, &xs[buf][2 * g + 1][0], 16);
         const _Float16 w1 = (_Float16)(float)decode4((unsigned)c1);
 #pragma unroll
         for (int p = 0; p < 4; ++p) top[p] = x1[p] * h2{w1, w1};
-        unsigned char* dst = lds + (size_t)(c1 * 16) * kBCodeStride + g * 16;
+        unsigned char* dst = lds + (g >> 4) * kBHalfBytes + (size_t)(c1 * 16) * kBCodeStride + (g & 15) * 16;
 #pragma unroll
         for (int cc = 0; cc < kBuildEach; ++cc) {
             const int c0 = part * kBuildEach + cc;
@@ -219,13 +225,15 @@ batched_kernel(BatchedArgs a)
             const int kt_next = more ? kt + 1 : kt;  // (the last tile re-requests its own tail: harmless, and branch-free)
 #pragma unroll
             for (int t = 0; t < kLoadsPerPanel; ++t) {
-                const uint32_t lane_off = (uint32_t)(16 * qg + ((j + t) & 15)) * 16u;
+                // byte 0: the slot of this lane's group within a code's 256 bytes; byte 2: the half
+                const uint32_t lane_off = (uint32_t)((j + t) & 15) * 16u | ((uint32_t)qg << 16);
                 const LoadT d = ring[t % kBRing];
 #pragma unroll
                 for (int s = 0; s < kBLB; ++s) {
                     const uint32_t w = load_word<kBLB>(d, s >> 2);
-                    const uint32_t code = (w >> (8 * (s & 3))) & 0xffu;
-                    const uint4 e = *(const uint4*)(lds + code * kBCodeStride + lane_off);
+                    // address bytes (3..0) = (0, half, code, slot)
+                    const uint32_t addr = __builtin_amdgcn_perm(w, lane_off, 0x0c020000u | ((4u + (s & 3)) << 8));
+                    const uint4 e = *(const uint4*)(lds + addr);
                     h4 lo, up;
                     __builtin_memcpy(&lo, &e.x, 8);
                     __builtin_memcpy(&up, &e.z, 8);
@@ -404,7 +412,7 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
     a.div_tiles_per_block = make_fastdiv((uint32_t)a.tiles_per_block);
     const int64_t grid = (int64_t)kXcds * a.col_passes * ((a.units + kXcds - 1) / kXcds);
     const int lb = p.fs.lane_bytes;
-    const dim3 g((unsigned)grid), blk((unsigned)(64 / lb) * 64);
+    const dim3 g((unsigned)grid), blk((unsigned)(lb == 8 ? 8 : 12) * 64);
     const bool scaled = p.scales != nullptr;
 #define MSGEMM_BATCHED(XD, XT, YT, AT)                                                              \
     if (p.x_dtype == XD) {                                                                          \

@@ -654,9 +654,9 @@ ShapeChoice pick_shape(const Plan& p, int requested_variant)
     const bool narrow_ok = p.x_dtype != MSGEMM_F32;
     const bool narrow = requested_variant == MSGEMM_VARIANT_FUSED_LDS16 ||
                         (requested_variant == MSGEMM_VARIANT_AUTO && p.b > 2);
-    // (MSGEMM_TUNE_BATCH_LB = 4: the 16-wavefront form of the batched kernel, tuning aid)
+    // (MSGEMM_TUNE_BATCH_LB = 4: the 12-wavefront form of the batched kernel, tuning aid)
     if (narrow && narrow_ok)
-        return env_int("MSGEMM_TUNE_BATCH_LB", 8) == 4 ? ShapeChoice{8, 32, 4, 2, 16} : ShapeChoice{8, 32, 8, 2, 8};
+        return env_int("MSGEMM_TUNE_BATCH_LB", 8) == 4 ? ShapeChoice{8, 32, 4, 2, 12} : ShapeChoice{8, 32, 8, 2, 8};
     if (p.b > 2 && p.x_dtype == MSGEMM_F32) return ShapeChoice{4, 32, 8, 4, 8};
     return lb1 == 8 ? ShapeChoice{1, 64, 8, 4, 16} : ShapeChoice{1, 64, 16, 4, 8};
 }
