@@ -18,9 +18,10 @@ from __future__ import annotations
 
 import numpy as np
 
-# The five benchmark configurations (LLM-shaped GeMMs; the paper itself measures
-# nothing, its only shapes are the GPT-3 MLP ones of Section 5, kept as "mlp1"
-# and "mlp2" for the operation-count report).
+# The five benchmark configurations (LLM-shaped GeMMs), then the paper's own
+# shapes -- the two GeMMs of the GPT-3 MLP block, Section 5 -- as a second
+# workload ("mlp1", "mlp2": one activation vector; "_b16": a batch of 16).  The
+# paper gives no data for them either: same recipe, seeds 11 and 12.
 CONFIGS = {
     "cfg1":  dict(m=1024,  k=1024, b=1,  x="f32",  y="f32",  scale_group=0,   d=2, seed=0),
     "cfg2":  dict(m=16384, k=4096, b=1,  x="f16",  y="f16",  scale_group=0,   d=2, seed=2),
@@ -29,6 +30,10 @@ CONFIGS = {
     "cfg4":  dict(m=8192,  k=8192, b=16, x="i8",   y="i32",  scale_group=0,   d=2, seed=4),
     "cfg5":  dict(m=28672, k=8192, b=64, x="bf16", y="bf16", scale_group=128, d=2, seed=5,
                   outliers=True),
+    "mlp1":     dict(m=12288, k=49152, b=1,  x="f16", y="f16", scale_group=0, d=2, seed=11),
+    "mlp2":     dict(m=49152, k=12288, b=1,  x="f16", y="f16", scale_group=0, d=2, seed=12),
+    "mlp1_b16": dict(m=12288, k=49152, b=16, x="f16", y="f16", scale_group=0, d=2, seed=11),
+    "mlp2_b16": dict(m=49152, k=12288, b=16, x="f16", y="f16", scale_group=0, d=2, seed=12),
 }
 PAPER_SHAPES = {"mlp1": (12288, 49152), "mlp2": (49152, 12288)}
 
