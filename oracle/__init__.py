@@ -45,6 +45,8 @@ def _load():
         lib.msgemm_oracle_num_threads.restype = ci
         lib.msgemm_oracle_set_threads.argtypes = [ci]
         lib.msgemm_oracle_gemm_f64.argtypes = [i64, i64, i64, vp, vp, i64, vp, i64, vp, i64]
+        lib.msgemm_oracle_gemm_f64_values.argtypes = [i64, i64, i64, vp, vp, vp, i64, vp, i64, vp, i64]
+        lib.msgemm_oracle_lut_build_f64_values.argtypes = [i64, i64, ci, i64, vp, vp, i64, vp]
         lib.msgemm_oracle_gemm_i32.argtypes = [i64, i64, i64, vp, vp, i64, vp, i64]
         lib.msgemm_oracle_lut_groups.argtypes = [i64, ci, i64]
         lib.msgemm_oracle_lut_groups.restype = i64
@@ -110,9 +112,20 @@ def _as_f64_cols(X) -> np.ndarray:
     return np.ascontiguousarray(X, dtype=np.float64)
 
 
-def gemm_f64(codes, X, scales=None, scale_group: int = 0) -> np.ndarray:
+def _values16(codebook):
+    if codebook is None:
+        return None
+    v = np.ascontiguousarray(codebook, dtype=np.float64)
+    if v.shape != (16,):
+        raise ValueError("a codebook has 16 values, one per bit pattern")
+    return v
+
+
+def gemm_f64(codes, X, scales=None, scale_group: int = 0, codebook=None) -> np.ndarray:
     """Direct decode-and-multiply GeMM in fp64 (Section 3.2, first line of the
-    y(i) equation; Section 3.3 for the per-block scales).
+    y(i) equation; Section 3.3 for the per-block scales).  ``codebook``: 16
+    values replacing b(.) of Section 3.1, indexed by bit pattern (None = the
+    paper's two's complement).
 
     codes: uint8 [m][k/2]; X: [b][k] (each row one activation vector, i.e. one
     column of the paper's X); scales: [m][k/scale_group] or None.
@@ -130,8 +143,9 @@ def gemm_f64(codes, X, scales=None, scale_group: int = 0) -> np.ndarray:
         if s.shape != (m, k // scale_group):
             raise ValueError("scales must be [m][k/scale_group]")
     Y = np.empty((b, m), dtype=np.float64)
-    _check(_load().msgemm_oracle_gemm_f64(m, k, b, _ptr(codes), _ptr(s), int(scale_group),
-                                          _ptr(X), k, _ptr(Y), m), "gemm_f64")
+    v = _values16(codebook)
+    _check(_load().msgemm_oracle_gemm_f64_values(m, k, b, _ptr(codes), _ptr(v), _ptr(s), int(scale_group),
+                                                 _ptr(X), k, _ptr(Y), m), "gemm_f64")
     return Y
 
 
@@ -162,7 +176,7 @@ def lut_groups(k: int, d: int, scale_group: int = 0) -> int:
     return g
 
 
-def lut_build(X, d: int, scale_group: int = 0) -> np.ndarray:
+def lut_build(X, d: int, scale_group: int = 0, codebook=None) -> np.ndarray:
     """Phase 1 (Section 3.1): L[j][idx][c] = sum_r b(i_r) X(j d + r, c), with
     idx = sum_r i_r << 4r.  int8 X gives int32 entries, anything else fp64."""
     X = np.asarray(X)
@@ -180,7 +194,8 @@ def lut_build(X, d: int, scale_group: int = 0) -> np.ndarray:
         return L
     X = _as_f64_cols(X)
     L = np.empty((G, E, b), dtype=np.float64)
-    _check(_load().msgemm_oracle_lut_build_f64(k, b, d, int(scale_group), _ptr(X), k, _ptr(L)),
+    v = _values16(codebook)
+    _check(_load().msgemm_oracle_lut_build_f64_values(k, b, d, int(scale_group), _ptr(v), _ptr(X), k, _ptr(L)),
            "lut_build_f64")
     return L
 

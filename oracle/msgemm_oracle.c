@@ -109,11 +109,17 @@ static int check_shape(int64_t m, int64_t k, int64_t b, int64_t scale_group)
  * y(i,c) = sum_g q(i,g) * sum_{j in block g} b(code(i,j)) * X(j,c)
  * (Section 3.2 first line; Section 3.3 for q).  fp64 throughout.
  */
-int msgemm_oracle_gemm_f64(int64_t m, int64_t k, int64_t b,
-                           const uint8_t* codes,
-                           const double* scales, int64_t scale_group,
-                           const double* X, int64_t ldx,
-                           double* Y, int64_t ldy)
+/*
+ * The same sum with b(.) replaced by an arbitrary map from the 16 bit patterns
+ * to values (Section 2: the exact datatype of the weights is irrelevant to the
+ * method; b(.) of Section 3.1 is the only place where the encoding enters).
+ * values16 == NULL means the two's-complement b(.) of the paper.
+ */
+int msgemm_oracle_gemm_f64_values(int64_t m, int64_t k, int64_t b,
+                                  const uint8_t* codes, const double* values16,
+                                  const double* scales, int64_t scale_group,
+                                  const double* X, int64_t ldx,
+                                  double* Y, int64_t ldy)
 {
     if (check_shape(m, k, b, scale_group) || !codes || !X || !Y) return -1;
     if (ldx < k || ldy < m) return -1;
@@ -127,7 +133,8 @@ int msgemm_oracle_gemm_f64(int64_t m, int64_t k, int64_t b,
 #pragma omp for schedule(static)
         for (int64_t i = 0; i < m; ++i) {
             for (int64_t j = 0; j < k; ++j)
-                w[j] = (double)msgemm_oracle_decode(code_at(codes, k, i, j));
+                w[j] = values16 ? values16[code_at(codes, k, i, j)]
+                                : (double)msgemm_oracle_decode(code_at(codes, k, i, j));
             for (int64_t c = 0; c < b; ++c) {
                 const double* x = X + c * ldx;
                 double y = 0.0;
@@ -144,6 +151,15 @@ int msgemm_oracle_gemm_f64(int64_t m, int64_t k, int64_t b,
         free(w);
     }
     return 0;
+}
+
+int msgemm_oracle_gemm_f64(int64_t m, int64_t k, int64_t b,
+                           const uint8_t* codes,
+                           const double* scales, int64_t scale_group,
+                           const double* X, int64_t ldx,
+                           double* Y, int64_t ldy)
+{
+    return msgemm_oracle_gemm_f64_values(m, k, b, codes, NULL, scales, scale_group, X, ldx, Y, ldy);
 }
 
 /* int8 activations, int32 accumulation, no scales: the unique exact result. */
@@ -202,8 +218,9 @@ static void group_span(int64_t jg, int64_t k, int d, int64_t scale_group,
 }
 
 /* Phase 1: L(i_0..i_{d-1}, j, c) = sum_r b(i_r) * X(j*d + r, c). */
-int msgemm_oracle_lut_build_f64(int64_t k, int64_t b, int d, int64_t scale_group,
-                                const double* X, int64_t ldx, double* L)
+int msgemm_oracle_lut_build_f64_values(int64_t k, int64_t b, int d, int64_t scale_group,
+                                       const double* values16,
+                                       const double* X, int64_t ldx, double* L)
 {
     const int64_t G = msgemm_oracle_lut_groups(k, d, scale_group);
     if (G < 0 || b <= 0 || !X || !L || ldx < k) return -1;
@@ -216,12 +233,19 @@ int msgemm_oracle_lut_build_f64(int64_t k, int64_t b, int d, int64_t scale_group
                 double s = 0.0;
                 for (int r = 0; r < len; ++r) {
                     unsigned ir = (unsigned)(idx >> (4 * r)) & 15u;
-                    s += (double)msgemm_oracle_decode(ir) * X[c * ldx + first + r];
+                    const double w = values16 ? values16[ir] : (double)msgemm_oracle_decode(ir);
+                    s += w * X[c * ldx + first + r];
                 }
                 L[(jg * E + idx) * b + c] = s;
             }
     }
     return 0;
+}
+
+int msgemm_oracle_lut_build_f64(int64_t k, int64_t b, int d, int64_t scale_group,
+                                const double* X, int64_t ldx, double* L)
+{
+    return msgemm_oracle_lut_build_f64_values(k, b, d, scale_group, NULL, X, ldx, L);
 }
 
 int msgemm_oracle_lut_build_i32(int64_t k, int64_t b, int d,

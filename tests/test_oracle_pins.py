@@ -385,3 +385,65 @@ def test_generators_are_seeded_and_shaped():
     assert 1.0 < xf.std() < 1.8  # N(0,1) plus 1 % of x10 outliers: var = 0.99 + 0.01*100
     xi = inputs.make_x(8192, 16, "i8", seed=4)
     assert xi.min() == -128 and xi.max() == 127
+
+
+# --------------------------------------------------------------------------
+# other 16-value encodings of the codes: only b(.) changes (Sections 2 and 3.1)
+
+UINT4 = np.arange(16, dtype=np.float64)
+# a made-up non-uniform, asymmetric table (dyadic values: every product below is exact)
+NONUNIFORM = np.array([0.0, 0.125, 0.25, 0.5, 1.0, 1.5, 2.5, 4.0,
+                       -6.0, -3.0, -2.0, -1.25, -0.75, -0.375, -0.1875, -0.0625])
+
+
+def test_codebook_default_is_the_papers_b():
+    codes = inputs.make_codes(33, 40, seed=21)
+    X = inputs.make_x(40, 3, "f32", seed=22)
+    sc = inputs.make_scales(33, 40, 8, seed=23)
+    paper = PAPER_B_ARR.astype(np.float64)
+    assert np.array_equal(oracle.gemm_f64(codes, X, sc, 8), oracle.gemm_f64(codes, X, sc, 8, codebook=paper))
+    assert np.array_equal(oracle.lut_build(X, 3, 8), oracle.lut_build(X, 3, 8, codebook=paper))
+
+
+@pytest.mark.parametrize("table", [UINT4, NONUNIFORM])
+def test_codebook_unit_vector_probe(table):
+    nib = np.stack([np.arange(16), np.arange(15, -1, -1)], axis=1)
+    Y = oracle.gemm_f64(inputs.pack_nibbles(nib), np.eye(2), codebook=table)
+    assert list(Y[0]) == list(table) and list(Y[1]) == list(table[::-1])
+
+
+@pytest.mark.parametrize("table", [UINT4, NONUNIFORM])
+def test_codebook_vs_numpy_matmul(table):
+    m, k, b, sg = 70, 96, 4, 32
+    codes = inputs.make_codes(m, k, seed=31)
+    X = inputs.make_x(k, b, "f32", seed=32).astype(np.float64)
+    sc = inputs.make_scales(m, k, sg, seed=33).astype(np.float64)
+    W = table[unpack_independent(codes)] * np.repeat(sc, sg, axis=1)  # independently decoded and scaled
+    ref = X @ W.T
+    got = oracle.gemm_f64(codes, X, sc, sg, codebook=table)
+    assert np.max(np.abs(got - ref)) <= 1e-12 * np.max(np.abs(ref))
+
+
+def test_uint4_differs_from_twos_complement_by_sixteen_on_high_patterns():
+    # pattern p as unsigned is p, as two's complement p - 16 [p >= 8]
+    m, k = 50, 64
+    codes = inputs.make_codes(m, k, seed=41)
+    x = np.round(inputs.make_x(k, 1, "f32", seed=42).astype(np.float64) * 8) / 8  # dyadic: exact sums
+    high = (unpack_independent(codes) >= 8).astype(np.float64)
+    diff = oracle.gemm_f64(codes, x, codebook=UINT4) - oracle.gemm_f64(codes, x)
+    assert np.array_equal(diff, 16.0 * (x @ high.T))
+
+
+@pytest.mark.parametrize("d", [1, 2, 3])
+def test_codebook_lut_enumeration(d):
+    x = [0.5, -1.25, 2.0][:d]
+    L = oracle.lut_build(np.array([x]), d, codebook=NONUNIFORM)
+    for digits in itertools.product(range(16), repeat=d):
+        idx = sum(digits[r] << (4 * r) for r in range(d))
+        assert L[0, idx, 0] == sum(NONUNIFORM[digits[r]] * x[r] for r in range(d))
+    # consuming that table equals the direct sum with the same value map
+    codes = inputs.make_codes(19, 12, seed=51)
+    X = np.array([[0.5, -1.25, 2.0, 0.75, -0.5, 1.5, 0.25, -2.0, 1.0, 3.0, -0.125, 0.375]])
+    direct = oracle.gemm_f64(codes, X, codebook=NONUNIFORM)
+    via = oracle.lut_consume(codes, oracle.lut_build(X, d, codebook=NONUNIFORM), d)
+    assert np.array_equal(direct, via)
