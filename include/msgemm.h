@@ -116,6 +116,21 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b,
                 int x_dtype, int y_dtype, int d, int scale_group,
                 const void* W_codes, const void* scales, int variant, void* stream);
 
+/*
+ * Other encodings of the 4-bit codes.  Section 2 notes that the exact datatype
+ * of the weights is irrelevant to the method; b(.) of Section 3.1 is the only
+ * place where the encoding enters.  values16 (host, 16 floats, finite) gives the
+ * value of each bit pattern 0000..1111 -- e.g. 0..15 for unsigned int4, or a
+ * non-uniform 16-entry codebook -- and replaces b(.) in every table this plan
+ * builds from now on (msgemm_build_lut, msgemm_run).  NULL restores the
+ * paper's two's complement.  Floating-point plans only (MSGEMM_ERR_UNSUPPORTED
+ * for int8 activations, whose integer tables keep b(.)); with 16-bit table
+ * entries the values are rounded to fp16.  The comparison entry point
+ * msgemm_dequant_mfma_run refuses a plan with a custom map.  The map travels
+ * in the arguments of each launch: launches already enqueued keep the old one.
+ */
+int msgemm_plan_set_codebook(msgemm_plan_t* plan, const float* values16);
+
 /* Fill *info with what the plan chose. */
 int msgemm_plan_get_info(const msgemm_plan_t* plan, msgemm_plan_info_t* info);
 

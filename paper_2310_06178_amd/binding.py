@@ -20,7 +20,7 @@ VARIANT_AUTO, VARIANT_GLOBAL_LUT, VARIANT_FUSED_LDS, VARIANT_FUSED_LDS16 = 0, 1,
 OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, -1, -2, -3, -4
 
 EXPORTS = (
-    "msgemm_plan", "msgemm_plan_get_info", "msgemm_lut_bytes", "msgemm_build_lut",
+    "msgemm_plan", "msgemm_plan_set_codebook", "msgemm_plan_get_info", "msgemm_lut_bytes", "msgemm_build_lut",
     "msgemm_consume_lut", "msgemm_run", "msgemm_dequant_mfma_run", "msgemm_calib_stream_read", "msgemm_destroy",
     "msgemm_status_string", "msgemm_last_hip_error", "msgemm_version",
 )
@@ -65,6 +65,8 @@ def load():
     vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
     lib.msgemm_plan.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci, ci, ci, ci, vp, vp, ci, vp]
     lib.msgemm_plan.restype = ci
+    lib.msgemm_plan_set_codebook.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+    lib.msgemm_plan_set_codebook.restype = ci
     lib.msgemm_plan_get_info.argtypes = [vp, ctypes.POINTER(PlanInfo)]
     lib.msgemm_plan_get_info.restype = ci
     lib.msgemm_lut_bytes.argtypes = [vp]
@@ -182,6 +184,20 @@ def msgemm_calib_stream_read(src, nbytes, sink, stream=None):
     rc = load().msgemm_calib_stream_read(_ptr(src), int(nbytes), _ptr(sink), _stream(stream))
     if rc != OK:
         raise MsgemmError(rc, "msgemm_calib_stream_read")
+
+
+def msgemm_plan_set_codebook(plan, values16, check: bool = True):
+    """values16: 16 floats (value of each bit pattern) or None for the paper's two's complement."""
+    arr = None
+    if values16 is not None:
+        vals = [float(v) for v in values16]
+        if len(vals) != 16:
+            raise ValueError("a codebook has 16 values")
+        arr = (ctypes.c_float * 16)(*vals)
+    rc = load().msgemm_plan_set_codebook(ctypes.c_void_p(plan), arr)
+    if check and rc != OK:
+        raise MsgemmError(rc, "msgemm_plan_set_codebook")
+    return rc
 
 
 def msgemm_destroy(plan) -> None:

@@ -12,6 +12,13 @@ struct bf16_t { uint16_t bits; };  // bfloat16 storage
 // b(.) of Section 3.1: two's-complement value of a 4-bit pattern.
 __device__ __forceinline__ int decode4(unsigned nibble) { return (int)((nibble ^ 8u) & 15u) - 8; }
 
+// Value of a 4-bit pattern for a table build: the plan's 16-entry value map for
+// floating-point tables (the paper's b(.) unless the caller installed another
+// encoding), b(.) itself for integer tables.
+struct ValueMap { float v[16]; };  // travels by value in the launch arguments
+__device__ __forceinline__ float code_value(const ValueMap& values, unsigned nibble, float) { return values.v[nibble & 15u]; }
+__device__ __forceinline__ int code_value(const ValueMap&, unsigned nibble, int) { return decode4(nibble); }
+
 template <typename T> struct XTraits;
 template <> struct XTraits<float> {
     using acc_t = float;

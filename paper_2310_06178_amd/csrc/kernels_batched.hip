@@ -71,6 +71,7 @@ struct BatchedArgs {
     int64_t ldx;
     void* Y;
     int64_t ldy;
+    ValueMap values;         // value of each 4-bit pattern
     const __half* scales;    // [block][panel][lane][LB]: scale of the row behind each of a lane's look-ups; or nullptr
     float* partials;         // [segment][column][panel][lane][LB / 2]
     int64_t m, k, b, m_pad, b_pad;
@@ -152,6 +153,16 @@ batched_kernel(BatchedArgs a)
     };
 
     // ---- phase 1: L(c0 | c1 << 4, g, c) = b(c0) X(2g, c) + b(c1) X(2g + 1, c), in packed fp16
+    // values of this thread's high code and of its low codes (fetched once, ahead of
+    // the first table build; exact in fp16 for the paper's b(.))
+    const _Float16 w1_mine = (_Float16)a.values.v[(tid >> 5) & 15];
+    _Float16 w0_mine[16 / (kThreads % (kBG * 16) == 0 ? kThreads / (kBG * 16) : 1)];
+    {
+        constexpr int kParts = kThreads % (kBG * 16) == 0 ? kThreads / (kBG * 16) : 1;
+        const int first = kParts == 1 ? 0 : (tid >> 9) * (16 / kParts);
+#pragma unroll
+        for (int cc = 0; cc < 16 / kParts; ++cc) w0_mine[cc] = (_Float16)a.values.v[(first + cc) & 15];
+    }
     // thread (g, c1, part) writes 16 / parts entries of its c1 for group g
     constexpr int kBuildParts = kThreads % (kBG * 16) == 0 ? kThreads / (kBG * 16) : 1;
     constexpr int kBuildEach = 16 / kBuildParts;
@@ -161,14 +172,14 @@ batched_kernel(BatchedArgs a)
         h2 x0[4], x1[4], top[4];
         __builtin_memcpy(x0, &xs[buf][2 * g][0], 16);
         __builtin_memcpy(x1, &xs[buf][2 * g + 1][0], 16);
-        const _Float16 w1 = (_Float16)(float)decode4((unsigned)c1);
+        const _Float16 w1 = w1_mine;
 #pragma unroll
         for (int p = 0; p < 4; ++p) top[p] = x1[p] * h2{w1, w1};
         unsigned char* dst = lds + (g >> 4) * kBHalfBytes + (size_t)(c1 * 16) * kBCodeStride + (g & 15) * 16;
 #pragma unroll
         for (int cc = 0; cc < kBuildEach; ++cc) {
             const int c0 = part * kBuildEach + cc;
-            const _Float16 w0 = (_Float16)(float)decode4((unsigned)c0);
+            const _Float16 w0 = w0_mine[cc];
             h2 e[4];
 #pragma unroll
             for (int p = 0; p < 4; ++p) e[p] = __builtin_elementwise_fma(h2{w0, w0}, x0[p], top[p]);
@@ -392,6 +403,7 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
     BatchedArgs a;
     a.tiled = p.codes_tiled;
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy;
+    for (int i = 0; i < 16; ++i) a.values.v[i] = p.values[i];
     a.scales = (const __half*)p.scales_ordered;
     a.partials = p.partials;
     a.m = p.m; a.k = p.k; a.b = p.b; a.m_pad = p.m_pad;

@@ -33,6 +33,7 @@
 //   wavefront keeps a ring of kRing loads in flight and refills a slot as soon
 //   as its bytes have been turned into LDS addresses.
 #include <stdlib.h>
+#include <type_traits>
 
 #include "device_types.h"
 #include "fused_common.h"
@@ -99,6 +100,7 @@ struct FusedArgs {
     FastDiv div_ktiles, div_col_passes, div_tiles_per_block;
     int fused_wgs;          // workgroups of the grid that do the fused work; the rest reduce (in-launch mode)
     int red_units;          // (panel, column pass) pairs to reduce, one trailing workgroup each
+    ValueMap values;        // value of each 4-bit pattern; last, read only by the forms built for a custom map
 };
 
 enum ReduceMode {
@@ -231,7 +233,10 @@ __device__ __forceinline__ void reduce_in_launch(const FusedArgs& a, int unit, i
 // 16-wavefront form has no room for more wavefronts in a workgroup.)
 template <int C, int kWaves> constexpr int dedicated_builders() { return (C == 1 && kWaves <= 8) ? MSGEMM_DEDICATED_1COL : 0; }
 
-template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves>
+// kCustomValues: the tables are built from the plan's 16-value map instead of
+// b(.) (Section 3.1).  A form of its own, so that the default encoding keeps its
+// compile-time constants and never touches that part of the argument buffer.
+template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves, bool kCustomValues>
 __global__ void __launch_bounds__((kWaves + dedicated_builders<C, kWaves>()) * 64)
 fused_kernel(FusedArgs a)
 {
@@ -267,6 +272,10 @@ fused_kernel(FusedArgs a)
 #define MSGEMM_ARG_NOW(x) asm volatile("" ::"s"(x))
     MSGEMM_ARG_NOW((uint64_t)a.tiled); MSGEMM_ARG_NOW((uint64_t)a.X); MSGEMM_ARG_NOW(a.ldx);
     MSGEMM_ARG_NOW((uint64_t)a.Y); MSGEMM_ARG_NOW(a.ldy); MSGEMM_ARG_NOW((uint64_t)a.scales);
+    if constexpr (kCustomValues) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) MSGEMM_ARG_NOW(a.values.v[i]);
+    }
     MSGEMM_ARG_NOW((uint64_t)a.partials); MSGEMM_ARG_NOW(a.m); MSGEMM_ARG_NOW(a.k); MSGEMM_ARG_NOW(a.b);
     MSGEMM_ARG_NOW(a.m_pad); MSGEMM_ARG_NOW(a.b_pad); MSGEMM_ARG_NOW(a.ktiles); MSGEMM_ARG_NOW(a.panels_total);
     MSGEMM_ARG_NOW(a.panels_per_wg); MSGEMM_ARG_NOW(a.col_passes); MSGEMM_ARG_NOW(a.row_groups);
@@ -347,6 +356,11 @@ fused_kernel(FusedArgs a)
         const int64_t kk = ((int64_t)kt * G + g) * 2;
         // raw values from clamped (always valid) addresses first, conversion after
         // the early code loads: nothing waits for the activations before those are out
+        constexpr int kC1PerThread = (16 + kBuildParts - 1) / kBuildParts;
+        auto value_of = [&](unsigned nibble) -> AT {
+            if constexpr (kCustomValues) return code_value(a.values, nibble, AT());
+            else return (AT)decode4(nibble);
+        };
         XT xr0[C], xr1[C];
         bool live[C];
 #pragma unroll
@@ -364,9 +378,12 @@ fused_kernel(FusedArgs a)
             x0[c] = live[c] ? (AT)XTraits<XT>::load(&xr0[c]) : (AT)0;
             x1[c] = live[c] ? (AT)XTraits<XT>::load(&xr1[c]) : (AT)0;
         }
-        for (int c1 = tid / G; c1 < 16; c1 += kBuildParts) {
+#pragma unroll
+        for (int u = 0; u < kC1PerThread; ++u) {
+            const int c1 = tid / G + u * kBuildParts;
+            if (c1 >= 16) break;
             AT hi[C];
-            const AT w1 = (AT)decode4(c1);
+            const AT w1 = value_of((unsigned)c1);
 #pragma unroll
             for (int c = 0; c < C; ++c) hi[c] = w1 * x1[c];
             unsigned char* dst = lds + (size_t)(c1 * 16) * kCodeStride + g * kEntryBytes;
@@ -374,7 +391,7 @@ fused_kernel(FusedArgs a)
             for (int c0 = 0; c0 < 16; ++c0) {
                 Entry e;
 #pragma unroll
-                for (int c = 0; c < C; ++c) e.v[c] = EntryAcc<ET>::make(mul_add((AT)decode4(c0), x0[c], hi[c]));
+                for (int c = 0; c < C; ++c) e.v[c] = EntryAcc<ET>::make(mul_add(value_of((unsigned)c0), x0[c], hi[c]));
                 *(Entry*)(dst + c0 * kCodeStride) = e;
             }
         }
@@ -661,12 +678,12 @@ ShapeChoice pick_shape(const Plan& p, int requested_variant)
     return lb1 == 8 ? ShapeChoice{1, 64, 8, 4, 16} : ShapeChoice{1, 64, 16, 4, 8};
 }
 
-template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves>
+template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves, bool kCustomValues>
 int launch_one(const Plan& p, FusedArgs& a, hipStream_t s)
 {
     using AT = typename EntryAcc<ET>::type;
     constexpr int kFinal = LB / (G / 16);
-    auto kern = fused_kernel<XT, YT, ET, C, G, LB, kWaves>;
+    auto kern = fused_kernel<XT, YT, ET, C, G, LB, kWaves, kCustomValues>;
     a.fused_wgs = a.xcd_map ? (int)(p.ktiles * kXcds * ((a.row_groups + kXcds - 1) / kXcds)) : (int)(p.ktiles * a.row_groups);
     a.red_units = a.panels_total * a.col_passes;
     int64_t grid = a.fused_wgs;
@@ -680,6 +697,16 @@ int launch_one(const Plan& p, FusedArgs& a, hipStream_t s)
         MSGEMM_HIP_TRY(hipGetLastError());
     }
     return MSGEMM_OK;
+}
+
+// integer tables have the one encoding; floating-point ones also a form that reads the plan's map
+template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves>
+int launch_for_values(const Plan& p, FusedArgs& a, hipStream_t s)
+{
+    if constexpr (!std::is_same<ET, int>::value) {
+        if (p.custom_values) return launch_one<XT, YT, ET, C, G, LB, kWaves, true>(p, a, s);
+    }
+    return launch_one<XT, YT, ET, C, G, LB, kWaves, false>(p, a, s);
 }
 
 }  // namespace
@@ -798,6 +825,7 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     FusedArgs a;
     a.tiled = p.codes_tiled;
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy;
+    for (int i = 0; i < 16; ++i) a.values.v[i] = p.values[i];
     a.scales = (const __half*)p.scales_ordered;
     a.partials = p.partials;
     a.flags = p.flags;
@@ -835,7 +863,7 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     const int C = p.fs.cols, G = p.fs.groups, LB = p.fs.lane_bytes, EB = p.fs.entry_bytes;
 #define MSGEMM_CASE(CC, GG, LL, EE, XD, XT, YT, ET)                                   \
     if (C == CC && G == GG && LB == LL && EB == EE && p.x_dtype == XD)               \
-        return launch_one<XT, YT, ET, CC, GG, LL, (CC == 1 && LL == 8) ? 16 : 8>(p, a, s);
+        return launch_for_values<XT, YT, ET, CC, GG, LL, (CC == 1 && LL == 8) ? 16 : 8>(p, a, s);
     // single column, full-width entries
     MSGEMM_CASE(1, 64, 16, 4, MSGEMM_F32, float, float, float)
     MSGEMM_CASE(1, 64, 16, 4, MSGEMM_F16, __half, __half, float)

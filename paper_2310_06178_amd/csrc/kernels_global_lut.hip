@@ -26,7 +26,7 @@ __device__ __forceinline__ void group_span(const GroupGeom& g, int64_t jg, int64
 template <typename XT, typename LT>
 __global__ void __launch_bounds__(256)
 build_lut_kernel(GroupGeom g, int64_t groups, int64_t b, const XT* __restrict__ X, int64_t ldx,
-                 LT* __restrict__ L)
+                 ValueMap values, LT* __restrict__ L)
 {
     const int64_t E = (int64_t)1 << (4 * g.d);
     const int64_t total = groups * E * b;
@@ -41,7 +41,7 @@ build_lut_kernel(GroupGeom g, int64_t groups, int64_t b, const XT* __restrict__ 
         group_span(g, jg, first, len);
         LT s = 0;
         for (int r = 0; r < len; ++r) {
-            LT w = (LT)decode4((unsigned)(idx >> (4 * r)) & 15u);
+            LT w = code_value(values, (unsigned)(idx >> (4 * r)) & 15u, LT());
             s += w * (LT)XTraits<XT>::load(X + c * ldx + first + r);
         }
         L[t] = s;
@@ -104,24 +104,26 @@ inline unsigned grid_for(int64_t total, int threads)
 int launch_build_lut(const Plan& p, const void* X, int64_t ldx, void* L, hipStream_t s)
 {
     GroupGeom g{p.k, p.block, p.gpb, p.d};
+    ValueMap vm;
+    for (int i = 0; i < 16; ++i) vm.v[i] = p.values[i];
     const int64_t total = p.lut_groups * ((int64_t)1 << (4 * p.d)) * p.b;
     dim3 grid(grid_for(total, 256)), blk(256);
     switch (p.x_dtype) {
     case MSGEMM_F32:
         hipLaunchKernelGGL((build_lut_kernel<float, float>), grid, blk, 0, s, g, p.lut_groups, p.b,
-                           (const float*)X, ldx, (float*)L);
+                           (const float*)X, ldx, vm, (float*)L);
         break;
     case MSGEMM_F16:
         hipLaunchKernelGGL((build_lut_kernel<__half, float>), grid, blk, 0, s, g, p.lut_groups, p.b,
-                           (const __half*)X, ldx, (float*)L);
+                           (const __half*)X, ldx, vm, (float*)L);
         break;
     case MSGEMM_BF16:
         hipLaunchKernelGGL((build_lut_kernel<bf16_t, float>), grid, blk, 0, s, g, p.lut_groups, p.b,
-                           (const bf16_t*)X, ldx, (float*)L);
+                           (const bf16_t*)X, ldx, vm, (float*)L);
         break;
     case MSGEMM_I8:
         hipLaunchKernelGGL((build_lut_kernel<int8_t, int>), grid, blk, 0, s, g, p.lut_groups, p.b,
-                           (const int8_t*)X, ldx, (int*)L);
+                           (const int8_t*)X, ldx, vm, (int*)L);
         break;
     default:
         return MSGEMM_ERR_INVALID_ARG;

@@ -94,6 +94,10 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtyp
         }
     }
 
+    // the value of each 4-bit pattern: b(.) of Section 3.1 until the caller installs another map
+    for (int i = 0; i < 16; ++i) p->values[i] = (float)(((i ^ 8) & 15) - 8);
+    p->custom_values = false;
+
     // the plan's own copies of the weights
     const size_t code_bytes = (size_t)m * (size_t)(k / 2);
     e = hipMalloc((void**)&p->codes, code_bytes);
@@ -139,6 +143,21 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtyp
         if (rc != MSGEMM_OK) return fail(rc);
     }
     *out = reinterpret_cast<msgemm_plan_t*>(p);
+    return MSGEMM_OK;
+}
+
+int msgemm_plan_set_codebook(msgemm_plan_t* plan, const float* values16)
+{
+    if (!plan) return MSGEMM_ERR_INVALID_ARG;
+    Plan& p = *reinterpret_cast<Plan*>(plan);
+    float v[16];
+    for (int i = 0; i < 16; ++i) v[i] = values16 ? values16[i] : (float)(((i ^ 8) & 15) - 8);
+    for (int i = 0; i < 16; ++i)
+        if (!(v[i] == v[i]) || v[i] > 3.0e38f || v[i] < -3.0e38f) return MSGEMM_ERR_INVALID_ARG;  // NaN / infinity
+    // integer tables are built from b(.) itself: the int8 path keeps the paper's encoding
+    if (values16 && p.x_dtype == MSGEMM_I8) return MSGEMM_ERR_UNSUPPORTED;
+    for (int i = 0; i < 16; ++i) p.values[i] = v[i];  // travels in the arguments of every later launch
+    p.custom_values = values16 != nullptr;
     return MSGEMM_OK;
 }
 
@@ -199,7 +218,7 @@ int msgemm_dequant_mfma_run(const msgemm_plan_t* plan, const void* X, int64_t ld
     if (!plan || !X || !Y) return MSGEMM_ERR_INVALID_ARG;
     const Plan& p = *reinterpret_cast<const Plan*>(plan);
     if (ldx < p.k || ldy < p.m) return MSGEMM_ERR_INVALID_ARG;
-    if (p.x_dtype == MSGEMM_I8) return MSGEMM_ERR_UNSUPPORTED;
+    if (p.x_dtype == MSGEMM_I8 || p.custom_values) return MSGEMM_ERR_UNSUPPORTED;  // it dequantises with b(.) only
     return msgemm::launch_dequant_mfma(p, X, ldx, Y, ldy, (hipStream_t)stream);
 }
 

@@ -35,6 +35,8 @@ struct Plan {
     int64_t lut_groups;   // nblocks * gpb
     int device;
 
+    float values[16];     // value of each 4-bit pattern (b(.) of Section 3.1 by default)
+    bool custom_values;   // another encoding has been installed with msgemm_plan_set_codebook
     uint8_t* codes;       // device, [m][k/2], plan-owned copy
     uint16_t* scales;     // device fp16 [m][nblocks] or nullptr
     float* lut_ws;        // device workspace for the two-launch variant

@@ -417,3 +417,88 @@ def test_calibration_stream_read_entry_point():
             B.msgemm_calib_stream_read(buf, bad, sink)
     with pytest.raises(B.MsgemmError):
         B.msgemm_calib_stream_read(buf.data_ptr() + 4, unit, sink)
+
+
+# ---------------------------------------------------------------------------
+# other 16-value encodings of the codes (only b(.) changes)
+
+UINT4 = [float(i) for i in range(16)]
+NONUNIFORM = [0.0, 0.125, 0.25, 0.5, 1.0, 1.5, 2.5, 4.0, -6.0, -3.0, -2.0, -1.25, -0.75, -0.375, -0.1875, -0.0625]
+
+CODEBOOK_CASES = [
+    # m, k, b, xd, sg, d, variant
+    (700, 768, 1, "f16", 128, 2, B.VARIANT_FUSED_LDS),     # single-column fused kernel, several k-tiles
+    (300, 520, 2, "f32", 0, 2, B.VARIANT_FUSED_LDS),       # two column passes
+    (515, 512, 9, "f16", 128, 2, B.VARIANT_FUSED_LDS16),   # batched kernel, fp16 table values
+    (300, 260, 5, "bf16", 0, 2, B.VARIANT_FUSED_LDS16),
+    (260, 256, 6, "f32", 0, 2, B.VARIANT_FUSED_LDS),       # 4-column fp32 kernel
+    (64, 96, 3, "f16", 32, 1, B.VARIANT_GLOBAL_LUT),
+    (64, 96, 3, "f32", 0, 3, B.VARIANT_GLOBAL_LUT),
+]
+
+
+@pytest.mark.parametrize("table", [UINT4, NONUNIFORM])
+@pytest.mark.parametrize("m,k,b,xd,sg,d,variant", CODEBOOK_CASES)
+def test_codebook_against_oracle(m, k, b, xd, sg, d, variant, table):
+    codes = inputs.make_codes(m, k, seed=m + k + 1)
+    X = inputs.make_x(k, b, xd, seed=k + b + 3)
+    scales = inputs.make_scales(m, k, sg, seed=13) if sg else None
+    dC, dS, dX = torch_io.to_device(codes, "codes"), torch_io.to_device(scales, "scales"), torch_io.to_device(X, xd)
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], d, sg, dC, dS, variant)
+    try:
+        assert B.msgemm_plan_get_info(plan)["variant"] == variant
+        Y = torch_io.empty_output(b, m, Y_OF_X[xd])
+        B.msgemm_plan_set_codebook(plan, table)
+        B.msgemm_run(plan, dX, k, Y, m)
+        torch.cuda.synchronize()
+        ref = oracle.gemm_f64(codes, x_to_f64(X, xd), scales, sg, codebook=table)
+        check(torch_io.to_host(Y), ref, xd, "codebook")
+        # back to the paper's encoding
+        B.msgemm_plan_set_codebook(plan, None)
+        B.msgemm_run(plan, dX, k, Y, m)
+        torch.cuda.synchronize()
+        check(torch_io.to_host(Y), oracle_y(codes, X, xd, scales, sg), xd, "codebook restored")
+    finally:
+        B.msgemm_destroy(plan)
+
+
+def test_codebook_table_build_against_phase1_reference():
+    m, k, b, d = 8, 128, 2, 2
+    codes = inputs.make_codes(m, k, seed=1)
+    X = inputs.make_x(k, b, "f16", seed=2)
+    plan = B.msgemm_plan(m, k, b, "f16", "f16", d, 0, torch_io.to_device(codes, "codes"), None, B.VARIANT_GLOBAL_LUT)
+    try:
+        B.msgemm_plan_set_codebook(plan, NONUNIFORM)
+        G = oracle.lut_groups(k, d, 0)
+        L = torch.empty((G, 16 ** d, b), dtype=torch.float32, device="cuda:0")
+        B.msgemm_build_lut(plan, torch_io.to_device(X, "f16"), k, L)
+        torch.cuda.synchronize()
+        ref = oracle.lut_build(X.astype(np.float64), d, 0, codebook=NONUNIFORM)
+        # dyadic table values times fp16 activations: products exact, one rounding of the sum
+        assert np.array_equal(L.cpu().numpy(), ref.astype(np.float32))
+    finally:
+        B.msgemm_destroy(plan)
+
+
+def test_codebook_is_refused_where_it_cannot_apply():
+    dC = torch.zeros(64 * 32, dtype=torch.uint8, device="cuda:0")
+    plan = B.msgemm_plan(64, 64, 4, "i8", "i32", 2, 0, dC, None, B.VARIANT_AUTO)
+    try:
+        assert B.msgemm_plan_set_codebook(plan, UINT4, check=False) == B.ERR_UNSUPPORTED
+        assert B.msgemm_plan_set_codebook(plan, None, check=False) == B.OK
+    finally:
+        B.msgemm_destroy(plan)
+    plan = B.msgemm_plan(128, 128, 4, "f16", "f16", 2, 0, torch.zeros(128 * 64, dtype=torch.uint8, device="cuda:0"),
+                         None, B.VARIANT_AUTO)
+    try:
+        bad = list(UINT4)
+        bad[3] = float("nan")
+        assert B.msgemm_plan_set_codebook(plan, bad, check=False) == B.ERR_INVALID_ARG
+        B.msgemm_plan_set_codebook(plan, UINT4)
+        X = torch.zeros((4, 128), dtype=torch.float16, device="cuda:0")
+        Y = torch_io.empty_output(4, 128, "f16")
+        with pytest.raises(B.MsgemmError):
+            B.msgemm_dequant_mfma_run(plan, X, 128, Y, 128)
+    finally:
+        B.msgemm_destroy(plan)
+    assert B.msgemm_plan_set_codebook(None, UINT4, check=False) == B.ERR_INVALID_ARG
