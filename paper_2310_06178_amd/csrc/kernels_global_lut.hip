@@ -1,8 +1,23 @@
 // Two-launch msGeMM: the table L lives in device memory and is shared by all
-// rows (Section 4: "L computed in phase 1 is kept in cache").  Works for every
-// d in 1..4, every dtype pair and every scale block size; it is the reference
-// schedule on the GPU, not the fast one.
+// rows (Section 4: the table of phase 1 stays in cache for phase 2).  Works for
+// every d in 1..4, every dtype pair and every scale block size.
+//
+// Two consumers.  The plain one takes one thread per output and reads the
+// row-major codes nibble by nibble: any shape.  The tiled one needs scale blocks
+// that are whole 32-bit words of codes (block % 8 == 0) and a plan of this
+// variant (it reads a transposed copy of the codes made at plan time):
+//   * codes as [64-row tile][word of the row][lane]: the w-th words of 64 rows
+//     are one contiguous 256-byte load;
+//   * a thread owns one row and walks its code words three at a time (96 bits =
+//     24 nibbles hold a whole number of groups for every d), pulling the 4d-bit
+//     indices out with shifts whose amounts are compile-time constants;
+//   * the k dimension is cut into chunks of groups whose tables are about one
+//     MiB; a segment is a run of chunks, and the workgroups of one segment run
+//     on one XCD (ids congruent modulo 8), so the tables a workgroup gathers
+//     from are in that XCD's L2 after the first touch;
+//   * per-segment partial sums, then a reduction in segment order.
 #include "device_types.h"
+#include "fused_common.h"
 #include "msgemm_internal.h"
 
 namespace msgemm {
@@ -22,29 +37,35 @@ __device__ __forceinline__ void group_span(const GroupGeom& g, int64_t jg, int64
     len = (int)((first + g.d <= end) ? g.d : (end - first));
 }
 
-// Phase 1 (Section 3.1): one thread per (group, code combination, column).
+// Phase 1 (Section 3.1).  A workgroup writes kBuildPerWg consecutive entries of
+// one group: [code combination][column], the column fastest.
+constexpr int kBuildThreads = 256;
+constexpr int kBuildItems = 8;
+constexpr int kBuildPerWg = kBuildThreads * kBuildItems;
+
 template <typename XT, typename LT>
-__global__ void __launch_bounds__(256)
-build_lut_kernel(GroupGeom g, int64_t groups, int64_t b, const XT* __restrict__ X, int64_t ldx,
+__global__ void __launch_bounds__(kBuildThreads)
+build_lut_kernel(GroupGeom g, int parts, int b, const XT* __restrict__ X, int64_t ldx,
                  ValueMap values, LT* __restrict__ L)
 {
-    const int64_t E = (int64_t)1 << (4 * g.d);
-    const int64_t total = groups * E * b;
-    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total;
-         t += (int64_t)gridDim.x * blockDim.x) {
-        int64_t c = t % b;
-        int64_t rest = t / b;
-        int64_t idx = rest & (E - 1);
-        int64_t jg = rest >> (4 * g.d);
-        int64_t first;
-        int len;
-        group_span(g, jg, first, len);
+    const int64_t jg = blockIdx.x / (unsigned)parts;
+    const int part = (int)(blockIdx.x - (unsigned)jg * (unsigned)parts);
+    const unsigned per_group = (1u << (4 * g.d)) * (unsigned)b;
+    int64_t first;
+    int len;
+    group_span(g, jg, first, len);
+    LT* Lg = L + jg * (int64_t)per_group;
+#pragma unroll
+    for (int i = 0; i < kBuildItems; ++i) {
+        const unsigned t = (unsigned)part * kBuildPerWg + (unsigned)i * kBuildThreads + threadIdx.x;
+        if (t >= per_group) break;
+        const unsigned idx = b == 1 ? t : t / (unsigned)b;
+        const unsigned c = b == 1 ? 0u : t - idx * (unsigned)b;
+        const XT* xc = X + (int64_t)c * ldx + first;
         LT s = 0;
-        for (int r = 0; r < len; ++r) {
-            LT w = code_value(values, (unsigned)(idx >> (4 * r)) & 15u, LT());
-            s += w * (LT)XTraits<XT>::load(X + c * ldx + first + r);
-        }
-        L[t] = s;
+        for (int r = 0; r < len; ++r)
+            s += code_value(values, (idx >> (4 * r)) & 15u, LT()) * (LT)XTraits<XT>::load(xc + r);
+        Lg[t] = s;
     }
 }
 
@@ -92,6 +113,244 @@ consume_lut_kernel(GroupGeom g, int64_t m, int64_t b, int64_t nblocks,
     }
 }
 
+// ---------------------------------------------------------------------------
+// tiled consumer
+
+constexpr int kUnitWords = 3;       // code words a thread takes per step: 24 nibbles
+constexpr int kTiledThreads = 256;  // one row per thread
+
+struct TiledGeom {
+    int d;
+    int block_words;      // code words per scale block and row
+    int row_words;        // code words per row
+    int gpb;              // groups per block
+    int units_per_block;  // ceil(block_words / kUnitWords)
+    int chunk_units;      // units per chunk
+    int chunks_per_block;
+    int chunks;           // nblocks * chunks_per_block
+    int chunks_per_segment;
+    int segments;
+    int row_tiles;        // 64-row tiles that hold rows
+    int wg_rows;          // workgroups along m
+    int col_passes;
+    int xcd_map;          // 1: segment = id % 8 + 8 * ...
+};
+
+// Transposed copy of the codes: T[tile][word][lane] = word `word` of row tile*64+lane (zero beyond m, k).
+__global__ void __launch_bounds__(256)
+transpose_codes_kernel(const uint8_t* __restrict__ codes, uint32_t* __restrict__ T, int64_t m, int64_t row_bytes,
+                       int row_words, int64_t total)
+{
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int lane = (int)(t & 63);
+        const int64_t rest = t >> 6;
+        const int w = (int)(rest % row_words);
+        const int64_t row = (rest / row_words) * 64 + lane;
+        uint32_t v = 0;
+        if (row < m) {
+            for (int i = 0; i < 4; ++i) {
+                const int64_t at = (int64_t)w * 4 + i;
+                if (at < row_bytes) v |= (uint32_t)codes[row * row_bytes + at] << (8 * i);
+            }
+        }
+        T[t] = v;
+    }
+}
+
+// the 4*D-bit field number f of a 96-bit window (f is a constant once the caller's loop is unrolled)
+template <int D>
+__device__ __forceinline__ unsigned window_field(const uint32_t (&w)[kUnitWords], int f)
+{
+    constexpr int kBits = 4 * D;
+    constexpr unsigned mask = (1u << kBits) - 1u;
+    const int at = kBits * f;
+    const int word = at >> 5, shift = at & 31;
+    unsigned v = w[word] >> shift;
+    if (shift + kBits > 32) v |= w[word + 1 < kUnitWords ? word + 1 : word] << ((32 - shift) & 31);
+    return v & mask;
+}
+
+template <int D, typename LT, typename YT, int CB>
+__global__ void __launch_bounds__(kTiledThreads)
+consume_tiled_kernel(TiledGeom g, int64_t m, int b, int64_t nblocks, const uint32_t* __restrict__ T,
+                     const __half* __restrict__ scales, const LT* __restrict__ L, LT* __restrict__ partials,
+                     YT* __restrict__ Y, int64_t ldy)
+{
+    constexpr int kFields = 24 / D;  // groups per unit
+    constexpr unsigned E = 1u << (4 * D);
+    // which (segment, column pass, rows) this workgroup takes
+    int seg, rest;
+    const int per_seg = g.wg_rows * g.col_passes;
+    if (g.xcd_map) {
+        const int x = blockIdx.x % kXcds, j = blockIdx.x / kXcds;
+        seg = x + kXcds * (j / per_seg);
+        rest = j % per_seg;
+    } else {
+        seg = blockIdx.x / per_seg;
+        rest = blockIdx.x % per_seg;
+    }
+    const int cp = rest / g.wg_rows;
+    const int wr = rest - cp * g.wg_rows;
+    const int tile = wr * (kTiledThreads / 64) + (int)(threadIdx.x >> 6);
+    if (tile >= g.row_tiles) return;  // whole wavefront beyond m
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)tile * 64 + lane;
+    const bool live = row < m;
+    const int c0 = cp * CB;
+    const uint32_t* Trow = T + (int64_t)tile * g.row_words * 64 + lane;
+
+    LT y[CB];
+#pragma unroll
+    for (int c = 0; c < CB; ++c) y[c] = 0;
+
+    const int q_begin = seg * g.chunks_per_segment;
+    const int q_end = min(g.chunks, q_begin + g.chunks_per_segment);
+    for (int q = q_begin; q < q_end; ++q) {
+        const int blk = q / g.chunks_per_block;
+        const int u_begin = (q - blk * g.chunks_per_block) * g.chunk_units;
+        const int u_end = min(g.units_per_block, u_begin + g.chunk_units);
+        const uint32_t* Tblk = Trow + (int64_t)blk * g.block_words * 64;
+        // words past the end of the block read as zero: a short last group then
+        // indexes its table with zeros in the positions it does not have
+        auto load_unit = [&](int u, uint32_t (&w)[kUnitWords]) {
+#pragma unroll
+            for (int i = 0; i < kUnitWords; ++i) {
+                const int at = u * kUnitWords + i;
+                const uint32_t v = Tblk[(int64_t)min(at, g.block_words - 1) * 64];
+                w[i] = at < g.block_words ? v : 0u;
+            }
+        };
+        LT s[CB];
+#pragma unroll
+        for (int c = 0; c < CB; ++c) s[c] = 0;
+        uint32_t cur[kUnitWords], nxt[kUnitWords];
+        load_unit(u_begin, cur);
+        for (int u = u_begin; u < u_end; ++u) {
+            if (u + 1 < u_end) load_unit(u + 1, nxt);
+            const int t0 = u * kFields;
+            const LT* Lu = L + ((int64_t)blk * g.gpb + t0) * (int64_t)E * b + c0;
+            if (t0 + kFields <= g.gpb) {
+                // a whole unit: every look-up is requested before the first is added
+                LT got[kFields][CB];
+#pragma unroll
+                for (int f = 0; f < kFields; ++f) {
+                    const LT* e = Lu + (int64_t)f * E * b + (int64_t)window_field<D>(cur, f) * b;
+#pragma unroll
+                    for (int c = 0; c < CB; ++c) got[f][c] = (c0 + c < b) ? e[c] : (LT)0;
+                }
+#pragma unroll
+                for (int f = 0; f < kFields; ++f) {
+#pragma unroll
+                    for (int c = 0; c < CB; ++c) s[c] += got[f][c];
+                }
+            } else {
+                // the last unit of a block: only the groups the block has
+#pragma unroll
+                for (int f = 0; f < kFields; ++f) {
+                    if (t0 + f < g.gpb) {  // uniform
+                        const LT* e = Lu + (int64_t)f * E * b + (int64_t)window_field<D>(cur, f) * b;
+#pragma unroll
+                        for (int c = 0; c < CB; ++c) s[c] += (c0 + c < b) ? e[c] : (LT)0;
+                    }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < kUnitWords; ++i) cur[i] = nxt[i];
+        }
+        const int64_t at = live ? row * nblocks + blk : 0;
+#pragma unroll
+        for (int c = 0; c < CB; ++c) y[c] = add_block(scales, at, s[c], y[c]);
+    }
+    if (!live) return;
+#pragma unroll
+    for (int c = 0; c < CB; ++c) {
+        if (c0 + c >= b) break;
+        if (g.segments == 1) Y[(int64_t)(c0 + c) * ldy + row] = to_output<YT, LT>(y[c]);
+        else partials[((int64_t)seg * b + c0 + c) * m + row] = y[c];
+    }
+}
+
+// Y(i, c) = sum over segments, in segment order
+template <typename LT, typename YT>
+__global__ void __launch_bounds__(256)
+sum_segments_kernel(const LT* __restrict__ partials, YT* __restrict__ Y, int64_t ldy, int64_t m, int64_t b, int segments)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= m * b) return;
+    const int64_t c = t / m, row = t - c * m;
+    LT y = 0;
+    for (int sgm = 0; sgm < segments; ++sgm) y += partials[((int64_t)sgm * b + c) * m + row];
+    Y[c * ldy + row] = to_output<YT, LT>(y);
+}
+
+bool tiled_applies(const Plan& p)
+{
+    return p.variant == MSGEMM_VARIANT_GLOBAL_LUT && p.codes_words && (p.block % 8) == 0 &&
+           env_int("MSGEMM_TUNE_GLOBAL_PLAIN", 0) == 0;
+}
+
+TiledGeom tiled_geometry(const Plan& p, int cb)
+{
+    TiledGeom g{};
+    g.d = p.d;
+    g.block_words = (int)(p.block / 8);
+    g.row_words = (int)(p.k / 8);
+    g.gpb = (int)p.gpb;
+    g.units_per_block = (g.block_words + kUnitWords - 1) / kUnitWords;
+    // chunks of about one MiB of tables (tuning aid: MSGEMM_TUNE_GLOBAL_CHUNK_KIB)
+    const int64_t unit_bytes = (int64_t)(24 / p.d) * ((int64_t)1 << (4 * p.d)) * p.b * 4;
+    const int64_t want = (int64_t)env_int("MSGEMM_TUNE_GLOBAL_CHUNK_KIB", 1024) * 1024;
+    int64_t cu = want / unit_bytes;
+    if (cu < 1) cu = 1;
+    if (cu > g.units_per_block) cu = g.units_per_block;
+    g.chunk_units = (int)cu;
+    g.chunks_per_block = (g.units_per_block + g.chunk_units - 1) / g.chunk_units;
+    g.chunks = (int)(p.nblocks * g.chunks_per_block);
+    g.row_tiles = (int)((p.m + 63) / 64);
+    g.wg_rows = (g.row_tiles + kTiledThreads / 64 - 1) / (kTiledThreads / 64);
+    g.col_passes = (int)((p.b + cb - 1) / cb);
+    g.segments = p.global_segments;
+    g.chunks_per_segment = (g.chunks + g.segments - 1) / g.segments;
+    g.xcd_map = (g.segments % kXcds) == 0;
+    return g;
+}
+
+template <int D, typename LT, typename YT>
+int launch_tiled(const Plan& p, const void* L, void* Y, int64_t ldy, hipStream_t s)
+{
+    const int cb = p.b >= 4 ? 4 : (p.b >= 2 ? 2 : 1);
+    const TiledGeom g = tiled_geometry(p, cb);
+    const unsigned grid = (unsigned)g.segments * (unsigned)g.wg_rows * (unsigned)g.col_passes;
+    const __half* sc = (const __half*)p.scales;
+#define MSGEMM_TILED(CB)                                                                                   \
+    hipLaunchKernelGGL((consume_tiled_kernel<D, LT, YT, CB>), dim3(grid), dim3(kTiledThreads), 0, s, g, p.m, \
+                       (int)p.b, p.nblocks, p.codes_words, sc, (const LT*)L, (LT*)p.global_partials, (YT*)Y, ldy)
+    if (cb == 4) MSGEMM_TILED(4);
+    else if (cb == 2) MSGEMM_TILED(2);
+    else MSGEMM_TILED(1);
+#undef MSGEMM_TILED
+    MSGEMM_HIP_TRY(hipGetLastError());
+    if (g.segments > 1) {
+        const int64_t total = p.m * p.b;
+        hipLaunchKernelGGL((sum_segments_kernel<LT, YT>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                           (const LT*)p.global_partials, (YT*)Y, ldy, p.m, p.b, g.segments);
+        MSGEMM_HIP_TRY(hipGetLastError());
+    }
+    return MSGEMM_OK;
+}
+
+template <typename LT, typename YT>
+int launch_tiled_d(const Plan& p, const void* L, void* Y, int64_t ldy, hipStream_t s)
+{
+    switch (p.d) {
+    case 1: return launch_tiled<1, LT, YT>(p, L, Y, ldy, s);
+    case 2: return launch_tiled<2, LT, YT>(p, L, Y, ldy, s);
+    case 3: return launch_tiled<3, LT, YT>(p, L, Y, ldy, s);
+    case 4: return launch_tiled<4, LT, YT>(p, L, Y, ldy, s);
+    }
+    return MSGEMM_ERR_INVALID_ARG;
+}
+
 inline unsigned grid_for(int64_t total, int threads)
 {
     int64_t blocks = (total + threads - 1) / threads;
@@ -106,23 +365,25 @@ int launch_build_lut(const Plan& p, const void* X, int64_t ldx, void* L, hipStre
     GroupGeom g{p.k, p.block, p.gpb, p.d};
     ValueMap vm;
     for (int i = 0; i < 16; ++i) vm.v[i] = p.values[i];
-    const int64_t total = p.lut_groups * ((int64_t)1 << (4 * p.d)) * p.b;
-    dim3 grid(grid_for(total, 256)), blk(256);
+    const int64_t per_group = ((int64_t)1 << (4 * p.d)) * p.b;
+    const int64_t parts = (per_group + kBuildPerWg - 1) / kBuildPerWg;
+    if (per_group >= ((int64_t)1 << 31) || p.lut_groups * parts >= ((int64_t)1 << 31)) return MSGEMM_ERR_UNSUPPORTED;
+    dim3 grid((unsigned)(p.lut_groups * parts)), blk(kBuildThreads);
     switch (p.x_dtype) {
     case MSGEMM_F32:
-        hipLaunchKernelGGL((build_lut_kernel<float, float>), grid, blk, 0, s, g, p.lut_groups, p.b,
+        hipLaunchKernelGGL((build_lut_kernel<float, float>), grid, blk, 0, s, g, (int)parts, (int)p.b,
                            (const float*)X, ldx, vm, (float*)L);
         break;
     case MSGEMM_F16:
-        hipLaunchKernelGGL((build_lut_kernel<__half, float>), grid, blk, 0, s, g, p.lut_groups, p.b,
+        hipLaunchKernelGGL((build_lut_kernel<__half, float>), grid, blk, 0, s, g, (int)parts, (int)p.b,
                            (const __half*)X, ldx, vm, (float*)L);
         break;
     case MSGEMM_BF16:
-        hipLaunchKernelGGL((build_lut_kernel<bf16_t, float>), grid, blk, 0, s, g, p.lut_groups, p.b,
+        hipLaunchKernelGGL((build_lut_kernel<bf16_t, float>), grid, blk, 0, s, g, (int)parts, (int)p.b,
                            (const bf16_t*)X, ldx, vm, (float*)L);
         break;
     case MSGEMM_I8:
-        hipLaunchKernelGGL((build_lut_kernel<int8_t, int>), grid, blk, 0, s, g, p.lut_groups, p.b,
+        hipLaunchKernelGGL((build_lut_kernel<int8_t, int>), grid, blk, 0, s, g, (int)parts, (int)p.b,
                            (const int8_t*)X, ldx, vm, (int*)L);
         break;
     default:
@@ -134,6 +395,15 @@ int launch_build_lut(const Plan& p, const void* X, int64_t ldx, void* L, hipStre
 
 int launch_consume_lut(const Plan& p, const void* L, void* Y, int64_t ldy, hipStream_t s)
 {
+    if (tiled_applies(p)) {
+        switch (p.y_dtype) {
+        case MSGEMM_F32: return launch_tiled_d<float, float>(p, L, Y, ldy, s);
+        case MSGEMM_F16: return launch_tiled_d<float, __half>(p, L, Y, ldy, s);
+        case MSGEMM_BF16: return launch_tiled_d<float, bf16_t>(p, L, Y, ldy, s);
+        case MSGEMM_I32: return launch_tiled_d<int, int>(p, L, Y, ldy, s);
+        default: return MSGEMM_ERR_INVALID_ARG;
+        }
+    }
     GroupGeom g{p.k, p.block, p.gpb, p.d};
     dim3 grid(grid_for(p.m * p.b, 256)), blk(256);
     const __half* sc = (const __half*)p.scales;
@@ -157,6 +427,54 @@ int launch_consume_lut(const Plan& p, const void* L, void* Y, int64_t ldy, hipSt
     default:
         return MSGEMM_ERR_INVALID_ARG;
     }
+    MSGEMM_HIP_TRY(hipGetLastError());
+    return MSGEMM_OK;
+}
+
+// Plan-time part of the tiled consumer: how many segments, the transposed codes,
+// the partial sums.  Leaves the plan on the plain consumer when the shape does
+// not fit (p.codes_words stays null).
+int global_plan_setup(Plan& p, hipStream_t s)
+{
+    p.codes_words = nullptr;
+    p.global_partials = nullptr;
+    p.global_segments = 1;
+    if ((p.block % 8) != 0) return MSGEMM_OK;
+    if (p.k / 8 > 0x3fffffff || (p.m + 63) / 64 > 0x3fffffff || p.gpb > 0x3fffffff) return MSGEMM_OK;
+    // one table entry offset fits 32 bits with room to spare
+    if ((((int64_t)1 << (4 * p.d)) * p.b * 24) >= ((int64_t)1 << 31)) return MSGEMM_OK;
+    int cus = 256;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, p.device) == hipSuccess && prop.multiProcessorCount > 0)
+        cus = prop.multiProcessorCount;
+    p.cus = cus;
+    const int cb = p.b >= 4 ? 4 : (p.b >= 2 ? 2 : 1);
+    p.global_segments = 1;
+    TiledGeom g = tiled_geometry(p, cb);
+    if ((int64_t)g.chunks > 0x3fffffff) return MSGEMM_OK;
+    // enough workgroups for four per compute unit, in multiples of the XCD count
+    const int64_t per_seg = (int64_t)g.wg_rows * g.col_passes;
+    int seg = g.chunks < kXcds ? g.chunks : kXcds;
+    while (g.chunks >= kXcds && seg * per_seg < 4 * (int64_t)cus && 2 * seg <= g.chunks) seg *= 2;
+    const int forced = env_int("MSGEMM_TUNE_GLOBAL_SEGMENTS", 0);
+    if (forced >= 1 && forced <= g.chunks) seg = forced;
+    const int cps = (g.chunks + seg - 1) / seg;
+    seg = (g.chunks + cps - 1) / cps;
+    if (seg * per_seg >= ((int64_t)1 << 31)) return MSGEMM_OK;
+    p.global_segments = seg;
+
+    const int64_t words = (int64_t)g.row_tiles * g.row_words * 64;
+    MSGEMM_HIP_TRY(hipMalloc((void**)&p.codes_words, (size_t)words * 4u));
+    p.workspace_bytes += (size_t)words * 4u;
+    if (seg > 1) {
+        const size_t pb = (size_t)seg * (size_t)p.b * (size_t)p.m * 4u;
+        MSGEMM_HIP_TRY(hipMalloc((void**)&p.global_partials, pb));
+        p.workspace_bytes += pb;
+    }
+    int64_t blocks = (words + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(transpose_codes_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p.codes, p.codes_words, p.m,
+                       p.k / 2, g.row_words, words);
     MSGEMM_HIP_TRY(hipGetLastError());
     return MSGEMM_OK;
 }

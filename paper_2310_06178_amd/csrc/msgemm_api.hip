@@ -23,6 +23,8 @@ void free_plan(Plan* p)
     if (p->codes) (void)hipFree(p->codes);
     if (p->scales) (void)hipFree(p->scales);
     if (p->lut_ws) (void)hipFree(p->lut_ws);
+    if (p->codes_words) (void)hipFree(p->codes_words);
+    if (p->global_partials) (void)hipFree(p->global_partials);
     if (p->codes_tiled) (void)hipFree(p->codes_tiled);
     if (p->scales_ordered) (void)hipFree(p->scales_ordered);
     if (p->partials) (void)hipFree(p->partials);
@@ -117,6 +119,8 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtyp
         e = hipMalloc((void**)&p->lut_ws, p->lut_ws_bytes);
         if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
         p->workspace_bytes = p->lut_ws_bytes;
+        rc = msgemm::global_plan_setup(*p, s);
+        if (rc != MSGEMM_OK) return fail(rc);
     } else {
         const size_t tiled = (size_t)p->ktiles * (size_t)p->m_pad * (size_t)(p->fs.groups);
         const size_t b_pad = (size_t)p->col_passes * (size_t)p->fs.cols;

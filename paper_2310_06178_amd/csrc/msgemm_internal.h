@@ -41,6 +41,9 @@ struct Plan {
     uint16_t* scales;     // device fp16 [m][nblocks] or nullptr
     float* lut_ws;        // device workspace for the two-launch variant
     size_t lut_ws_bytes;
+    uint32_t* codes_words;   // two-launch variant: codes as [64-row tile][word of the row][lane], or nullptr
+    float* global_partials;  // two-launch variant: [segment][b][m] fp32 / int32, or nullptr
+    int global_segments;     // two-launch variant: runs of k handled by different workgroups
 
     // fused variant
     FusedShape fs;
@@ -72,6 +75,7 @@ void set_hip_error(hipError_t e);
 // kernels_global_lut.hip
 int launch_build_lut(const Plan& p, const void* X, int64_t ldx, void* L, hipStream_t s);
 int launch_consume_lut(const Plan& p, const void* L, void* Y, int64_t ldy, hipStream_t s);
+int global_plan_setup(Plan& p, hipStream_t s);  // transposed codes and partial sums of the tiled consumer
 
 // kernels_fused.hip
 int fused_choose_shape(Plan& p, int requested_variant);  // fills p.fs, ktiles, ...; MSGEMM_ERR_UNSUPPORTED if not applicable

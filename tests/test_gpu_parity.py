@@ -362,6 +362,38 @@ def test_config2_d3_sweep_point():
     check(out, oracle_y(codes, X, "f16", None, 0), "f16", "cfg2 d=3")
 
 
+@pytest.mark.parametrize("d", [1, 2, 3, 4])
+def test_config2_full_size_two_launch_variant(d):
+    """The table in device memory, the launch configuration the d-sweep is timed in."""
+    cfg, codes, X, scales = inputs.make_config("cfg2")
+    out, info = run_gpu(codes, X, cfg["x"], scales, cfg["scale_group"], d, B.VARIANT_GLOBAL_LUT)
+    assert info["variant"] == B.VARIANT_GLOBAL_LUT and info["d"] == d
+    check(out, oracle_y(codes, X, cfg["x"], scales, cfg["scale_group"]), cfg["x"], f"cfg2 two-launch d={d}")
+
+
+@pytest.mark.parametrize("m,k,b,xd,sg,d", [
+    (700, 2048, 1, "f16", 128, 3),   # several segments, short last group per block
+    (130, 1032, 3, "f32", 0, 3),     # one long block cut into chunks, ragged column pass
+    (257, 768, 5, "bf16", 64, 4),
+    (90, 512, 4, "i8", 0, 2),
+    (64, 4096, 2, "f16", 0, 1),
+])
+def test_two_launch_consumers_agree_with_oracle(monkeypatch, m, k, b, xd, sg, d):
+    """The tiled consumer and the plain one-thread-per-output consumer against the oracle."""
+    codes = inputs.make_codes(m, k, seed=m + d)
+    X = inputs.make_x(k, b, xd, seed=k + d)
+    scales = inputs.make_scales(m, k, sg, seed=8) if sg else None
+    ref = oracle_y(codes, X, xd, scales, sg)
+    monkeypatch.setenv("MSGEMM_TUNE_GLOBAL_CHUNK_KIB", "64")  # several chunks per block where the block is long
+    out_t, _ = run_gpu(codes, X, xd, scales, sg, d, B.VARIANT_GLOBAL_LUT, ldx_pad=2, ldy_pad=5)
+    check(out_t, ref, xd, "tiled consumer")
+    monkeypatch.setenv("MSGEMM_TUNE_GLOBAL_PLAIN", "1")
+    out_p, _ = run_gpu(codes, X, xd, scales, sg, d, B.VARIANT_GLOBAL_LUT, ldx_pad=2, ldy_pad=5)
+    check(out_p, ref, xd, "plain consumer")
+    if xd == "i8":
+        assert np.array_equal(out_t, out_p)
+
+
 # ---------------------------------------------------------------------------
 # the dense matrix-core comparison kernel (not msGeMM) computes the same Y
 
