@@ -157,6 +157,10 @@ transpose_codes_kernel(const uint8_t* __restrict__ codes, uint32_t* __restrict__
     }
 }
 
+template <typename T> __device__ __forceinline__ T bits_to(unsigned u);
+template <> __device__ __forceinline__ float bits_to<float>(unsigned u) { return __uint_as_float(u); }
+template <> __device__ __forceinline__ int bits_to<int>(unsigned u) { return (int)u; }
+
 // the 4*D-bit field number f of a 96-bit window (f is a constant once the caller's loop is unrolled)
 template <int D>
 __device__ __forceinline__ unsigned window_field(const uint32_t (&w)[kUnitWords], int f)
@@ -170,7 +174,8 @@ __device__ __forceinline__ unsigned window_field(const uint32_t (&w)[kUnitWords]
     return v & mask;
 }
 
-template <int D, typename LT, typename YT, int CB>
+// kVec (CB = 4 only): the four columns of a pass are one aligned 16-byte load.
+template <int D, typename LT, typename YT, int CB, bool kVec>
 __global__ void __launch_bounds__(kTiledThreads)
 consume_tiled_kernel(TiledGeom g, int64_t m, int b, int64_t nblocks, const uint32_t* __restrict__ T,
                      const __half* __restrict__ scales, const LT* __restrict__ L, LT* __restrict__ partials,
@@ -235,8 +240,14 @@ consume_tiled_kernel(TiledGeom g, int64_t m, int b, int64_t nblocks, const uint3
 #pragma unroll
                 for (int f = 0; f < kFields; ++f) {
                     const LT* e = Lu + (int64_t)f * E * b + (int64_t)window_field<D>(cur, f) * b;
+                    if constexpr (kVec) {
+                        const v4u raw = *(const v4u*)e;
 #pragma unroll
-                    for (int c = 0; c < CB; ++c) got[f][c] = (c0 + c < b) ? e[c] : (LT)0;
+                        for (int c = 0; c < CB; ++c) got[f][c] = bits_to<LT>(raw[c]);
+                    } else {
+#pragma unroll
+                        for (int c = 0; c < CB; ++c) got[f][c] = (c0 + c < b) ? e[c] : (LT)0;
+                    }
                 }
 #pragma unroll
                 for (int f = 0; f < kFields; ++f) {
@@ -322,12 +333,14 @@ int launch_tiled(const Plan& p, const void* L, void* Y, int64_t ldy, hipStream_t
     const TiledGeom g = tiled_geometry(p, cb);
     const unsigned grid = (unsigned)g.segments * (unsigned)g.wg_rows * (unsigned)g.col_passes;
     const __half* sc = (const __half*)p.scales;
-#define MSGEMM_TILED(CB)                                                                                   \
-    hipLaunchKernelGGL((consume_tiled_kernel<D, LT, YT, CB>), dim3(grid), dim3(kTiledThreads), 0, s, g, p.m, \
+    const bool vec = cb == 4 && (p.b % 4) == 0 && ((uintptr_t)L & 15u) == 0;
+#define MSGEMM_TILED(CB, VEC)                                                                                   \
+    hipLaunchKernelGGL((consume_tiled_kernel<D, LT, YT, CB, VEC>), dim3(grid), dim3(kTiledThreads), 0, s, g, p.m, \
                        (int)p.b, p.nblocks, p.codes_words, sc, (const LT*)L, (LT*)p.global_partials, (YT*)Y, ldy)
-    if (cb == 4) MSGEMM_TILED(4);
-    else if (cb == 2) MSGEMM_TILED(2);
-    else MSGEMM_TILED(1);
+    if (vec) MSGEMM_TILED(4, true);
+    else if (cb == 4) MSGEMM_TILED(4, false);
+    else if (cb == 2) MSGEMM_TILED(2, false);
+    else MSGEMM_TILED(1, false);
 #undef MSGEMM_TILED
     MSGEMM_HIP_TRY(hipGetLastError());
     if (g.segments > 1) {
@@ -458,7 +471,16 @@ int global_plan_setup(Plan& p, hipStream_t s)
     while (g.chunks >= kXcds && seg * per_seg < 4 * (int64_t)cus && 2 * seg <= g.chunks) seg *= 2;
     const int forced = env_int("MSGEMM_TUNE_GLOBAL_SEGMENTS", 0);
     if (forced >= 1 && forced <= g.chunks) seg = forced;
-    const int cps = (g.chunks + seg - 1) / seg;
+    int cps = (g.chunks + seg - 1) / seg;
+    // Workgroups of one segment that run side by side walk its chunks together,
+    // and the L2 then holds one chunk at a time.  Once a segment has more
+    // workgroups than an XCD runs at once they start at different times and are
+    // spread over all of its chunks: then keep a segment's tables within half an
+    // L2 (4 MiB per XCD).
+    const int64_t chunk_bytes = (int64_t)g.chunk_units * (24 / p.d) * ((int64_t)1 << (4 * p.d)) * p.b * 4;
+    const int64_t fit = ((int64_t)2 << 20) / chunk_bytes;
+    const bool staggered = per_seg > 4 * (int64_t)(cus / kXcds);
+    if (forced == 0 && staggered && cps > (fit < 1 ? 1 : fit)) cps = (int)(fit < 1 ? 1 : fit);
     seg = (g.chunks + cps - 1) / cps;
     if (seg * per_seg >= ((int64_t)1 << 31)) return MSGEMM_OK;
     p.global_segments = seg;
