@@ -100,6 +100,9 @@ struct FusedArgs {
     FastDiv div_ktiles, div_col_passes, div_tiles_per_block;
     int fused_wgs;          // workgroups of the grid that do the fused work; the rest reduce (in-launch mode)
     int red_units;          // (panel, column pass) pairs to reduce, one trailing workgroup each
+    int slices;             // partial sums per output: k-tiles, or k-segments in the long-k form
+    int tiles_per_segment;  // long-k form: k-tiles a workgroup runs through
+    FastDiv div_slices;
     ValueMap values;        // value of each 4-bit pattern; last, read only by the forms built for a custom map
 };
 
@@ -165,8 +168,8 @@ __device__ __forceinline__ void reduce_in_launch(const FusedArgs& a, int unit, i
     for (int i = 0; i < kFinal; ++i) sum[i] = 0;
     AT* wave_sums = (AT*)lds;  // [kRedSplit][kFinal][64]: consecutive lanes, consecutive banks
     if (w < kRedSplit) {
-        const int mine = w < a.ktiles ? (a.ktiles - w + kRedSplit - 1) / kRedSplit : 0;  // k-tiles of this wavefront
-        unsigned* flags = a.flags + (int64_t)unit * a.ktiles;
+        const int mine = w < a.slices ? (a.slices - w + kRedSplit - 1) / kRedSplit : 0;  // slices of this wavefront
+        unsigned* flags = a.flags + (int64_t)unit * a.slices;
         for (int base = 0; base < mine; base += 64) {
             const int idx = base + lane;
             const bool need = idx < mine;
@@ -558,6 +561,263 @@ fused_kernel(FusedArgs a)
     }
 }
 
+// ---------------------------------------------------------------------------
+// Long-k form of the single-column kernel.  When there are more (k-tile, row
+// group) pairs than compute units, a workgroup takes a *segment* of consecutive
+// k-tiles for its rows instead of one:
+//   * two table buffers (2 x 64 KiB): the four builder wavefronts build the
+//     tables of k-tile i + 1 while the eight streaming wavefronts gather from
+//     those of k-tile i, so the activations -> table start-up is paid once per
+//     workgroup and not once per k-tile;
+//   * a streaming wavefront keeps the scaled sums of its (at most two) panels in
+//     registers across the k-tiles: one partial sum per segment instead of one
+//     per k-tile, and its ring of code loads runs on across k-tile boundaries;
+//   * hand-over by counters in LDS, one pair per buffer: `built` (builder
+//     wavefronts that have finished a generation) and `done` (streaming
+//     wavefronts that have).  A builder waits for generation i - 2 to be consumed
+//     before it overwrites its buffer; a streamer waits for generation i to be
+//     built.  Each wait is for work that does not wait for the waiter: no cycle.
+// Same code layout, look-up, fold, scale and reduction as fused_kernel with
+// C = 1, G = 64, LB = 16.
+constexpr int kLongWaves = 8, kLongBuilders = 4, kLongTableBytes = 65536;
+
+template <typename XT, typename YT, typename ET, bool kCustomValues>
+__global__ void __launch_bounds__((kLongWaves + kLongBuilders) * 64)
+fused_long_kernel(FusedArgs a)
+{
+    using AT = typename EntryAcc<ET>::type;
+    constexpr int G = 64, LB = 16, NQ = 4, kFinal = 4, kPanelRows = 256;
+    constexpr int kRing = kRingBytes / LB < kLoadsPerPanel ? kRingBytes / LB : kLoadsPerPanel;
+    static_assert(sizeof(ET) == 4 && kLoadsPerPanel % kRing == 0, "entries are 4 bytes; ring period divides the panel");
+    using LoadT = uint4;
+
+    __shared__ __align__(16) unsigned char lds[2 * kLongTableBytes];
+    __shared__ unsigned built[2], done[2];  // per table buffer: generations i with i & 1 == index
+
+#define MSGEMM_ARG_NOW(x) asm volatile("" ::"s"(x))
+    MSGEMM_ARG_NOW((uint64_t)a.tiled); MSGEMM_ARG_NOW((uint64_t)a.X); MSGEMM_ARG_NOW(a.ldx);
+    MSGEMM_ARG_NOW((uint64_t)a.Y); MSGEMM_ARG_NOW(a.ldy); MSGEMM_ARG_NOW((uint64_t)a.scales);
+    MSGEMM_ARG_NOW((uint64_t)a.partials); MSGEMM_ARG_NOW(a.m); MSGEMM_ARG_NOW(a.k); MSGEMM_ARG_NOW(a.b);
+    MSGEMM_ARG_NOW(a.m_pad); MSGEMM_ARG_NOW(a.b_pad); MSGEMM_ARG_NOW(a.ktiles); MSGEMM_ARG_NOW(a.panels_total);
+    MSGEMM_ARG_NOW(a.panels_per_wg); MSGEMM_ARG_NOW(a.col_passes); MSGEMM_ARG_NOW(a.row_groups);
+    MSGEMM_ARG_NOW(a.xcd_map); MSGEMM_ARG_NOW(a.partial_span); MSGEMM_ARG_NOW(a.reduce_mode);
+    MSGEMM_ARG_NOW(a.slices); MSGEMM_ARG_NOW(a.tiles_per_segment); MSGEMM_ARG_NOW(a.fused_wgs);
+#undef MSGEMM_ARG_NOW
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = (tid >> 6) - kLongBuilders;  // streaming wavefront index; negative: builder
+    const int q = lane >> 4, j = lane & 15;
+
+    if ((int)blockIdx.x >= a.fused_wgs) {  // trailing workgroups: the reduction over the segments
+        reduce_in_launch<YT, AT, kFinal>(a, (int)blockIdx.x - a.fused_wgs, tid >> 6, lane, lds);
+        return;
+    }
+    int sgm, rg;
+    {
+        const uint32_t bid = blockIdx.x;
+        const uint32_t n = a.xcd_map ? bid / kXcds : bid;
+        const uint32_t nq = fast_div(n, a.div_slices);
+        sgm = (int)(n - nq * (uint32_t)a.slices);
+        rg = a.xcd_map ? (int)((bid % kXcds) + kXcds * nq) : (int)nq;
+        if (rg >= a.row_groups) return;
+    }
+    const int rb = (int)fast_div((uint32_t)rg, a.div_col_passes);
+    const int cp = rg - rb * a.col_passes;
+    const int64_t col0 = cp;
+    const int kt0 = sgm * a.tiles_per_segment;
+    const int ngen = min(a.ktiles - kt0, a.tiles_per_segment);  // >= 1: the host makes no empty segment
+
+    const int panel_first = rb * a.panels_per_wg;
+    int panels_here = a.panels_total - panel_first;
+    if (panels_here > a.panels_per_wg) panels_here = a.panels_per_wg;
+    const int active = panels_here < kLongWaves ? panels_here : kLongWaves;  // streaming wavefronts with work
+
+    if (tid < 2) {
+        built[tid] = 0;
+        done[tid] = 0;
+    }
+    __syncthreads();
+
+    if (wave < 0) {
+        // ---- builders: the tables of k-tile kt0 + i into buffer i & 1
+        const XT* __restrict__ X = (const XT*)a.X;
+        const int g = tid % G;
+        const int part = tid / G;  // 0..3: this thread's high codes are part, part + 4, ...
+        auto value_of = [&](unsigned nibble) -> AT {
+            if constexpr (kCustomValues) return code_value(a.values, nibble, AT());
+            else return (AT)decode4(nibble);
+        };
+        for (int i = 0; i < ngen; ++i) {
+            const int64_t kk = ((int64_t)(kt0 + i) * G + g) * 2;
+            const bool live = (col0 < a.b) && (kk < a.k);
+            const XT* px = X + (live ? col0 * a.ldx + kk : 0);
+            const XT xr0 = px[0], xr1 = px[1];  // requested before the wait below
+            if (i >= 2) {
+                // generation i - 2, the last to use this buffer, consumed by every streaming wavefront.
+                // (One counter per buffer: a wavefront that runs ahead can only add to the other one.)
+                const unsigned need = (unsigned)(i / 2) * (unsigned)active;
+                while (__hip_atomic_load(&done[i & 1], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < need)
+                    __builtin_amdgcn_s_sleep(1);
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            }
+            const AT x0 = live ? (AT)XTraits<XT>::load(&xr0) : (AT)0;
+            const AT x1 = live ? (AT)XTraits<XT>::load(&xr1) : (AT)0;
+            unsigned char* buf = lds + (i & 1) * kLongTableBytes;
+#pragma unroll
+            for (int u = 0; u < 16 / kLongBuilders; ++u) {
+                const int c1 = part + u * kLongBuilders;
+                const AT hi = value_of((unsigned)c1) * x1;
+                unsigned char* dst = buf + (size_t)(c1 * 16) * 256 + g * 4;
+#pragma unroll
+                for (int c0 = 0; c0 < 16; ++c0)
+                    *(ET*)(dst + c0 * 256) = EntryAcc<ET>::make(mul_add(value_of((unsigned)c0), x0, hi));
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            if (lane == 0) __hip_atomic_fetch_add(&built[i & 1], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        return;
+    }
+    if (wave >= active) return;  // nothing to stream; `done` does not count this wavefront
+
+    // ---- streamers
+    YT* __restrict__ Y = (YT*)a.Y;
+    const int npan = (panels_here - wave + kLongWaves - 1) / kLongWaves;  // 1 or 2
+    const int64_t step_stride = (int64_t)a.ktiles * a.panels_total * 64;  // LoadT elements between loads
+    auto unit_base = [&](int kt, int panel) {
+        return (const LoadT*)a.tiled + ((int64_t)kt * a.panels_total + panel) * 64 + lane;
+    };
+    const LoadT* cur = unit_base(kt0, panel_first + wave);
+    LoadT ring[kRing];
+#pragma unroll
+    for (int u = 0; u < kRing; ++u) {
+        ring[u] = cur[u * step_stride];
+        __builtin_amdgcn_sched_barrier(0);  // loads return in issue order: keep slot 0 first
+    }
+
+    __amdgpu_buffer_rsrc_t part_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)a.partials, 0, (int)a.partial_span, 0x00020000);
+    __amdgpu_buffer_rsrc_t scale_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(a.scales ? (const void*)a.scales : (const void*)a.tiled), 0, a.scales ? (int)a.scale_span : 0, 0x00020000);
+    const uint32_t class_base = (uint32_t)(16 * (q % NQ)) * 4u;
+
+    AT y_run[2][kFinal];
+#pragma unroll
+    for (int pi = 0; pi < 2; ++pi)
+#pragma unroll
+        for (int i = 0; i < kFinal; ++i) y_run[pi][i] = 0;
+
+    for (int gen = 0; gen < ngen; ++gen) {
+        const int kt = kt0 + gen;
+        const int scale_block = kt / a.tiles_per_block;
+        {
+            const unsigned need = (unsigned)(gen / 2 + 1) * kLongBuilders;  // this buffer's generations so far, all builders
+            while (__hip_atomic_load(&built[gen & 1], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < need)
+                __builtin_amdgcn_s_sleep(1);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        }
+        const uint32_t table_bit = (uint32_t)(gen & 1) << 16;  // which buffer: bit 16 of every LDS address
+#pragma unroll
+        for (int pi = 0; pi < 2; ++pi) {
+            if (pi >= npan) break;
+            const int panel_g = panel_first + wave + pi * kLongWaves;
+            // where the ring continues after this panel
+            const bool more = (pi + 1 < npan) || (gen + 1 < ngen);
+            const LoadT* nxt = (pi + 1 < npan) ? cur + kLongWaves * 64
+                             : (gen + 1 < ngen) ? unit_base(kt + 1, panel_first + wave) : cur;
+
+            struct alignas(8) PackedScales { __half h[kFinal]; };
+            PackedScales qraw;
+            if constexpr (__is_same(AT, float)) {
+                const int64_t qat = (int64_t)scale_block * a.m_pad + (int64_t)panel_g * kPanelRows + lane * kFinal;
+                const v2u qv = __builtin_amdgcn_raw_buffer_load_b64(scale_rsrc, (int)(qat * 2), 0, 0);
+                __builtin_memcpy(&qraw, &qv, sizeof(qraw));
+            }
+
+            AT acc[LB];
+#pragma unroll
+            for (int s = 0; s < LB; ++s) acc[s] = 0;
+            auto issue = [&](int t, ET (&dst)[LB]) {
+                const uint32_t lane_off = (class_base + (uint32_t)((j + t) & 15) * 4u) | table_bit;
+                const LoadT d = ring[t % kRing];
+#pragma unroll
+                for (int s = 0; s < LB; ++s) {
+                    const uint32_t w = load_word<LB>(d, s >> 2);
+                    // code byte into address bits 15:8, the lane's group offset in bits 7:0, the buffer in bit 16
+                    const uint32_t addr = __builtin_amdgcn_perm(w, lane_off, 0x0c020000u | ((4u + (s & 3)) << 8));
+                    dst[s] = *(const ET*)(lds + addr);
+                }
+                if (t + kRing < kLoadsPerPanel) {
+                    ring[t % kRing] = cur[(t + kRing) * step_stride];
+                } else if (more) {
+                    ring[t % kRing] = nxt[(t + kRing - kLoadsPerPanel) * step_stride];
+                }
+            };
+            auto consume = [&](const ET (&src)[LB]) {
+#pragma unroll
+                for (int s = 0; s < LB; ++s) {
+                    acc[s] += EntryAcc<ET>::widen(src[s]);
+                    asm volatile("" : "+v"(acc[s]));  // keep the adds in their stage
+                }
+            };
+            ET e0[LB], e1[LB];
+            issue(0, e0);
+#pragma unroll
+            for (int t = 0; t < kLoadsPerPanel; t += 2) {
+                issue(t + 1, e1);
+                consume(e0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (t + 2 < kLoadsPerPanel) issue(t + 2, e0);
+                consume(e1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // fold the four group classes: each lane ends with rows 64 * i + lane; then the block scale (Section 3.3)
+            AT half[LB / 2];
+#pragma unroll
+            for (int s = 0; s < LB / 2; ++s) half[s] = fold32(acc[s], acc[s + LB / 2]);
+#pragma unroll
+            for (int i = 0; i < kFinal; ++i) {
+                AT fin = fold16(half[i], half[i + kFinal]);
+                if constexpr (__is_same(AT, float)) fin *= (a.scales ? __half2float(qraw.h[i]) : 1.0f);
+                y_run[pi][i] += fin;
+            }
+            cur = nxt;
+        }
+        // every look-up of this generation has returned (its value has been added)
+        if (lane == 0) __hip_atomic_fetch_add(&done[gen & 1], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+
+    // ---- one sum per (segment, row): Y, or a partial with its flag
+    const uint32_t col_stride = (uint32_t)(a.m_pad * 4);
+    const uint32_t tile_stride = (uint32_t)(a.b_pad * a.m_pad * 4);
+    const bool in_launch = a.reduce_mode == kReduceInLaunch;
+#pragma unroll
+    for (int pi = 0; pi < 2; ++pi) {
+        if (pi >= npan) break;
+        const int panel_g = panel_first + wave + pi * kLongWaves;
+        if (a.reduce_mode == kReduceDirect) {
+#pragma unroll
+            for (int i = 0; i < kFinal; ++i) {
+                const int64_t row = (int64_t)panel_g * kPanelRows + lane + 64 * i;
+                if (row < a.m && col0 < a.b) Y[col0 * a.ldy + row] = to_output<YT, AT>(y_run[pi][i]);
+            }
+            continue;
+        }
+        unsigned out[kFinal];
+#pragma unroll
+        for (int i = 0; i < kFinal; ++i) out[i] = bits_of(y_run[pi][i]);
+        const uint32_t off = (uint32_t)sgm * tile_stride + (uint32_t)col0 * col_stride +
+                             (uint32_t)(panel_g * kPanelRows + lane * kFinal) * 4u;
+        if (in_launch) store_partials<kFinal, kAuxSc1>(part_rsrc, off, out);
+        else store_partials<kFinal, 0>(part_rsrc, off, out);
+        if (!in_launch) continue;
+        wait_vmem();
+        if (lane == 0)
+            __hip_atomic_store(a.flags + ((int64_t)panel_g * a.col_passes + cp) * a.slices + sgm, 1u, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 // Second pass of the k-tile reduction.  A workgroup of kReduceWaves wavefronts
 // owns 64 consecutive partial sums of one column; wavefront w adds the k-tiles
 // t = w, w + kReduceWaves, ... in increasing order, the wavefront sums are then
@@ -693,7 +953,27 @@ int launch_one(const Plan& p, FusedArgs& a, hipStream_t s)
     if (a.reduce_mode == kReduceSecondPass) {
         const int64_t blocks = (a.m_pad / 64) * a.b;
         hipLaunchKernelGGL((reduce_kernel<YT, AT, kFinal>), dim3((unsigned)blocks), dim3(kReduceWaves * 64), 0, s,
-                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.ktiles, a.partial_span);
+                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.slices, a.partial_span);
+        MSGEMM_HIP_TRY(hipGetLastError());
+    }
+    return MSGEMM_OK;
+}
+
+template <typename XT, typename YT, typename ET, bool kCustomValues>
+int launch_long(const Plan& p, FusedArgs& a, hipStream_t s)
+{
+    using AT = typename EntryAcc<ET>::type;
+    auto kern = fused_long_kernel<XT, YT, ET, kCustomValues>;
+    a.fused_wgs = a.xcd_map ? (int)(a.slices * kXcds * ((a.row_groups + kXcds - 1) / kXcds)) : (int)(a.slices * a.row_groups);
+    a.red_units = a.panels_total * a.col_passes;
+    int64_t grid = a.fused_wgs;
+    if (a.reduce_mode == kReduceInLaunch) grid += a.red_units;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3((kLongWaves + kLongBuilders) * 64), 0, s, a);
+    MSGEMM_HIP_TRY(hipGetLastError());
+    if (a.reduce_mode == kReduceSecondPass) {
+        const int64_t blocks = (a.m_pad / 64) * a.b;
+        hipLaunchKernelGGL((reduce_kernel<YT, AT, 4>), dim3((unsigned)blocks), dim3(kReduceWaves * 64), 0, s,
+                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.slices, a.partial_span);
         MSGEMM_HIP_TRY(hipGetLastError());
     }
     return MSGEMM_OK;
@@ -703,6 +983,14 @@ int launch_one(const Plan& p, FusedArgs& a, hipStream_t s)
 template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves>
 int launch_for_values(const Plan& p, FusedArgs& a, hipStream_t s)
 {
+    if constexpr (C == 1 && LB == 16) {
+        if (p.segments > 0) {  // long-k form
+            if constexpr (!std::is_same<ET, int>::value) {
+                if (p.custom_values) return launch_long<XT, YT, ET, true>(p, a, s);
+            }
+            return launch_long<XT, YT, ET, false>(p, a, s);
+        }
+    }
     if constexpr (!std::is_same<ET, int>::value) {
         if (p.custom_values) return launch_one<XT, YT, ET, C, G, LB, kWaves, true>(p, a, s);
     }
@@ -756,7 +1044,21 @@ int fused_choose_shape(Plan& p, int requested_variant)
     p.segments = 0;
     p.tiles_per_segment = 0;
     if (batched16) batched_choose_segments(p);
-    const int64_t slices = batched16 ? p.segments : p.ktiles;
+    // Single-column kernel, more (k-tile, row group) pairs than compute units: the
+    // long-k form, a workgroup per (run of k-tiles, row group), all in one round.
+    // MSGEMM_TUNE_LONGK = 1 keeps one k-tile per workgroup, n > 1 forces runs of n.
+    if (!batched16 && sc.C == 1 && sc.LB == 16 && ppw <= 2 * kLongWaves) {  // (a streaming wavefront holds two panels' sums)
+        const int64_t units = p.ktiles * row_groups;
+        int64_t tps = (units + cus - 1) / cus;
+        while (tps < p.ktiles && row_groups * ((p.ktiles + tps - 1) / tps) > cus) ++tps;
+        const int forced_tps = env_int("MSGEMM_TUNE_LONGK", 0);
+        if (forced_tps >= 1) tps = forced_tps < p.ktiles ? forced_tps : p.ktiles;
+        if (tps >= 2) {
+            p.tiles_per_segment = (int)tps;
+            p.segments = (int)((p.ktiles + tps - 1) / tps);
+        }
+    }
+    const int64_t slices = p.segments > 0 ? p.segments : p.ktiles;
     if (slices * p.col_passes * sc.C * p.m_pad * 4 >= 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
     if (p.nblocks * p.m_pad * 4 >= 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
     return MSGEMM_OK;
@@ -841,9 +1143,14 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     // one row block ids that are congruent modulo the XCD count keeps the traffic
     // on their shared counter and partials on one L2 slice.  Purely a locality
     // choice: the accesses are agent-coherent wherever the workgroups land.
-    a.xcd_map = (a.row_groups >= kXcds && env_int("MSGEMM_TUNE_XCD_MAP", 1)) ? 1 : 0;
+    // (Only when the row groups divide evenly over the XCDs: otherwise some XCDs
+    // would get twice the workgroups of others.)
+    a.xcd_map = (a.row_groups % kXcds == 0 && env_int("MSGEMM_TUNE_XCD_MAP", 1)) ? 1 : 0;
     a.nblocks = p.nblocks;
-    a.partial_span = (int64_t)p.ktiles * a.b_pad * p.m_pad * 4;
+    a.slices = p.segments > 0 ? p.segments : (int)p.ktiles;
+    a.tiles_per_segment = p.segments > 0 ? p.tiles_per_segment : 1;
+    a.div_slices = make_fastdiv((uint32_t)a.slices);
+    a.partial_span = (int64_t)a.slices * a.b_pad * p.m_pad * 4;
     a.scale_span = p.nblocks * p.m_pad * 2;  // nblocks <= ktiles: within the bound checked for the partials
     a.tiles_per_block = p.scale_group > 0 ? (int)(p.scale_group / (2 * p.fs.groups)) : 1;
     a.div_ktiles = make_fastdiv((uint32_t)a.ktiles);
@@ -854,7 +1161,7 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     // pass.  MSGEMM_TUNE_REDUCE = 1 (second pass) or 2 (in launch) overrides the
     // choice for the single-column kernels (tuning aid).
     a.reduce_mode = kReduceDirect;
-    if (p.ktiles > 1) {
+    if (a.slices > 1) {
         a.reduce_mode = p.fs.cols == 1 ? kReduceInLaunch : kReduceSecondPass;
         const int forced = env_int("MSGEMM_TUNE_REDUCE", 0);
         if (p.fs.cols == 1 && (forced == kReduceSecondPass || forced == kReduceInLaunch)) a.reduce_mode = forced;

@@ -308,6 +308,49 @@ def test_fused_k_tile_reduction_modes(monkeypatch, m, k, b, xd, sg, mode):
         B.msgemm_destroy(plan)
 
 
+LONG_K_CASES = [
+    # m, k, b, xd, sg, k-tiles per workgroup, panels per workgroup (0: the library's choice)
+    (700, 1024, 1, "f16", 128, 3, 0),     # 8 k-tiles in runs of 3, 3, 2
+    (300, 8320, 1, "f32", 0, 7, 0),       # 65 k-tiles in runs of 7: ten segments, the last two tiles long
+    (4100, 1280, 2, "i8", 0, 4, 16),      # 17 panels: two per wavefront and a second row block; two column passes
+    (2300, 768, 1, "bf16", 256, 2, 16),   # 9 panels: one wavefront with two; scale block = two k-tiles
+    (515, 640, 1, "f16", 128, 5, 0),      # one run holds all 5 k-tiles: written straight to Y
+    (1000, 512, 1, "f16", 128, 2, 4),     # fewer panels than streaming wavefronts: idle wavefronts
+]
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("m,k,b,xd,sg,tps,ppw", LONG_K_CASES)
+def test_fused_long_k_form(monkeypatch, m, k, b, xd, sg, tps, ppw, mode):
+    """The single-column kernel that runs through several k-tiles per workgroup
+    (two table buffers, sums kept in registers), forced on small shapes; both
+    reductions over the segments; twice on one plan."""
+    monkeypatch.setenv("MSGEMM_TUNE_LONGK", str(tps))
+    monkeypatch.setenv("MSGEMM_TUNE_REDUCE", str(mode))
+    if ppw:
+        monkeypatch.setenv("MSGEMM_TUNE_PPW", str(ppw))
+    codes = inputs.make_codes(m, k, seed=m + k + tps)
+    scales = inputs.make_scales(m, k, sg, seed=6) if sg else None
+    dC = torch_io.to_device(codes, "codes")
+    dS = torch_io.to_device(scales, "scales")
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS, B.VARIANT_FUSED_LDS)
+    try:
+        ktiles = -(-(k // 2) // 64)
+        assert B.msgemm_plan_get_info(plan)["split_k"] == -(-ktiles // tps)
+        for rep in range(2):
+            X = inputs.make_x(k, b, xd, seed=77 + rep)
+            dX = torch_io.to_device(X, xd)
+            Y = torch_io.empty_output(b, m, Y_OF_X[xd], ldy=m + 3)
+            Y.fill_(-3)
+            B.msgemm_run(plan, dX, k, Y, m + 3)
+            torch.cuda.synchronize()
+            out = torch_io.to_host(Y)
+            check(np.ascontiguousarray(out[:, :m]), oracle_y(codes, X, xd, scales, sg), xd,
+                  f"long-k tps {tps} reduce mode {mode} call {rep}")
+    finally:
+        B.msgemm_destroy(plan)
+
+
 def test_fused_repeated_calls_reuse_workspace():
     """Partial sums and arrival flags of one launch must not leak into the next."""
     m, k, b = 1000, 1024, 2
