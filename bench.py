@@ -239,7 +239,7 @@ def main() -> int:
             "workload": f"{args.config}: m={m} k={k} b={b} int4 W, {cfg['x']} X, {cfg['y']} Y, "
                         f"scale_group={cfg['scale_group']}, d={info['d']}",
             "variant": "dequant_mfma_comparison" if args.mfma else
-                       {1: "global_lut", 2: "fused_lds", 3: "fused_lds16"}[info["variant"]],
+                       {1: "global_lut", 2: "fused_lds", 3: "fused_lds16", 4: "global_lut_half"}[info["variant"]],
             "tile_rows": info["tile_rows"], "tile_groups": info["tile_groups"],
             "split_k": info["split_k"], "col_chunk": info["col_chunk"],
             "weight_copies_rotated": n_copies,

@@ -72,14 +72,25 @@ typedef enum {
     MSGEMM_VARIANT_GLOBAL_LUT = 1,
     /* One launch, d = 2: each workgroup builds the tables of its k-tile in LDS
      * (phase 1 and 2 pipelined over the last dimension of L, Section 4), streams
-     * its repacked code tile; partial sums over k-tiles are added by a small
-     * second kernel.  Table entries are fp32 (int32 for int8 X). */
+     * its repacked code tile; partial sums over k-tiles are added by trailing
+     * workgroups of the same launch (b <= 2) or by a small second kernel.
+     * Table entries are fp32 (int32 for int8 X). */
     MSGEMM_VARIANT_FUSED_LDS = 2,
     /* Same schedule with 16-bit table entries, 8 batch columns per entry: int16
      * for int8 X (exact), fp16 for fp16 / bf16 X (each entry rounded to fp16,
      * which needs |16 x| inside the fp16 range; accumulation stays fp32).
      * Not available for fp32 X.  AUTO picks it for b > 2. */
-    MSGEMM_VARIANT_FUSED_LDS16 = 3
+    MSGEMM_VARIANT_FUSED_LDS16 = 3,
+    /* GLOBAL_LUT with half of every table (the optimisation sketched in Section
+     * 4.1): only the combinations whose last code has its top bit clear are
+     * stored.  With a value map that satisfies value(~i) + value(i) = c for all i
+     * (two's complement: c = -1; uint4: c = 15) the other half follows from
+     *   L(~i_0, .., ~i_{d-1}, j) = c * S(j) - L(i_0, .., i_{d-1}, j),
+     * S(j) = the sum of the group's activations.  L_out of msgemm_build_lut is
+     * then [group][16^d / 2][b] followed by S as [group][b] (msgemm_lut_bytes
+     * covers both).  msgemm_plan_set_codebook refuses a map without that
+     * property on such a plan.  Never chosen by AUTO. */
+    MSGEMM_VARIANT_GLOBAL_LUT_HALF = 4
 } msgemm_variant_t;
 
 typedef struct {

@@ -45,12 +45,13 @@ constexpr int kBuildPerWg = kBuildThreads * kBuildItems;
 
 template <typename XT, typename LT>
 __global__ void __launch_bounds__(kBuildThreads)
-build_lut_kernel(GroupGeom g, int parts, int b, const XT* __restrict__ X, int64_t ldx,
+build_lut_kernel(GroupGeom g, int parts, int b, int half, const XT* __restrict__ X, int64_t ldx,
                  ValueMap values, LT* __restrict__ L)
 {
     const int64_t jg = blockIdx.x / (unsigned)parts;
     const int part = (int)(blockIdx.x - (unsigned)jg * (unsigned)parts);
-    const unsigned per_group = (1u << (4 * g.d)) * (unsigned)b;
+    // half tables: the combinations with the top bit of the last code clear are the first half of the index range
+    const unsigned per_group = ((1u << (4 * g.d)) >> half) * (unsigned)b;
     int64_t first;
     int len;
     group_span(g, jg, first, len);
@@ -67,6 +68,23 @@ build_lut_kernel(GroupGeom g, int parts, int b, const XT* __restrict__ X, int64_
             s += code_value(values, (idx >> (4 * r)) & 15u, LT()) * (LT)XTraits<XT>::load(xc + r);
         Lg[t] = s;
     }
+}
+
+// S(j, c): the sum of a group's activations (half tables: L(~idx) = c * S - L(idx), Section 4.1)
+template <typename XT, typename LT>
+__global__ void __launch_bounds__(256)
+group_sums_kernel(GroupGeom g, int64_t groups, int b, const XT* __restrict__ X, int64_t ldx, LT* __restrict__ S)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= groups * b) return;
+    const int64_t jg = t / b;
+    const int c = (int)(t - jg * b);
+    int64_t first;
+    int len;
+    group_span(g, jg, first, len);
+    LT sum = 0;
+    for (int r = 0; r < len; ++r) sum += (LT)XTraits<XT>::load(X + (int64_t)c * ldx + first + r);
+    S[t] = sum;
 }
 
 __device__ __forceinline__ unsigned code_at(const uint8_t* __restrict__ row, int64_t j)
@@ -86,11 +104,12 @@ __device__ __forceinline__ int add_block(const __half* __restrict__, int64_t, in
 // have been consumed (Section 3.3): one thread per output element.
 template <typename LT, typename YT>
 __global__ void __launch_bounds__(256)
-consume_lut_kernel(GroupGeom g, int64_t m, int64_t b, int64_t nblocks,
+consume_lut_kernel(GroupGeom g, int64_t m, int64_t b, int64_t nblocks, int half, LT half_c,
                    const uint8_t* __restrict__ codes, const __half* __restrict__ scales,
-                   const LT* __restrict__ L, YT* __restrict__ Y, int64_t ldy)
+                   const LT* __restrict__ L, const LT* __restrict__ S, YT* __restrict__ Y, int64_t ldy)
 {
     const int64_t E = (int64_t)1 << (4 * g.d);
+    const int64_t stored = E >> half;  // entries per group in memory
     const int64_t total = m * b;
     for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total;
          t += (int64_t)gridDim.x * blockDim.x) {
@@ -105,7 +124,12 @@ consume_lut_kernel(GroupGeom g, int64_t m, int64_t b, int64_t nblocks,
                 group_span(g, jg, first, len);
                 int64_t idx = 0;
                 for (int r = 0; r < len; ++r) idx |= (int64_t)code_at(row, first + r) << (4 * r);
-                s += L[(jg * E + idx) * b + c];
+                if (half && idx >= stored) {  // the stored entry is that of the complemented codes
+                    idx = ~idx & (E - 1);
+                    s += half_c * S[jg * b + c] - L[(jg * stored + idx) * b + c];
+                } else {
+                    s += L[(jg * stored + idx) * b + c];
+                }
             }
             y = add_block(scales, i * nblocks + blk, s, y);
         }
@@ -175,14 +199,17 @@ __device__ __forceinline__ unsigned window_field(const uint32_t (&w)[kUnitWords]
 }
 
 // kVec (CB = 4 only): the four columns of a pass are one aligned 16-byte load.
-template <int D, typename LT, typename YT, int CB, bool kVec>
+// kHalf: half tables (see build_lut_kernel): a look-up whose index has its top
+// bit set reads the entry of the complemented index and takes c * S - entry.
+template <int D, typename LT, typename YT, int CB, bool kVec, bool kHalf>
 __global__ void __launch_bounds__(kTiledThreads)
 consume_tiled_kernel(TiledGeom g, int64_t m, int b, int64_t nblocks, const uint32_t* __restrict__ T,
-                     const __half* __restrict__ scales, const LT* __restrict__ L, LT* __restrict__ partials,
-                     YT* __restrict__ Y, int64_t ldy)
+                     const __half* __restrict__ scales, const LT* __restrict__ L, const LT* __restrict__ S, LT half_c,
+                     LT* __restrict__ partials, YT* __restrict__ Y, int64_t ldy)
 {
     constexpr int kFields = 24 / D;  // groups per unit
-    constexpr unsigned E = 1u << (4 * D);
+    constexpr unsigned kAll = 1u << (4 * D);   // index range
+    constexpr unsigned E = kHalf ? kAll / 2 : kAll;  // entries per group in memory
     // which (segment, column pass, rows) this workgroup takes
     int seg, rest;
     const int per_seg = g.wg_rows * g.col_passes;
@@ -234,12 +261,20 @@ consume_tiled_kernel(TiledGeom g, int64_t m, int b, int64_t nblocks, const uint3
             if (u + 1 < u_end) load_unit(u + 1, nxt);
             const int t0 = u * kFields;
             const LT* Lu = L + ((int64_t)blk * g.gpb + t0) * (int64_t)E * b + c0;
+            const LT* Su = S + ((int64_t)blk * g.gpb + t0) * (int64_t)b + c0;  // group sums (half tables only)
             if (t0 + kFields <= g.gpb) {
                 // a whole unit: every look-up is requested before the first is added
                 LT got[kFields][CB];
+                unsigned flipped = 0;  // bit f: look-up f read the complemented entry
 #pragma unroll
                 for (int f = 0; f < kFields; ++f) {
-                    const LT* e = Lu + (int64_t)f * E * b + (int64_t)window_field<D>(cur, f) * b;
+                    unsigned idx = window_field<D>(cur, f);
+                    if constexpr (kHalf) {
+                        const unsigned top = idx >> (4 * D - 1);
+                        idx ^= (0u - top) & (kAll - 1u);
+                        flipped |= top << f;  // per lane
+                    }
+                    const LT* e = Lu + (int64_t)f * E * b + (int64_t)idx * b;
                     if constexpr (kVec) {
                         const v4u raw = *(const v4u*)e;
 #pragma unroll
@@ -252,16 +287,33 @@ consume_tiled_kernel(TiledGeom g, int64_t m, int b, int64_t nblocks, const uint3
 #pragma unroll
                 for (int f = 0; f < kFields; ++f) {
 #pragma unroll
-                    for (int c = 0; c < CB; ++c) s[c] += got[f][c];
+                    for (int c = 0; c < CB; ++c) {
+                        if constexpr (kHalf) {
+                            const LT sj = (c0 + c < b) ? Su[(int64_t)f * b + c] : (LT)0;  // uniform
+                            s[c] += ((flipped >> f) & 1u) ? half_c * sj - got[f][c] : got[f][c];
+                        } else {
+                            s[c] += got[f][c];
+                        }
+                    }
                 }
             } else {
                 // the last unit of a block: only the groups the block has
 #pragma unroll
                 for (int f = 0; f < kFields; ++f) {
                     if (t0 + f < g.gpb) {  // uniform
-                        const LT* e = Lu + (int64_t)f * E * b + (int64_t)window_field<D>(cur, f) * b;
+                        unsigned idx = window_field<D>(cur, f);
+                        unsigned top = 0;
+                        if constexpr (kHalf) {
+                            top = idx >> (4 * D - 1);
+                            idx ^= (0u - top) & (kAll - 1u);
+                        }
+                        const LT* e = Lu + (int64_t)f * E * b + (int64_t)idx * b;
 #pragma unroll
-                        for (int c = 0; c < CB; ++c) s[c] += (c0 + c < b) ? e[c] : (LT)0;
+                        for (int c = 0; c < CB; ++c) {
+                            if (c0 + c >= b) continue;
+                            if constexpr (kHalf) s[c] += top ? half_c * Su[(int64_t)f * b + c] - e[c] : e[c];
+                            else s[c] += e[c];
+                        }
                     }
                 }
             }
@@ -294,6 +346,12 @@ sum_segments_kernel(const LT* __restrict__ partials, YT* __restrict__ Y, int64_t
     Y[c * ldy + row] = to_output<YT, LT>(y);
 }
 
+// where the group sums start in a half-table L (in table elements)
+int64_t half_sums_offset(const Plan& p)
+{
+    return p.half_table ? p.lut_groups * (((int64_t)1 << (4 * p.d)) / 2) * p.b : 0;
+}
+
 bool tiled_applies(const Plan& p)
 {
     return p.variant == MSGEMM_VARIANT_GLOBAL_LUT && p.codes_words && (p.block % 8) == 0 &&
@@ -309,7 +367,7 @@ TiledGeom tiled_geometry(const Plan& p, int cb)
     g.gpb = (int)p.gpb;
     g.units_per_block = (g.block_words + kUnitWords - 1) / kUnitWords;
     // chunks of about one MiB of tables (tuning aid: MSGEMM_TUNE_GLOBAL_CHUNK_KIB)
-    const int64_t unit_bytes = (int64_t)(24 / p.d) * ((int64_t)1 << (4 * p.d)) * p.b * 4;
+    const int64_t unit_bytes = (int64_t)(24 / p.d) * (((int64_t)1 << (4 * p.d)) >> (p.half_table ? 1 : 0)) * p.b * 4;
     const int64_t want = (int64_t)env_int("MSGEMM_TUNE_GLOBAL_CHUNK_KIB", 1024) * 1024;
     int64_t cu = want / unit_bytes;
     if (cu < 1) cu = 1;
@@ -334,13 +392,19 @@ int launch_tiled(const Plan& p, const void* L, void* Y, int64_t ldy, hipStream_t
     const unsigned grid = (unsigned)g.segments * (unsigned)g.wg_rows * (unsigned)g.col_passes;
     const __half* sc = (const __half*)p.scales;
     const bool vec = cb == 4 && (p.b % 4) == 0 && ((uintptr_t)L & 15u) == 0;
-#define MSGEMM_TILED(CB, VEC)                                                                                   \
-    hipLaunchKernelGGL((consume_tiled_kernel<D, LT, YT, CB, VEC>), dim3(grid), dim3(kTiledThreads), 0, s, g, p.m, \
-                       (int)p.b, p.nblocks, p.codes_words, sc, (const LT*)L, (LT*)p.global_partials, (YT*)Y, ldy)
-    if (vec) MSGEMM_TILED(4, true);
-    else if (cb == 4) MSGEMM_TILED(4, false);
-    else if (cb == 2) MSGEMM_TILED(2, false);
-    else MSGEMM_TILED(1, false);
+    const LT* S = (const LT*)L + half_sums_offset(p);
+    const LT half_c = (LT)p.half_c;
+#define MSGEMM_TILED(CB, VEC, HALF)                                                                                  \
+    hipLaunchKernelGGL((consume_tiled_kernel<D, LT, YT, CB, VEC, HALF>), dim3(grid), dim3(kTiledThreads), 0, s, g,    \
+                       p.m, (int)p.b, p.nblocks, p.codes_words, sc, (const LT*)L, S, half_c, (LT*)p.global_partials, \
+                       (YT*)Y, ldy)
+#define MSGEMM_TILED_CB(HALF)                     \
+    if (vec) MSGEMM_TILED(4, true, HALF);         \
+    else if (cb == 4) MSGEMM_TILED(4, false, HALF); \
+    else if (cb == 2) MSGEMM_TILED(2, false, HALF); \
+    else MSGEMM_TILED(1, false, HALF)
+    if (p.half_table) { MSGEMM_TILED_CB(true); } else { MSGEMM_TILED_CB(false); }
+#undef MSGEMM_TILED_CB
 #undef MSGEMM_TILED
     MSGEMM_HIP_TRY(hipGetLastError());
     if (g.segments > 1) {
@@ -378,31 +442,56 @@ int launch_build_lut(const Plan& p, const void* X, int64_t ldx, void* L, hipStre
     GroupGeom g{p.k, p.block, p.gpb, p.d};
     ValueMap vm;
     for (int i = 0; i < 16; ++i) vm.v[i] = p.values[i];
-    const int64_t per_group = ((int64_t)1 << (4 * p.d)) * p.b;
+    const int half = p.half_table ? 1 : 0;
+    const int64_t per_group = (((int64_t)1 << (4 * p.d)) >> half) * p.b;
     const int64_t parts = (per_group + kBuildPerWg - 1) / kBuildPerWg;
     if (per_group >= ((int64_t)1 << 31) || p.lut_groups * parts >= ((int64_t)1 << 31)) return MSGEMM_ERR_UNSUPPORTED;
     dim3 grid((unsigned)(p.lut_groups * parts)), blk(kBuildThreads);
     switch (p.x_dtype) {
     case MSGEMM_F32:
-        hipLaunchKernelGGL((build_lut_kernel<float, float>), grid, blk, 0, s, g, (int)parts, (int)p.b,
+        hipLaunchKernelGGL((build_lut_kernel<float, float>), grid, blk, 0, s, g, (int)parts, (int)p.b, half,
                            (const float*)X, ldx, vm, (float*)L);
         break;
     case MSGEMM_F16:
-        hipLaunchKernelGGL((build_lut_kernel<__half, float>), grid, blk, 0, s, g, (int)parts, (int)p.b,
+        hipLaunchKernelGGL((build_lut_kernel<__half, float>), grid, blk, 0, s, g, (int)parts, (int)p.b, half,
                            (const __half*)X, ldx, vm, (float*)L);
         break;
     case MSGEMM_BF16:
-        hipLaunchKernelGGL((build_lut_kernel<bf16_t, float>), grid, blk, 0, s, g, (int)parts, (int)p.b,
+        hipLaunchKernelGGL((build_lut_kernel<bf16_t, float>), grid, blk, 0, s, g, (int)parts, (int)p.b, half,
                            (const bf16_t*)X, ldx, vm, (float*)L);
         break;
     case MSGEMM_I8:
-        hipLaunchKernelGGL((build_lut_kernel<int8_t, int>), grid, blk, 0, s, g, (int)parts, (int)p.b,
+        hipLaunchKernelGGL((build_lut_kernel<int8_t, int>), grid, blk, 0, s, g, (int)parts, (int)p.b, half,
                            (const int8_t*)X, ldx, vm, (int*)L);
         break;
     default:
         return MSGEMM_ERR_INVALID_ARG;
     }
     MSGEMM_HIP_TRY(hipGetLastError());
+    if (p.half_table) {
+        const int64_t total = p.lut_groups * p.b;
+        dim3 sgrid((unsigned)((total + 255) / 256));
+        const int64_t at = half_sums_offset(p);
+        switch (p.x_dtype) {
+        case MSGEMM_F32:
+            hipLaunchKernelGGL((group_sums_kernel<float, float>), sgrid, dim3(256), 0, s, g, p.lut_groups, (int)p.b,
+                               (const float*)X, ldx, (float*)L + at);
+            break;
+        case MSGEMM_F16:
+            hipLaunchKernelGGL((group_sums_kernel<__half, float>), sgrid, dim3(256), 0, s, g, p.lut_groups, (int)p.b,
+                               (const __half*)X, ldx, (float*)L + at);
+            break;
+        case MSGEMM_BF16:
+            hipLaunchKernelGGL((group_sums_kernel<bf16_t, float>), sgrid, dim3(256), 0, s, g, p.lut_groups, (int)p.b,
+                               (const bf16_t*)X, ldx, (float*)L + at);
+            break;
+        default:
+            hipLaunchKernelGGL((group_sums_kernel<int8_t, int>), sgrid, dim3(256), 0, s, g, p.lut_groups, (int)p.b,
+                               (const int8_t*)X, ldx, (int*)L + at);
+            break;
+        }
+        MSGEMM_HIP_TRY(hipGetLastError());
+    }
     return MSGEMM_OK;
 }
 
@@ -420,22 +509,23 @@ int launch_consume_lut(const Plan& p, const void* L, void* Y, int64_t ldy, hipSt
     GroupGeom g{p.k, p.block, p.gpb, p.d};
     dim3 grid(grid_for(p.m * p.b, 256)), blk(256);
     const __half* sc = (const __half*)p.scales;
+    const int half = p.half_table ? 1 : 0;
     switch (p.y_dtype) {
     case MSGEMM_F32:
-        hipLaunchKernelGGL((consume_lut_kernel<float, float>), grid, blk, 0, s, g, p.m, p.b, p.nblocks,
-                           p.codes, sc, (const float*)L, (float*)Y, ldy);
+        hipLaunchKernelGGL((consume_lut_kernel<float, float>), grid, blk, 0, s, g, p.m, p.b, p.nblocks, half, (float)p.half_c,
+                           p.codes, sc, (const float*)L, (const float*)L + half_sums_offset(p), (float*)Y, ldy);
         break;
     case MSGEMM_F16:
-        hipLaunchKernelGGL((consume_lut_kernel<float, __half>), grid, blk, 0, s, g, p.m, p.b, p.nblocks,
-                           p.codes, sc, (const float*)L, (__half*)Y, ldy);
+        hipLaunchKernelGGL((consume_lut_kernel<float, __half>), grid, blk, 0, s, g, p.m, p.b, p.nblocks, half, (float)p.half_c,
+                           p.codes, sc, (const float*)L, (const float*)L + half_sums_offset(p), (__half*)Y, ldy);
         break;
     case MSGEMM_BF16:
-        hipLaunchKernelGGL((consume_lut_kernel<float, bf16_t>), grid, blk, 0, s, g, p.m, p.b, p.nblocks,
-                           p.codes, sc, (const float*)L, (bf16_t*)Y, ldy);
+        hipLaunchKernelGGL((consume_lut_kernel<float, bf16_t>), grid, blk, 0, s, g, p.m, p.b, p.nblocks, half, (float)p.half_c,
+                           p.codes, sc, (const float*)L, (const float*)L + half_sums_offset(p), (bf16_t*)Y, ldy);
         break;
     case MSGEMM_I32:
-        hipLaunchKernelGGL((consume_lut_kernel<int, int>), grid, blk, 0, s, g, p.m, p.b, p.nblocks,
-                           p.codes, (const __half*)nullptr, (const int*)L, (int*)Y, ldy);
+        hipLaunchKernelGGL((consume_lut_kernel<int, int>), grid, blk, 0, s, g, p.m, p.b, p.nblocks, half, (int)p.half_c,
+                           p.codes, (const __half*)nullptr, (const int*)L, (const int*)L + half_sums_offset(p), (int*)Y, ldy);
         break;
     default:
         return MSGEMM_ERR_INVALID_ARG;
@@ -477,7 +567,8 @@ int global_plan_setup(Plan& p, hipStream_t s)
     // workgroups than an XCD runs at once they start at different times and are
     // spread over all of its chunks: then keep a segment's tables within half an
     // L2 (4 MiB per XCD).
-    const int64_t chunk_bytes = (int64_t)g.chunk_units * (24 / p.d) * ((int64_t)1 << (4 * p.d)) * p.b * 4;
+    const int64_t chunk_bytes =
+        (int64_t)g.chunk_units * (24 / p.d) * (((int64_t)1 << (4 * p.d)) >> (p.half_table ? 1 : 0)) * p.b * 4;
     const int64_t fit = ((int64_t)2 << 20) / chunk_bytes;
     const bool staggered = per_seg > 4 * (int64_t)(cus / kXcds);
     if (forced == 0 && staggered && cps > (fit < 1 ? 1 : fit)) cps = (int)(fit < 1 ? 1 : fit);

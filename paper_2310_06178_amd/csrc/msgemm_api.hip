@@ -34,7 +34,9 @@ void free_plan(Plan* p)
 
 size_t lut_bytes_of(const Plan& p)
 {
-    return (size_t)p.lut_groups * ((size_t)1 << (4 * p.d)) * (size_t)p.b * 4u;
+    const size_t entries = (size_t)1 << (4 * p.d);
+    if (p.half_table) return (size_t)p.lut_groups * (entries / 2 + 1) * (size_t)p.b * 4u;  // half tables, then the group sums
+    return (size_t)p.lut_groups * entries * (size_t)p.b * 4u;
 }
 
 }  // namespace
@@ -53,7 +55,9 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtyp
     if (m > ((int64_t)1 << 31) || k > ((int64_t)1 << 31) || b > 65536) return MSGEMM_ERR_INVALID_ARG;
     if (d < 0 || d > 4) return MSGEMM_ERR_INVALID_ARG;  // Section 5: d cannot usefully exceed 4
     if (!msgemm::dtype_pair_ok(x_dtype, y_dtype)) return MSGEMM_ERR_INVALID_ARG;
-    if (variant < MSGEMM_VARIANT_AUTO || variant > MSGEMM_VARIANT_FUSED_LDS16) return MSGEMM_ERR_INVALID_ARG;
+    if (variant < MSGEMM_VARIANT_AUTO || variant > MSGEMM_VARIANT_GLOBAL_LUT_HALF) return MSGEMM_ERR_INVALID_ARG;
+    const bool half_table = variant == MSGEMM_VARIANT_GLOBAL_LUT_HALF;
+    if (half_table) variant = MSGEMM_VARIANT_GLOBAL_LUT;
     if (scale_group < 0) return MSGEMM_ERR_INVALID_ARG;
     if (scale_group > 0) {
         if (!scales || x_dtype == MSGEMM_I8) return MSGEMM_ERR_INVALID_ARG;
@@ -76,6 +80,8 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtyp
     p->nblocks = k / p->block;
     p->gpb = (p->block + p->d - 1) / p->d;
     p->lut_groups = p->nblocks * p->gpb;
+    p->half_table = half_table;
+    p->half_c = -1.0f;  // two's complement: b(~i) = -1 - b(i)
 
     hipStream_t s = (hipStream_t)stream;
     int rc = MSGEMM_OK;
@@ -160,6 +166,13 @@ int msgemm_plan_set_codebook(msgemm_plan_t* plan, const float* values16)
         if (!(v[i] == v[i]) || v[i] > 3.0e38f || v[i] < -3.0e38f) return MSGEMM_ERR_INVALID_ARG;  // NaN / infinity
     // integer tables are built from b(.) itself: the int8 path keeps the paper's encoding
     if (values16 && p.x_dtype == MSGEMM_I8) return MSGEMM_ERR_UNSUPPORTED;
+    if (p.half_table) {
+        // half tables need value(~i) + value(i) to be one constant
+        const float c = v[0] + v[15];
+        for (int i = 1; i < 8; ++i)
+            if (v[i] + v[15 - i] != c) return MSGEMM_ERR_UNSUPPORTED;
+        p.half_c = c;
+    }
     for (int i = 0; i < 16; ++i) p.values[i] = v[i];  // travels in the arguments of every later launch
     p.custom_values = values16 != nullptr;
     return MSGEMM_OK;
@@ -171,7 +184,7 @@ int msgemm_plan_get_info(const msgemm_plan_t* plan, msgemm_plan_info_t* info)
     const Plan& p = *reinterpret_cast<const Plan*>(plan);
     info->m = p.m; info->k = p.k; info->b = p.b;
     info->x_dtype = p.x_dtype; info->y_dtype = p.y_dtype; info->lut_dtype = p.lut_dtype;
-    info->d = p.d; info->scale_group = p.scale_group; info->variant = p.variant;
+    info->d = p.d; info->scale_group = p.scale_group; info->variant = p.half_table ? (int)MSGEMM_VARIANT_GLOBAL_LUT_HALF : p.variant;
     info->lut_groups = p.lut_groups;
     const bool fused = p.variant != MSGEMM_VARIANT_GLOBAL_LUT;
     info->tile_rows = fused ? p.fs.tile_rows : 0;

@@ -41,6 +41,8 @@ struct Plan {
     uint16_t* scales;     // device fp16 [m][nblocks] or nullptr
     float* lut_ws;        // device workspace for the two-launch variant
     size_t lut_ws_bytes;
+    bool half_table;         // two-launch variant: only the half of each table with the last code's top bit clear
+    float half_c;            // value(~i) + value(i) of the plan's value map (half tables)
     uint32_t* codes_words;   // two-launch variant: codes as [64-row tile][word of the row][lane], or nullptr
     float* global_partials;  // two-launch variant: [segment][b][m] fp32 / int32, or nullptr
     int global_segments;     // two-launch variant: runs of k handled by different workgroups

@@ -438,6 +438,86 @@ def test_two_launch_consumers_agree_with_oracle(monkeypatch, m, k, b, xd, sg, d)
 
 
 # ---------------------------------------------------------------------------
+# half tables (Section 4.1): the two-launch variant storing only the combinations
+# whose last code has its top bit clear
+
+HALF_CASES = [
+    # m, k, b, xd, sg, d
+    (300, 520, 3, "f32", 0, 3),      # 520 = 173 * 3 + 1: a short last group; tiled consumer
+    (257, 384, 5, "f16", 128, 3),    # short last group in every block
+    (64, 256, 2, "bf16", 64, 2),
+    (131, 130, 4, "i8", 0, 2),       # k not a multiple of 8: the plain consumer
+    (90, 512, 4, "i8", 0, 1),        # 16-byte table reads
+    (40, 64, 1, "f16", 16, 4),
+    (2100, 1024, 1, "f16", 128, 3),  # several segments
+]
+
+
+@pytest.mark.parametrize("m,k,b,xd,sg,d", HALF_CASES)
+def test_half_table_variant_against_oracle(m, k, b, xd, sg, d):
+    codes = inputs.make_codes(m, k, seed=m + 3 * d)
+    X = inputs.make_x(k, b, xd, seed=k + d)
+    scales = inputs.make_scales(m, k, sg, seed=9) if sg else None
+    ref = oracle_y(codes, X, xd, scales, sg)
+    out, info = run_gpu(codes, X, xd, scales, sg, d, B.VARIANT_GLOBAL_LUT_HALF, ldx_pad=4, ldy_pad=2)
+    assert info["variant"] == B.VARIANT_GLOBAL_LUT_HALF and info["d"] == d
+    check(out, ref, xd, f"half tables d={d}")
+    out2, _ = run_gpu(codes, X, xd, scales, sg, d, B.VARIANT_GLOBAL_LUT_HALF, use_phases=True)
+    assert np.array_equal(out2, out), "phases called separately differ from msgemm_run"
+
+
+@pytest.mark.parametrize("xd,sg,d", [("f32", 0, 2), ("f16", 128, 3), ("i8", 0, 3), ("bf16", 0, 1)])
+def test_half_table_contents_against_phase1_reference(xd, sg, d):
+    """L_out = the first half of the oracle's table (last code 0..7), then S(j) =
+    the oracle's entry for codes 0001..0001 (b = 1: the plain sum of the group)."""
+    m, k, b = 8, 256, 3
+    codes = inputs.make_codes(m, k, seed=1)
+    X = inputs.make_x(k, b, xd, seed=2)
+    scales = inputs.make_scales(m, k, sg, seed=3) if sg else None
+    dC, dS = torch_io.to_device(codes, "codes"), torch_io.to_device(scales, "scales")
+    dX = torch_io.to_device(X, xd)
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], d, sg, dC, dS, B.VARIANT_GLOBAL_LUT_HALF)
+    try:
+        G, E = oracle.lut_groups(k, d, sg), 16 ** d
+        assert B.msgemm_lut_bytes(plan) == G * (E // 2 + 1) * b * 4
+        L = torch.empty(G * (E // 2 + 1) * b, dtype=torch.int32 if xd == "i8" else torch.float32, device="cuda:0")
+        B.msgemm_build_lut(plan, dX, k, L)
+        torch.cuda.synchronize()
+        Lh = L.cpu().numpy()
+    finally:
+        B.msgemm_destroy(plan)
+    table = Lh[: G * (E // 2) * b].reshape(G, E // 2, b)
+    sums = Lh[G * (E // 2) * b:].reshape(G, b)
+    ref = oracle.lut_build(X if xd == "i8" else x_to_f64(X, xd), d, sg)
+    ones = sum(1 << (4 * r) for r in range(d))
+    if xd == "i8":
+        assert np.array_equal(table, ref[:, : E // 2, :]) and np.array_equal(sums, ref[:, ones, :])
+    else:
+        tol = d * 2.0 ** -23 * np.abs(ref).max()
+        assert np.max(np.abs(table.astype(np.float64) - ref[:, : E // 2, :])) <= tol
+        assert np.max(np.abs(sums.astype(np.float64) - ref[:, ones, :])) <= tol
+
+
+def test_half_table_value_maps():
+    """An unsigned map has value(~i) + value(i) = 15 and works with half tables; a map without such a constant is refused."""
+    m, k, b, d = 200, 384, 2, 3
+    codes = inputs.make_codes(m, k, seed=21)
+    X = inputs.make_x(k, b, "f16", seed=22)
+    dC, dX = torch_io.to_device(codes, "codes"), torch_io.to_device(X, "f16")
+    plan = B.msgemm_plan(m, k, b, "f16", "f16", d, 0, dC, None, B.VARIANT_GLOBAL_LUT_HALF)
+    try:
+        assert B.msgemm_plan_set_codebook(plan, NONUNIFORM, check=False) == B.ERR_UNSUPPORTED
+        B.msgemm_plan_set_codebook(plan, UINT4)
+        Y = torch_io.empty_output(b, m, "f16")
+        B.msgemm_run(plan, dX, k, Y, m)
+        torch.cuda.synchronize()
+        ref = oracle.gemm_f64(codes, x_to_f64(X, "f16"), codebook=UINT4)
+        check(torch_io.to_host(Y), ref, "f16", "half tables, unsigned map")
+    finally:
+        B.msgemm_destroy(plan)
+
+
+# ---------------------------------------------------------------------------
 # the dense matrix-core comparison kernel (not msGeMM) computes the same Y
 
 @pytest.mark.parametrize("m,k,b,xd,sg", [

@@ -447,3 +447,26 @@ def test_codebook_lut_enumeration(d):
     direct = oracle.gemm_f64(codes, X, codebook=NONUNIFORM)
     via = oracle.lut_consume(codes, oracle.lut_build(X, d, codebook=NONUNIFORM), d)
     assert np.array_equal(direct, via)
+
+
+# ---------------------------------------------------------------------------
+# the linearity remark of Section 4.1 as an invariant of the oracle's tables
+
+@pytest.mark.parametrize("d", [1, 2, 3])
+def test_table_of_complemented_codes_follows_from_the_other_half(d):
+    """Two's complement has b(~i) = -1 - b(i), so complementing every code of an
+    index gives L(~idx, j) = -S(j) - L(idx, j) with S(j) the sum of the group's
+    activations; S(j) itself is the entry whose codes are all 0001 (b = 1).  A
+    dropped term or a wrong sign in the table builder breaks this for some idx."""
+    k, b = 12 * d, 2
+    X = inputs.make_x(k, b, "f32", seed=40 + d).astype(np.float64)
+    L = oracle.lut_build(X, d)
+    E = 16 ** d
+    ones = sum(1 << (4 * r) for r in range(d))
+    S = L[:, ones, :]
+    assert np.allclose(S, X.reshape(b, k // d, d).sum(axis=2).T, rtol=0, atol=1e-12)
+    idx = np.arange(E)
+    assert np.allclose(L[:, (~idx) & (E - 1), :], -S[:, None, :] - L[:, idx, :], rtol=0, atol=1e-9)
+    # an unsigned map (value = pattern) has value(~i) = 15 - value(i)
+    Lu = oracle.lut_build(X, d, codebook=np.arange(16, dtype=np.float64))
+    assert np.allclose(Lu[:, (~idx) & (E - 1), :], 15.0 * S[:, None, :] - Lu[:, idx, :], rtol=0, atol=1e-9)
