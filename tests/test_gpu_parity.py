@@ -397,6 +397,24 @@ def test_config_full_size(name):
     print(f"{name}: rows checked {len(rows)}/{m}, rel L2 {err:.3e}")
 
 
+@pytest.mark.parametrize("m,k,xd,sg", [
+    ((1 << 20) + 3, 1024, "f16", 128),   # a million rows: 4097 panels, offsets of the partial buffer near their range
+    (515, 1 << 18, "f16", 0),            # 2048 k-tiles: the long-k form at scale
+    (259, 1 << 17, "i8", 0),             # the same with integer tables
+])
+def test_extreme_aspect_ratios(m, k, xd, sg):
+    """Very tall and very wide problems (b = 1); the oracle takes a seeded sample of rows."""
+    codes = inputs.make_codes(m, k, seed=17)
+    X = inputs.make_x(k, 1, xd, seed=18)
+    scales = inputs.make_scales(m, k, sg, seed=19) if sg else None
+    out, info = run_gpu(codes, X, xd, scales, sg, 2, B.VARIANT_AUTO)
+    assert info["variant"] == B.VARIANT_FUSED_LDS
+    rows = np.sort(np.random.default_rng(5).choice(m, size=min(m, 4096), replace=False))
+    rows[0], rows[-1] = 0, m - 1
+    ref = oracle_y(codes[rows], X, xd, None if scales is None else scales[rows], sg)
+    check(np.ascontiguousarray(out[:, rows]), ref, xd, f"{m}x{k}")
+
+
 def test_config2_d3_sweep_point():
     """Config 2 also asks for d = 3 (k = 4096 is not a multiple of 3: short last group)."""
     cfg, codes, X, _ = inputs.make_config("cfg2", m=2048)
