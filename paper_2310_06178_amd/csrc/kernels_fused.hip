@@ -999,6 +999,43 @@ int launch_for_values(const Plan& p, FusedArgs& a, hipStream_t s)
 
 }  // namespace
 
+namespace {
+// Panels per workgroup and k-tiles per workgroup of the single-column kernel.
+// A workgroup's time is counted in units of one panel per streaming wavefront
+// (8 panels of 16 KiB: about 5 us of a compute unit's share of the stream) plus
+// half a unit for the activations -> table start-up, which the long-k form pays
+// once per workgroup; the workgroups run in rounds over the compute units; a
+// reduction over several slices costs a little at the end.  The cheapest of the
+// candidates wins, the first of equals (more panels, shorter runs).
+void choose_rows_and_segments(int64_t panels, int64_t ktiles, int col_passes, int cus, int& ppw_out, int64_t& tps_out)
+{
+    double best = 1e300;
+    for (int ppw = 2 * kLongWaves; ppw >= 1; ppw >>= 1) {
+        const int64_t row_groups = ((panels + ppw - 1) / ppw) * col_passes;
+        const int64_t here = panels < ppw ? panels : ppw;
+        // (up to four panels: as many wavefronts stream, and what they keep in flight bounds the compute unit's rate)
+        const double per_tile = here > 4 ? (double)here / kLongWaves : 0.57;
+        int64_t last_tps = 0;
+        for (int64_t segs = ktiles; segs >= 1; segs = segs > 4 * (int64_t)cus ? 4 * (int64_t)cus : segs - 1) {
+            const int64_t tps = (ktiles + segs - 1) / segs;
+            if (tps == last_tps) continue;
+            last_tps = tps;
+            if (tps > 1 && ppw < kLongWaves) break;  // runs of k-tiles only with every streaming wavefront at work
+            const int64_t n_seg = (ktiles + tps - 1) / tps;
+            const int64_t wgs = row_groups * n_seg;
+            const double rounds = wgs <= 4 * (int64_t)cus ? (double)((wgs + cus - 1) / cus) : (double)wgs / cus + 0.5;
+            const double idle = wgs < cus ? 0.2 * (double)(cus - wgs) / cus : 0.0;  // equal otherwise: the wider spread wins
+            const double cost = rounds * ((double)tps * per_tile + 0.5) + (n_seg > 1 ? 0.3 : 0.0) + idle + 0.1 * (rounds - 1.0);  // (rounds do not line up as neatly as counted)
+            if (cost < best - 1e-9) {
+                best = cost;
+                ppw_out = ppw;
+                tps_out = tps;
+            }
+        }
+    }
+}
+}  // namespace
+
 int fused_choose_shape(Plan& p, int requested_variant)
 {
     if (p.d != 2) return MSGEMM_ERR_UNSUPPORTED;
@@ -1030,10 +1067,16 @@ int fused_choose_shape(Plan& p, int requested_variant)
     // (The batched 16-bit kernel keeps one panel per wavefront and runs through
     // several k-tiles instead; its split over k is chosen below.)
     const bool batched16 = sc.entry_bytes == 2;
+    const bool can_run_long = !batched16 && sc.C == 1 && sc.LB == 16;  // the long-k form exists for this kernel
     int ppw = batched16 ? sc.waves : 2 * sc.waves;
     while (ppw > 1 && (int64_t)p.ktiles * p.col_passes * ((panels + ppw - 1) / ppw) < cus) ppw >>= 1;
+    int64_t tps = 1;
+    if (can_run_long) choose_rows_and_segments(panels, p.ktiles, p.col_passes, cus, ppw, tps);
     const int forced = env_int("MSGEMM_TUNE_PPW", 0);
     if (forced >= 1 && forced <= 64) ppw = forced;
+    // MSGEMM_TUNE_LONGK = 1 keeps one k-tile per workgroup, n > 1 forces runs of n (tuning aid).
+    const int forced_tps = env_int("MSGEMM_TUNE_LONGK", 0);
+    if (forced_tps >= 1) tps = forced_tps < p.ktiles ? forced_tps : p.ktiles;
     fs.panels = ppw;
     fs.tile_rows = ppw * fs.panel_rows;
     p.row_blocks = (panels + ppw - 1) / ppw;
@@ -1044,19 +1087,10 @@ int fused_choose_shape(Plan& p, int requested_variant)
     p.segments = 0;
     p.tiles_per_segment = 0;
     if (batched16) batched_choose_segments(p);
-    // Single-column kernel, more (k-tile, row group) pairs than compute units: the
-    // long-k form, a workgroup per (run of k-tiles, row group), all in one round.
-    // MSGEMM_TUNE_LONGK = 1 keeps one k-tile per workgroup, n > 1 forces runs of n.
-    if (!batched16 && sc.C == 1 && sc.LB == 16 && ppw <= 2 * kLongWaves) {  // (a streaming wavefront holds two panels' sums)
-        const int64_t units = p.ktiles * row_groups;
-        int64_t tps = (units + cus - 1) / cus;
-        while (tps < p.ktiles && row_groups * ((p.ktiles + tps - 1) / tps) > cus) ++tps;
-        const int forced_tps = env_int("MSGEMM_TUNE_LONGK", 0);
-        if (forced_tps >= 1) tps = forced_tps < p.ktiles ? forced_tps : p.ktiles;
-        if (tps >= 2) {
-            p.tiles_per_segment = (int)tps;
-            p.segments = (int)((p.ktiles + tps - 1) / tps);
-        }
+    // (a streaming wavefront of the long-k form holds the sums of at most two panels)
+    if (can_run_long && ppw <= 2 * kLongWaves && tps >= 2) {
+        p.tiles_per_segment = (int)tps;
+        p.segments = (int)((p.ktiles + tps - 1) / tps);
     }
     const int64_t slices = p.segments > 0 ? p.segments : p.ktiles;
     if (slices * p.col_passes * sc.C * p.m_pad * 4 >= 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
