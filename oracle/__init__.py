@@ -46,6 +46,7 @@ def _load():
         lib.msgemm_oracle_set_threads.argtypes = [ci]
         lib.msgemm_oracle_gemm_f64.argtypes = [i64, i64, i64, vp, vp, i64, vp, i64, vp, i64]
         lib.msgemm_oracle_gemm_f64_values.argtypes = [i64, i64, i64, vp, vp, vp, i64, vp, i64, vp, i64]
+        lib.msgemm_oracle_gemm_f64_codes8.argtypes = [i64, i64, i64, vp, vp, vp, i64, vp, i64, vp, i64]
         lib.msgemm_oracle_lut_build_f64_values.argtypes = [i64, i64, ci, i64, vp, vp, i64, vp]
         lib.msgemm_oracle_gemm_i32.argtypes = [i64, i64, i64, vp, vp, i64, vp, i64]
         lib.msgemm_oracle_lut_groups.argtypes = [i64, ci, i64]
@@ -146,6 +147,31 @@ def gemm_f64(codes, X, scales=None, scale_group: int = 0, codebook=None) -> np.n
     v = _values16(codebook)
     _check(_load().msgemm_oracle_gemm_f64_values(m, k, b, _ptr(codes), _ptr(v), _ptr(s), int(scale_group),
                                                  _ptr(X), k, _ptr(Y), m), "gemm_f64")
+    return Y
+
+
+def gemm_f64_codes8(codes8, X, values256, scales=None, scale_group: int = 0) -> np.ndarray:
+    """The direct GeMM for 8-bit weights (Section 2 names an 8-bit floating-point
+    weight matrix as another possible datatype): y = sum_j values256[code(i, j)] x(j),
+    per-block scales as in Section 3.3.  codes8: uint8 [m][k]; values256: the
+    value of each of the 256 bit patterns; X: [b][k].  Returns fp64 [b][m]."""
+    codes8 = np.ascontiguousarray(codes8, dtype=np.uint8)
+    X = _as_f64_cols(X)
+    m, k = codes8.shape
+    b = X.shape[0]
+    if X.shape[1] != k:
+        raise ValueError("X must be [b][k]")
+    v = np.ascontiguousarray(values256, dtype=np.float64)
+    if v.shape != (256,):
+        raise ValueError("values256 has one value per 8-bit pattern")
+    s = None
+    if scale_group:
+        s = np.ascontiguousarray(scales, dtype=np.float64)
+        if s.shape != (m, k // scale_group):
+            raise ValueError("scales must be [m][k/scale_group]")
+    Y = np.empty((b, m), dtype=np.float64)
+    _check(_load().msgemm_oracle_gemm_f64_codes8(m, k, b, _ptr(codes8), _ptr(v), _ptr(s), int(scale_group),
+                                                 _ptr(X), k, _ptr(Y), m), "gemm_f64_codes8")
     return Y
 
 

@@ -153,6 +153,41 @@ int msgemm_oracle_gemm_f64_values(int64_t m, int64_t k, int64_t b,
     return 0;
 }
 
+/*
+ * The same sum for weights of 8 bits: one code byte per element, values256
+ * maps each of the 256 bit patterns to its value (Section 2: an 8-bit floating
+ * point weight matrix is named as one such datatype).  codes8 is [m][k].
+ *   y(i,c) = sum_g q(i,g) * sum_{j in block g} values256[code(i,j)] * X(j,c)
+ */
+int msgemm_oracle_gemm_f64_codes8(int64_t m, int64_t k, int64_t b,
+                                  const uint8_t* codes8, const double* values256,
+                                  const double* scales, int64_t scale_group,
+                                  const double* X, int64_t ldx,
+                                  double* Y, int64_t ldy)
+{
+    if (m <= 0 || k <= 0 || b <= 0 || scale_group < 0 || !codes8 || !values256 || !X || !Y) return -1;
+    if (scale_group > 0 && ((k % scale_group) != 0 || !scales)) return -1;
+    if (ldx < k || ldy < m) return -1;
+    const int64_t block = scale_group > 0 ? scale_group : k;
+    const int64_t nblocks = k / block;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i) {
+        for (int64_t c = 0; c < b; ++c) {
+            const double* x = X + c * ldx;
+            double y = 0.0;
+            for (int64_t g = 0; g < nblocks; ++g) {
+                double s = 0.0;
+                for (int64_t j = g * block; j < (g + 1) * block; ++j)
+                    s += values256[codes8[i * k + j]] * x[j];
+                double q = scale_group > 0 ? scales[i * nblocks + g] : 1.0;
+                y += q * s;
+            }
+            Y[c * ldy + i] = y;
+        }
+    }
+    return 0;
+}
+
 int msgemm_oracle_gemm_f64(int64_t m, int64_t k, int64_t b,
                            const uint8_t* codes,
                            const double* scales, int64_t scale_group,

@@ -1,7 +1,7 @@
 """Seeded synthetic inputs for msGeMM (arxiv 2310.06178).
 
-This module only *makes bytes*: 4-bit weight codes, activations, scales, and
-the table of benchmark shapes.  It holds none of the method's arithmetic (no
+This module only *makes bytes*: 4-bit (and 8-bit) weight codes, activations,
+scales, value maps and the table of benchmark shapes.  It holds none of the method's arithmetic (no
 decoding of codes, no products, no tables), so both the CPU oracle's tests and
 the HIP path's tests can feed the very same arrays to the two sides.
 
@@ -60,6 +60,32 @@ def make_codes(m: int, k: int, seed: int) -> np.ndarray:
     if k % 2:
         raise ValueError("k must be even")
     return _rng(seed, _STREAM_CODES).integers(0, 256, size=(m, k // 2), dtype=np.uint8)
+
+
+def make_codes8(m: int, k: int, seed: int) -> np.ndarray:
+    """8-bit weight codes, uint8 [m][k], uniform over the bit patterns except the
+    two that an E4M3 value map reads as NaN (0x7f, 0xff become 0x7e, 0xfe)."""
+    c = _rng(seed, 5).integers(0, 256, size=(m, k), dtype=np.uint8)
+    c[(c & 0x7f) == 0x7f] -= 1
+    return c
+
+
+def fp8_e4m3_values() -> np.ndarray:
+    """The value of each 8-bit pattern in the OCP 8-bit floating point format
+    E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no infinities,
+    S.1111.111 is NaN).  A value map is an input of the method, like the codes:
+    this is the data format's definition, not arithmetic of the method."""
+    v = np.empty(256, dtype=np.float64)
+    for p in range(256):
+        sign = -1.0 if p & 0x80 else 1.0
+        e, f = (p >> 3) & 15, p & 7
+        if e == 15 and f == 7:
+            v[p] = np.nan
+        elif e == 0:
+            v[p] = sign * f * 2.0 ** -9
+        else:
+            v[p] = sign * (1.0 + f / 8.0) * 2.0 ** (e - 7)
+    return v
 
 
 def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:

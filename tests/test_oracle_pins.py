@@ -470,3 +470,42 @@ def test_table_of_complemented_codes_follows_from_the_other_half(d):
     # an unsigned map (value = pattern) has value(~i) = 15 - value(i)
     Lu = oracle.lut_build(X, d, codebook=np.arange(16, dtype=np.float64))
     assert np.allclose(Lu[:, (~idx) & (E - 1), :], 15.0 * S[:, None, :] - Lu[:, idx, :], rtol=0, atol=1e-9)
+
+
+# ---------------------------------------------------------------------------
+# 8-bit weights: one code byte per element, a 256-entry value map (Section 2)
+
+def test_e4m3_value_map_against_the_format_definition():
+    v = inputs.fp8_e4m3_values()
+    assert v[0x00] == 0.0 and v[0x80] == 0.0 and np.signbit(v[0x80])
+    assert v[0x38] == 1.0 and v[0xb8] == -1.0 and v[0x40] == 2.0 and v[0x3c] == 1.5
+    assert v[0x01] == 2.0 ** -9 and v[0x07] == 7 * 2.0 ** -9 and v[0x08] == 2.0 ** -6   # subnormals, smallest normal
+    assert v[0x7e] == 448.0 and v[0xfe] == -448.0                                        # largest finite
+    assert np.isnan(v[0x7f]) and np.isnan(v[0xff]) and np.isfinite(np.delete(v, [0x7f, 0xff])).all()
+    assert np.all(np.diff(v[:0x7f]) > 0)                                                  # monotone in the pattern
+    codes = inputs.make_codes8(64, 96, seed=3)
+    assert codes.dtype == np.uint8 and not np.any((codes & 0x7f) == 0x7f)
+
+
+def test_codes8_gemm_against_library_matmul_and_probes():
+    m, k, b, sg = 37, 96, 3, 32
+    codes = inputs.make_codes8(m, k, seed=4)
+    X = inputs.make_x(k, b, "f32", seed=5).astype(np.float64)
+    v = inputs.fp8_e4m3_values()
+    S = inputs.make_scales(m, k, sg, seed=6).astype(np.float64)
+    W = v[codes]
+    # dequantise, then a library matmul (blocks scaled one by one)
+    want = np.zeros((b, m))
+    for g in range(k // sg):
+        want += (W[:, g * sg:(g + 1) * sg] @ X[:, g * sg:(g + 1) * sg].T).T * S[:, g][None, :]
+    got = oracle.gemm_f64_codes8(codes, X, v, S, sg)
+    assert np.allclose(got, want, rtol=1e-13, atol=1e-12)
+    # a unit vector reads one column of the dequantised matrix back
+    for j in (0, 31, 95):
+        e = np.zeros((1, k)); e[0, j] = 1.0
+        assert np.array_equal(oracle.gemm_f64_codes8(codes, e, v)[0], W[:, j])
+    # value = pattern: plain integer arithmetic
+    ints = oracle.gemm_f64_codes8(codes, np.round(X * 8), np.arange(256.0))
+    assert np.array_equal(ints, (codes.astype(np.int64) @ np.round(X * 8).astype(np.int64).T).T.astype(np.float64))
+    # a transposed operand, a dropped block or an index off by one changes the result
+    assert not np.allclose(got, oracle.gemm_f64_codes8(codes[:, ::-1].copy(), X, v, S, sg))
