@@ -128,6 +128,28 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b,
                 const void* W_codes, const void* scales, int variant, void* stream);
 
 /*
+ * The same for weights of 8 bits (Section 2 names an 8-bit floating-point
+ * weight matrix as another datatype the method applies to).  One code byte per
+ * element: W_codes8 is device, uint8 [m][k], row-major, copied and repacked
+ * like the 4-bit codes.  values256 (host, 256 finite floats) gives the value of
+ * each bit pattern -- e.g. the E4M3 or E5M2 values, or a 256-entry codebook;
+ * patterns that stand for NaN or infinity in such a format need a finite
+ * stand-in and must not occur in W_codes8.  The table of a k-index then holds
+ * values256[code] * x(j) for the 256 codes (the paper's look-up table with one
+ * element per group and 256 instead of 16 patterns per element), and an output
+ * is the sum of one entry per element (Section 3.2).  scale_group (0, or a
+ * multiple of 64 that divides k) and scales as in msgemm_plan.  Runs with the
+ * tables in LDS; b <= 2 and floating-point activations only
+ * (MSGEMM_ERR_UNSUPPORTED otherwise).  The plan works with msgemm_run,
+ * msgemm_plan_get_info (d reads 1, lut_groups k) and msgemm_destroy; the
+ * other entry points refuse it.
+ */
+int msgemm_plan_codes8(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b,
+                       int x_dtype, int y_dtype, int scale_group,
+                       const void* W_codes8, const void* scales,
+                       const float* values256, void* stream);
+
+/*
  * Other encodings of the 4-bit codes.  Section 2 notes that the exact datatype
  * of the weights is irrelevant to the method; b(.) of Section 3.1 is the only
  * place where the encoding enters.  values16 (host, 16 floats, finite) gives the

@@ -20,7 +20,7 @@ VARIANT_AUTO, VARIANT_GLOBAL_LUT, VARIANT_FUSED_LDS, VARIANT_FUSED_LDS16, VARIAN
 OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, -1, -2, -3, -4
 
 EXPORTS = (
-    "msgemm_plan", "msgemm_plan_set_codebook", "msgemm_plan_get_info", "msgemm_lut_bytes", "msgemm_build_lut",
+    "msgemm_plan", "msgemm_plan_codes8", "msgemm_plan_set_codebook", "msgemm_plan_get_info", "msgemm_lut_bytes", "msgemm_build_lut",
     "msgemm_consume_lut", "msgemm_run", "msgemm_dequant_mfma_run", "msgemm_calib_stream_read", "msgemm_destroy",
     "msgemm_status_string", "msgemm_last_hip_error", "msgemm_version",
 )
@@ -65,6 +65,9 @@ def load():
     vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
     lib.msgemm_plan.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci, ci, ci, ci, vp, vp, ci, vp]
     lib.msgemm_plan.restype = ci
+    lib.msgemm_plan_codes8.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci, ci, ci, vp, vp,
+                                       ctypes.POINTER(ctypes.c_float), vp]
+    lib.msgemm_plan_codes8.restype = ci
     lib.msgemm_plan_set_codebook.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.msgemm_plan_set_codebook.restype = ci
     lib.msgemm_plan_get_info.argtypes = [vp, ctypes.POINTER(PlanInfo)]
@@ -140,6 +143,23 @@ def msgemm_plan(m, k, b, x_dtype, y_dtype, d, scale_group, W_codes, scales=None,
         return rc, out.value
     if rc != OK:
         raise MsgemmError(rc, "msgemm_plan")
+    return out.value
+
+
+def msgemm_plan_codes8(m, k, b, x_dtype, y_dtype, scale_group, W_codes8, scales, values256,
+                       stream=None, check=True):
+    """Plan for 8-bit weights; values256: 256 floats (host).  Returns the handle,
+    or (status, handle) with check=False."""
+    lib = load()
+    out = ctypes.c_void_p()
+    vals = (ctypes.c_float * 256)(*[float(v) for v in values256])
+    rc = lib.msgemm_plan_codes8(ctypes.byref(out), int(m), int(k), int(b),
+                                DTYPES.get(x_dtype, x_dtype), DTYPES.get(y_dtype, y_dtype),
+                                int(scale_group), _ptr(W_codes8), _ptr(scales), vals, _stream(stream))
+    if not check:
+        return rc, out.value
+    if rc != OK:
+        raise MsgemmError(rc, "msgemm_plan_codes8")
     return out.value
 
 

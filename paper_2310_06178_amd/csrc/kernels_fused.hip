@@ -103,6 +103,7 @@ struct FusedArgs {
     int slices;             // partial sums per output: k-tiles, or k-segments in the long-k form
     int tiles_per_segment;  // long-k form: k-tiles a workgroup runs through
     FastDiv div_slices;
+    const float* values256; // 8-bit codes: the value of each of the 256 bit patterns (device), else nullptr
     ValueMap values;        // value of each 4-bit pattern; last, read only by the forms built for a custom map
 };
 
@@ -236,10 +237,15 @@ __device__ __forceinline__ void reduce_in_launch(const FusedArgs& a, int unit, i
 // 16-wavefront form has no room for more wavefronts in a workgroup.)
 template <int C, int kWaves> constexpr int dedicated_builders() { return (C == 1 && kWaves <= 8) ? MSGEMM_DEDICATED_1COL : 0; }
 
-// kCustomValues: the tables are built from the plan's 16-value map instead of
-// b(.) (Section 3.1).  A form of its own, so that the default encoding keeps its
-// compile-time constants and never touches that part of the argument buffer.
-template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves, bool kCustomValues>
+// kValueMode: what the tables are built from.  kValuesDefault: b(.) of Section
+// 3.1 as compile-time constants.  kValuesMap16: the plan's 16-value map (a form
+// of its own, so that the default never touches that part of the argument
+// buffer).  kValuesMap256: 8-bit weights -- a code byte is one element, a group
+// is one k-column and an entry is values256[code] * x; everything after the
+// table build is the same kernel.
+enum { kValuesDefault = 0, kValuesMap16 = 1, kValuesMap256 = 2 };
+
+template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves, int kValueMode>
 __global__ void __launch_bounds__((kWaves + dedicated_builders<C, kWaves>()) * 64)
 fused_kernel(FusedArgs a)
 {
@@ -275,10 +281,11 @@ fused_kernel(FusedArgs a)
 #define MSGEMM_ARG_NOW(x) asm volatile("" ::"s"(x))
     MSGEMM_ARG_NOW((uint64_t)a.tiled); MSGEMM_ARG_NOW((uint64_t)a.X); MSGEMM_ARG_NOW(a.ldx);
     MSGEMM_ARG_NOW((uint64_t)a.Y); MSGEMM_ARG_NOW(a.ldy); MSGEMM_ARG_NOW((uint64_t)a.scales);
-    if constexpr (kCustomValues) {
+    if constexpr (kValueMode == kValuesMap16) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) MSGEMM_ARG_NOW(a.values.v[i]);
     }
+    if constexpr (kValueMode == kValuesMap256) MSGEMM_ARG_NOW((uint64_t)a.values256);
     MSGEMM_ARG_NOW((uint64_t)a.partials); MSGEMM_ARG_NOW(a.m); MSGEMM_ARG_NOW(a.k); MSGEMM_ARG_NOW(a.b);
     MSGEMM_ARG_NOW(a.m_pad); MSGEMM_ARG_NOW(a.b_pad); MSGEMM_ARG_NOW(a.ktiles); MSGEMM_ARG_NOW(a.panels_total);
     MSGEMM_ARG_NOW(a.panels_per_wg); MSGEMM_ARG_NOW(a.col_passes); MSGEMM_ARG_NOW(a.row_groups);
@@ -361,17 +368,38 @@ fused_kernel(FusedArgs a)
         // the early code loads: nothing waits for the activations before those are out
         constexpr int kC1PerThread = (16 + kBuildParts - 1) / kBuildParts;
         auto value_of = [&](unsigned nibble) -> AT {
-            if constexpr (kCustomValues) return code_value(a.values, nibble, AT());
+            if constexpr (kValueMode == kValuesMap16) return code_value(a.values, nibble, AT());
             else return (AT)decode4(nibble);
         };
+        // 8-bit codes: the 16 values behind each of this thread's high nibbles, requested before anything else
+        float v256[kValueMode == kValuesMap256 ? kC1PerThread : 1][16];
+        if constexpr (kValueMode == kValuesMap256) {
+#pragma unroll
+            for (int u = 0; u < kC1PerThread; ++u) {
+                const int c1 = (tid / G + u * kBuildParts) & 15;
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    const float4 q = *(const float4*)(a.values256 + c1 * 16 + v4 * 4);
+                    v256[u][v4 * 4 + 0] = q.x; v256[u][v4 * 4 + 1] = q.y;
+                    v256[u][v4 * 4 + 2] = q.z; v256[u][v4 * 4 + 3] = q.w;
+                }
+            }
+        }
         XT xr0[C], xr1[C];
         bool live[C];
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             live[c] = (col0 + c < a.b) && (kk < a.k);
-            const XT* px = X + (live[c] ? (col0 + c) * a.ldx + kk : 0);
-            xr0[c] = px[0];
-            xr1[c] = px[1];
+            if constexpr (kValueMode == kValuesMap256) {
+                // a group is one k-column (a.k counts two per code byte)
+                const XT* px = X + (live[c] ? (col0 + c) * a.ldx + (kk >> 1) : 0);
+                xr0[c] = px[0];
+                xr1[c] = px[0];
+            } else {
+                const XT* px = X + (live[c] ? (col0 + c) * a.ldx + kk : 0);
+                xr0[c] = px[0];
+                xr1[c] = px[1];
+            }
         }
         if constexpr (!kDedicated) fill_ring(0, kEarlyBuilder);
         MSGEMM_TRACE(1);
@@ -385,17 +413,27 @@ fused_kernel(FusedArgs a)
         for (int u = 0; u < kC1PerThread; ++u) {
             const int c1 = tid / G + u * kBuildParts;
             if (c1 >= 16) break;
-            AT hi[C];
-            const AT w1 = value_of((unsigned)c1);
-#pragma unroll
-            for (int c = 0; c < C; ++c) hi[c] = w1 * x1[c];
             unsigned char* dst = lds + (size_t)(c1 * 16) * kCodeStride + g * kEntryBytes;
+            if constexpr (kValueMode == kValuesMap256) {
 #pragma unroll
-            for (int c0 = 0; c0 < 16; ++c0) {
-                Entry e;
+                for (int c0 = 0; c0 < 16; ++c0) {
+                    Entry e;
 #pragma unroll
-                for (int c = 0; c < C; ++c) e.v[c] = EntryAcc<ET>::make(mul_add(value_of((unsigned)c0), x0[c], hi[c]));
-                *(Entry*)(dst + c0 * kCodeStride) = e;
+                    for (int c = 0; c < C; ++c) e.v[c] = EntryAcc<ET>::make((AT)v256[u][c0] * x0[c]);
+                    *(Entry*)(dst + c0 * kCodeStride) = e;
+                }
+            } else {
+                AT hi[C];
+                const AT w1 = value_of((unsigned)c1);
+#pragma unroll
+                for (int c = 0; c < C; ++c) hi[c] = w1 * x1[c];
+#pragma unroll
+                for (int c0 = 0; c0 < 16; ++c0) {
+                    Entry e;
+#pragma unroll
+                    for (int c = 0; c < C; ++c) e.v[c] = EntryAcc<ET>::make(mul_add(value_of((unsigned)c0), x0[c], hi[c]));
+                    *(Entry*)(dst + c0 * kCodeStride) = e;
+                }
             }
         }
         // this wavefront's LDS writes have landed; then count it
@@ -581,7 +619,7 @@ fused_kernel(FusedArgs a)
 // C = 1, G = 64, LB = 16.
 constexpr int kLongWaves = 8, kLongBuilders = 4, kLongTableBytes = 65536;
 
-template <typename XT, typename YT, typename ET, bool kCustomValues>
+template <typename XT, typename YT, typename ET, int kValueMode>
 __global__ void __launch_bounds__((kLongWaves + kLongBuilders) * 64)
 fused_long_kernel(FusedArgs a)
 {
@@ -645,14 +683,27 @@ fused_long_kernel(FusedArgs a)
         const int g = tid % G;
         const int part = tid / G;  // 0..3: this thread's high codes are part, part + 4, ...
         auto value_of = [&](unsigned nibble) -> AT {
-            if constexpr (kCustomValues) return code_value(a.values, nibble, AT());
+            if constexpr (kValueMode == kValuesMap16) return code_value(a.values, nibble, AT());
             else return (AT)decode4(nibble);
         };
+        // 8-bit codes: the 16 values behind each of this thread's high nibbles (see fused_kernel)
+        float v256[kValueMode == kValuesMap256 ? 16 / kLongBuilders : 1][16];
+        if constexpr (kValueMode == kValuesMap256) {
+#pragma unroll
+            for (int u = 0; u < 16 / kLongBuilders; ++u) {
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    const float4 q = *(const float4*)(a.values256 + (part + u * kLongBuilders) * 16 + v4 * 4);
+                    v256[u][v4 * 4 + 0] = q.x; v256[u][v4 * 4 + 1] = q.y;
+                    v256[u][v4 * 4 + 2] = q.z; v256[u][v4 * 4 + 3] = q.w;
+                }
+            }
+        }
         for (int i = 0; i < ngen; ++i) {
             const int64_t kk = ((int64_t)(kt0 + i) * G + g) * 2;
             const bool live = (col0 < a.b) && (kk < a.k);
-            const XT* px = X + (live ? col0 * a.ldx + kk : 0);
-            const XT xr0 = px[0], xr1 = px[1];  // requested before the wait below
+            const XT* px = X + (live ? col0 * a.ldx + (kValueMode == kValuesMap256 ? (kk >> 1) : kk) : 0);
+            const XT xr0 = px[0], xr1 = px[kValueMode == kValuesMap256 ? 0 : 1];  // requested before the wait below
             if (i >= 2) {
                 // generation i - 2, the last to use this buffer, consumed by every streaming wavefront.
                 // (One counter per buffer: a wavefront that runs ahead can only add to the other one.)
@@ -667,11 +718,16 @@ fused_long_kernel(FusedArgs a)
 #pragma unroll
             for (int u = 0; u < 16 / kLongBuilders; ++u) {
                 const int c1 = part + u * kLongBuilders;
-                const AT hi = value_of((unsigned)c1) * x1;
                 unsigned char* dst = buf + (size_t)(c1 * 16) * 256 + g * 4;
+                if constexpr (kValueMode == kValuesMap256) {
 #pragma unroll
-                for (int c0 = 0; c0 < 16; ++c0)
-                    *(ET*)(dst + c0 * 256) = EntryAcc<ET>::make(mul_add(value_of((unsigned)c0), x0, hi));
+                    for (int c0 = 0; c0 < 16; ++c0) *(ET*)(dst + c0 * 256) = EntryAcc<ET>::make((AT)v256[u][c0] * x0);
+                } else {
+                    const AT hi = value_of((unsigned)c1) * x1;
+#pragma unroll
+                    for (int c0 = 0; c0 < 16; ++c0)
+                        *(ET*)(dst + c0 * 256) = EntryAcc<ET>::make(mul_add(value_of((unsigned)c0), x0, hi));
+                }
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             if (lane == 0) __hip_atomic_fetch_add(&built[i & 1], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -938,12 +994,12 @@ ShapeChoice pick_shape(const Plan& p, int requested_variant)
     return lb1 == 8 ? ShapeChoice{1, 64, 8, 4, 16} : ShapeChoice{1, 64, 16, 4, 8};
 }
 
-template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves, bool kCustomValues>
+template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves, int kValueMode>
 int launch_one(const Plan& p, FusedArgs& a, hipStream_t s)
 {
     using AT = typename EntryAcc<ET>::type;
     constexpr int kFinal = LB / (G / 16);
-    auto kern = fused_kernel<XT, YT, ET, C, G, LB, kWaves, kCustomValues>;
+    auto kern = fused_kernel<XT, YT, ET, C, G, LB, kWaves, kValueMode>;
     a.fused_wgs = a.xcd_map ? (int)(p.ktiles * kXcds * ((a.row_groups + kXcds - 1) / kXcds)) : (int)(p.ktiles * a.row_groups);
     a.red_units = a.panels_total * a.col_passes;
     int64_t grid = a.fused_wgs;
@@ -959,11 +1015,11 @@ int launch_one(const Plan& p, FusedArgs& a, hipStream_t s)
     return MSGEMM_OK;
 }
 
-template <typename XT, typename YT, typename ET, bool kCustomValues>
+template <typename XT, typename YT, typename ET, int kValueMode>
 int launch_long(const Plan& p, FusedArgs& a, hipStream_t s)
 {
     using AT = typename EntryAcc<ET>::type;
-    auto kern = fused_long_kernel<XT, YT, ET, kCustomValues>;
+    auto kern = fused_long_kernel<XT, YT, ET, kValueMode>;
     a.fused_wgs = a.xcd_map ? (int)(a.slices * kXcds * ((a.row_groups + kXcds - 1) / kXcds)) : (int)(a.slices * a.row_groups);
     a.red_units = a.panels_total * a.col_passes;
     int64_t grid = a.fused_wgs;
@@ -983,18 +1039,26 @@ int launch_long(const Plan& p, FusedArgs& a, hipStream_t s)
 template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves>
 int launch_for_values(const Plan& p, FusedArgs& a, hipStream_t s)
 {
+    constexpr bool kFloatTables = !std::is_same<ET, int>::value;
+    if (p.codes8) {  // 8-bit weights: the single-column kernels with 16 rows per lane only
+        if constexpr (C == 1 && LB == 16 && kFloatTables) {
+            if (p.segments > 0) return launch_long<XT, YT, ET, kValuesMap256>(p, a, s);
+            return launch_one<XT, YT, ET, C, G, LB, kWaves, kValuesMap256>(p, a, s);
+        }
+        return MSGEMM_ERR_UNSUPPORTED;
+    }
     if constexpr (C == 1 && LB == 16) {
         if (p.segments > 0) {  // long-k form
-            if constexpr (!std::is_same<ET, int>::value) {
-                if (p.custom_values) return launch_long<XT, YT, ET, true>(p, a, s);
+            if constexpr (kFloatTables) {
+                if (p.custom_values) return launch_long<XT, YT, ET, kValuesMap16>(p, a, s);
             }
-            return launch_long<XT, YT, ET, false>(p, a, s);
+            return launch_long<XT, YT, ET, kValuesDefault>(p, a, s);
         }
     }
-    if constexpr (!std::is_same<ET, int>::value) {
-        if (p.custom_values) return launch_one<XT, YT, ET, C, G, LB, kWaves, true>(p, a, s);
+    if constexpr (kFloatTables) {
+        if (p.custom_values) return launch_one<XT, YT, ET, C, G, LB, kWaves, kValuesMap16>(p, a, s);
     }
-    return launch_one<XT, YT, ET, C, G, LB, kWaves, false>(p, a, s);
+    return launch_one<XT, YT, ET, C, G, LB, kWaves, kValuesDefault>(p, a, s);
 }
 
 }  // namespace
@@ -1162,6 +1226,7 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     a.tiled = p.codes_tiled;
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy;
     for (int i = 0; i < 16; ++i) a.values.v[i] = p.values[i];
+    a.values256 = p.values256;
     a.scales = (const __half*)p.scales_ordered;
     a.partials = p.partials;
     a.flags = p.flags;

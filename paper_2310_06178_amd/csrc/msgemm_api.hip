@@ -23,6 +23,7 @@ void free_plan(Plan* p)
     if (p->codes) (void)hipFree(p->codes);
     if (p->scales) (void)hipFree(p->scales);
     if (p->lut_ws) (void)hipFree(p->lut_ws);
+    if (p->values256) (void)hipFree(p->values256);
     if (p->codes_words) (void)hipFree(p->codes_words);
     if (p->global_partials) (void)hipFree(p->global_partials);
     if (p->codes_tiled) (void)hipFree(p->codes_tiled);
@@ -44,10 +45,12 @@ size_t lut_bytes_of(const Plan& p)
 
 using msgemm::Plan;
 
-extern "C" {
-
-int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtype, int y_dtype, int d,
-                int scale_group, const void* W_codes, const void* scales, int variant, void* stream)
+// values256 != nullptr: 8-bit weights.  k and scale_group then count two per code
+// byte (the kernels see a code byte as the pair of 4-bit codes it would be for
+// int4 weights; only the table build knows better), d is 2, the variant FUSED_LDS.
+static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtype, int y_dtype, int d,
+                     int scale_group, const void* W_codes, const void* scales, int variant, void* stream,
+                     const float* values256)
 {
     if (!out) return MSGEMM_ERR_INVALID_ARG;
     *out = nullptr;
@@ -82,6 +85,7 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtyp
     p->lut_groups = p->nblocks * p->gpb;
     p->half_table = half_table;
     p->half_c = -1.0f;  // two's complement: b(~i) = -1 - b(i)
+    p->codes8 = values256 != nullptr;
 
     hipStream_t s = (hipStream_t)stream;
     int rc = MSGEMM_OK;
@@ -100,6 +104,15 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtyp
         } else if (variant != MSGEMM_VARIANT_AUTO || rc != MSGEMM_ERR_UNSUPPORTED) {
             return fail(rc);
         }
+    }
+
+    if (p->codes8) {
+        if (p->variant != MSGEMM_VARIANT_FUSED_LDS || p->fs.cols != 1 || p->fs.lane_bytes != 16)
+            return fail(MSGEMM_ERR_UNSUPPORTED);
+        e = hipMalloc((void**)&p->values256, 256 * sizeof(float));
+        if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
+        e = hipMemcpy(p->values256, values256, 256 * sizeof(float), hipMemcpyHostToDevice);
+        if (e != hipSuccess) return hip_fail(e);
     }
 
     // the value of each 4-bit pattern: b(.) of Section 3.1 until the caller installs another map
@@ -156,10 +169,36 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtyp
     return MSGEMM_OK;
 }
 
+extern "C" {
+
+int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtype, int y_dtype, int d,
+                int scale_group, const void* W_codes, const void* scales, int variant, void* stream)
+{
+    return plan_impl(out, m, k, b, x_dtype, y_dtype, d, scale_group, W_codes, scales, variant, stream, nullptr);
+}
+
+int msgemm_plan_codes8(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtype, int y_dtype,
+                       int scale_group, const void* W_codes8, const void* scales, const float* values256,
+                       void* stream)
+{
+    if (!out) return MSGEMM_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!values256 || k <= 0 || k > ((int64_t)1 << 30) || scale_group < 0 || scale_group > (1 << 30))
+        return MSGEMM_ERR_INVALID_ARG;
+    if (x_dtype == MSGEMM_I8) return MSGEMM_ERR_UNSUPPORTED;  // the value map is floating point
+    for (int i = 0; i < 256; ++i)
+        if (!(values256[i] == values256[i]) || values256[i] > 3.0e38f || values256[i] < -3.0e38f)
+            return MSGEMM_ERR_INVALID_ARG;  // NaN / infinity: give such patterns a finite value (they must not occur)
+    if (b > 2) return MSGEMM_ERR_UNSUPPORTED;  // the single-column kernels only
+    return plan_impl(out, m, 2 * k, b, x_dtype, y_dtype, 2, 2 * scale_group, W_codes8, scales,
+                     MSGEMM_VARIANT_FUSED_LDS, stream, values256);
+}
+
 int msgemm_plan_set_codebook(msgemm_plan_t* plan, const float* values16)
 {
     if (!plan) return MSGEMM_ERR_INVALID_ARG;
     Plan& p = *reinterpret_cast<Plan*>(plan);
+    if (p.codes8) return MSGEMM_ERR_UNSUPPORTED;  // its value map is given when the plan is made
     float v[16];
     for (int i = 0; i < 16; ++i) v[i] = values16 ? values16[i] : (float)(((i ^ 8) & 15) - 8);
     for (int i = 0; i < 16; ++i)
@@ -182,10 +221,10 @@ int msgemm_plan_get_info(const msgemm_plan_t* plan, msgemm_plan_info_t* info)
 {
     if (!plan || !info) return MSGEMM_ERR_INVALID_ARG;
     const Plan& p = *reinterpret_cast<const Plan*>(plan);
-    info->m = p.m; info->k = p.k; info->b = p.b;
+    info->m = p.m; info->k = p.codes8 ? p.k / 2 : p.k; info->b = p.b;
     info->x_dtype = p.x_dtype; info->y_dtype = p.y_dtype; info->lut_dtype = p.lut_dtype;
-    info->d = p.d; info->scale_group = p.scale_group; info->variant = p.half_table ? (int)MSGEMM_VARIANT_GLOBAL_LUT_HALF : p.variant;
-    info->lut_groups = p.lut_groups;
+    info->d = p.codes8 ? 1 : p.d; info->scale_group = p.codes8 ? p.scale_group / 2 : p.scale_group; info->variant = p.half_table ? (int)MSGEMM_VARIANT_GLOBAL_LUT_HALF : p.variant;
+    info->lut_groups = p.codes8 ? p.k / 2 : p.lut_groups;
     const bool fused = p.variant != MSGEMM_VARIANT_GLOBAL_LUT;
     info->tile_rows = fused ? p.fs.tile_rows : 0;
     info->tile_groups = fused ? p.fs.groups : 0;
@@ -197,7 +236,7 @@ int msgemm_plan_get_info(const msgemm_plan_t* plan, msgemm_plan_info_t* info)
 
 size_t msgemm_lut_bytes(const msgemm_plan_t* plan)
 {
-    if (!plan) return 0;
+    if (!plan || reinterpret_cast<const Plan*>(plan)->codes8) return 0;
     return msgemm::lut_bytes_of(*reinterpret_cast<const Plan*>(plan));
 }
 
@@ -205,6 +244,7 @@ int msgemm_build_lut(const msgemm_plan_t* plan, const void* X, int64_t ldx, void
 {
     if (!plan || !X || !L_out) return MSGEMM_ERR_INVALID_ARG;
     const Plan& p = *reinterpret_cast<const Plan*>(plan);
+    if (p.codes8) return MSGEMM_ERR_UNSUPPORTED;
     if (ldx < p.k) return MSGEMM_ERR_INVALID_ARG;
     return msgemm::launch_build_lut(p, X, ldx, L_out, (hipStream_t)stream);
 }
@@ -213,6 +253,7 @@ int msgemm_consume_lut(const msgemm_plan_t* plan, const void* L, void* Y, int64_
 {
     if (!plan || !L || !Y) return MSGEMM_ERR_INVALID_ARG;
     const Plan& p = *reinterpret_cast<const Plan*>(plan);
+    if (p.codes8) return MSGEMM_ERR_UNSUPPORTED;
     if (ldy < p.m) return MSGEMM_ERR_INVALID_ARG;
     return msgemm::launch_consume_lut(p, L, Y, ldy, (hipStream_t)stream);
 }
@@ -221,7 +262,7 @@ int msgemm_run(const msgemm_plan_t* plan, const void* X, int64_t ldx, void* Y, i
 {
     if (!plan || !X || !Y) return MSGEMM_ERR_INVALID_ARG;
     const Plan& p = *reinterpret_cast<const Plan*>(plan);
-    if (ldx < p.k || ldy < p.m) return MSGEMM_ERR_INVALID_ARG;
+    if (ldx < (p.codes8 ? p.k / 2 : p.k) || ldy < p.m) return MSGEMM_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
     if (p.variant != MSGEMM_VARIANT_GLOBAL_LUT) return msgemm::launch_fused(p, X, ldx, Y, ldy, s);
     int rc = msgemm::launch_build_lut(p, X, ldx, p.lut_ws, s);
@@ -235,7 +276,7 @@ int msgemm_dequant_mfma_run(const msgemm_plan_t* plan, const void* X, int64_t ld
     if (!plan || !X || !Y) return MSGEMM_ERR_INVALID_ARG;
     const Plan& p = *reinterpret_cast<const Plan*>(plan);
     if (ldx < p.k || ldy < p.m) return MSGEMM_ERR_INVALID_ARG;
-    if (p.x_dtype == MSGEMM_I8 || p.custom_values) return MSGEMM_ERR_UNSUPPORTED;  // it dequantises with b(.) only
+    if (p.x_dtype == MSGEMM_I8 || p.custom_values || p.codes8) return MSGEMM_ERR_UNSUPPORTED;  // it dequantises with b(.) only
     return msgemm::launch_dequant_mfma(p, X, ldx, Y, ldy, (hipStream_t)stream);
 }
 

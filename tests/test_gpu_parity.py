@@ -536,6 +536,97 @@ def test_half_table_value_maps():
 
 
 # ---------------------------------------------------------------------------
+# 8-bit weights with a 256-entry value map (Section 2: an 8-bit floating-point
+# weight matrix is another datatype the method applies to)
+
+def e4m3_finite():
+    v = inputs.fp8_e4m3_values()
+    v[np.isnan(v)] = 0.0  # the two NaN patterns never occur in the codes
+    return v
+
+
+CODES8_CASES = [
+    # m, k, b, xd, sg, env
+    (300, 520, 1, "f32", 0, {}),                       # ragged rows and a ragged last k-tile
+    (2049, 512, 1, "f16", 128, {}),                    # 8 k-tiles, 9 panels, scales
+    (700, 384, 2, "bf16", 64, {}),                     # two column passes, scale block = one k-tile
+    (515, 4096, 1, "f16", 0, {"MSGEMM_TUNE_LONGK": "5"}),   # the long-k form: runs of 5 k-tiles
+    (4100, 640, 1, "f16", 128, {"MSGEMM_TUNE_LONGK": "3", "MSGEMM_TUNE_PPW": "16"}),
+    (64, 64, 1, "f32", 64, {}),                        # a single k-tile: straight to Y
+]
+
+
+@pytest.mark.parametrize("m,k,b,xd,sg,env", CODES8_CASES)
+def test_codes8_against_oracle(monkeypatch, m, k, b, xd, sg, env):
+    for name, value in env.items():
+        monkeypatch.setenv(name, value)
+    codes = inputs.make_codes8(m, k, seed=m + k)
+    X = inputs.make_x(k, b, xd, seed=k + 1)
+    scales = inputs.make_scales(m, k, sg, seed=10) if sg else None
+    values = e4m3_finite() / 16.0   # keeps fp16 outputs in range
+    ref = oracle.gemm_f64_codes8(codes, x_to_f64(X, xd), values, scales, sg)
+    dC, dS, dX = torch_io.to_device(codes, "codes"), torch_io.to_device(scales, "scales"), torch_io.to_device(X, xd)
+    plan = B.msgemm_plan_codes8(m, k, b, xd, Y_OF_X[xd], sg, dC, dS, values)
+    try:
+        info = B.msgemm_plan_get_info(plan)
+        assert (info["k"], info["d"], info["lut_groups"], info["scale_group"]) == (k, 1, k, sg)
+        assert info["variant"] == B.VARIANT_FUSED_LDS
+        for rep in range(2):
+            Y = torch_io.empty_output(b, m, Y_OF_X[xd], ldy=m + 1)
+            Y.fill_(-3)
+            B.msgemm_run(plan, dX, k, Y, m + 1)
+            torch.cuda.synchronize()
+            out = torch_io.to_host(Y)
+            check(np.ascontiguousarray(out[:, :m]), ref, xd, f"8-bit weights call {rep}")
+    finally:
+        B.msgemm_destroy(plan)
+
+
+def test_codes8_full_size_and_arbitrary_map():
+    """cfg2's shape with 8-bit weights and a seeded 256-entry codebook; sampled rows against the oracle."""
+    m, k = 16384, 4096
+    codes = inputs.make_codes8(m, k, seed=31)
+    X = inputs.make_x(k, 1, "f16", seed=32)
+    values = np.sort(np.random.default_rng(33).normal(size=256)).astype(np.float32).astype(np.float64) / 4
+    dC, dX = torch_io.to_device(codes, "codes"), torch_io.to_device(X, "f16")
+    plan = B.msgemm_plan_codes8(m, k, 1, "f16", "f16", 0, dC, None, values)
+    try:
+        Y = torch_io.empty_output(1, m, "f16")
+        B.msgemm_run(plan, dX, k, Y, m)
+        torch.cuda.synchronize()
+        out = torch_io.to_host(Y)
+    finally:
+        B.msgemm_destroy(plan)
+    rows = np.sort(np.random.default_rng(34).choice(m, size=2048, replace=False))
+    ref = oracle.gemm_f64_codes8(codes[rows], x_to_f64(X, "f16"), values)
+    check(np.ascontiguousarray(out[:, rows]), ref, "f16", "8-bit weights, cfg2 shape")
+
+
+def test_codes8_refusals():
+    codes = inputs.make_codes8(64, 128, seed=1)
+    dC = torch_io.to_device(codes, "codes")
+    v = e4m3_finite()
+    bad = v.copy(); bad[0x7f] = np.nan
+    rc = lambda *a: B.msgemm_plan_codes8(*a, check=False)[0]
+    assert rc(64, 128, 1, "f16", "f16", 0, dC, None, bad) == B.ERR_INVALID_ARG       # a NaN in the map
+    assert rc(64, 128, 3, "f16", "f16", 0, dC, None, v) == B.ERR_UNSUPPORTED         # batches: not built
+    assert rc(64, 128, 1, "i8", "i32", 0, dC, None, v) == B.ERR_UNSUPPORTED          # integer tables
+    assert rc(64, 128, 1, "f16", "f16", 32, dC, dC, v) == B.ERR_UNSUPPORTED          # scale block below a k-tile
+    plan = B.msgemm_plan_codes8(64, 128, 1, "f16", "f16", 0, dC, None, v)
+    try:
+        assert B.msgemm_lut_bytes(plan) == 0
+        assert B.msgemm_plan_set_codebook(plan, UINT4, check=False) == B.ERR_UNSUPPORTED
+        Y = torch_io.empty_output(1, 64, "f16")
+        dX = torch_io.to_device(inputs.make_x(128, 1, "f16", seed=2), "f16")
+        with pytest.raises(B.MsgemmError):
+            B.msgemm_dequant_mfma_run(plan, dX, 128, Y, 64)
+        with pytest.raises(B.MsgemmError):
+            B.msgemm_build_lut(plan, dX, 128, Y)
+    finally:
+        B.msgemm_destroy(plan)
+
+
+# ---------------------------------------------------------------------------
 # the dense matrix-core comparison kernel (not msGeMM) computes the same Y
 
 @pytest.mark.parametrize("m,k,b,xd,sg", [
