@@ -536,6 +536,35 @@ def test_half_table_value_maps():
 
 
 # ---------------------------------------------------------------------------
+# shared exponents (Section 3.3 names int4 mantissas with a shared 8-bit exponent):
+# block scales that are powers of two
+
+@pytest.mark.parametrize("m,k,b,variant", [(700, 1024, 1, B.VARIANT_FUSED_LDS), (300, 512, 2, B.VARIANT_GLOBAL_LUT),
+                                           (520, 512, 8, B.VARIANT_FUSED_LDS16)])
+def test_power_of_two_block_scales_are_exact(m, k, b, variant):
+    """int4 mantissas times 2^e per block of 128, small integer activations: every
+    partial sum is an integer times a power of two well inside fp32 (and fp16
+    tables), so the fp32 result must equal the oracle's bit for bit."""
+    sg = 128
+    rng = np.random.default_rng(m + b)
+    codes = inputs.make_codes(m, k, seed=41)
+    X = rng.integers(-4, 5, size=(b, k)).astype(np.float32)
+    scales = (2.0 ** rng.integers(-6, 3, size=(m, k // sg))).astype(np.float16)
+    xd = "f32" if variant != B.VARIANT_FUSED_LDS16 else "f16"
+    Xd = X if xd == "f32" else X.astype(np.float16)
+    ref = oracle.gemm_f64(codes, X.astype(np.float64), scales, sg)
+    out, info = run_gpu(codes, Xd, xd, scales, sg, 2, variant)
+    assert info["variant"] == variant
+    got = torch_io.to_f64(out)
+    if xd == "f32":
+        assert np.array_equal(got, ref)
+    else:
+        # fp16 output: the exact sum rounded once
+        want = oracle.f16_bits_to_f64(oracle.round_to(ref, "f16"))
+        assert np.array_equal(got, want)
+
+
+# ---------------------------------------------------------------------------
 # 8-bit weights with a 256-entry value map (Section 2: an 8-bit floating-point
 # weight matrix is another datatype the method applies to)
 
