@@ -1104,6 +1104,8 @@ int fused_choose_shape(Plan& p, int requested_variant)
 {
     if (p.d != 2) return MSGEMM_ERR_UNSUPPORTED;
     if (requested_variant == MSGEMM_VARIANT_FUSED_LDS16 && p.x_dtype == MSGEMM_F32) return MSGEMM_ERR_UNSUPPORTED;
+    p.xcd_map_allowed = env_int("MSGEMM_TUNE_XCD_MAP", 1);
+    p.forced_reduce = env_int("MSGEMM_TUNE_REDUCE", 0);
     const ShapeChoice sc = pick_shape(p, requested_variant);
     const int cols_per_tile = 2 * sc.G;
     if (p.scale_group > 0 && (p.scale_group % cols_per_tile) != 0) return MSGEMM_ERR_UNSUPPORTED;
@@ -1244,7 +1246,7 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     // choice: the accesses are agent-coherent wherever the workgroups land.
     // (Only when the row groups divide evenly over the XCDs: otherwise some XCDs
     // would get twice the workgroups of others.)
-    a.xcd_map = (a.row_groups % kXcds == 0 && env_int("MSGEMM_TUNE_XCD_MAP", 1)) ? 1 : 0;
+    a.xcd_map = (a.row_groups % kXcds == 0 && p.xcd_map_allowed) ? 1 : 0;
     a.nblocks = p.nblocks;
     a.slices = p.segments > 0 ? p.segments : (int)p.ktiles;
     a.tiles_per_segment = p.segments > 0 ? p.tiles_per_segment : 1;
@@ -1262,7 +1264,7 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     a.reduce_mode = kReduceDirect;
     if (a.slices > 1) {
         a.reduce_mode = p.fs.cols == 1 ? kReduceInLaunch : kReduceSecondPass;
-        const int forced = env_int("MSGEMM_TUNE_REDUCE", 0);
+        const int forced = p.forced_reduce;
         if (p.fs.cols == 1 && (forced == kReduceSecondPass || forced == kReduceInLaunch)) a.reduce_mode = forced;
     }
 

@@ -355,7 +355,7 @@ int64_t half_sums_offset(const Plan& p)
 bool tiled_applies(const Plan& p)
 {
     return p.variant == MSGEMM_VARIANT_GLOBAL_LUT && p.codes_words && (p.block % 8) == 0 &&
-           env_int("MSGEMM_TUNE_GLOBAL_PLAIN", 0) == 0;
+           p.global_plain == 0;
 }
 
 TiledGeom tiled_geometry(const Plan& p, int cb)
@@ -368,7 +368,7 @@ TiledGeom tiled_geometry(const Plan& p, int cb)
     g.units_per_block = (g.block_words + kUnitWords - 1) / kUnitWords;
     // chunks of about one MiB of tables (tuning aid: MSGEMM_TUNE_GLOBAL_CHUNK_KIB)
     const int64_t unit_bytes = (int64_t)(24 / p.d) * (((int64_t)1 << (4 * p.d)) >> (p.half_table ? 1 : 0)) * p.b * 4;
-    const int64_t want = (int64_t)env_int("MSGEMM_TUNE_GLOBAL_CHUNK_KIB", 1024) * 1024;
+    const int64_t want = (int64_t)(p.global_chunk_kib > 0 ? p.global_chunk_kib : 1024) * 1024;
     int64_t cu = want / unit_bytes;
     if (cu < 1) cu = 1;
     if (cu > g.units_per_block) cu = g.units_per_block;
@@ -542,6 +542,8 @@ int global_plan_setup(Plan& p, hipStream_t s)
     p.codes_words = nullptr;
     p.global_partials = nullptr;
     p.global_segments = 1;
+    p.global_plain = env_int("MSGEMM_TUNE_GLOBAL_PLAIN", 0);
+    p.global_chunk_kib = env_int("MSGEMM_TUNE_GLOBAL_CHUNK_KIB", 1024);
     if ((p.block % 8) != 0) return MSGEMM_OK;
     if (p.k / 8 > 0x3fffffff || (p.m + 63) / 64 > 0x3fffffff || p.gpb > 0x3fffffff) return MSGEMM_OK;
     // one table entry offset fits 32 bits with room to spare
