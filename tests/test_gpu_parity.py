@@ -372,7 +372,7 @@ def test_fused_repeated_calls_reuse_workspace():
 # ---------------------------------------------------------------------------
 # the benchmark configurations at full size, library's own choice of variant
 
-@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3a", "cfg3b", "cfg4", "cfg5", "mlp1", "mlp2", "mlp2_b16"])
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3a", "cfg3b", "cfg4", "cfg5", "mlp1", "mlp2", "mlp2_b16", "big1"])
 def test_config_full_size(name):
     cfg, codes, X, scales = inputs.make_config(name)
     m, k, b, xd, sg = cfg["m"], cfg["k"], cfg["b"], cfg["x"], cfg["scale_group"]
