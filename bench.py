@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same
 # counter reads for a 64 MiB elementwise kernel in the same run.
 # Source: profiles/fused_kernel_cfg2_hbm_traffic.txt
-MEASURED_TRAFFIC_BYTES = {"cfg2": 38167930}
+MEASURED_TRAFFIC_BYTES = {"cfg2": 38167930, "mlp2": 310518000}
 
 
 def algorithmic_bytes(cfg) -> int:
