@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the dominant (fused) kernel, reads + writes, from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same
 # counter reads for a 64 MiB elementwise kernel in the same run.
-# Source: profiles/fused_kernel_cfg2_hbm_traffic.txt
+# Sources: profiles/fused_kernel_cfg2_hbm_traffic.txt, profiles/fused_long_kernel_mlp2_big1_trace_and_traffic.txt
 MEASURED_TRAFFIC_BYTES = {"cfg2": 38167930, "mlp2": 310518000}
 
 
