@@ -138,9 +138,11 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b,
  * values256[code] * x(j) for the 256 codes (the paper's look-up table with one
  * element per group and 256 instead of 16 patterns per element), and an output
  * is the sum of one entry per element (Section 3.2).  scale_group (0, or a
- * multiple of 64 that divides k) and scales as in msgemm_plan.  Runs with the
- * tables in LDS; b <= 2 and floating-point activations only
- * (MSGEMM_ERR_UNSUPPORTED otherwise).  The plan works with msgemm_run,
+ * multiple of 64 that divides k; 32 for fp16 / bf16 activations with b > 2)
+ * and scales as in msgemm_plan.  Runs with the tables in LDS, full-width
+ * entries for b <= 2 and for fp32 activations, fp16 entries (values256[code] *
+ * x rounded to fp16) for wider fp16 / bf16 batches; floating-point activations
+ * only (MSGEMM_ERR_UNSUPPORTED for int8).  The plan works with msgemm_run,
  * msgemm_plan_get_info (d reads 1, lut_groups k) and msgemm_destroy; the
  * other entry points refuse it.
  */

@@ -30,6 +30,8 @@
 //
 // Shared scales (Section 3.3) are applied when a scale block of k-columns has
 // been consumed: y += q(row, block) * (sum over the block's tables).
+#include <type_traits>
+
 #include "device_types.h"
 #include "fused_common.h"
 #include "msgemm_internal.h"
@@ -72,6 +74,7 @@ struct BatchedArgs {
     void* Y;
     int64_t ldy;
     ValueMap values;         // value of each 4-bit pattern
+    const float* values256;  // 8-bit weights: the value of each of the 256 bit patterns (device), else nullptr
     const __half* scales;    // [block][panel][lane][LB]: scale of the row behind each of a lane's look-ups; or nullptr
     float* partials;         // [segment][column][panel][lane][LB / 2]
     int64_t m, k, b, m_pad, b_pad;
@@ -103,7 +106,10 @@ template <int I> __device__ __forceinline__ float quad_broadcast(float v)
     return __uint_as_float((unsigned)__builtin_amdgcn_mov_dpp((int)__float_as_uint(v), I * 0x55, 0xf, 0xf, true));
 }
 
-template <typename XT, typename YT, typename AT, bool kScaled, int kBLB>
+// kCodes8: 8-bit weights.  A code byte is one element, a table group one k-column
+// (a.k counts two per byte), an entry values256[code] * x; only the table build
+// and the activations it reads differ.
+template <typename XT, typename YT, typename AT, bool kScaled, int kBLB, bool kCodes8>
 __global__ void __launch_bounds__(batched_waves<kBLB>() * 64)
 batched_kernel(BatchedArgs a)
 {
@@ -144,7 +150,8 @@ batched_kernel(BatchedArgs a)
     auto x_fetch = [&](int kt) -> XT {
         const int64_t kk = (int64_t)kt * (2 * kBG) + xkc;
         const bool live = (col0 + xc < a.b) && (kk < a.k);
-        return X[live ? (col0 + xc) * a.ldx + kk : 0];  // (a clamped, always valid address; masked below)
+        // (8-bit weights: slots 2g and 2g + 1 both hold the column of group g)
+        return X[live ? (col0 + xc) * a.ldx + (kCodes8 ? (kk >> 1) : kk) : 0];  // (a clamped, always valid address; masked below)
     };
     auto x_store = [&](int buf, int kt, XT raw) {
         const int64_t kk = (int64_t)kt * (2 * kBG) + xkc;
@@ -176,6 +183,24 @@ batched_kernel(BatchedArgs a)
 #pragma unroll
         for (int p = 0; p < 4; ++p) top[p] = x1[p] * h2{w1, w1};
         unsigned char* dst = lds + (g >> 4) * kBHalfBytes + (size_t)(c1 * 16) * kBCodeStride + (g & 15) * 16;
+        if constexpr (kCodes8) {
+            // the 16 values behind this thread's high nibble, fetched at every build (no registers to keep them in)
+            float v[16];
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const float4 q4 = *(const float4*)(a.values256 + c1 * 16 + v4 * 4);
+                v[v4 * 4 + 0] = q4.x; v[v4 * 4 + 1] = q4.y; v[v4 * 4 + 2] = q4.z; v[v4 * 4 + 3] = q4.w;
+            }
+#pragma unroll
+            for (int c0 = 0; c0 < 16; ++c0) {
+                const _Float16 w = (_Float16)v[c0];
+                h2 e[4];
+#pragma unroll
+                for (int p = 0; p < 4; ++p) e[p] = x0[p] * h2{w, w};
+                __builtin_memcpy(dst + c0 * kBCodeStride, e, 16);
+            }
+            return;
+        }
 #pragma unroll
         for (int cc = 0; cc < kBuildEach; ++cc) {
             const int c0 = part * kBuildEach + cc;
@@ -404,6 +429,7 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
     a.tiled = p.codes_tiled;
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy;
     for (int i = 0; i < 16; ++i) a.values.v[i] = p.values[i];
+    a.values256 = p.values256;
     a.scales = (const __half*)p.scales_ordered;
     a.partials = p.partials;
     a.m = p.m; a.k = p.k; a.b = p.b; a.m_pad = p.m_pad;
@@ -426,12 +452,18 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
     const int lb = p.fs.lane_bytes;
     const dim3 g((unsigned)grid), blk((unsigned)(lb == 8 ? 8 : 12) * 64);
     const bool scaled = p.scales != nullptr;
+    if (p.codes8 && (lb != 8 || p.x_dtype == MSGEMM_I8)) return MSGEMM_ERR_UNSUPPORTED;
 #define MSGEMM_BATCHED(XD, XT, YT, AT)                                                              \
     if (p.x_dtype == XD) {                                                                          \
-        if (scaled && lb == 8) hipLaunchKernelGGL((batched_kernel<XT, YT, AT, true, 8>), g, blk, 0, s, a);        \
-        else if (scaled) hipLaunchKernelGGL((batched_kernel<XT, YT, AT, true, 4>), g, blk, 0, s, a);              \
-        else if (lb == 8) hipLaunchKernelGGL((batched_kernel<XT, YT, AT, false, 8>), g, blk, 0, s, a);            \
-        else hipLaunchKernelGGL((batched_kernel<XT, YT, AT, false, 4>), g, blk, 0, s, a);                         \
+        if constexpr (!std::is_same<AT, int>::value) {                                              \
+            if (p.codes8 && scaled) hipLaunchKernelGGL((batched_kernel<XT, YT, AT, true, 8, true>), g, blk, 0, s, a);  \
+            else if (p.codes8) hipLaunchKernelGGL((batched_kernel<XT, YT, AT, false, 8, true>), g, blk, 0, s, a);      \
+        }                                                                                           \
+        if (p.codes8) { }                                                                           \
+        else if (scaled && lb == 8) hipLaunchKernelGGL((batched_kernel<XT, YT, AT, true, 8, false>), g, blk, 0, s, a);   \
+        else if (scaled) hipLaunchKernelGGL((batched_kernel<XT, YT, AT, true, 4, false>), g, blk, 0, s, a);              \
+        else if (lb == 8) hipLaunchKernelGGL((batched_kernel<XT, YT, AT, false, 8, false>), g, blk, 0, s, a);            \
+        else hipLaunchKernelGGL((batched_kernel<XT, YT, AT, false, 4, false>), g, blk, 0, s, a);                         \
         MSGEMM_HIP_TRY(hipGetLastError());                                                          \
         if (!a.direct) return launch_reduce_second_pass(p, a.partials, Y, ldy, a.segments, a.partial_span, s); \
         return MSGEMM_OK;                                                                           \

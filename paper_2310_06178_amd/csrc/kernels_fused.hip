@@ -1040,11 +1040,12 @@ template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWave
 int launch_for_values(const Plan& p, FusedArgs& a, hipStream_t s)
 {
     constexpr bool kFloatTables = !std::is_same<ET, int>::value;
-    if (p.codes8) {  // 8-bit weights: the single-column kernels with 16 rows per lane only
+    if (p.codes8) {  // 8-bit weights: the single-column kernels with 16 rows per lane, and the four-column fp32 one
         if constexpr (C == 1 && LB == 16 && kFloatTables) {
             if (p.segments > 0) return launch_long<XT, YT, ET, kValuesMap256>(p, a, s);
             return launch_one<XT, YT, ET, C, G, LB, kWaves, kValuesMap256>(p, a, s);
         }
+        if constexpr (C == 4 && kFloatTables) return launch_one<XT, YT, ET, C, G, LB, kWaves, kValuesMap256>(p, a, s);
         return MSGEMM_ERR_UNSUPPORTED;
     }
     if constexpr (C == 1 && LB == 16) {

@@ -107,8 +107,12 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
     }
 
     if (p->codes8) {
-        if (p->variant != MSGEMM_VARIANT_FUSED_LDS || p->fs.cols != 1 || p->fs.lane_bytes != 16)
-            return fail(MSGEMM_ERR_UNSUPPORTED);
+        // the kernels that have a table build for it: one column with 16 rows per lane,
+        // four fp32 columns, eight fp16 columns with 8 rows per lane
+        const bool ok = (p->variant == MSGEMM_VARIANT_FUSED_LDS && p->fs.cols == 1 && p->fs.lane_bytes == 16) ||
+                        (p->variant == MSGEMM_VARIANT_FUSED_LDS && p->fs.cols == 4) ||
+                        (p->variant == MSGEMM_VARIANT_FUSED_LDS16 && p->fs.lane_bytes == 8);
+        if (!ok) return fail(MSGEMM_ERR_UNSUPPORTED);
         e = hipMalloc((void**)&p->values256, 256 * sizeof(float));
         if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
         e = hipMemcpy(p->values256, values256, 256 * sizeof(float), hipMemcpyHostToDevice);
@@ -189,9 +193,10 @@ int msgemm_plan_codes8(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int
     for (int i = 0; i < 256; ++i)
         if (!(values256[i] == values256[i]) || values256[i] > 3.0e38f || values256[i] < -3.0e38f)
             return MSGEMM_ERR_INVALID_ARG;  // NaN / infinity: give such patterns a finite value (they must not occur)
-    if (b > 2) return MSGEMM_ERR_UNSUPPORTED;  // the single-column kernels only
-    return plan_impl(out, m, 2 * k, b, x_dtype, y_dtype, 2, 2 * scale_group, W_codes8, scales,
-                     MSGEMM_VARIANT_FUSED_LDS, stream, values256);
+    // full-width tables for one or two columns and for fp32 activations, 16-bit tables for wider batches
+    const int variant = (b <= 2 || x_dtype == MSGEMM_F32) ? MSGEMM_VARIANT_FUSED_LDS : MSGEMM_VARIANT_FUSED_LDS16;
+    return plan_impl(out, m, 2 * k, b, x_dtype, y_dtype, 2, 2 * scale_group, W_codes8, scales, variant, stream,
+                     values256);
 }
 
 int msgemm_plan_set_codebook(msgemm_plan_t* plan, const float* values16)

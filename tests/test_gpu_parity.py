@@ -582,6 +582,11 @@ CODES8_CASES = [
     (515, 4096, 1, "f16", 0, {"MSGEMM_TUNE_LONGK": "5"}),   # the long-k form: runs of 5 k-tiles
     (4100, 640, 1, "f16", 128, {"MSGEMM_TUNE_LONGK": "3", "MSGEMM_TUNE_PPW": "16"}),
     (64, 64, 1, "f32", 64, {}),                        # a single k-tile: straight to Y
+    (520, 512, 8, "f16", 128, {}),                     # batches: fp16 tables of 8 columns
+    (300, 384, 5, "bf16", 0, {}),                      # a ragged column pass
+    (1000, 1024, 16, "f16", 32, {}),                   # two column passes, scale block = one k-tile of 32 columns
+    (257, 256, 4, "f32", 0, {}),                       # fp32 activations: four fp32 columns per entry
+    (130, 320, 7, "f32", 64, {}),
 ]
 
 
@@ -599,7 +604,7 @@ def test_codes8_against_oracle(monkeypatch, m, k, b, xd, sg, env):
     try:
         info = B.msgemm_plan_get_info(plan)
         assert (info["k"], info["d"], info["lut_groups"], info["scale_group"]) == (k, 1, k, sg)
-        assert info["variant"] == B.VARIANT_FUSED_LDS
+        assert info["variant"] == (B.VARIANT_FUSED_LDS if b <= 2 or xd == "f32" else B.VARIANT_FUSED_LDS16)
         for rep in range(2):
             Y = torch_io.empty_output(b, m, Y_OF_X[xd], ldy=m + 1)
             Y.fill_(-3)
@@ -638,7 +643,6 @@ def test_codes8_refusals():
     bad = v.copy(); bad[0x7f] = np.nan
     rc = lambda *a: B.msgemm_plan_codes8(*a, check=False)[0]
     assert rc(64, 128, 1, "f16", "f16", 0, dC, None, bad) == B.ERR_INVALID_ARG       # a NaN in the map
-    assert rc(64, 128, 3, "f16", "f16", 0, dC, None, v) == B.ERR_UNSUPPORTED         # batches: not built
     assert rc(64, 128, 1, "i8", "i32", 0, dC, None, v) == B.ERR_UNSUPPORTED          # integer tables
     assert rc(64, 128, 1, "f16", "f16", 32, dC, dC, v) == B.ERR_UNSUPPORTED          # scale block below a k-tile
     plan = B.msgemm_plan_codes8(64, 128, 1, "f16", "f16", 0, dC, None, v)
