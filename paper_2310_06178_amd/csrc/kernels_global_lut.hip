@@ -70,6 +70,61 @@ build_lut_kernel(GroupGeom g, int parts, int b, int half, const XT* __restrict__
     }
 }
 
+// Phase 1 on the matrix cores, for batches.  The table of a group is the product
+// of the [16^d x d] matrix of code values with the group's [d x b] activations
+// (Section 6 points out that phase 1 can use the matrix units).  One
+// v_mfma_f32_16x16x4_f32 makes 16 combinations x 16 columns: operand A holds, for
+// lane l, the value of nibble l / 16 of combination 16 rt + l % 16 (zero for
+// positions the group does not have), operand B the activation X(first + l / 16,
+// column l % 16); fp32 throughout, so an entry is the same sum of d products as in
+// build_lut_kernel.  A wavefront owns one tile of 16 columns of one group and
+// walks down the combinations; the four wavefronts of a workgroup take
+// neighbouring column tiles, so a row of the table is written by one workgroup.
+typedef float f4_t __attribute__((ext_vector_type(4)));
+constexpr unsigned kBuildTilesPerWg = 16;
+
+template <typename XT>
+__global__ void __launch_bounds__(256)
+build_lut_mfma_kernel(GroupGeom g, unsigned chunks, int col_tiles, int b, int half, const XT* __restrict__ X, int64_t ldx,
+                      ValueMap values, float* __restrict__ L)
+{
+    const int64_t jg = blockIdx.x / chunks;
+    const unsigned chunk = blockIdx.x % chunks;
+    const int ct = (int)blockIdx.y * 4 + (int)(threadIdx.x >> 6);
+    if (ct >= col_tiles) return;
+    const int lane = threadIdx.x & 63;
+    const int i = lane & 15, kq = lane >> 4;
+    int64_t first;
+    int len;
+    group_span(g, jg, first, len);
+    const int col = ct * 16 + i;
+    const float bval = (kq < len && col < b) ? (float)XTraits<XT>::load(X + (int64_t)col * ldx + first + kq) : 0.0f;
+    const float vals = values.v[i];  // lane l keeps the value of pattern l % 16
+    const float v_low = kq < len ? vals : 0.0f;  // nibble 0 of a combination is l % 16 itself
+    const unsigned stored = (1u << (4 * g.d)) >> half;
+    float* Lg = L + jg * (int64_t)stored * b;
+    // A workgroup makes kBuildTilesPerWg tiles of 16 combinations, so that the
+    // workgroups running at any moment write one compact stretch of the table.
+    const unsigned tiles = (stored + 15) / 16;
+    const unsigned rt0 = chunk * kBuildTilesPerWg;
+    const unsigned rt1 = rt0 + kBuildTilesPerWg < tiles ? rt0 + kBuildTilesPerWg : tiles;
+    for (unsigned rt = rt0; rt < rt1; ++rt) {
+        // nibbles 1..3 of the combinations of this tile are the same for all 16 of them
+        const float u1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vals), (int)(rt & 15)));
+        const float u2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vals), (int)((rt >> 4) & 15)));
+        const float u3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vals), (int)((rt >> 8) & 15)));
+        float aval = kq == 0 ? v_low : (kq == 1 ? u1 : (kq == 2 ? u2 : u3));
+        if (kq >= len) aval = 0.0f;
+        f4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(aval, bval, acc, 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const unsigned row = rt * 16 + 4 * kq + v;  // register v of lane l: combination 4 (l / 16) + v of the tile, column l % 16
+            if (row < stored && col < b) Lg[(int64_t)row * b + col] = acc[v];
+        }
+    }
+}
+
 // S(j, c): the sum of a group's activations (half tables: L(~idx) = c * S - L(idx), Section 4.1)
 template <typename XT, typename LT>
 __global__ void __launch_bounds__(256)
@@ -446,6 +501,24 @@ int launch_build_lut(const Plan& p, const void* X, int64_t ldx, void* L, hipStre
     const int64_t per_group = (((int64_t)1 << (4 * p.d)) >> half) * p.b;
     const int64_t parts = (per_group + kBuildPerWg - 1) / kBuildPerWg;
     if (per_group >= ((int64_t)1 << 31) || p.lut_groups * parts >= ((int64_t)1 << 31)) return MSGEMM_ERR_UNSUPPORTED;
+    // batches of floating-point activations: the product on the matrix cores
+    const int use_mfma = p.build_mfma;
+    const unsigned tiles = (unsigned)((((int64_t)1 << (4 * p.d)) >> half) + 15) / 16;
+    const unsigned chunks = (tiles + kBuildTilesPerWg - 1) / kBuildTilesPerWg;
+    if (use_mfma && p.x_dtype != MSGEMM_I8 && p.lut_groups * chunks < ((int64_t)1 << 31)) {
+        const int col_tiles = (int)((p.b + 15) / 16);
+        dim3 mgrid((unsigned)(p.lut_groups * chunks), (unsigned)((col_tiles + 3) / 4)), mblk(256);
+        if (p.x_dtype == MSGEMM_F32)
+            hipLaunchKernelGGL((build_lut_mfma_kernel<float>), mgrid, mblk, 0, s, g, chunks, col_tiles, (int)p.b, half,
+                               (const float*)X, ldx, vm, (float*)L);
+        else if (p.x_dtype == MSGEMM_F16)
+            hipLaunchKernelGGL((build_lut_mfma_kernel<__half>), mgrid, mblk, 0, s, g, chunks, col_tiles, (int)p.b, half,
+                               (const __half*)X, ldx, vm, (float*)L);
+        else
+            hipLaunchKernelGGL((build_lut_mfma_kernel<bf16_t>), mgrid, mblk, 0, s, g, chunks, col_tiles, (int)p.b, half,
+                               (const bf16_t*)X, ldx, vm, (float*)L);
+        MSGEMM_HIP_TRY(hipGetLastError());
+    } else {
     dim3 grid((unsigned)(p.lut_groups * parts)), blk(kBuildThreads);
     switch (p.x_dtype) {
     case MSGEMM_F32:
@@ -468,6 +541,7 @@ int launch_build_lut(const Plan& p, const void* X, int64_t ldx, void* L, hipStre
         return MSGEMM_ERR_INVALID_ARG;
     }
     MSGEMM_HIP_TRY(hipGetLastError());
+    }
     if (p.half_table) {
         const int64_t total = p.lut_groups * p.b;
         dim3 sgrid((unsigned)((total + 255) / 256));

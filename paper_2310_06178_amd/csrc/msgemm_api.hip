@@ -3,6 +3,7 @@
 #include <new>
 
 #include "msgemm_internal.h"
+#include "fused_common.h"
 
 namespace msgemm {
 
@@ -137,6 +138,7 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
         if (e != hipSuccess) return hip_fail(e);
     }
 
+    p->build_mfma = msgemm::env_int("MSGEMM_TUNE_BUILD_MFMA", p->b >= 16 ? 1 : 0);
     if (p->variant == MSGEMM_VARIANT_GLOBAL_LUT) {
         p->lut_ws_bytes = msgemm::lut_bytes_of(*p);
         e = hipMalloc((void**)&p->lut_ws, p->lut_ws_bytes);

@@ -61,6 +61,7 @@ struct Plan {
     int forced_reduce;    // MSGEMM_TUNE_REDUCE: 0 none, 1 second pass, 2 in launch (single-column kernels)
     int global_plain;     // MSGEMM_TUNE_GLOBAL_PLAIN: two-launch variant with the plain consumer
     int global_chunk_kib; // MSGEMM_TUNE_GLOBAL_CHUNK_KIB (default 1024)
+    int build_mfma;       // MSGEMM_TUNE_BUILD_MFMA: phase 1 alone on the matrix cores (default: from 16 batch columns on)
     int segments;         // batched kernel: k-segments (partial sums per output); 0 otherwise
     int tiles_per_segment; // batched kernel: k-tiles a workgroup runs through
     uint16_t* scales_ordered;  // device fp16 [nblocks][m_pad], rows in the order the lanes own outputs; nullptr without scales

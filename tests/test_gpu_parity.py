@@ -92,6 +92,8 @@ SMALL = [
     (131, 130, 4, "i8", 0),
     (40, 64, 2, "f16", 16),
     (1, 2, 1, "f32", 0),
+    (70, 132, 16, "f16", 0),
+    (33, 96, 35, "f32", 32),
 ]
 
 
@@ -120,10 +122,11 @@ def test_worked_example_on_gpu():
         assert out[0, 0] == 5.75
 
 
+@pytest.mark.parametrize("b", [3, 16, 40])  # from 16 columns on the floating-point tables are built on the matrix cores
 @pytest.mark.parametrize("d", [1, 2, 3])
 @pytest.mark.parametrize("xd,sg", [("f32", 0), ("f16", 128), ("i8", 0), ("bf16", 0)])
-def test_build_lut_matches_phase1_reference(xd, sg, d):
-    m, k, b = 8, 256, 3
+def test_build_lut_matches_phase1_reference(xd, sg, d, b):
+    m, k = 8, 256
     codes = inputs.make_codes(m, k, seed=1)
     X = inputs.make_x(k, b, xd, seed=2)
     scales = inputs.make_scales(m, k, sg, seed=3) if sg else None
@@ -468,6 +471,7 @@ HALF_CASES = [
     (90, 512, 4, "i8", 0, 1),        # 16-byte table reads
     (40, 64, 1, "f16", 16, 4),
     (2100, 1024, 1, "f16", 128, 3),  # several segments
+    (50, 260, 20, "f16", 0, 3),      # tables built on the matrix cores, ragged column tile
 ]
 
 
@@ -484,11 +488,12 @@ def test_half_table_variant_against_oracle(m, k, b, xd, sg, d):
     assert np.array_equal(out2, out), "phases called separately differ from msgemm_run"
 
 
+@pytest.mark.parametrize("b", [3, 24])
 @pytest.mark.parametrize("xd,sg,d", [("f32", 0, 2), ("f16", 128, 3), ("i8", 0, 3), ("bf16", 0, 1)])
-def test_half_table_contents_against_phase1_reference(xd, sg, d):
+def test_half_table_contents_against_phase1_reference(xd, sg, d, b):
     """L_out = the first half of the oracle's table (last code 0..7), then S(j) =
     the oracle's entry for codes 0001..0001 (b = 1: the plain sum of the group)."""
-    m, k, b = 8, 256, 3
+    m, k = 8, 256
     codes = inputs.make_codes(m, k, seed=1)
     X = inputs.make_x(k, b, xd, seed=2)
     scales = inputs.make_scales(m, k, sg, seed=3) if sg else None
@@ -731,6 +736,7 @@ CODEBOOK_CASES = [
     (260, 256, 6, "f32", 0, 2, B.VARIANT_FUSED_LDS),       # 4-column fp32 kernel
     (64, 96, 3, "f16", 32, 1, B.VARIANT_GLOBAL_LUT),
     (64, 96, 3, "f32", 0, 3, B.VARIANT_GLOBAL_LUT),
+    (64, 100, 18, "f16", 0, 3, B.VARIANT_GLOBAL_LUT),      # tables built on the matrix cores
 ]
 
 
@@ -759,8 +765,9 @@ def test_codebook_against_oracle(m, k, b, xd, sg, d, variant, table):
         B.msgemm_destroy(plan)
 
 
-def test_codebook_table_build_against_phase1_reference():
-    m, k, b, d = 8, 128, 2, 2
+@pytest.mark.parametrize("b", [2, 32])
+def test_codebook_table_build_against_phase1_reference(b):
+    m, k, d = 8, 128, 2
     codes = inputs.make_codes(m, k, seed=1)
     X = inputs.make_x(k, b, "f16", seed=2)
     plan = B.msgemm_plan(m, k, b, "f16", "f16", d, 0, torch_io.to_device(codes, "codes"), None, B.VARIANT_GLOBAL_LUT)
