@@ -101,7 +101,7 @@ typedef struct {
     int variant;         /* the variant actually chosen */
     int64_t lut_groups;  /* last dimension of L */
     int tile_rows;       /* rows per workgroup (fused variant), else 0 */
-    int tile_groups;     /* table groups resident in LDS per workgroup, else 0 */
+    int tile_groups;     /* table groups of a k-tile (one table in LDS), else 0 */
     int split_k;         /* partial sums reduced per output: k-tiles, or runs of k-tiles (long k, batches) */
     int col_chunk;       /* batch columns handled per pass over the codes */
     int64_t workspace_bytes; /* device memory the plan owns besides the codes */

@@ -1,5 +1,9 @@
 // Fused msGeMM for batches (b > 2, d = 2) on gfx950: tables of 8 batch columns
 // per entry in LDS, the table-adds of phase 2 done by the matrix cores.
+// Two kernels: batched_kernel (one table of 32 groups, rebuilt in a phase of
+// its own for every k-tile; described first) and batched_pipe_kernel (two
+// tables of 16 groups, the next one built while the current one is gathered
+// from; chosen for large problems, described where it is defined).
 //
 // Work decomposition
 //   A k-tile is 32 table groups (64 k-columns); its table -- 256 entries per
@@ -68,7 +72,7 @@ typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 
 struct BatchedArgs {
-    const uint8_t* tiled;    // codes in streaming order [load][k-tile][panel][lane][8]
+    const uint8_t* tiled;    // codes in streaming order [load][k-tile][panel][lane][8] (pipelined form: [panel][k-tile][load][lane][8])
     const void* X;
     int64_t ldx;
     void* Y;
@@ -361,14 +365,300 @@ batched_kernel(BatchedArgs a)
     }
 }
 
+// Pipelined form: the table of the next k-tile is built while the current one is
+// gathered from.
+//   A k-tile is 16 table groups (32 k-columns, 64 KiB of table); LDS holds two
+//   tables.  All 64 lanes of a wavefront look up the same 16 groups (lane j of
+//   each 16-lane row starts at group j and rotates), each for rows of its own:
+//   a panel is 512 rows, a lane owns rows 64 s + lane, no fold across lanes.
+//   While the wavefronts gather from table `gen & 1` every thread writes its 8
+//   entries of table `(gen + 1) & 1`, one after every second code load, so the
+//   build costs its LDS writes and nothing else: no build phase, and one
+//   barrier per k-tile (everyone has finished reading the old table and
+//   writing the new one).  The activations of k-tile gen + 2 are fetched during
+//   k-tile gen and handed over through `xs` at that barrier.
+constexpr int kPG = 16;                   // table groups per k-tile
+constexpr int kPTableBytes = 256 * kPG * 16;
+// kPLB = rows (code bytes) a lane takes per load: 8 (8 wavefronts, 512-row panels) or 4
+// (16 wavefronts, 256-row panels: four wavefronts per SIMD, which matters because a
+// single wavefront cannot issue its look-ups fast enough to keep the LDS busy).
+template <int LB> constexpr int pipe_waves() { return 64 / LB; }
+
+template <typename XT, typename YT, typename AT, bool kScaled, bool kCodes8, int kPLB>
+__global__ void __launch_bounds__(pipe_waves<kPLB>() * 64)
+batched_pipe_kernel(BatchedArgs a)
+{
+    constexpr int kPWaves = pipe_waves<kPLB>();
+    constexpr int kPEach = 256 * kPG / (kPWaves * 64);      // entries a thread writes per table: 8 or 4
+    constexpr int kBuildEvery = kLoadsPerPanel / kPEach;    // one entry after every second / fourth code load
+    constexpr int kPanelRows = 64 * kPLB;
+    using LoadT = typename LaneLoad<kPLB>::type;
+    __shared__ __align__(16) unsigned char lds[2 * kPTableBytes];
+    __shared__ __align__(16) _Float16 xs[2][2 * kPG][kBC];  // activations of a k-tile: [k-column][batch column]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int j = lane & 15;
+
+    // block id -> (k-segment, row block, column pass), as in batched_kernel
+    const uint32_t bid = blockIdx.x;
+    const uint32_t n = bid / kXcds;
+    const uint32_t hi = fast_div(n, a.div_col_passes);
+    const int cp = (int)(n - hi * (uint32_t)a.col_passes);
+    const int unit = (int)((bid % kXcds) + kXcds * hi);
+    if (unit >= a.units) return;
+    const int rb = (int)fast_div((uint32_t)unit, a.div_segments);
+    const int seg = unit - rb * a.segments;
+    const int kt_begin = seg * a.tiles_per_segment;
+    const int ngen = min(a.tiles_per_segment, a.ktiles - kt_begin);  // >= 1: the host makes no empty segment
+    const int64_t col0 = (int64_t)cp * kBC;
+    const int panel = rb * a.panels_per_wg + wave;
+    const bool active = wave < a.panels_per_wg && panel < a.panels_total;
+
+    const XT* __restrict__ X = (const XT*)a.X;
+
+    // ---- activations of a k-tile: thread (c, kc) of the first 256 fetches X(32 kt + kc, col0 + c)
+    const int xc = (tid >> 5) & (kBC - 1), xkc = tid & 31;
+    auto x_fetch = [&](int kt) -> XT {
+        const int64_t kk = (int64_t)kt * (2 * kPG) + xkc;
+        const bool live = (col0 + xc < a.b) && (kk < a.k);
+        // (8-bit weights: slots 2g and 2g + 1 both hold the column of group g)
+        return X[live ? (col0 + xc) * a.ldx + (kCodes8 ? (kk >> 1) : kk) : 0];  // (a clamped, always valid address; masked below)
+    };
+    auto x_store = [&](int buf, int kt, XT raw) {
+        const int64_t kk = (int64_t)kt * (2 * kPG) + xkc;
+        const bool live = (col0 + xc < a.b) && (kk < a.k);
+        if (tid < 2 * kPG * kBC) xs[buf][xkc][xc] = live ? to_half<XT>(raw) : (_Float16)0.0f;
+    };
+
+    // ---- phase 1: thread (g, c1, part) writes the entries c0 = kPEach part .. kPEach part + kPEach - 1 of its (g, c1):
+    // L(c0 | c1 << 4, g, c) = b(c0) X(2g, c) + b(c1) X(2g + 1, c) in packed fp16
+    const int bg = tid & (kPG - 1), bc1 = (tid >> 4) & 15, bpart = tid >> 8;
+    _Float16 w_mine[kPEach];  // the values of this thread's low codes (8-bit weights: of its 8 code bytes)
+    _Float16 w1_mine = (_Float16)0.0f;
+    if constexpr (kCodes8) {
+#pragma unroll
+        for (int v4 = 0; v4 < kPEach / 4; ++v4) {
+            const float4 q4 = *(const float4*)(a.values256 + bc1 * 16 + bpart * kPEach + v4 * 4);
+            w_mine[v4 * 4 + 0] = (_Float16)q4.x; w_mine[v4 * 4 + 1] = (_Float16)q4.y;
+            w_mine[v4 * 4 + 2] = (_Float16)q4.z; w_mine[v4 * 4 + 3] = (_Float16)q4.w;
+        }
+    } else {
+        w1_mine = (_Float16)a.values.v[bc1];
+#pragma unroll
+        for (int cc = 0; cc < kPEach; ++cc) w_mine[cc] = (_Float16)a.values.v[(bpart * kPEach + cc) & 15];
+    }
+    const uint32_t build_off = (uint32_t)((bc1 * 16 + bpart * kPEach) * kBCodeStride + bg * 16);
+    h2 bx0[4], btop[4];  // this thread's group of the table being built: X(2g, .) and b(c1) X(2g + 1, .)
+    auto build_operands = [&](int xbuf) {
+        h2 x1[4];
+        __builtin_memcpy(bx0, &xs[xbuf][2 * bg][0], 16);
+        __builtin_memcpy(x1, &xs[xbuf][2 * bg + 1][0], 16);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) btop[p] = kCodes8 ? h2{(_Float16)0.0f, (_Float16)0.0f} : x1[p] * h2{w1_mine, w1_mine};
+    };
+    auto build_entry = [&](unsigned char* table, int cc) {
+        const _Float16 w = w_mine[cc];
+        h2 e[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) e[p] = __builtin_elementwise_fma(h2{w, w}, bx0[p], btop[p]);
+        __builtin_memcpy(table + build_off + cc * kBCodeStride, e, 16);
+    };
+
+    // ---- the code stream of this wavefront: load t of k-tile kt; the k-tiles of a
+    // panel follow each other in memory, 16 loads of 512 bytes each
+    const LoadT* __restrict__ tiled = (const LoadT*)a.tiled + (int64_t)panel * a.ktiles * (kLoadsPerPanel * 64) + lane;
+    auto code_at = [&](int kt, int t) -> const LoadT* { return tiled + ((int64_t)kt * kLoadsPerPanel + t) * 64; };
+    LoadT ring[kBRing];
+
+    XT xraw = x_fetch(kt_begin);
+    XT xraw1 = x_fetch(ngen > 1 ? kt_begin + 1 : kt_begin);
+    if (active) {
+#pragma unroll
+        for (int u = 0; u < kBRing; ++u) {
+            ring[u] = *code_at(kt_begin, u);
+            __builtin_amdgcn_sched_barrier(0);  // loads return in issue order: keep slot 0 first
+        }
+    }
+    x_store(0, kt_begin, xraw);
+    if (ngen > 1) x_store(1, kt_begin + 1, xraw1);
+    lds_barrier();
+    build_operands(0);
+#pragma unroll
+    for (int cc = 0; cc < kPEach; ++cc) build_entry(lds, cc);
+    lds_barrier();
+
+    h4 onehot;  // column (lane % 4) of the 4 x 4 identity
+#pragma unroll
+    for (int e = 0; e < 4; ++e) onehot[e] = (_Float16)((lane & 3) == e ? 1.0f : 0.0f);
+    f4 dlo[kPLB], dhi[kPLB];  // sums of the current scale block (of everything, without scales)
+    f4 ylo[kScaled ? kPLB : 1], yhi[kScaled ? kPLB : 1];
+#pragma unroll
+    for (int s = 0; s < kPLB; ++s) {
+        dlo[s] = f4{0, 0, 0, 0};
+        dhi[s] = f4{0, 0, 0, 0};
+        if constexpr (kScaled) {
+            ylo[s] = f4{0, 0, 0, 0};
+            yhi[s] = f4{0, 0, 0, 0};
+        }
+    }
+
+    for (int gen = 0; gen < ngen; ++gen) {
+        const int kt = kt_begin + gen;
+        const bool more = gen + 1 < ngen;   // a table to build during this k-tile
+        const bool more2 = gen + 2 < ngen;  // activations to fetch for the one after it
+        if (more2) xraw = x_fetch(kt + 2);
+        if (more) build_operands((gen + 1) & 1);
+        unsigned char* next_table = lds + ((gen + 1) & 1) * kPTableBytes;
+        const uint32_t table_bit = (uint32_t)(gen & 1) << 16;
+        struct alignas(2 * kPLB) LaneScales { __half h[kPLB]; };
+        LaneScales qraw;
+        if constexpr (kScaled) {
+            if (active) {
+                const int blk = (int)fast_div((uint32_t)kt, a.div_tiles_per_block);
+                qraw = *(const LaneScales*)(a.scales + (((int64_t)blk * a.panels_total + panel) * 64 + lane) * kPLB);
+            }
+        }
+        const int kt_next = more ? kt + 1 : kt;  // (the last tile re-requests its own tail: harmless, and branch-free)
+        // One k-tile as straight-line code (no branch inside, so the counters of the
+        // code loads in flight stay known to the compiler): look-ups if this
+        // wavefront has a panel, an entry of the next table after every second load
+        // if there is a next table.
+        auto tile = [&](auto gather_c, auto build_c) {
+            constexpr bool kGather = decltype(gather_c)::value, kBuild = decltype(build_c)::value;
+            // Look-up s of load t.  byte 0 of the address: the slot of this lane's group within a
+            // code's 256 bytes; byte 1: the code; byte 2: the table.
+            uint4 e[kPLB];
+            // (the slot advances by one group per load; kept in one register that is updated,
+            // not in sixteen precomputed ones)
+            uint32_t lane_off = (uint32_t)j * 16u | table_bit;
+            auto next_slot = [&]() {
+                lane_off = ((lane_off + 16u) & 0xf0u) | table_bit;
+                asm volatile("" : "+v"(lane_off));
+            };
+            auto look_up = [&](int t, int s) {
+                const LoadT d = ring[t % kBRing];
+                const uint32_t addr =
+                    __builtin_amdgcn_perm(load_word<kPLB>(d, s >> 2), lane_off, 0x0c020000u | ((4u + (s & 3)) << 8));
+                e[s] = *(const uint4*)(lds + addr);
+            };
+            // once the addresses of load t are out, its ring slot takes the load kBRing ahead
+            auto refill = [&](int t) {
+                ring[t % kBRing] = (t + kBRing < kLoadsPerPanel) ? *code_at(kt, t + kBRing)
+                                                                   : *code_at(kt_next, t + kBRing - kLoadsPerPanel);
+            };
+            if constexpr (kGather) {
+#pragma unroll
+                for (int s = 0; s < kPLB; ++s) look_up(0, s);
+                refill(0);
+                next_slot();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int t = 0; t < kLoadsPerPanel; ++t) {
+                if constexpr (kGather) {
+                    // the entry of look-up s is added, then its register takes look-up s of the next
+                    // load: kPLB look-ups stay in flight
+#pragma unroll
+                    for (int s = 0; s < kPLB; ++s) {
+                        h4 lo, up;
+                        __builtin_memcpy(&lo, &e[s].x, 8);
+                        __builtin_memcpy(&up, &e[s].z, 8);
+                        dlo[s] = __builtin_amdgcn_mfma_f32_4x4x4f16(lo, onehot, dlo[s], 0, 0, 0);
+                        dhi[s] = __builtin_amdgcn_mfma_f32_4x4x4f16(up, onehot, dhi[s], 0, 0, 0);
+                        if (t + 1 < kLoadsPerPanel) look_up(t + 1, s);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (t + 1 < kLoadsPerPanel) refill(t + 1);
+                    next_slot();
+                }
+                if constexpr (kBuild) {
+                    if (t % kBuildEvery == 0) build_entry(next_table, t / kBuildEvery);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        using yes = std::true_type;
+        using no = std::false_type;
+        if (active && more) tile(yes{}, yes{});
+        else if (active) tile(yes{}, no{});
+        else if (more) tile(no{}, yes{});
+        if constexpr (kScaled) {
+            // a scale block ends with this k-tile: y += q(row) * block sum (Section 3.3).
+            // Register i of the accumulators belongs to the row of quad lane i.
+            const int blk = (int)fast_div((uint32_t)kt, a.div_tiles_per_block);
+            if (active && (!more || (kt + 1) == (blk + 1) * a.tiles_per_block)) {
+#pragma unroll
+                for (int s = 0; s < kPLB; ++s) {
+                    const float qf = __half2float(qraw.h[s]);
+                    const float q0 = quad_broadcast<0>(qf), q1 = quad_broadcast<1>(qf);
+                    const float q2 = quad_broadcast<2>(qf), q3 = quad_broadcast<3>(qf);
+                    ylo[s][0] = fmaf(q0, dlo[s][0], ylo[s][0]); yhi[s][0] = fmaf(q0, dhi[s][0], yhi[s][0]);
+                    ylo[s][1] = fmaf(q1, dlo[s][1], ylo[s][1]); yhi[s][1] = fmaf(q1, dhi[s][1], yhi[s][1]);
+                    ylo[s][2] = fmaf(q2, dlo[s][2], ylo[s][2]); yhi[s][2] = fmaf(q2, dhi[s][2], yhi[s][2]);
+                    ylo[s][3] = fmaf(q3, dlo[s][3], ylo[s][3]); yhi[s][3] = fmaf(q3, dhi[s][3], yhi[s][3]);
+                    dlo[s] = f4{0, 0, 0, 0};
+                    dhi[s] = f4{0, 0, 0, 0};
+                }
+            }
+        }
+        if (more2) x_store(gen & 1, kt + 2, xraw);
+        // everyone has finished reading table gen & 1 and writing the other one (and the activations)
+        if (more) lds_barrier();
+    }
+    if (!active) return;
+
+    // ---- lane (quad b, j'), register (s, i) holds row 64 s + 4 b + i of the panel,
+    // column 4 h + j' of the pass (the matrix cores hand the sums back transposed within a quad)
+    const int quad = lane >> 2, jq = lane & 3;
+    YT* __restrict__ Y = (YT*)a.Y;
+    __amdgpu_buffer_rsrc_t part_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)a.partials, 0, (int)a.partial_span, 0x00020000);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int64_t col = col0 + 4 * h + jq;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float fin[kPLB];
+#pragma unroll
+            for (int s = 0; s < kPLB; ++s) {
+                if constexpr (kScaled) fin[s] = h ? yhi[s][i] : ylo[s][i];
+                else fin[s] = h ? dhi[s][i] : dlo[s][i];
+            }
+            const int owner = 4 * quad + i;  // the lane whose look-ups these sums come from
+            if (a.direct) {
+#pragma unroll
+                for (int s = 0; s < kPLB; ++s) {
+                    const int64_t row = (int64_t)panel * kPanelRows + 64 * s + owner;
+                    if (row < a.m && col < a.b) {
+                        if constexpr (__is_same(AT, int)) Y[col * a.ldy + row] = (YT)__float2int_rn(fin[s]);
+                        else Y[col * a.ldy + row] = to_output<YT, float>(fin[s]);
+                    }
+                }
+            } else {
+                unsigned out[kPLB];
+#pragma unroll
+                for (int s = 0; s < kPLB; ++s) {
+                    if constexpr (__is_same(AT, int)) out[s] = (unsigned)__float2int_rn(fin[s]);
+                    else out[s] = __float_as_uint(fin[s]);
+                }
+                const uint32_t off =
+                    (uint32_t)((((int64_t)seg * a.b_pad + col) * a.m_pad + (int64_t)panel * kPanelRows + owner * kPLB) * 4);
+                store_partials<kPLB, 0>(part_rsrc, off, out);
+            }
+        }
+    }
+}
+
 // One-off reorder of the block scales ([m][nblocks]) for the batched kernel:
 // [block][panel][lane][s] = scale of the row behind look-up s of that lane.
-template <int kBLB>
+template <int NQ, int kBLB>
 __global__ void __launch_bounds__(256)
 repack_scales_batched_kernel(const __half* __restrict__ scales, __half* __restrict__ ordered, int64_t m,
                              int64_t nblocks, int64_t panels)
 {
-    constexpr int kBPanelRows = 32 * kBLB;
+    constexpr int kBPanelRows = 64 * kBLB / NQ;
     const int64_t total = nblocks * panels * 64 * kBLB;
     for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < total;
          o += (int64_t)gridDim.x * blockDim.x) {
@@ -377,7 +667,7 @@ repack_scales_batched_kernel(const __half* __restrict__ scales, __half* __restri
         const int lane = (int)(r % 64); r /= 64;
         const int64_t panel = r % panels;
         const int64_t blk = r / panels;
-        const int64_t row = panel * kBPanelRows + panel_row<2, kBLB>(lane >> 4, lane & 15, s);
+        const int64_t row = panel * kBPanelRows + panel_row<NQ, kBLB>(lane >> 4, lane & 15, s);
         ordered[o] = row < m ? scales[row * nblocks + blk] : __float2half(1.0f);
     }
 }
@@ -388,7 +678,7 @@ repack_scales_batched_kernel(const __half* __restrict__ scales, __half* __restri
 // every compute unit a workgroup, preferring grids that fill whole rounds.
 void batched_choose_segments(Plan& p)
 {
-    const int tpb = p.scale_group > 0 ? (int)(p.scale_group / (2 * kBG)) : 1;
+    const int tpb = p.scale_group > 0 ? (int)(p.scale_group / (2 * p.fs.groups)) : 1;
     const int64_t blocks = (p.ktiles + tpb - 1) / tpb;  // indivisible runs of k-tiles
     const int64_t units_per_seg = p.row_blocks * p.col_passes;
     int64_t best_s = blocks;
@@ -408,16 +698,64 @@ void batched_choose_segments(Plan& p)
     p.segments = (int)((p.ktiles + p.tiles_per_segment - 1) / p.tiles_per_segment);
 }
 
+// Pipelined form: panels per workgroup and segment length together, by a model
+// of the time (microseconds).  A workgroup costs a start-up (activations, first
+// table, first codes) and a time per k-tile; workgroups run in rounds of one
+// per compute unit; the second pass reads one partial sum per segment and
+// output.
+void batched_choose_rows_and_segments(Plan& p, int64_t panels, int& ppw_out)
+{
+    const int tpb = p.scale_group > 0 ? (int)(p.scale_group / (2 * p.fs.groups)) : 1;
+    const int64_t blocks = (p.ktiles + tpb - 1) / tpb;  // indivisible runs of k-tiles
+    const double outputs = (double)panels * p.fs.panel_rows * p.col_passes * kBC;
+    double best = 1e300;
+    int best_ppw = p.fs.waves;
+    int64_t best_per = blocks;
+    // Measured: a k-tile takes a workgroup 3.0 us + 0.125 us per active wavefront (8 rows per
+    // lane; 1.9 + 0.085 with 4): what bounds it is the rate at which a wavefront issues its
+    // look-ups, and wavefronts that share a SIMD overlap almost completely.
+    const double tile_base_us = p.fs.lane_bytes == 8 ? 3.0 : 1.9, tile_wave_us = p.fs.lane_bytes == 8 ? 0.125 : 0.085;
+    for (int ppw = p.fs.waves; ppw >= 1; ppw >>= 1) {
+        const int64_t row_blocks = (panels + ppw - 1) / ppw;
+        const double tile_us = tile_base_us + tile_wave_us * ppw;
+        for (int64_t per = blocks; per >= 1; --per) {
+            const int64_t segs = (blocks + per - 1) / per;
+            if ((blocks + segs - 1) / segs != per) continue;  // the same split again
+            const int64_t wgs = segs * row_blocks * p.col_passes;
+            const int64_t rounds = (wgs + p.cus - 1) / p.cus;
+            double cost = (double)rounds * (3.5 + (double)(per * tpb) * tile_us);
+            if (segs > 1) cost += 3.0 + (double)segs * outputs * 4.0 / 3.0e6;
+            if (cost < best) { best = cost; best_ppw = ppw; best_per = per; }
+            if (rounds > 64) break;  // shorter segments only add rounds from here on
+        }
+    }
+    const int forced_ppw = env_int("MSGEMM_TUNE_PPW", 0);
+    if (forced_ppw >= 1 && forced_ppw <= p.fs.waves) best_ppw = forced_ppw;
+    int64_t segs = (blocks + best_per - 1) / best_per;
+    const int forced = env_int("MSGEMM_TUNE_SEGMENTS", 0);
+    if (forced >= 1 && forced <= blocks) segs = forced;
+    const int64_t per = (blocks + segs - 1) / segs;
+    ppw_out = best_ppw;
+    p.tiles_per_segment = (int)(per * tpb);
+    p.segments = (int)((p.ktiles + p.tiles_per_segment - 1) / p.tiles_per_segment);
+}
+
 int launch_repack_scales_batched(const Plan& p, hipStream_t s)
 {
     const int64_t panels = p.m_pad / p.fs.panel_rows;
     int64_t blocks = (p.nblocks * panels * 64 * p.fs.lane_bytes + 255) / 256;
     if (blocks > 65536) blocks = 65536;
-    if (p.fs.lane_bytes == 8)
-        hipLaunchKernelGGL(repack_scales_batched_kernel<8>, dim3((unsigned)blocks), dim3(256), 0, s,
+    if (p.fs.groups == kPG && p.fs.lane_bytes == 8)
+        hipLaunchKernelGGL((repack_scales_batched_kernel<1, 8>), dim3((unsigned)blocks), dim3(256), 0, s,
+                           (const __half*)p.scales, (__half*)p.scales_ordered, p.m, p.nblocks, panels);
+    else if (p.fs.groups == kPG)
+        hipLaunchKernelGGL((repack_scales_batched_kernel<1, 4>), dim3((unsigned)blocks), dim3(256), 0, s,
+                           (const __half*)p.scales, (__half*)p.scales_ordered, p.m, p.nblocks, panels);
+    else if (p.fs.lane_bytes == 8)
+        hipLaunchKernelGGL((repack_scales_batched_kernel<2, 8>), dim3((unsigned)blocks), dim3(256), 0, s,
                            (const __half*)p.scales, (__half*)p.scales_ordered, p.m, p.nblocks, panels);
     else
-        hipLaunchKernelGGL(repack_scales_batched_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, s,
+        hipLaunchKernelGGL((repack_scales_batched_kernel<2, 4>), dim3((unsigned)blocks), dim3(256), 0, s,
                            (const __half*)p.scales, (__half*)p.scales_ordered, p.m, p.nblocks, panels);
     MSGEMM_HIP_TRY(hipGetLastError());
     return MSGEMM_OK;
@@ -441,7 +779,7 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
     a.col_passes = p.col_passes;
     a.segments = p.segments;
     a.tiles_per_segment = p.tiles_per_segment;
-    a.tiles_per_block = p.scale_group > 0 ? (int)(p.scale_group / (2 * kBG)) : 1;
+    a.tiles_per_block = p.scale_group > 0 ? (int)(p.scale_group / (2 * p.fs.groups)) : 1;
     a.units = (int)(p.segments * p.row_blocks);
     a.direct = p.segments == 1;
     a.partial_span = (int64_t)p.segments * a.b_pad * p.m_pad * 4;
@@ -452,7 +790,28 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
     const int lb = p.fs.lane_bytes;
     const dim3 g((unsigned)grid), blk((unsigned)(lb == 8 ? 8 : 12) * 64);
     const bool scaled = p.scales != nullptr;
-    if (p.codes8 && (lb != 8 || p.x_dtype == MSGEMM_I8)) return MSGEMM_ERR_UNSUPPORTED;
+    const bool pipe = p.fs.groups == kPG;
+    if (pipe && lb != 8 && lb != 4) return MSGEMM_ERR_UNSUPPORTED;
+    if (pipe && p.codes8 && p.x_dtype == MSGEMM_I8) return MSGEMM_ERR_UNSUPPORTED;
+#define MSGEMM_PIPE_LB(XT, YT, AT, SC, C8)                                                           \
+    do {                                                                                            \
+        if (lb == 8) hipLaunchKernelGGL((batched_pipe_kernel<XT, YT, AT, SC, C8, 8>), g, dim3(pipe_waves<8>() * 64), 0, s, a); \
+        else hipLaunchKernelGGL((batched_pipe_kernel<XT, YT, AT, SC, C8, 4>), g, dim3(pipe_waves<4>() * 64), 0, s, a);         \
+    } while (0)
+#define MSGEMM_BATCHED_PIPE(XD, XT, YT, AT)                                                         \
+    if (pipe && p.x_dtype == XD) {                                                                  \
+        if constexpr (!std::is_same<AT, int>::value) {                                              \
+            if (p.codes8 && scaled) MSGEMM_PIPE_LB(XT, YT, AT, true, true);                         \
+            else if (p.codes8) MSGEMM_PIPE_LB(XT, YT, AT, false, true);                             \
+        }                                                                                           \
+        if (p.codes8) { }                                                                           \
+        else if (scaled) MSGEMM_PIPE_LB(XT, YT, AT, true, false);                                   \
+        else MSGEMM_PIPE_LB(XT, YT, AT, false, false);                                              \
+        MSGEMM_HIP_TRY(hipGetLastError());                                                          \
+        if (!a.direct) return launch_reduce_second_pass(p, a.partials, Y, ldy, a.segments, a.partial_span, s); \
+        return MSGEMM_OK;                                                                           \
+    }
+    if (!pipe && p.codes8 && (lb != 8 || p.x_dtype == MSGEMM_I8)) return MSGEMM_ERR_UNSUPPORTED;
 #define MSGEMM_BATCHED(XD, XT, YT, AT)                                                              \
     if (p.x_dtype == XD) {                                                                          \
         if constexpr (!std::is_same<AT, int>::value) {                                              \
@@ -468,6 +827,11 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
         if (!a.direct) return launch_reduce_second_pass(p, a.partials, Y, ldy, a.segments, a.partial_span, s); \
         return MSGEMM_OK;                                                                           \
     }
+    MSGEMM_BATCHED_PIPE(MSGEMM_F16, __half, __half, float)
+    MSGEMM_BATCHED_PIPE(MSGEMM_BF16, bf16_t, bf16_t, float)
+    MSGEMM_BATCHED_PIPE(MSGEMM_I8, int8_t, int, int)
+#undef MSGEMM_BATCHED_PIPE
+#undef MSGEMM_PIPE_LB
     MSGEMM_BATCHED(MSGEMM_F16, __half, __half, float)
     MSGEMM_BATCHED(MSGEMM_BF16, bf16_t, bf16_t, float)
     MSGEMM_BATCHED(MSGEMM_I8, int8_t, int, int)

@@ -927,8 +927,11 @@ reduce_kernel(const float* __restrict__ partials, YT* __restrict__ Y, int64_t ld
     }
 }
 
-// One-off reorder of the row-major code bytes into streaming order.
-template <int G, int LB>
+// One-off reorder of the row-major code bytes into streaming order:
+// [load t][k-tile][panel][lane][LB], or, kPanelMajor, [panel][k-tile][load t][lane][LB]
+// (a wavefront that runs through the k-tiles of its panel then reads one
+// sequential stream).
+template <int G, int LB, bool kPanelMajor = false>
 __global__ void __launch_bounds__(256)
 repack_kernel(const uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled, int64_t m, int64_t kbytes,
               int ktiles, int panels_total)
@@ -941,9 +944,17 @@ repack_kernel(const uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled, in
         int64_t r = o;
         const int s = (int)(r % LB); r /= LB;
         const int lane = (int)(r % 64); r /= 64;
-        const int64_t panel = r % panels_total; r /= panels_total;
-        const int64_t kt = r % ktiles;
-        const int t = (int)(r / ktiles);
+        int64_t panel, kt;
+        int t;
+        if constexpr (kPanelMajor) {
+            t = (int)(r % kLoadsPerPanel); r /= kLoadsPerPanel;
+            kt = r % ktiles;
+            panel = r / ktiles;
+        } else {
+            panel = r % panels_total; r /= panels_total;
+            kt = r % ktiles;
+            t = (int)(r / ktiles);
+        }
         const int q = lane >> 4, j = lane & 15;
         const int qg = q % NQ;
         const int64_t row = panel * kPanelRows + panel_row<NQ, LB>(q, j, s);
@@ -988,8 +999,20 @@ ShapeChoice pick_shape(const Plan& p, int requested_variant)
     const bool narrow = requested_variant == MSGEMM_VARIANT_FUSED_LDS16 ||
                         (requested_variant == MSGEMM_VARIANT_AUTO && p.b > 2);
     // (MSGEMM_TUNE_BATCH_LB = 4: the 12-wavefront form of the batched kernel, tuning aid)
-    if (narrow && narrow_ok)
-        return env_int("MSGEMM_TUNE_BATCH_LB", 8) == 4 ? ShapeChoice{8, 32, 4, 2, 12} : ShapeChoice{8, 32, 8, 2, 8};
+    // (MSGEMM_TUNE_BATCH_PIPE = 0: its form with one 32-group table and a build phase per k-tile)
+    if (narrow && narrow_ok) {
+        // The batched kernel has two forms.  The pipelined one (16-group k-tiles, the next table
+        // built under the look-ups) wins once every compute unit has a long run of k-tiles for
+        // eight full panels; below that the form with 32-group k-tiles and a build phase does
+        // (half as many k-tiles to issue per row).  MSGEMM_TUNE_BATCH_PIPE = 0 / 1 overrides.
+        const int64_t panels512 = (p.m + 511) / 512, tiles16 = (p.k / 2 + 15) / 16;
+        const int64_t units = ((panels512 + 7) / 8) * ((p.b + 7) / 8);
+        const int pipe_default = units * tiles16 >= 16 * (int64_t)p.cus ? 1 : 0;
+        const int lb = env_int("MSGEMM_TUNE_BATCH_LB", 8) == 4 ? 4 : 8;
+        if (env_int("MSGEMM_TUNE_BATCH_PIPE", pipe_default))
+            return lb == 4 ? ShapeChoice{8, 16, 4, 2, 16} : ShapeChoice{8, 16, 8, 2, 8};
+        return lb == 4 ? ShapeChoice{8, 32, 4, 2, 12} : ShapeChoice{8, 32, 8, 2, 8};
+    }
     if (p.b > 2 && p.x_dtype == MSGEMM_F32) return ShapeChoice{4, 32, 8, 4, 8};
     return lb1 == 8 ? ShapeChoice{1, 64, 8, 4, 16} : ShapeChoice{1, 64, 16, 4, 8};
 }
@@ -1107,6 +1130,13 @@ int fused_choose_shape(Plan& p, int requested_variant)
     if (requested_variant == MSGEMM_VARIANT_FUSED_LDS16 && p.x_dtype == MSGEMM_F32) return MSGEMM_ERR_UNSUPPORTED;
     p.xcd_map_allowed = env_int("MSGEMM_TUNE_XCD_MAP", 1);
     p.forced_reduce = env_int("MSGEMM_TUNE_REDUCE", 0);
+    {
+        int cus = 256;
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, p.device) == hipSuccess && prop.multiProcessorCount > 0)
+            cus = prop.multiProcessorCount;
+        p.cus = cus;
+    }
     const ShapeChoice sc = pick_shape(p, requested_variant);
     const int cols_per_tile = 2 * sc.G;
     if (p.scale_group > 0 && (p.scale_group % cols_per_tile) != 0) return MSGEMM_ERR_UNSUPPORTED;
@@ -1123,11 +1153,7 @@ int fused_choose_shape(Plan& p, int requested_variant)
     const int64_t panels = (p.m + fs.panel_rows - 1) / fs.panel_rows;
     if (panels > (1 << 30) || p.ktiles > (1 << 20)) return MSGEMM_ERR_UNSUPPORTED;
 
-    int cus = 256;
-    hipDeviceProp_t prop;
-    if (hipGetDeviceProperties(&prop, p.device) == hipSuccess && prop.multiProcessorCount > 0)
-        cus = prop.multiProcessorCount;
-    p.cus = cus;
+    const int cus = p.cus;
     // Rows per table build: as many panels per workgroup as still leave one
     // workgroup per compute unit (each build costs 256 entries per group).
     // MSGEMM_TUNE_PPW overrides the choice (tuning aid).
@@ -1139,8 +1165,12 @@ int fused_choose_shape(Plan& p, int requested_variant)
     while (ppw > 1 && (int64_t)p.ktiles * p.col_passes * ((panels + ppw - 1) / ppw) < cus) ppw >>= 1;
     int64_t tps = 1;
     if (can_run_long) choose_rows_and_segments(panels, p.ktiles, p.col_passes, cus, ppw, tps);
+    const bool batched_pipe = batched16 && sc.G == 16;
+    p.segments = 0;
+    p.tiles_per_segment = 0;
+    if (batched_pipe) batched_choose_rows_and_segments(p, panels, ppw);
     const int forced = env_int("MSGEMM_TUNE_PPW", 0);
-    if (forced >= 1 && forced <= 64) ppw = forced;
+    if (forced >= 1 && forced <= 64 && !batched_pipe) ppw = forced;
     // MSGEMM_TUNE_LONGK = 1 keeps one k-tile per workgroup, n > 1 forces runs of n (tuning aid).
     const int forced_tps = env_int("MSGEMM_TUNE_LONGK", 0);
     if (forced_tps >= 1) tps = forced_tps < p.ktiles ? forced_tps : p.ktiles;
@@ -1151,9 +1181,7 @@ int fused_choose_shape(Plan& p, int requested_variant)
     const int64_t row_groups = p.row_blocks * p.col_passes;
     if ((int64_t)p.ktiles * (row_groups + kXcds) + panels * p.col_passes > 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
     // the k-tile reduction addresses the partial buffer with 32-bit byte offsets
-    p.segments = 0;
-    p.tiles_per_segment = 0;
-    if (batched16) batched_choose_segments(p);
+    if (batched16 && !batched_pipe) batched_choose_segments(p);
     // (a streaming wavefront of the long-k form holds the sums of at most two panels)
     if (can_run_long && ppw <= 2 * kLongWaves && tps >= 2) {
         p.tiles_per_segment = (int)tps;
@@ -1192,6 +1220,16 @@ int launch_repack(const Plan& p, hipStream_t s)
     MSGEMM_REPACK(64, 8)
     MSGEMM_REPACK(32, 8)
     MSGEMM_REPACK(32, 4)
+    if (p.fs.groups == 16 && (p.fs.lane_bytes == 8 || p.fs.lane_bytes == 4)) {
+        if (p.fs.lane_bytes == 8)
+            hipLaunchKernelGGL((repack_kernel<16, 8, true>), dim3((unsigned)blocks), dim3(256), 0, s, p.codes,
+                               p.codes_tiled, p.m, p.k / 2, (int)p.ktiles, (int)panels);
+        else
+            hipLaunchKernelGGL((repack_kernel<16, 4, true>), dim3((unsigned)blocks), dim3(256), 0, s, p.codes,
+                               p.codes_tiled, p.m, p.k / 2, (int)p.ktiles, (int)panels);
+        MSGEMM_HIP_TRY(hipGetLastError());
+        return MSGEMM_OK;
+    }
 #undef MSGEMM_REPACK
     return MSGEMM_ERR_UNSUPPORTED;
 }
@@ -1201,9 +1239,12 @@ int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int
 {
     const int64_t b_pad = (int64_t)p.col_passes * p.fs.cols;
     const dim3 grid((unsigned)((p.m_pad / 64) * p.b)), blk(kReduceWaves * 64);
-    const int f = p.fs.panel_rows / 64;  // outputs per lane of the producing kernel: 4 or 2
+    const int f = p.fs.panel_rows / 64;  // outputs per lane of the producing kernel: 8, 4 or 2
 #define MSGEMM_REDUCE(YT, AT)                                                                                   \
-    if (f == 4)                                                                                                 \
+    if (f == 8)                                                                                                 \
+        hipLaunchKernelGGL((reduce_kernel<YT, AT, 8>), grid, blk, 0, s, partials, (YT*)Y, ldy, p.m, p.b, p.m_pad, \
+                           b_pad, slices, span);                                                                \
+    else if (f == 4)                                                                                            \
         hipLaunchKernelGGL((reduce_kernel<YT, AT, 4>), grid, blk, 0, s, partials, (YT*)Y, ldy, p.m, p.b, p.m_pad, \
                            b_pad, slices, span);                                                                \
     else                                                                                                        \

@@ -112,7 +112,7 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
         // four fp32 columns, eight fp16 columns with 8 rows per lane
         const bool ok = (p->variant == MSGEMM_VARIANT_FUSED_LDS && p->fs.cols == 1 && p->fs.lane_bytes == 16) ||
                         (p->variant == MSGEMM_VARIANT_FUSED_LDS && p->fs.cols == 4) ||
-                        (p->variant == MSGEMM_VARIANT_FUSED_LDS16 && p->fs.lane_bytes == 8);
+                        (p->variant == MSGEMM_VARIANT_FUSED_LDS16 && (p->fs.lane_bytes == 8 || p->fs.groups == 16));
         if (!ok) return fail(MSGEMM_ERR_UNSUPPORTED);
         e = hipMalloc((void**)&p->values256, 256 * sizeof(float));
         if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }

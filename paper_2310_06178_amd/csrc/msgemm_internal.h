@@ -97,6 +97,8 @@ int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int
 
 // kernels_batched.hip (16-bit table entries, 8 batch columns per pass)
 void batched_choose_segments(Plan& p);  // needs ktiles, row_blocks, col_passes, cus; fills segments, tiles_per_segment
+// pipelined batched kernel: panels per workgroup and segments together (needs fs, ktiles, col_passes, cus)
+void batched_choose_rows_and_segments(Plan& p, int64_t panels, int& ppw_out);
 int launch_repack_scales_batched(const Plan& p, hipStream_t s);
 int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s);
 

@@ -260,6 +260,61 @@ def test_fused_variant_batched(m, k, b, xd, sg, variant):
         assert np.array_equal(out_auto, out)
 
 
+PIPELINED_CASES = [
+    # m, k, b, xd, sg, rows per lane, panels per workgroup (0: chosen), segments (0: chosen)
+    (300, 520, 5, "f16", 0, 8, 0, 0),        # ragged rows, columns and last k-tile (17 k-tiles of 32 columns)
+    (1025, 1024, 8, "f16", 128, 8, 0, 0),    # 3 panels of 512 rows, scale block = 4 k-tiles
+    (513, 512, 11, "bf16", 64, 8, 0, 4),     # two column passes, scale block = 2 k-tiles, 4 segments
+    (700, 768, 16, "i8", 0, 8, 0, 1),        # one segment of 24 k-tiles: written straight to Y
+    (260, 130, 3, "i8", 0, 8, 0, 0),
+    (5000, 640, 9, "f16", 32, 8, 8, 5),      # 10 panels: two row blocks of 8 wavefronts; scale block = one k-tile
+    (2100, 384, 8, "f16", 128, 8, 2, 3),     # 5 panels, two per workgroup: idle wavefronts that only build
+    (1025, 1024, 8, "f16", 128, 4, 0, 0),    # 16 wavefronts, 256-row panels
+    (700, 768, 16, "i8", 0, 4, 4, 6),
+    (300, 520, 13, "bf16", 0, 4, 0, 0),
+    (3000, 256, 7, "f16", 64, 4, 16, 2),     # 12 panels in one workgroup of 16 wavefronts
+]
+
+
+@pytest.mark.parametrize("m,k,b,xd,sg,lb,ppw,segments", PIPELINED_CASES)
+def test_batched_pipelined_form(monkeypatch, m, k, b, xd, sg, lb, ppw, segments):
+    """The batched kernel that builds the next table while it gathers from the current one
+    (chosen by itself only for large problems), forced on small shapes; twice on one plan."""
+    monkeypatch.setenv("MSGEMM_TUNE_BATCH_PIPE", "1")
+    monkeypatch.setenv("MSGEMM_TUNE_BATCH_LB", str(lb))
+    if ppw:
+        monkeypatch.setenv("MSGEMM_TUNE_PPW", str(ppw))
+    if segments:
+        monkeypatch.setenv("MSGEMM_TUNE_SEGMENTS", str(segments))
+    codes = inputs.make_codes(m, k, seed=m + 5 * k)
+    scales = inputs.make_scales(m, k, sg, seed=8) if sg else None
+    dC = torch_io.to_device(codes, "codes")
+    dS = torch_io.to_device(scales, "scales")
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS, B.VARIANT_FUSED_LDS16)
+    try:
+        info = B.msgemm_plan_get_info(plan)
+        assert info["tile_groups"] == 16 and info["col_chunk"] == 8
+        assert info["tile_rows"] % (64 * lb) == 0
+        if segments:
+            assert info["split_k"] == segments
+        for rep in range(2):
+            X = inputs.make_x(k, b, xd, seed=41 + rep)
+            Xp = np.zeros((b, k + 6), dtype=X.dtype)
+            Xp[:, :k] = X
+            Xp[:, k:] = 77 if xd != "bf16" else 0x4300  # poison: must never reach the result
+            dX = torch_io.to_device(Xp, xd)
+            Y = torch_io.empty_output(b, m, Y_OF_X[xd], ldy=m + 3)
+            Y.fill_(-3)
+            B.msgemm_run(plan, dX, k + 6, Y, m + 3)
+            torch.cuda.synchronize()
+            out = torch_io.to_host(Y)
+            check(np.ascontiguousarray(out[:, :m]), oracle_y(codes, X, xd, scales, sg), xd, f"pipelined call {rep}")
+            minus3 = torch_io.to_host(torch.full((1,), -3, dtype=Y.dtype))[0]
+            assert np.all(out[:, m:] == minus3), "output padding was written"
+    finally:
+        B.msgemm_destroy(plan)
+
+
 def test_fused_lds16_not_for_fp32():
     dC = torch.zeros(64 * 32, dtype=torch.uint8, device="cuda:0")
     status, handle = B.msgemm_plan(64, 64, 4, "f32", "f32", 2, 0, dC, None, B.VARIANT_FUSED_LDS16, check=False)
@@ -592,6 +647,9 @@ CODES8_CASES = [
     (1000, 1024, 16, "f16", 32, {}),                   # two column passes, scale block = one k-tile of 32 columns
     (257, 256, 4, "f32", 0, {}),                       # fp32 activations: four fp32 columns per entry
     (130, 320, 7, "f32", 64, {}),
+    (520, 512, 8, "f16", 128, {"MSGEMM_TUNE_BATCH_PIPE": "1"}),                        # the pipelined batched form
+    (1000, 1024, 16, "f16", 32, {"MSGEMM_TUNE_BATCH_PIPE": "1", "MSGEMM_TUNE_BATCH_LB": "4"}),
+    (300, 384, 5, "bf16", 0, {"MSGEMM_TUNE_BATCH_PIPE": "1", "MSGEMM_TUNE_SEGMENTS": "3"}),
 ]
 
 
@@ -740,9 +798,13 @@ CODEBOOK_CASES = [
 ]
 
 
+@pytest.mark.parametrize("pipelined", [0, 1])
 @pytest.mark.parametrize("table", [UINT4, NONUNIFORM])
 @pytest.mark.parametrize("m,k,b,xd,sg,d,variant", CODEBOOK_CASES)
-def test_codebook_against_oracle(m, k, b, xd, sg, d, variant, table):
+def test_codebook_against_oracle(monkeypatch, m, k, b, xd, sg, d, variant, table, pipelined):
+    if pipelined and variant != B.VARIANT_FUSED_LDS16:
+        pytest.skip("only the batched kernel has a pipelined form")
+    monkeypatch.setenv("MSGEMM_TUNE_BATCH_PIPE", str(pipelined))
     codes = inputs.make_codes(m, k, seed=m + k + 1)
     X = inputs.make_x(k, b, xd, seed=k + b + 3)
     scales = inputs.make_scales(m, k, sg, seed=13) if sg else None
