@@ -868,3 +868,44 @@ def test_codebook_is_refused_where_it_cannot_apply():
     finally:
         B.msgemm_destroy(plan)
     assert B.msgemm_plan_set_codebook(None, UINT4, check=False) == B.ERR_INVALID_ARG
+
+
+# ---------------------------------------------------------------------------
+# seeded random shapes: every variant, dtype, scale block and batch width mixed
+
+def _random_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        xd = ["f32", "f16", "bf16", "i8"][rng.integers(4)]
+        m = int(rng.integers(1, 1500))
+        sg = 0 if xd == "i8" else int([0, 0, 32, 64, 128, 256][rng.integers(6)])
+        k = 2 * int(rng.integers(1, 700))
+        if sg:
+            k = max(sg, (k // sg) * sg)  # scale blocks divide k
+        b = int([1, 1, 2, 3, 5, 8, 9, 16, 17, 24][rng.integers(10)])
+        variant = [B.VARIANT_AUTO, B.VARIANT_FUSED_LDS, B.VARIANT_FUSED_LDS16, B.VARIANT_GLOBAL_LUT,
+                   B.VARIANT_GLOBAL_LUT_HALF][rng.integers(5)]
+        d = 2
+        if variant in (B.VARIANT_GLOBAL_LUT, B.VARIANT_GLOBAL_LUT_HALF):
+            d = int(rng.integers(1, 4))
+        if variant == B.VARIANT_FUSED_LDS16 and xd == "f32":
+            continue  # no 16-bit tables for fp32 activations
+        if variant == B.VARIANT_FUSED_LDS and sg % 128 or variant == B.VARIANT_FUSED_LDS16 and sg % 64:
+            continue  # the fused kernels need scale blocks of whole k-tiles (128 resp. 64 columns)
+        pipe = int(rng.integers(2))
+        cases.append((m, k, b, xd, sg, d, variant, pipe))
+    return cases
+
+
+@pytest.mark.parametrize("m,k,b,xd,sg,d,variant,pipe", _random_cases(160, seed=20231006))
+def test_random_shapes(monkeypatch, m, k, b, xd, sg, d, variant, pipe):
+    monkeypatch.setenv("MSGEMM_TUNE_BATCH_PIPE", str(pipe))
+    codes = inputs.make_codes(m, k, seed=m * 31 + k)
+    X = inputs.make_x(k, b, xd, seed=k * 7 + b)
+    scales = inputs.make_scales(m, k, sg, seed=m + b) if sg else None
+    ref = oracle_y(codes, X, xd, scales, sg)
+    out, info = run_gpu(codes, X, xd, scales, sg, 0 if variant == B.VARIANT_AUTO else d, variant, ldx_pad=2, ldy_pad=1)
+    if variant != B.VARIANT_AUTO:
+        assert info["variant"] == variant
+    check(out, ref, xd, f"random shape {m}x{k}x{b} {xd} sg={sg} d={d} variant={variant}")
