@@ -258,6 +258,15 @@ def main() -> int:
             "kernel_us": kernel_us,
         },
     }
+    if not args.mfma and info["variant"] == 3:
+        # batches: the gather reads one 16-byte table entry (8 fp16 columns) per row, group and column pass from
+        # LDS; peak = 256 compute units x 256 B per clock x 2.4 GHz (gfx950 LDS read width; SQ_LDS_IDX_ACTIVE
+        # counts 4.3 cycles per 1 KiB ds_read_b128 in the profile of this kernel)
+        lds_bytes = float(m) * (k // 2) * ((b + 7) // 8) * 16
+        lds_peak = 256 * 256 * 2.4  # GB/s
+        out["roofline"]["lds"] = {"bound": "lds", "achieved": lds_bytes / (kernel_us * 1e-6) / 1e9, "peak": lds_peak,
+                                  "unit": "GB/s", "frac": lds_bytes / (kernel_us * 1e-6) / 1e9 / lds_peak,
+                                  "table_bytes_gathered": lds_bytes}
     if graph is not None and not args.no_ceiling and not args.hot:
         try:
             out["roofline"]["stream_read_kernel"] = stream_read_ceiling(B, torch, stream, code_bytes, n_copies, args.steps)
