@@ -473,6 +473,28 @@ def test_extreme_aspect_ratios(m, k, xd, sg):
     check(np.ascontiguousarray(out[:, rows]), ref, xd, f"{m}x{k}")
 
 
+@pytest.mark.parametrize("pipelined", [0, 1])
+@pytest.mark.parametrize("m,k,b,xd,sg", [
+    (300001, 512, 8, "f16", 128),        # tall: 1172 panels of 256 rows (586 of 512)
+    (515, 1 << 17, 8, "bf16", 0),        # wide: 2048 (4096) k-tiles, long segments
+    (259, 1 << 16, 16, "i8", 0),         # the same with integer tables and two column passes
+])
+def test_extreme_aspect_ratios_batched(monkeypatch, m, k, b, xd, sg, pipelined):
+    """Very tall and very wide batched problems in both forms of the batched kernel; sampled rows."""
+    monkeypatch.setenv("MSGEMM_TUNE_BATCH_PIPE", str(pipelined))
+    codes = inputs.make_codes(m, k, seed=23)
+    X = inputs.make_x(k, b, xd, seed=24)
+    if xd != "i8" and k > 4096:
+        X = (X.astype(np.float32) / 8).astype(X.dtype) if xd == "f16" else X  # keep fp16 outputs in range
+    scales = inputs.make_scales(m, k, sg, seed=25) if sg else None
+    out, info = run_gpu(codes, X, xd, scales, sg, 2, B.VARIANT_AUTO)
+    assert info["variant"] == B.VARIANT_FUSED_LDS16 and info["tile_groups"] == (16 if pipelined else 32)
+    rows = np.sort(np.random.default_rng(6).choice(m, size=min(m, 2048), replace=False))
+    rows[0], rows[-1] = 0, m - 1
+    ref = oracle_y(codes[rows], X, xd, None if scales is None else scales[rows], sg)
+    check(np.ascontiguousarray(out[:, rows]), ref, xd, f"{m}x{k}x{b}")
+
+
 def test_config2_d3_sweep_point():
     """Config 2 also asks for d = 3 (k = 4096 is not a multiple of 3: short last group)."""
     cfg, codes, X, _ = inputs.make_config("cfg2", m=2048)
