@@ -370,9 +370,10 @@ batched_kernel(BatchedArgs a)
 //   A k-tile is 16 table groups (32 k-columns, 64 KiB of table); LDS holds two
 //   tables.  All 64 lanes of a wavefront look up the same 16 groups (lane j of
 //   each 16-lane row starts at group j and rotates), each for rows of its own:
-//   a panel is 512 rows, a lane owns rows 64 s + lane, no fold across lanes.
-//   While the wavefronts gather from table `gen & 1` every thread writes its 8
-//   entries of table `(gen + 1) & 1`, one after every second code load, so the
+//   a panel is 512 rows (8 rows per lane), a lane owns rows 64 s + lane, no
+//   fold across lanes.  While the wavefronts gather from table `gen & 1` every
+//   thread writes its 8 entries of table `(gen + 1) & 1`, one after every
+//   second code load (with 4 rows per lane: 4 entries, every fourth), so the
 //   build costs its LDS writes and nothing else: no build phase, and one
 //   barrier per k-tile (everyone has finished reading the old table and
 //   writing the new one).  The activations of k-tile gen + 2 are fetched during
@@ -380,8 +381,8 @@ batched_kernel(BatchedArgs a)
 constexpr int kPG = 16;                   // table groups per k-tile
 constexpr int kPTableBytes = 256 * kPG * 16;
 // kPLB = rows (code bytes) a lane takes per load: 8 (8 wavefronts, 512-row panels) or 4
-// (16 wavefronts, 256-row panels: four wavefronts per SIMD, which matters because a
-// single wavefront cannot issue its look-ups fast enough to keep the LDS busy).
+// (16 wavefronts, 256-row panels, four wavefronts per SIMD; measured no faster, and its
+// variant with scales spills registers: kept as a tuning aid).
 template <int LB> constexpr int pipe_waves() { return 64 / LB; }
 
 template <typename XT, typename YT, typename AT, bool kScaled, bool kCodes8, int kPLB>
