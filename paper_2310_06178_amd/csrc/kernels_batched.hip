@@ -677,21 +677,26 @@ repack_scales_batched_kernel(const __half* __restrict__ scales, __half* __restri
 
 // Segment length: the longest (a multiple of the scale block) that still gives
 // every compute unit a workgroup, preferring grids that fill whole rounds.
-void batched_choose_segments(Plan& p)
+static int64_t phase_form_segments(int64_t blocks, int64_t units_per_seg, int64_t cus)
 {
-    const int tpb = p.scale_group > 0 ? (int)(p.scale_group / (2 * p.fs.groups)) : 1;
-    const int64_t blocks = (p.ktiles + tpb - 1) / tpb;  // indivisible runs of k-tiles
-    const int64_t units_per_seg = p.row_blocks * p.col_passes;
     int64_t best_s = blocks;
     double best_eff = -1.0;
     for (int64_t per = blocks; per >= 1; --per) {  // scale blocks per segment, longest first
         const int64_t segs = (blocks + per - 1) / per;
         const int64_t wgs = segs * units_per_seg;
-        if (4 * wgs < 3 * (int64_t)p.cus && per > 1) continue;  // too few workgroups: shorter segments
-        const double eff = (double)wgs / (double)(((wgs + p.cus - 1) / p.cus) * p.cus);
+        if (4 * wgs < 3 * cus && per > 1) continue;  // too few workgroups: shorter segments
+        const double eff = (double)wgs / (double)(((wgs + cus - 1) / cus) * cus);
         if (eff > best_eff + 0.05) { best_eff = eff; best_s = segs; }  // shorter only if clearly better balanced
-        if (wgs >= 8 * (int64_t)p.cus) break;  // enough rounds to balance: stop shortening
+        if (wgs >= 8 * cus) break;  // enough rounds to balance: stop shortening
     }
+    return best_s;
+}
+
+void batched_choose_segments(Plan& p)
+{
+    const int tpb = p.scale_group > 0 ? (int)(p.scale_group / (2 * p.fs.groups)) : 1;
+    const int64_t blocks = (p.ktiles + tpb - 1) / tpb;  // indivisible runs of k-tiles
+    int64_t best_s = phase_form_segments(blocks, p.row_blocks * p.col_passes, p.cus);
     const int forced = env_int("MSGEMM_TUNE_SEGMENTS", 0);
     if (forced >= 1 && forced <= blocks) best_s = forced;
     const int64_t per = (blocks + best_s - 1) / best_s;
@@ -704,32 +709,71 @@ void batched_choose_segments(Plan& p)
 // table, first codes) and a time per k-tile; workgroups run in rounds of one
 // per compute unit; the second pass reads one partial sum per segment and
 // output.
-void batched_choose_rows_and_segments(Plan& p, int64_t panels, int& ppw_out)
+static double pipe_form_choice(int64_t panels, int64_t ktiles, int tpb, int col_passes, int64_t cus, int lane_bytes,
+                               int waves, int& best_ppw, int64_t& best_per)
 {
-    const int tpb = p.scale_group > 0 ? (int)(p.scale_group / (2 * p.fs.groups)) : 1;
-    const int64_t blocks = (p.ktiles + tpb - 1) / tpb;  // indivisible runs of k-tiles
-    const double outputs = (double)panels * p.fs.panel_rows * p.col_passes * kBC;
+    const int64_t blocks = (ktiles + tpb - 1) / tpb;  // indivisible runs of k-tiles
+    const double outputs = (double)panels * (64 * lane_bytes) * col_passes * kBC;
     double best = 1e300;
-    int best_ppw = p.fs.waves;
-    int64_t best_per = blocks;
+    best_ppw = waves;
+    best_per = blocks;
     // Measured: a k-tile takes a workgroup 3.0 us + 0.125 us per active wavefront (8 rows per
     // lane; 1.9 + 0.085 with 4): what bounds it is the rate at which a wavefront issues its
-    // look-ups, and wavefronts that share a SIMD overlap almost completely.
-    const double tile_base_us = p.fs.lane_bytes == 8 ? 3.0 : 1.9, tile_wave_us = p.fs.lane_bytes == 8 ? 0.125 : 0.085;
-    for (int ppw = p.fs.waves; ppw >= 1; ppw >>= 1) {
+    // look-ups, and wavefronts that share a SIMD overlap almost completely.  Start-up, launch
+    // and tail of a workgroup: 6.5 us.
+    const double tile_base_us = lane_bytes == 8 ? 3.0 : 1.9, tile_wave_us = lane_bytes == 8 ? 0.125 : 0.085;
+    for (int ppw = waves; ppw >= 1; ppw >>= 1) {
         const int64_t row_blocks = (panels + ppw - 1) / ppw;
         const double tile_us = tile_base_us + tile_wave_us * ppw;
         for (int64_t per = blocks; per >= 1; --per) {
             const int64_t segs = (blocks + per - 1) / per;
             if ((blocks + segs - 1) / segs != per) continue;  // the same split again
-            const int64_t wgs = segs * row_blocks * p.col_passes;
-            const int64_t rounds = (wgs + p.cus - 1) / p.cus;
-            double cost = (double)rounds * (3.5 + (double)(per * tpb) * tile_us);
+            const int64_t wgs = segs * row_blocks * col_passes;
+            const int64_t rounds = (wgs + cus - 1) / cus;
+            double cost = (double)rounds * (6.5 + (double)(per * tpb) * tile_us);
             if (segs > 1) cost += 3.0 + (double)segs * outputs * 4.0 / 3.0e6;
             if (cost < best) { best = cost; best_ppw = ppw; best_per = per; }
             if (rounds > 64) break;  // shorter segments only add rounds from here on
         }
     }
+    return best;
+}
+
+// Which of the two forms a problem gets: the one the models above predict to be faster, the
+// pipelined one only when by more than a tenth (the models are good to about that).  The form
+// with a build phase: 5 us of start-up, then 2.3 us of table build and 0.44 us of look-ups per
+// active wavefront for every k-tile of 64 columns.
+bool batched_pipelined_is_faster(int64_t m, int64_t k, int64_t b, int64_t scale_group, int cus)
+{
+    const int col_passes = (int)((b + kBC - 1) / kBC);
+    // pipelined form: 512-row panels, k-tiles of 32 columns
+    int ppw;
+    int64_t per;
+    const double pipe_us = pipe_form_choice((m + 511) / 512, (k / 2 + kPG - 1) / kPG, scale_group > 0 ? (int)(scale_group / (2 * kPG)) : 1,
+                                            col_passes, cus, 8, 8, ppw, per);
+    // form with a build phase: 256-row panels, k-tiles of 64 columns
+    const int64_t panels = (m + 255) / 256, ktiles = (k / 2 + kBG - 1) / kBG;
+    int ppw0 = 8;
+    while (ppw0 > 1 && ktiles * col_passes * ((panels + ppw0 - 1) / ppw0) < cus) ppw0 >>= 1;
+    const int64_t row_blocks = (panels + ppw0 - 1) / ppw0;
+    const int tpb = scale_group > 0 ? (int)(scale_group / (2 * kBG)) : 1;
+    if (tpb < 1) return true;  // scale blocks of 32 columns: only the pipelined form has k-tiles that small
+    const int64_t blocks = (ktiles + tpb - 1) / tpb;
+    const int64_t segs = phase_form_segments(blocks, row_blocks * col_passes, cus);
+    const int64_t tiles_per_seg = ((blocks + segs - 1) / segs) * tpb;
+    const int64_t wgs = segs * row_blocks * col_passes;
+    double phase_us = (double)((wgs + cus - 1) / cus) * (5.0 + (double)tiles_per_seg * (2.3 + 0.44 * ppw0));
+    if (segs > 1) phase_us += 3.0 + (double)segs * (double)(panels * 256) * col_passes * kBC * 4.0 / 3.0e6;
+    return pipe_us < 0.9 * phase_us;
+}
+
+void batched_choose_rows_and_segments(Plan& p, int64_t panels, int& ppw_out)
+{
+    const int tpb = p.scale_group > 0 ? (int)(p.scale_group / (2 * p.fs.groups)) : 1;
+    const int64_t blocks = (p.ktiles + tpb - 1) / tpb;  // indivisible runs of k-tiles
+    int best_ppw;
+    int64_t best_per;
+    pipe_form_choice(panels, p.ktiles, tpb, p.col_passes, p.cus, p.fs.lane_bytes, p.fs.waves, best_ppw, best_per);
     const int forced_ppw = env_int("MSGEMM_TUNE_PPW", 0);
     if (forced_ppw >= 1 && forced_ppw <= p.fs.waves) best_ppw = forced_ppw;
     int64_t segs = (blocks + best_per - 1) / best_per;

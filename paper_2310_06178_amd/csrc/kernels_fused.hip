@@ -1001,13 +1001,10 @@ ShapeChoice pick_shape(const Plan& p, int requested_variant)
     // (MSGEMM_TUNE_BATCH_LB = 4: the 12-wavefront form of the batched kernel, tuning aid)
     // (MSGEMM_TUNE_BATCH_PIPE = 0: its form with one 32-group table and a build phase per k-tile)
     if (narrow && narrow_ok) {
-        // The batched kernel has two forms.  The pipelined one (16-group k-tiles, the next table
-        // built under the look-ups) wins once every compute unit has a long run of k-tiles for
-        // eight full panels; below that the form with 32-group k-tiles and a build phase does
-        // (half as many k-tiles to issue per row).  MSGEMM_TUNE_BATCH_PIPE = 0 / 1 overrides.
-        const int64_t panels512 = (p.m + 511) / 512, tiles16 = (p.k / 2 + 15) / 16;
-        const int64_t units = ((panels512 + 7) / 8) * ((p.b + 7) / 8);
-        const int pipe_default = units * tiles16 >= 16 * (int64_t)p.cus ? 1 : 0;
+        // The batched kernel has two forms: 16-group k-tiles with the next table built under the
+        // look-ups (pipelined), or 32-group k-tiles with a build phase.  Time models of both decide;
+        // MSGEMM_TUNE_BATCH_PIPE = 0 / 1 overrides.
+        const int pipe_default = batched_pipelined_is_faster(p.m, p.k, p.b, p.scale_group, p.cus) ? 1 : 0;
         const int lb = env_int("MSGEMM_TUNE_BATCH_LB", 8) == 4 ? 4 : 8;
         if (env_int("MSGEMM_TUNE_BATCH_PIPE", pipe_default))
             return lb == 4 ? ShapeChoice{8, 16, 4, 2, 16} : ShapeChoice{8, 16, 8, 2, 8};

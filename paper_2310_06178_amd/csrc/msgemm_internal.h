@@ -99,6 +99,8 @@ int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int
 void batched_choose_segments(Plan& p);  // needs ktiles, row_blocks, col_passes, cus; fills segments, tiles_per_segment
 // pipelined batched kernel: panels per workgroup and segments together (needs fs, ktiles, col_passes, cus)
 void batched_choose_rows_and_segments(Plan& p, int64_t panels, int& ppw_out);
+// which form of the batched kernel the time models predict to be faster for a problem
+bool batched_pipelined_is_faster(int64_t m, int64_t k, int64_t b, int64_t scale_group, int cus);
 int launch_repack_scales_batched(const Plan& p, hipStream_t s);
 int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s);
 
