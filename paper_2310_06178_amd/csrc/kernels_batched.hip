@@ -30,7 +30,8 @@
 //   up.  Everything downstream (block scales, fold, stores) works on that
 //   layout directly.  Accumulation is in fp32 throughout; int8 activations use
 //   the same path (their table entries, |entry| <= 2048, are exact in fp16 and
-//   every sum stays below 2^24, so the fp32 sums are exact integers).
+//   a segment is kept short enough for every sum to stay within 2^24, so the
+//   fp32 sums are exact integers; the segments are then added in int32).
 //
 // Shared scales (Section 3.3) are applied when a scale block of k-columns has
 // been consumed: y += q(row, block) * (sum over the block's tables).
@@ -675,6 +676,17 @@ repack_scales_batched_kernel(const __half* __restrict__ scales, __half* __restri
 
 }  // namespace
 
+// int8 activations: a segment's sums are kept in fp32 and must stay exact integers.  An entry is
+// at most 8 * 128 * 2 = 2^11 in magnitude, so a sum over 2^13 groups stays within 2^24: a segment
+// is at most 8192 groups (16384 k-columns) long, whatever was chosen or forced.  (int8 plans have
+// no scale blocks, so any number of k-tiles is a valid segment.)
+static void cap_exact_segment(Plan& p)
+{
+    if (p.x_dtype != MSGEMM_I8) return;
+    const int max_tiles = 8192 / p.fs.groups;
+    if (p.tiles_per_segment > max_tiles) p.tiles_per_segment = max_tiles;
+}
+
 // Segment length: the longest (a multiple of the scale block) that still gives
 // every compute unit a workgroup, preferring grids that fill whole rounds.
 static int64_t phase_form_segments(int64_t blocks, int64_t units_per_seg, int64_t cus)
@@ -701,6 +713,7 @@ void batched_choose_segments(Plan& p)
     if (forced >= 1 && forced <= blocks) best_s = forced;
     const int64_t per = (blocks + best_s - 1) / best_s;
     p.tiles_per_segment = (int)(per * tpb);
+    cap_exact_segment(p);
     p.segments = (int)((p.ktiles + p.tiles_per_segment - 1) / p.tiles_per_segment);
 }
 
@@ -782,6 +795,7 @@ void batched_choose_rows_and_segments(Plan& p, int64_t panels, int& ppw_out)
     const int64_t per = (blocks + segs - 1) / segs;
     ppw_out = best_ppw;
     p.tiles_per_segment = (int)(per * tpb);
+    cap_exact_segment(p);
     p.segments = (int)((p.ktiles + p.tiles_per_segment - 1) / p.tiles_per_segment);
 }
 

@@ -495,6 +495,28 @@ def test_extreme_aspect_ratios_batched(monkeypatch, m, k, b, xd, sg, pipelined):
     check(np.ascontiguousarray(out[:, rows]), ref, xd, f"{m}x{k}x{b}")
 
 
+@pytest.mark.parametrize("pipelined", [0, 1])
+def test_int8_batched_sums_stay_exact_on_long_segments(monkeypatch, pipelined):
+    """The batched kernel adds int8 tables in fp32.  Worst case for that: the first half of k drives
+    every sum to 2^25 (codes -8, activations -128), the second half adds ones, which fp32 could no longer
+    hold if one segment ran through all of k.  A single segment is asked for; the library must cut it."""
+    monkeypatch.setenv("MSGEMM_TUNE_BATCH_PIPE", str(pipelined))
+    monkeypatch.setenv("MSGEMM_TUNE_SEGMENTS", "1")
+    m, k, b = 300, 1 << 16, 8
+    codes = np.empty((m, k // 2), dtype=np.uint8)
+    codes[:, : k // 4] = 0x88           # two codes of -8
+    codes[:, k // 4:] = 0x01            # codes +1 and 0
+    X = np.empty((b, k), dtype=np.int8)
+    X[:, : k // 2] = -128
+    X[:, k // 2:] = 1
+    X[3, k // 2:] = -1                  # one column counts down instead
+    ref = oracle.gemm_i32(codes, X)
+    assert ref[0, 0] == (1 << 25) + k // 4 and ref[3, 0] == (1 << 25) - k // 4
+    out, info = run_gpu(codes, X, "i8", None, 0, 2, B.VARIANT_FUSED_LDS16)
+    assert info["split_k"] >= (k // 2) // 8192  # at most 8192 groups per segment
+    assert np.array_equal(out, ref)
+
+
 def test_config2_d3_sweep_point():
     """Config 2 also asks for d = 3 (k = 4096 is not a multiple of 3: short last group)."""
     cfg, codes, X, _ = inputs.make_config("cfg2", m=2048)
