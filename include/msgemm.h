@@ -74,12 +74,17 @@ typedef enum {
      * (phase 1 and 2 pipelined over the last dimension of L, Section 4), streams
      * its repacked code tile; partial sums over k-tiles are added by trailing
      * workgroups of the same launch (b <= 2) or by a small second kernel.
-     * Table entries are fp32 (int32 for int8 X). */
+     * Table entries are fp32 (int32 for int8 X).  A scale block must be a whole
+     * number of k-tiles: scale_group % 128 == 0 (b <= 2 and 16-bit activations),
+     * % 64 == 0 (fp32 X with b > 2); otherwise MSGEMM_ERR_UNSUPPORTED, and AUTO
+     * takes GLOBAL_LUT. */
     MSGEMM_VARIANT_FUSED_LDS = 2,
-    /* Same schedule with 16-bit table entries, 8 batch columns per entry: int16
-     * for int8 X (exact), fp16 for fp16 / bf16 X (each entry rounded to fp16,
-     * which needs |16 x| inside the fp16 range; accumulation stays fp32).
-     * Not available for fp32 X.  AUTO picks it for b > 2. */
+    /* Same schedule with fp16 table entries, 8 batch columns per entry.  For
+     * int8 X the entries are integers of magnitude <= 2048, exact in fp16, and
+     * the sums are kept exact (result bit-exact); for fp16 / bf16 X each entry
+     * is rounded to fp16, which needs |16 x| inside the fp16 range; accumulation
+     * is fp32.  scale_group % 32 == 0.  Not available for fp32 X.  AUTO picks
+     * it for b > 2. */
     MSGEMM_VARIANT_FUSED_LDS16 = 3,
     /* GLOBAL_LUT with half of every table (the optimisation sketched in Section
      * 4.1): only the combinations whose last code has its top bit clear are

@@ -321,6 +321,17 @@ def test_fused_lds16_not_for_fp32():
     assert status == B.ERR_UNSUPPORTED and handle is None
 
 
+def test_batched_scale_blocks_of_32_columns_use_the_pipelined_form():
+    """Scale blocks of 32 columns are one k-tile of the pipelined batched form (the other form's k-tiles are 64)."""
+    m, k, b = 700, 512, 9
+    codes = inputs.make_codes(m, k, seed=4)
+    X = inputs.make_x(k, b, "f16", seed=5)
+    scales = inputs.make_scales(m, k, 32, seed=6)
+    out, info = run_gpu(codes, X, "f16", scales, 32, 0, B.VARIANT_AUTO, ldx_pad=2, ldy_pad=1)
+    assert info["variant"] == B.VARIANT_FUSED_LDS16 and info["tile_groups"] == 16
+    check(out, oracle_y(codes, X, "f16", scales, 32), "f16", "scale blocks of 32")
+
+
 def test_fused_scale_group_not_tileable_falls_back():
     m, k, b = 64, 256, 2
     codes = inputs.make_codes(m, k, seed=1)
