@@ -75,9 +75,8 @@ typedef enum {
      * its repacked code tile; partial sums over k-tiles are added by trailing
      * workgroups of the same launch (b <= 2) or by a small second kernel.
      * Table entries are fp32 (int32 for int8 X).  A scale block must be a whole
-     * number of k-tiles: scale_group % 128 == 0 (b <= 2 and 16-bit activations),
-     * % 64 == 0 (fp32 X with b > 2); otherwise MSGEMM_ERR_UNSUPPORTED, and AUTO
-     * takes GLOBAL_LUT. */
+     * number of k-tiles: scale_group % 128 == 0, or % 64 == 0 for fp32 X with
+     * b > 2; otherwise MSGEMM_ERR_UNSUPPORTED, and AUTO takes GLOBAL_LUT. */
     MSGEMM_VARIANT_FUSED_LDS = 2,
     /* Same schedule with fp16 table entries, 8 batch columns per entry.  For
      * int8 X the entries are integers of magnitude <= 2048, exact in fp16, and
