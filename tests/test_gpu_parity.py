@@ -159,6 +159,30 @@ def test_build_lut_matches_phase1_reference(xd, sg, d, b):
             assert np.array_equal(Lh, ref.astype(np.float32))
 
 
+@pytest.mark.parametrize("xd,b,half", [("f16", 20, 0), ("f32", 16, 1), ("bf16", 3, 0)])
+def test_build_lut_depth_four(xd, b, half):
+    """d = 4: 65536 combinations per group (k = 18: four full groups and one of two columns), plain and
+    matrix-core builders, full and half tables."""
+    m, k, d = 8, 18, 4
+    codes = inputs.make_codes(m, k, seed=1)
+    X = inputs.make_x(k, b, xd, seed=2)
+    dX = torch_io.to_device(X, xd)
+    variant = B.VARIANT_GLOBAL_LUT_HALF if half else B.VARIANT_GLOBAL_LUT
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], d, 0, torch_io.to_device(codes, "codes"), None, variant)
+    try:
+        G, E = oracle.lut_groups(k, d, 0), 16 ** d
+        assert G == 5
+        stored = E // 2 if half else E
+        L = torch.empty(B.msgemm_lut_bytes(plan) // 4, dtype=torch.float32, device="cuda:0")
+        B.msgemm_build_lut(plan, dX, k, L)
+        torch.cuda.synchronize()
+        Lh = L.cpu().numpy()[: G * stored * b].reshape(G, stored, b)
+    finally:
+        B.msgemm_destroy(plan)
+    ref = oracle.lut_build(x_to_f64(X, xd), d, 0)[:, :stored, :]
+    assert np.max(np.abs(Lh.astype(np.float64) - ref)) <= d * 2.0 ** -23 * np.abs(ref).max()
+
+
 # ---------------------------------------------------------------------------
 # argument checking through the ABI (no kernel is launched for any of these)
 
