@@ -107,6 +107,24 @@ def stream_read_ceiling(B, torch, stream, nbytes, n_copies, steps):
     return {"bytes": nbytes, "us": us, "GB/s": nbytes / (us * 1e-6) / 1e9}
 
 
+def lds_read_ceiling(B, torch, stream, width=16, reads=4096, launches=20):
+    """Measured LDS read bandwidth of the device: conflict-free `width`-byte reads by 16 wavefronts on
+    every compute unit (msgemm_calib_lds_read), HIP events on the launch stream."""
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
+    nbytes = 0
+    with torch.cuda.stream(stream):
+        for _ in range(3):
+            nbytes = B.msgemm_calib_lds_read(width, reads, sink, stream)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record(stream)
+        for _ in range(launches):
+            B.msgemm_calib_lds_read(width, reads, sink, stream)
+        ev1.record(stream)
+    torch.cuda.synchronize()
+    us = ev0.elapsed_time(ev1) * 1e3 / launches
+    return {"width_bytes": width, "bytes": nbytes, "us": us, "GB/s": nbytes / (us * 1e-6) / 1e9}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -267,6 +285,11 @@ def main() -> int:
         out["roofline"]["lds"] = {"bound": "lds", "achieved": lds_bytes / (kernel_us * 1e-6) / 1e9, "peak": lds_peak,
                                   "unit": "GB/s", "frac": lds_bytes / (kernel_us * 1e-6) / 1e9 / lds_peak,
                                   "table_bytes_gathered": lds_bytes}
+        if not args.no_ceiling:
+            # the same reads without anything else: what the LDS of this device delivers (measured in this run)
+            measured = lds_read_ceiling(B, torch, stream)
+            out["roofline"]["lds"]["measured_read_kernel"] = measured
+            out["roofline"]["lds"]["frac_of_measured"] = out["roofline"]["lds"]["achieved"] / measured["GB/s"]
     if graph is not None and not args.no_ceiling and not args.hot:
         try:
             out["roofline"]["stream_read_kernel"] = stream_read_ceiling(B, torch, stream, code_bytes, n_copies, args.steps)

@@ -222,6 +222,19 @@ int msgemm_dequant_mfma_run(const msgemm_plan_t* plan, const void* X, int64_t ld
  */
 int msgemm_calib_stream_read(const void* src, size_t bytes, void* sink, void* stream);
 
+/*
+ * Measurement aid, not msGeMM: one workgroup of 16 wavefronts per compute unit
+ * reads LDS and nothing else -- every lane `reads` times (a multiple of 8, at
+ * most 2^20) `width_bytes` (4, 8 or 16) bytes, consecutive lanes consecutive
+ * slots, i.e. free of bank conflicts, eight reads in flight per lane.  Timed
+ * like msgemm_run it gives the LDS read bandwidth of the device, the
+ * denominator for the gather of the batched kernels (Section 6 of the paper
+ * expects phase 2 to be bound by such look-ups).  *bytes_out (host, may be NULL)
+ * receives the bytes one launch reads; `sink` (device, >= 4 bytes) is only
+ * written if the data sums to a magic value.
+ */
+int msgemm_calib_lds_read(int width_bytes, int reads, void* sink, size_t* bytes_out, void* stream);
+
 /* Synchronise the device, free everything the plan owns.  NULL is allowed. */
 void msgemm_destroy(msgemm_plan_t* plan);
 

@@ -21,7 +21,7 @@ OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, -1, -2, -3, -4
 
 EXPORTS = (
     "msgemm_plan", "msgemm_plan_codes8", "msgemm_plan_set_codebook", "msgemm_plan_get_info", "msgemm_lut_bytes", "msgemm_build_lut",
-    "msgemm_consume_lut", "msgemm_run", "msgemm_dequant_mfma_run", "msgemm_calib_stream_read", "msgemm_destroy",
+    "msgemm_consume_lut", "msgemm_run", "msgemm_dequant_mfma_run", "msgemm_calib_stream_read", "msgemm_calib_lds_read", "msgemm_destroy",
     "msgemm_status_string", "msgemm_last_hip_error", "msgemm_version",
 )
 
@@ -84,6 +84,8 @@ def load():
     lib.msgemm_dequant_mfma_run.restype = ci
     lib.msgemm_calib_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     lib.msgemm_calib_stream_read.restype = ci
+    lib.msgemm_calib_lds_read.argtypes = [ci, ci, vp, ctypes.POINTER(ctypes.c_size_t), vp]
+    lib.msgemm_calib_lds_read.restype = ci
     lib.msgemm_destroy.argtypes = [vp]
     lib.msgemm_destroy.restype = None
     lib.msgemm_status_string.argtypes = [ci]
@@ -198,6 +200,15 @@ def msgemm_dequant_mfma_run(plan, X, ldx, Y, ldy, stream=None):
                                         _stream(stream))
     if rc != OK:
         raise MsgemmError(rc, "msgemm_dequant_mfma_run")
+
+
+def msgemm_calib_lds_read(width_bytes, reads, sink, stream=None):
+    """Returns the bytes one launch reads from LDS."""
+    out = ctypes.c_size_t(0)
+    rc = load().msgemm_calib_lds_read(int(width_bytes), int(reads), _ptr(sink), ctypes.byref(out), _stream(stream))
+    if rc != OK:
+        raise MsgemmError(rc, "msgemm_calib_lds_read")
+    return out.value
 
 
 def msgemm_calib_stream_read(src, nbytes, sink, stream=None):

@@ -45,7 +45,57 @@ stream_read_kernel(const uint4* __restrict__ src, uint32_t* sink, int64_t waves_
     if (acc == 0x12345678u) *sink = acc;
 }
 
+// Conflict-free LDS reads and nothing else: every lane reads `reads` times W bytes, consecutive lanes
+// consecutive W-byte slots (so the lanes served together cover all banks), eight reads in flight.
+constexpr int kLdsCalibWaves = 16;
+constexpr int kLdsCalibBytes = 65536;
+
+template <typename T>
+__global__ void __launch_bounds__(kLdsCalibWaves * 64)
+lds_read_kernel(uint32_t* sink, int reads)
+{
+    __shared__ __align__(16) unsigned char lds[kLdsCalibBytes];
+    constexpr int kSlots = kLdsCalibBytes / (int)sizeof(T);
+    for (int i = threadIdx.x; i < kLdsCalibBytes / 4; i += blockDim.x) ((uint32_t*)lds)[i] = (uint32_t)i * 2654435761u;
+    __syncthreads();
+    const T* table = (const T*)lds;
+    uint32_t acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    uint32_t slot = threadIdx.x;
+    for (int it = 0; it < reads; it += 8) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const T v = table[(slot + (uint32_t)u * 1024u) & (kSlots - 1)];
+            uint32_t w;
+            __builtin_memcpy(&w, &v, 4);
+            acc[u] ^= w;
+        }
+        slot += 8 * 1024 + 64;
+    }
+    uint32_t all = 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) all += acc[u];
+    if (all == 0x12345678u) *sink = all;
+}
+
 }  // namespace
+
+int launch_calib_lds_read(int width_bytes, int reads, void* sink, size_t* bytes_out, hipStream_t s)
+{
+    int cus = 256, dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+        prop.multiProcessorCount > 0)
+        cus = prop.multiProcessorCount;
+    if (!sink || reads < 8 || reads % 8 != 0 || reads > (1 << 20)) return MSGEMM_ERR_INVALID_ARG;
+    const dim3 grid((unsigned)cus), blk(kLdsCalibWaves * 64);
+    if (width_bytes == 16) hipLaunchKernelGGL(lds_read_kernel<uint4>, grid, blk, 0, s, (uint32_t*)sink, reads);
+    else if (width_bytes == 8) hipLaunchKernelGGL(lds_read_kernel<uint2>, grid, blk, 0, s, (uint32_t*)sink, reads);
+    else if (width_bytes == 4) hipLaunchKernelGGL(lds_read_kernel<uint32_t>, grid, blk, 0, s, (uint32_t*)sink, reads);
+    else return MSGEMM_ERR_INVALID_ARG;
+    MSGEMM_HIP_TRY(hipGetLastError());
+    if (bytes_out) *bytes_out = (size_t)cus * kLdsCalibWaves * 64 * (size_t)reads * (size_t)width_bytes;
+    return MSGEMM_OK;
+}
 
 int launch_calib_stream_read(const void* src, size_t bytes, void* sink, hipStream_t s)
 {

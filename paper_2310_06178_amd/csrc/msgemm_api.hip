@@ -293,6 +293,11 @@ int msgemm_calib_stream_read(const void* src, size_t bytes, void* sink, void* st
     return msgemm::launch_calib_stream_read(src, bytes, sink, (hipStream_t)stream);
 }
 
+int msgemm_calib_lds_read(int width_bytes, int reads, void* sink, size_t* bytes_out, void* stream)
+{
+    return msgemm::launch_calib_lds_read(width_bytes, reads, sink, bytes_out, (hipStream_t)stream);
+}
+
 void msgemm_destroy(msgemm_plan_t* plan)
 {
     if (!plan) return;

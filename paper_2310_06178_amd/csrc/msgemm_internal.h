@@ -106,6 +106,7 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
 
 // calibration.hip
 int launch_calib_stream_read(const void* src, size_t bytes, void* sink, hipStream_t s);
+int launch_calib_lds_read(int width_bytes, int reads, void* sink, size_t* bytes_out, hipStream_t s);
 
 // kernels_mfma.hip
 int launch_dequant_mfma(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s);

@@ -841,6 +841,20 @@ def test_dequant_mfma_unsupported_dtypes():
         B.msgemm_destroy(plan)
 
 
+def test_calibration_lds_read_entry_point():
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    for width in (4, 8, 16):
+        assert B.msgemm_calib_lds_read(width, 64, sink) == cus * 1024 * 64 * width
+    torch.cuda.synchronize()
+    assert int(sink[0]) == 0
+    for width, reads in ((3, 64), (16, 0), (16, 12), (16, (1 << 20) + 8)):
+        with pytest.raises(B.MsgemmError):
+            B.msgemm_calib_lds_read(width, reads, sink)
+    with pytest.raises(B.MsgemmError):
+        B.msgemm_calib_lds_read(16, 64, None)
+
+
 def test_calibration_stream_read_entry_point():
     """The measurement aid accepts whole multiples of its launch footprint only and leaves the sink alone."""
     cus = torch.cuda.get_device_properties(0).multi_processor_count
