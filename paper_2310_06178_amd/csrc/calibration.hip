@@ -58,22 +58,29 @@ lds_read_kernel(uint32_t* sink, int reads)
     constexpr int kSlots = kLdsCalibBytes / (int)sizeof(T);
     for (int i = threadIdx.x; i < kLdsCalibBytes / 4; i += blockDim.x) ((uint32_t*)lds)[i] = (uint32_t)i * 2654435761u;
     __syncthreads();
-    const T* table = (const T*)lds;
-    uint32_t acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    uint32_t slot = threadIdx.x;
+    // eight reads per round at fixed distances from the lane's own slot (immediate offsets: no
+    // address arithmetic competes with the reads); consecutive lanes read consecutive slots
+    uint32_t base = (uint32_t)(threadIdx.x * sizeof(T));  // byte offset of the lane's slot
+    constexpr int kStride = 1024 * (kSlots / 1024 >= 8 ? kSlots / 1024 / 8 : 1);  // slots between the eight reads
     for (int it = 0; it < reads; it += 8) {
+        // opaque copies of the offset: the reads are neither hoisted out of the loop nor merged into
+        // two-address forms (a gather cannot use those)
+        uint32_t at[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) at[u] = base;
+        asm volatile("" : "+v"(at[0]), "+v"(at[1]), "+v"(at[2]), "+v"(at[3]), "+v"(at[4]), "+v"(at[5]), "+v"(at[6]), "+v"(at[7]));
+        T v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = ((const T*)(lds + at[u]))[(u * kStride) % kSlots];
+        // every byte read is demanded in a register, by no instruction: nothing but the reads is timed
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const T v = table[(slot + (uint32_t)u * 1024u) & (kSlots - 1)];
-            uint32_t w;
-            __builtin_memcpy(&w, &v, 4);
-            acc[u] ^= w;
+            if constexpr (sizeof(T) == 16) asm volatile("" ::"v"(v[u].x), "v"(v[u].y), "v"(v[u].z), "v"(v[u].w));
+            else if constexpr (sizeof(T) == 8) asm volatile("" ::"v"(v[u].x), "v"(v[u].y));
+            else asm volatile("" ::"v"(v[u]));
         }
-        slot += 8 * 1024 + 64;
     }
-    uint32_t all = 0;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) all += acc[u];
+    const uint32_t all = base;
     if (all == 0x12345678u) *sink = all;
 }
 
