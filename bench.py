@@ -71,12 +71,26 @@ def cpu_baseline(cfg, codes, X, scales, budget_s=12.0):
         t_total += dt
         reps += 1
     mean = t_total / reps
+    cores = oracle.num_threads()
+    # the same on one core (a few passes): what a single host thread does
+    oracle.set_threads(1)
+    try:
+        run()
+        t1, n1 = 0.0, 0
+        while t1 < 3.0 and n1 < 5:
+            t0 = time.perf_counter()
+            run()
+            t1 += time.perf_counter() - t0
+            n1 += 1
+    finally:
+        oracle.set_threads(cores)
     return {
         "value": 2.0 * rows * k * b / mean / 1e12,
         "unit": "TOPS",
-        "cores": oracle.num_threads(),
+        "cores": cores,
         "kind": "oracle",
         "sample": f"{rows} of {m} rows x all k x all b, {reps} passes, mean {mean * 1e3:.2f} ms, best {best * 1e3:.2f} ms",
+        "one_core": {"value": 2.0 * rows * k * b / (t1 / n1) / 1e12, "unit": "TOPS", "passes": n1},
     }
 
 

@@ -34,6 +34,8 @@ CONFIGS = {
     "mlp2":     dict(m=49152, k=12288, b=1,  x="f16", y="f16", scale_group=0, d=2, seed=12),
     "mlp1_b16": dict(m=12288, k=49152, b=16, x="f16", y="f16", scale_group=0, d=2, seed=11),
     "mlp2_b16": dict(m=49152, k=12288, b=16, x="f16", y="f16", scale_group=0, d=2, seed=12),
+    "mlp1_b64": dict(m=12288, k=49152, b=64, x="f16", y="f16", scale_group=0, d=2, seed=11),
+    "mlp2_b64": dict(m=49152, k=12288, b=64, x="f16", y="f16", scale_group=0, d=2, seed=12),
     # 1.2 GB of codes: where the fixed costs of a launch no longer show (same recipe, seed 13)
     "big1":     dict(m=49152, k=49152, b=1,  x="f16", y="f16", scale_group=0, d=2, seed=13),
 }
