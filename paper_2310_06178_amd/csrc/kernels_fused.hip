@@ -927,6 +927,47 @@ reduce_kernel(const float* __restrict__ partials, YT* __restrict__ Y, int64_t ld
     }
 }
 
+// The same pass for few partial sums per output (at most kFewSlices): the kernel above would then be a
+// great many workgroups with one load each.  Here a lane owns four consecutive partial sums of a column
+// and requests all k-segments at once (16-byte loads); added in segment order.
+constexpr int kFewSlices = 16;
+
+template <typename YT, typename AT, int F, int kMax>
+__global__ void __launch_bounds__(64)
+reduce_few_kernel(const float* __restrict__ partials, YT* __restrict__ Y, int64_t ldy, int64_t m, int64_t b,
+                  int64_t m_pad, int64_t b_pad, int slices, int64_t span)
+{
+    const int lane = threadIdx.x;
+    const int64_t chunks_per_col = m_pad / 256;
+    const int64_t chunk = blockIdx.x % chunks_per_col;  // 256 consecutive partial sums of the column
+    const int64_t col = blockIdx.x / chunks_per_col;
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)partials, 0, (int)span, 0x00020000);
+    const uint32_t tile_stride = (uint32_t)(b_pad * m_pad * 4);
+    const uint32_t off0 = (uint32_t)(col * m_pad + chunk * 256 + lane * 4) * 4u;
+    v4u v[kMax];  // kMax = 4, 8 or 16: the smallest that holds the segments
+#pragma unroll
+    for (int t = 0; t < kMax; ++t)
+        v[t] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, t < slices ? (int)(off0 + (uint32_t)t * tile_stride) : 0x7ffffff0, 0, 0);
+    AT sum[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int t = 0; t < kMax; ++t) {  // (segments past the last read as zero: the load is out of the buffer's range)
+        AT x;
+        set_bits(x, v[t].x); sum[0] += x;
+        set_bits(x, v[t].y); sum[1] += x;
+        set_bits(x, v[t].z); sum[2] += x;
+        set_bits(x, v[t].w); sum[3] += x;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        // partial sum f of a panel belongs to lane f / F, output i = f % F, i.e. row 64*i + lane
+        const int64_t f = chunk * 256 + lane * 4 + e;
+        const int64_t panel = f / (64 * F);
+        const int in_panel = (int)(f % (64 * F));
+        const int64_t row = panel * (64 * F) + 64 * (in_panel % F) + in_panel / F;
+        if (row < m) Y[col * ldy + row] = to_output<YT, AT>(sum[e]);
+    }
+}
+
 // One-off reorder of the row-major code bytes into streaming order:
 // [load t][k-tile][panel][lane][LB], or, kPanelMajor, [panel][k-tile][load t][lane][LB]
 // (a wavefront that runs through the k-tiles of its panel then reads one
@@ -1237,8 +1278,25 @@ int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int
     const int64_t b_pad = (int64_t)p.col_passes * p.fs.cols;
     const dim3 grid((unsigned)((p.m_pad / 64) * p.b)), blk(kReduceWaves * 64);
     const int f = p.fs.panel_rows / 64;  // outputs per lane of the producing kernel: 8, 4 or 2
+    const bool few = slices <= kFewSlices && p.m_pad % 256 == 0;
+    const dim3 fgrid((unsigned)((p.m_pad / 256) * p.b)), fblk(64);
+#define MSGEMM_REDUCE_FEW(YT, AT, FF)                                                                           \
+    do {                                                                                                        \
+        if (slices <= 4)                                                                                        \
+            hipLaunchKernelGGL((reduce_few_kernel<YT, AT, FF, 4>), fgrid, fblk, 0, s, partials, (YT*)Y, ldy, p.m, p.b,  \
+                               p.m_pad, b_pad, slices, span);                                                   \
+        else if (slices <= 8)                                                                                   \
+            hipLaunchKernelGGL((reduce_few_kernel<YT, AT, FF, 8>), fgrid, fblk, 0, s, partials, (YT*)Y, ldy, p.m, p.b,  \
+                               p.m_pad, b_pad, slices, span);                                                   \
+        else                                                                                                    \
+            hipLaunchKernelGGL((reduce_few_kernel<YT, AT, FF, 16>), fgrid, fblk, 0, s, partials, (YT*)Y, ldy, p.m, p.b, \
+                               p.m_pad, b_pad, slices, span);                                                   \
+    } while (0)
 #define MSGEMM_REDUCE(YT, AT)                                                                                   \
-    if (f == 8)                                                                                                 \
+    if (few && f == 8) MSGEMM_REDUCE_FEW(YT, AT, 8);                                                            \
+    else if (few && f == 4) MSGEMM_REDUCE_FEW(YT, AT, 4);                                                       \
+    else if (few) MSGEMM_REDUCE_FEW(YT, AT, 2);                                                                 \
+    else if (f == 8)                                                                                            \
         hipLaunchKernelGGL((reduce_kernel<YT, AT, 8>), grid, blk, 0, s, partials, (YT*)Y, ldy, p.m, p.b, p.m_pad, \
                            b_pad, slices, span);                                                                \
     else if (f == 4)                                                                                            \
@@ -1256,6 +1314,7 @@ int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int
         return MSGEMM_ERR_INVALID_ARG;
     }
 #undef MSGEMM_REDUCE
+#undef MSGEMM_REDUCE_FEW
     MSGEMM_HIP_TRY(hipGetLastError());
     return MSGEMM_OK;
 }
