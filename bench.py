@@ -28,11 +28,47 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch of the dominant (fused) kernel, reads + writes, from two
-# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same
-# counter reads for a 64 MiB elementwise kernel in the same run.
-# Sources: profiles/fused_kernel_cfg2_hbm_traffic.txt, profiles/fused_long_kernel_mlp2_big1_trace_and_traffic.txt
-MEASURED_TRAFFIC_BYTES = {"cfg2": 38167930, "mlp2": 310518000}
+LDS_PEAK_GBS = 256 * 256 * 2.4  # 256 compute units x 256 B per clock (gfx950 LDS read width) x 2.4 GHz
+
+# HBM bytes per launch of the dominant kernel of each configuration, reads + writes, from two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for a
+# 64 MiB elementwise kernel in the same run: recorded in this table, one line per configuration.
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
+
+
+def measured_traffic(config: str):
+    """(bytes per launch, kernel name) recorded for `config`, or (None, None)."""
+    try:
+        with open(TRAFFIC_TABLE) as f:
+            for line in f:
+                w = line.split()
+                if len(w) >= 5 and not line.startswith("#") and w[0] == config:
+                    return int(w[2]) + int(w[3]), w[1]
+    except OSError:
+        pass
+    return None, None
+
+
+def parity_spot_check(cfg, codes, X, scales, Y_host, torch_io, max_macs=4e9):
+    """The output of the seeded weight copy against the oracle: every row when that is quick, else the first
+    and last rows and a seeded sample.  Bit-exact for int8, else the relative L2 error against the bound."""
+    import oracle
+    m, k, b = cfg["m"], cfg["k"], cfg["b"]
+    if m * k * b <= max_macs:
+        rows = np.arange(m)
+    else:
+        n = max(256, int(max_macs // (k * b)))
+        rows = np.unique(np.concatenate([[0, m - 1], np.random.default_rng(7).choice(m, size=n, replace=False)]))
+    c = codes[rows]
+    s = None if scales is None else scales[rows]
+    got = np.ascontiguousarray(Y_host[:, rows])
+    if cfg["x"] == "i8":
+        ok = bool(np.array_equal(got, oracle.gemm_i32(c, X)))
+        return {"rows": int(len(rows)), "bit_exact": ok, "ok": ok}
+    Xd = oracle.bf16_bits_to_f64(X) if cfg["x"] == "bf16" else X.astype(np.float64)
+    err = oracle.rel_l2(torch_io.to_f64(got), oracle.gemm_f64(c, Xd, s, cfg["scale_group"]))
+    bound = {"f32": 1e-5, "f16": 2e-3, "bf16": 1.6e-2}[cfg["y"]]
+    return {"rows": int(len(rows)), "rel_l2": err, "bound": bound, "ok": bool(err <= bound)}
 
 
 def algorithmic_bytes(cfg) -> int:
@@ -149,7 +185,7 @@ def main() -> int:
     ap.add_argument("--hot", action="store_true", help="one weight copy (cache-resident), labelled as such")
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--d", type=int, default=None)
-    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle legs (cpu_baseline and the parity spot check)")
     ap.add_argument("--mfma", action="store_true",
                     help="time the dequantise + MFMA comparison kernel instead of the msGeMM path (labelled as such)")
     ap.add_argument("--no-ceiling", action="store_true",
@@ -242,10 +278,12 @@ def main() -> int:
     wall = time.perf_counter() - t0
     gpu_ms = ev0.elapsed_time(ev1)
 
-    # the last step ran on plan (steps-1) % n_copies; copy 0 has a known answer:
-    # run it once more eagerly for the parity spot check
+    # the last step ran on plan (steps-1) % n_copies; copy 0 holds the seeded weights: run it once more,
+    # eagerly, and compare that output with the oracle
+    Y.zero_()
     step(0)
     torch.cuda.synchronize()
+    spot = None if args.no_cpu else parity_spot_check(cfg, codes, X, scales, torch_io.to_host(Y), torch_io)
 
     ms_per_step = wall * 1e3 / args.steps
     kernel_us = gpu_ms * 1e3 / args.steps  # HIP events on the launch stream
@@ -285,7 +323,8 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
+            "traffic": None if args.mfma else measured_traffic(args.config)[0],
+            "traffic_kernel": None if args.mfma else measured_traffic(args.config)[1],
             "algorithmic_bytes": alg,
             "kernel_us": kernel_us,
         },
@@ -295,7 +334,7 @@ def main() -> int:
         # LDS; peak = 256 compute units x 256 B per clock x 2.4 GHz (gfx950 LDS read width; SQ_LDS_IDX_ACTIVE
         # counts 4.3 cycles per 1 KiB ds_read_b128 in the profile of this kernel)
         lds_bytes = float(m) * (k // 2) * ((b + 7) // 8) * 16
-        lds_peak = 256 * 256 * 2.4  # GB/s
+        lds_peak = LDS_PEAK_GBS
         out["roofline"]["lds"] = {"bound": "lds", "achieved": lds_bytes / (kernel_us * 1e-6) / 1e9, "peak": lds_peak,
                                   "unit": "GB/s", "frac": lds_bytes / (kernel_us * 1e-6) / 1e9 / lds_peak,
                                   "table_bytes_gathered": lds_bytes}
@@ -310,11 +349,15 @@ def main() -> int:
         except Exception as e:  # a device with another CU count: the figure is optional
             print(f"bench.py: stream-read ceiling not measured ({e})", file=sys.stderr)
     if not args.no_cpu:
+        out["parity_spot_check"] = spot
         out["cpu_baseline"] = cpu_baseline(cfg, codes, X, scales)
 
     for p in plans:
         B.msgemm_destroy(p)
     print(json.dumps(out), flush=True)
+    if spot is not None and not spot["ok"]:
+        print(f"bench.py: the timed path does not match the oracle: {spot}", file=sys.stderr)
+        return 4
     return 0
 
 

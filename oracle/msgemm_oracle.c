@@ -106,14 +106,12 @@ static int check_shape(int64_t m, int64_t k, int64_t b, int64_t scale_group)
 }
 
 /*
- * y(i,c) = sum_g q(i,g) * sum_{j in block g} b(code(i,j)) * X(j,c)
+ * y(i,c) = sum_g q(i,g) * sum_{j in block g} value(code(i,j)) * X(j,c)
  * (Section 3.2 first line; Section 3.3 for q).  fp64 throughout.
- */
-/*
- * The same sum with b(.) replaced by an arbitrary map from the 16 bit patterns
- * to values (Section 2: the exact datatype of the weights is irrelevant to the
- * method; b(.) of Section 3.1 is the only place where the encoding enters).
- * values16 == NULL means the two's-complement b(.) of the paper.
+ * value(.) is b(.) of Section 3.1 (values16 == NULL), or an arbitrary map from
+ * the 16 bit patterns to values (Section 2: the exact datatype of the weights
+ * is irrelevant to the method; b(.) is the only place where the encoding
+ * enters).
  */
 int msgemm_oracle_gemm_f64_values(int64_t m, int64_t k, int64_t b,
                                   const uint8_t* codes, const double* values16,

@@ -319,6 +319,46 @@ def test_cost_model_identities():
     assert oracle.mem_accesses(m, k, b) == k * b + m * k
 
 
+def test_mem_accesses_on_the_worked_example():
+    """Section 4.2 counts k*b elements of X plus m*k elements of M for either method.  On the paper's
+    running example (m = 12, k = 4, b = 1) that is the 4 activations and the 48 codes: 52, counted by hand;
+    swapping m and k, or dropping the X term, gives another number."""
+    assert oracle.mem_accesses(12, 4, 1) == 52
+    assert oracle.mem_accesses(12, 4, 3) == 60      # two more activation vectors: 8 more elements
+    assert oracle.mem_accesses(4, 12, 1) == 60      # not symmetric in m and k
+
+
+def test_ops_on_the_worked_example():
+    """Section 4 on the running example at d = 2: the table has 16^2 entries for each of the k/d = 2 groups,
+    each built from d = 2 products (512 entries, 16^d * k = 1024 operations as the paper counts them), and a row
+    adds k/d - 1 = 1 time: 12 additions."""
+    assert oracle.ops_lut(4, 2) == 1024
+    assert oracle.ops_consume(12, 4, 2) == 12
+    assert oracle.ops_naive(12, 4) == 48
+
+
+# --------------------------------------------------------------------------
+# the error measure of every floating-point parity assertion
+
+def test_rel_l2_hand_worked():
+    """||y - ref|| / ||ref|| on vectors small enough to do by hand: y = (3, 4), ref = (0, 5): the difference is
+    (3, -1), its norm sqrt(10), the reference's norm 5.  A wrong denominator (||y|| is also 5 here, so a second
+    case tells them apart), a missing square root or a sum of absolute values all give other numbers."""
+    assert abs(oracle.rel_l2([3.0, 4.0], [0.0, 5.0]) - np.sqrt(10.0) / 5.0) < 1e-15
+    # ||y|| = 10, ||ref|| = 5, difference (6, 3): sqrt(45) / 5 = 3 / sqrt(5)
+    assert abs(oracle.rel_l2([6.0, 8.0], [0.0, 5.0]) - 3.0 / np.sqrt(5.0)) < 1e-15
+    assert oracle.rel_l2([1.0, 2.0, 3.0], [1.0, 2.0, 3.0]) == 0.0
+    # the whole output counts as one vector, whatever its shape
+    assert abs(oracle.rel_l2(np.array([[3.0], [4.0]]), np.array([[0.0], [5.0]])) - np.sqrt(10.0) / 5.0) < 1e-15
+    # a zero reference: the absolute error (nothing to divide by)
+    assert oracle.rel_l2([3.0, 4.0], [0.0, 0.0]) == 5.0
+    # not symmetric: the reference is the second argument
+    assert abs(oracle.rel_l2([0.0, 5.0], [3.0, 4.0]) - np.sqrt(10.0) / 5.0) < 1e-15
+    assert abs(oracle.rel_l2([0.0, 10.0], [3.0, 4.0]) - np.sqrt(45.0) / 5.0) < 1e-15
+    # fp32 inputs are widened, not compared in fp32: 1 + 2^-30 is not 1
+    assert oracle.rel_l2(np.array([1.0 + 2.0 ** -30]), np.array([1.0], dtype=np.float32)) == 2.0 ** -30
+
+
 # --------------------------------------------------------------------------
 # output rounding: against numpy (fp16) and torch (bf16) conversions
 
