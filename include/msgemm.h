@@ -112,6 +112,35 @@ typedef struct {
 } msgemm_plan_info_t;
 
 /*
+ * Choices the library otherwise makes itself, for tests and measurements that
+ * need a particular kernel form on a problem that would not get it.  A
+ * zero-filled structure (with struct_size set) asks for nothing.  Fields that
+ * do not apply to the plan's variant are ignored; values out of range fall
+ * back to the library's choice.  Nothing here changes what is computed.
+ */
+typedef struct {
+    size_t struct_size;          /* sizeof(msgemm_plan_options_t) as the caller was compiled; required */
+    int panels_per_workgroup;    /* fused kernels: panels of rows per workgroup (1..64); 0 = library's choice */
+    int k_tiles_per_workgroup;   /* single-column kernels: consecutive k-tiles a workgroup runs through
+                                    (1 = one k-tile per workgroup, n > 2 = the long-k form); 0 = library's choice */
+    int reduce_mode;             /* single-column kernels, sums over k-tiles: 0 = library's choice, 1 = a second
+                                    launch, 2 = trailing workgroups of the same launch, 3 = the workgroups that
+                                    produced them (needs the whole grid resident; else 1 is taken) */
+    int rows_per_lane;           /* single-column kernel: 16 (default) or 8 (its 16-wavefront form);
+                                    batched kernel: 8 (default) or 4 */
+    int no_xcd_map;              /* 1: workgroup ids in k-tile-major order instead of grouped per L2 */
+    int batched_form;            /* batched kernel: 0 = library's choice, 1 = build phase per k-tile, 2 = pipelined */
+    int batched_segments;        /* batched kernel: k-segments (partial sums per output); 0 = library's choice */
+    int global_plain_consumer;   /* two-launch variant: 1 = the one-thread-per-output consumer */
+    int global_chunk_kib;        /* two-launch variant: table KiB per chunk; 0 = 1024 */
+    int global_segments;         /* two-launch variant: runs of chunks; 0 = library's choice */
+    int build_on_matrix_cores;   /* msgemm_build_lut: 0 = from 16 columns on, 1 = never, 2 = always */
+    int poll_limit;              /* in-launch reductions: polls before a waiting wavefront gives up; 0 = 2^22 */
+    int skip_publish;            /* test aid: producers never announce their partial sums, so every waiting
+                                    wavefront gives up after poll_limit polls (see msgemm_plan_check) */
+} msgemm_plan_options_t;
+
+/*
  * Validate an m x k x b problem (Section 2), choose the kernel variant and
  * tile shape, and make the plan's own device copies of the weights: the
  * row-major codes, the scales and, for the fused variant, the codes reordered
@@ -131,6 +160,13 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b,
                 int x_dtype, int y_dtype, int d, int scale_group,
                 const void* W_codes, const void* scales, int variant, void* stream);
 
+/* The same with options (NULL = none).  MSGEMM_ERR_INVALID_ARG if options->struct_size is not the size this
+ * library was built with. */
+int msgemm_plan_with_options(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b,
+                             int x_dtype, int y_dtype, int d, int scale_group,
+                             const void* W_codes, const void* scales, int variant,
+                             const msgemm_plan_options_t* options, void* stream);
+
 /*
  * The same for weights of 8 bits (Section 2 names an 8-bit floating-point
  * weight matrix as another datatype the method applies to).  One code byte per
@@ -148,12 +184,12 @@ int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b,
  * x rounded to fp16) for wider fp16 / bf16 batches; floating-point activations
  * only (MSGEMM_ERR_UNSUPPORTED for int8).  The plan works with msgemm_run,
  * msgemm_plan_get_info (d reads 1, lut_groups k) and msgemm_destroy; the
- * other entry points refuse it.
+ * other entry points refuse it.  options: as for msgemm_plan_with_options, NULL = none.
  */
 int msgemm_plan_codes8(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b,
                        int x_dtype, int y_dtype, int scale_group,
                        const void* W_codes8, const void* scales,
-                       const float* values256, void* stream);
+                       const float* values256, const msgemm_plan_options_t* options, void* stream);
 
 /*
  * Other encodings of the 4-bit codes.  Section 2 notes that the exact datatype

@@ -20,7 +20,7 @@ VARIANT_AUTO, VARIANT_GLOBAL_LUT, VARIANT_FUSED_LDS, VARIANT_FUSED_LDS16, VARIAN
 OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, -1, -2, -3, -4
 
 EXPORTS = (
-    "msgemm_plan", "msgemm_plan_codes8", "msgemm_plan_set_codebook", "msgemm_plan_get_info", "msgemm_lut_bytes", "msgemm_build_lut",
+    "msgemm_plan", "msgemm_plan_with_options", "msgemm_plan_codes8", "msgemm_plan_set_codebook", "msgemm_plan_get_info", "msgemm_lut_bytes", "msgemm_build_lut",
     "msgemm_consume_lut", "msgemm_run", "msgemm_dequant_mfma_run", "msgemm_calib_stream_read", "msgemm_calib_lds_read", "msgemm_destroy",
     "msgemm_status_string", "msgemm_last_hip_error", "msgemm_version",
 )
@@ -49,6 +49,32 @@ class PlanInfo(ctypes.Structure):
         return {name: getattr(self, name) for name, _ in self._fields_}
 
 
+class PlanOptions(ctypes.Structure):
+    """msgemm_plan_options_t: requests for a particular kernel form (tests, measurements); zero = none."""
+    _fields_ = [
+        ("struct_size", ctypes.c_size_t),
+        ("panels_per_workgroup", ctypes.c_int), ("k_tiles_per_workgroup", ctypes.c_int),
+        ("reduce_mode", ctypes.c_int), ("rows_per_lane", ctypes.c_int), ("no_xcd_map", ctypes.c_int),
+        ("batched_form", ctypes.c_int), ("batched_segments", ctypes.c_int),
+        ("global_plain_consumer", ctypes.c_int), ("global_chunk_kib", ctypes.c_int), ("global_segments", ctypes.c_int),
+        ("build_on_matrix_cores", ctypes.c_int), ("poll_limit", ctypes.c_int), ("skip_publish", ctypes.c_int),
+    ]
+
+
+def _options(options):
+    """dict of field names -> ctypes structure (None stays None)."""
+    if options is None:
+        return None
+    o = PlanOptions()
+    o.struct_size = ctypes.sizeof(PlanOptions)
+    names = {n for n, _ in PlanOptions._fields_}
+    for key, value in options.items():
+        if key not in names or key == "struct_size":
+            raise ValueError(f"unknown plan option {key!r}")
+        setattr(o, key, int(value))
+    return o
+
+
 _lib = None
 
 
@@ -65,8 +91,11 @@ def load():
     vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
     lib.msgemm_plan.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci, ci, ci, ci, vp, vp, ci, vp]
     lib.msgemm_plan.restype = ci
+    lib.msgemm_plan_with_options.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci, ci, ci, ci, vp, vp, ci,
+                                             ctypes.POINTER(PlanOptions), vp]
+    lib.msgemm_plan_with_options.restype = ci
     lib.msgemm_plan_codes8.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci, ci, ci, vp, vp,
-                                       ctypes.POINTER(ctypes.c_float), vp]
+                                       ctypes.POINTER(ctypes.c_float), ctypes.POINTER(PlanOptions), vp]
     lib.msgemm_plan_codes8.restype = ci
     lib.msgemm_plan_set_codebook.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.msgemm_plan_set_codebook.restype = ci
@@ -133,8 +162,12 @@ def version() -> str:
 
 
 def msgemm_plan(m, k, b, x_dtype, y_dtype, d, scale_group, W_codes, scales=None,
-                variant=VARIANT_AUTO, stream=None, check=True):
-    """Returns the plan handle (an int).  With check=False returns (status, handle)."""
+                variant=VARIANT_AUTO, stream=None, check=True, options=None):
+    """Returns the plan handle (an int).  With check=False returns (status, handle).
+    options: dict of msgemm_plan_options_t fields; given, msgemm_plan_with_options is the call made."""
+    if options is not None:
+        return msgemm_plan_with_options(m, k, b, x_dtype, y_dtype, d, scale_group, W_codes, scales, variant,
+                                        options, stream, check)
     lib = load()
     out = ctypes.c_void_p()
     rc = lib.msgemm_plan(ctypes.byref(out), int(m), int(k), int(b),
@@ -148,8 +181,25 @@ def msgemm_plan(m, k, b, x_dtype, y_dtype, d, scale_group, W_codes, scales=None,
     return out.value
 
 
+def msgemm_plan_with_options(m, k, b, x_dtype, y_dtype, d, scale_group, W_codes, scales, variant, options,
+                             stream=None, check=True):
+    """options: dict of msgemm_plan_options_t fields, a PlanOptions, or None."""
+    lib = load()
+    out = ctypes.c_void_p()
+    opts = options if isinstance(options, PlanOptions) or options is None else _options(options)
+    rc = lib.msgemm_plan_with_options(ctypes.byref(out), int(m), int(k), int(b),
+                                      DTYPES.get(x_dtype, x_dtype), DTYPES.get(y_dtype, y_dtype),
+                                      int(d), int(scale_group), _ptr(W_codes), _ptr(scales), int(variant),
+                                      None if opts is None else ctypes.byref(opts), _stream(stream))
+    if not check:
+        return rc, out.value
+    if rc != OK:
+        raise MsgemmError(rc, "msgemm_plan_with_options")
+    return out.value
+
+
 def msgemm_plan_codes8(m, k, b, x_dtype, y_dtype, scale_group, W_codes8, scales, values256,
-                       stream=None, check=True):
+                       stream=None, check=True, options=None):
     """Plan for 8-bit weights; values256: 256 floats (host).  Returns the handle,
     or (status, handle) with check=False."""
     lib = load()
@@ -157,7 +207,8 @@ def msgemm_plan_codes8(m, k, b, x_dtype, y_dtype, scale_group, W_codes8, scales,
     vals = (ctypes.c_float * 256)(*[float(v) for v in values256])
     rc = lib.msgemm_plan_codes8(ctypes.byref(out), int(m), int(k), int(b),
                                 DTYPES.get(x_dtype, x_dtype), DTYPES.get(y_dtype, y_dtype),
-                                int(scale_group), _ptr(W_codes8), _ptr(scales), vals, _stream(stream))
+                                int(scale_group), _ptr(W_codes8), _ptr(scales), vals,
+                                None if options is None else ctypes.byref(_options(options)), _stream(stream))
     if not check:
         return rc, out.value
     if rc != OK:

@@ -12,12 +12,6 @@ constexpr int kLoadsPerPanel = 16;  // one load per group of a 16-group class
 constexpr int kAuxSc1 = 16;         // buffer cache policy bit: coherent at agent scope
 constexpr int kXcds = 8;            // L2 slices (XCDs); workgroups are dealt to them round-robin
 
-inline int env_int(const char* name, int fallback)
-{
-    const char* v = getenv(name);
-    return (v && *v) ? atoi(v) : fallback;
-}
-
 // n / d for a divisor fixed at launch, without the hardware-less division
 // sequence (round-up multiplier of Granlund and Montgomery; exact for every
 // 32-bit n): q = (t + ((n - t) >> s1)) >> s2 with t = high word of n * magic.

@@ -709,7 +709,7 @@ void batched_choose_segments(Plan& p)
     const int tpb = p.scale_group > 0 ? (int)(p.scale_group / (2 * p.fs.groups)) : 1;
     const int64_t blocks = (p.ktiles + tpb - 1) / tpb;  // indivisible runs of k-tiles
     int64_t best_s = phase_form_segments(blocks, p.row_blocks * p.col_passes, p.cus);
-    const int forced = env_int("MSGEMM_TUNE_SEGMENTS", 0);
+    const int forced = p.opt.batched_segments;
     if (forced >= 1 && forced <= blocks) best_s = forced;
     const int64_t per = (blocks + best_s - 1) / best_s;
     p.tiles_per_segment = (int)(per * tpb);
@@ -787,10 +787,10 @@ void batched_choose_rows_and_segments(Plan& p, int64_t panels, int& ppw_out)
     int best_ppw;
     int64_t best_per;
     pipe_form_choice(panels, p.ktiles, tpb, p.col_passes, p.cus, p.fs.lane_bytes, p.fs.waves, best_ppw, best_per);
-    const int forced_ppw = env_int("MSGEMM_TUNE_PPW", 0);
+    const int forced_ppw = p.opt.panels_per_workgroup;
     if (forced_ppw >= 1 && forced_ppw <= p.fs.waves) best_ppw = forced_ppw;
     int64_t segs = (blocks + best_per - 1) / best_per;
-    const int forced = env_int("MSGEMM_TUNE_SEGMENTS", 0);
+    const int forced = p.opt.batched_segments;
     if (forced >= 1 && forced <= blocks) segs = forced;
     const int64_t per = (blocks + segs - 1) / segs;
     ppw_out = best_ppw;

@@ -1033,21 +1033,21 @@ struct ShapeChoice { int C, G, LB, entry_bytes, waves; };
 // the int8 table values exactly (|entry| <= 2048); fp16 entries round.
 ShapeChoice pick_shape(const Plan& p, int requested_variant)
 {
-    // MSGEMM_TUNE_LB = 8 selects the 16-wavefront, 128-row-panel form of the single-column kernel (tuning aid;
-    // measured within 3 % of the default on the b = 1 GEMV)
-    const int lb1 = env_int("MSGEMM_TUNE_LB", 16) == 8 ? 8 : 16;
+    // rows_per_lane = 8 selects the 16-wavefront, 128-row-panel form of the single-column kernel (an option of the
+    // plan; measured within 3 % of the default on the b = 1 GEMV)
+    const int lb1 = p.opt.rows_per_lane == 8 ? 8 : 16;
     const bool narrow_ok = p.x_dtype != MSGEMM_F32;
     const bool narrow = requested_variant == MSGEMM_VARIANT_FUSED_LDS16 ||
                         (requested_variant == MSGEMM_VARIANT_AUTO && p.b > 2);
-    // (MSGEMM_TUNE_BATCH_LB = 4: the 12-wavefront form of the batched kernel, tuning aid)
-    // (MSGEMM_TUNE_BATCH_PIPE = 0: its form with one 32-group table and a build phase per k-tile)
+    // (plan options: rows_per_lane = 4, the 12- resp. 16-wavefront form of the batched kernel; batched_form = 1, its
+    // form with one 32-group table and a build phase per k-tile, 2 the pipelined one)
     if (narrow && narrow_ok) {
         // The batched kernel has two forms: 16-group k-tiles with the next table built under the
-        // look-ups (pipelined), or 32-group k-tiles with a build phase.  Time models of both decide;
-        // MSGEMM_TUNE_BATCH_PIPE = 0 / 1 overrides.
+        // look-ups (pipelined), or 32-group k-tiles with a build phase.  Time models of both decide unless
+        // the plan's options name one.
         const int pipe_default = batched_pipelined_is_faster(p.m, p.k, p.b, p.scale_group, p.cus) ? 1 : 0;
-        const int lb = env_int("MSGEMM_TUNE_BATCH_LB", 8) == 4 ? 4 : 8;
-        if (env_int("MSGEMM_TUNE_BATCH_PIPE", pipe_default))
+        const int lb = p.opt.rows_per_lane == 4 ? 4 : 8;
+        if (p.opt.batched_form == 2 || (p.opt.batched_form != 1 && pipe_default))
             return lb == 4 ? ShapeChoice{8, 16, 4, 2, 16} : ShapeChoice{8, 16, 8, 2, 8};
         return lb == 4 ? ShapeChoice{8, 32, 4, 2, 12} : ShapeChoice{8, 32, 8, 2, 8};
     }
@@ -1166,8 +1166,8 @@ int fused_choose_shape(Plan& p, int requested_variant)
 {
     if (p.d != 2) return MSGEMM_ERR_UNSUPPORTED;
     if (requested_variant == MSGEMM_VARIANT_FUSED_LDS16 && p.x_dtype == MSGEMM_F32) return MSGEMM_ERR_UNSUPPORTED;
-    p.xcd_map_allowed = env_int("MSGEMM_TUNE_XCD_MAP", 1);
-    p.forced_reduce = env_int("MSGEMM_TUNE_REDUCE", 0);
+    p.xcd_map_allowed = p.opt.no_xcd_map ? 0 : 1;
+    p.forced_reduce = p.opt.reduce_mode;
     {
         int cus = 256;
         hipDeviceProp_t prop;
@@ -1194,7 +1194,7 @@ int fused_choose_shape(Plan& p, int requested_variant)
     const int cus = p.cus;
     // Rows per table build: as many panels per workgroup as still leave one
     // workgroup per compute unit (each build costs 256 entries per group).
-    // MSGEMM_TUNE_PPW overrides the choice (tuning aid).
+    // The plan's option panels_per_workgroup overrides the choice.
     // (The batched 16-bit kernel keeps one panel per wavefront and runs through
     // several k-tiles instead; its split over k is chosen below.)
     const bool batched16 = sc.entry_bytes == 2;
@@ -1207,10 +1207,10 @@ int fused_choose_shape(Plan& p, int requested_variant)
     p.segments = 0;
     p.tiles_per_segment = 0;
     if (batched_pipe) batched_choose_rows_and_segments(p, panels, ppw);
-    const int forced = env_int("MSGEMM_TUNE_PPW", 0);
+    const int forced = p.opt.panels_per_workgroup;
     if (forced >= 1 && forced <= 64 && !batched_pipe) ppw = forced;
-    // MSGEMM_TUNE_LONGK = 1 keeps one k-tile per workgroup, n > 1 forces runs of n (tuning aid).
-    const int forced_tps = env_int("MSGEMM_TUNE_LONGK", 0);
+    // k_tiles_per_workgroup = 1 keeps one k-tile per workgroup, n > 1 forces runs of n.
+    const int forced_tps = p.opt.k_tiles_per_workgroup;
     if (forced_tps >= 1) tps = forced_tps < p.ktiles ? forced_tps : p.ktiles;
     fs.panels = ppw;
     fs.tile_rows = ppw * fs.panel_rows;
@@ -1357,8 +1357,8 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     a.div_tiles_per_block = make_fastdiv((uint32_t)a.tiles_per_block);
     // Several k-tiles: the single-column kernels reduce inside the launch (a second
     // launch costs more than the reduction itself), the batched ones in a second
-    // pass.  MSGEMM_TUNE_REDUCE = 1 (second pass) or 2 (in launch) overrides the
-    // choice for the single-column kernels (tuning aid).
+    // pass.  The plan's option reduce_mode = 1 (second pass) or 2 (in launch) overrides the
+    // choice for the single-column kernels.
     a.reduce_mode = kReduceDirect;
     if (a.slices > 1) {
         a.reduce_mode = p.fs.cols == 1 ? kReduceInLaunch : kReduceSecondPass;

@@ -421,7 +421,7 @@ TiledGeom tiled_geometry(const Plan& p, int cb)
     g.row_words = (int)(p.k / 8);
     g.gpb = (int)p.gpb;
     g.units_per_block = (g.block_words + kUnitWords - 1) / kUnitWords;
-    // chunks of about one MiB of tables (tuning aid: MSGEMM_TUNE_GLOBAL_CHUNK_KIB)
+    // chunks of about one MiB of tables (plan option global_chunk_kib)
     const int64_t unit_bytes = (int64_t)(24 / p.d) * (((int64_t)1 << (4 * p.d)) >> (p.half_table ? 1 : 0)) * p.b * 4;
     const int64_t want = (int64_t)(p.global_chunk_kib > 0 ? p.global_chunk_kib : 1024) * 1024;
     int64_t cu = want / unit_bytes;
@@ -616,8 +616,8 @@ int global_plan_setup(Plan& p, hipStream_t s)
     p.codes_words = nullptr;
     p.global_partials = nullptr;
     p.global_segments = 1;
-    p.global_plain = env_int("MSGEMM_TUNE_GLOBAL_PLAIN", 0);
-    p.global_chunk_kib = env_int("MSGEMM_TUNE_GLOBAL_CHUNK_KIB", 1024);
+    p.global_plain = p.opt.global_plain_consumer ? 1 : 0;
+    p.global_chunk_kib = p.opt.global_chunk_kib > 0 ? p.opt.global_chunk_kib : 1024;
     if ((p.block % 8) != 0) return MSGEMM_OK;
     if (p.k / 8 > 0x3fffffff || (p.m + 63) / 64 > 0x3fffffff || p.gpb > 0x3fffffff) return MSGEMM_OK;
     // one table entry offset fits 32 bits with room to spare
@@ -635,7 +635,7 @@ int global_plan_setup(Plan& p, hipStream_t s)
     const int64_t per_seg = (int64_t)g.wg_rows * g.col_passes;
     int seg = g.chunks < kXcds ? g.chunks : kXcds;
     while (g.chunks >= kXcds && seg * per_seg < 4 * (int64_t)cus && 2 * seg <= g.chunks) seg *= 2;
-    const int forced = env_int("MSGEMM_TUNE_GLOBAL_SEGMENTS", 0);
+    const int forced = p.opt.global_segments;
     if (forced >= 1 && forced <= g.chunks) seg = forced;
     int cps = (g.chunks + seg - 1) / seg;
     // Workgroups of one segment that run side by side walk its chunks together,

@@ -51,10 +51,11 @@ using msgemm::Plan;
 // int4 weights; only the table build knows better), d is 2, the variant FUSED_LDS.
 static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtype, int y_dtype, int d,
                      int scale_group, const void* W_codes, const void* scales, int variant, void* stream,
-                     const float* values256)
+                     const float* values256, const msgemm_plan_options_t* options)
 {
     if (!out) return MSGEMM_ERR_INVALID_ARG;
     *out = nullptr;
+    if (options && options->struct_size != sizeof(msgemm_plan_options_t)) return MSGEMM_ERR_INVALID_ARG;
     if (m <= 0 || k <= 0 || b <= 0 || (k & 1) || !W_codes) return MSGEMM_ERR_INVALID_ARG;
     if (m > ((int64_t)1 << 31) || k > ((int64_t)1 << 31) || b > 65536) return MSGEMM_ERR_INVALID_ARG;
     if (d < 0 || d > 4) return MSGEMM_ERR_INVALID_ARG;  // Section 5: d cannot usefully exceed 4
@@ -76,6 +77,7 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
     Plan* p = new (std::nothrow) Plan();
     if (!p) return MSGEMM_ERR_ALLOC;
     p->m = m; p->k = k; p->b = b;
+    if (options) p->opt = *options;  // (a new Plan is zero-filled: no requests)
     p->x_dtype = x_dtype; p->y_dtype = y_dtype;
     p->lut_dtype = (x_dtype == MSGEMM_I8) ? MSGEMM_I32 : MSGEMM_F32;
     p->d = d_eff;
@@ -138,7 +140,7 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
         if (e != hipSuccess) return hip_fail(e);
     }
 
-    p->build_mfma = msgemm::env_int("MSGEMM_TUNE_BUILD_MFMA", p->b >= 16 ? 1 : 0);
+    p->build_mfma = p->opt.build_on_matrix_cores == 1 ? 0 : p->opt.build_on_matrix_cores == 2 ? 1 : (p->b >= 16 ? 1 : 0);
     if (p->variant == MSGEMM_VARIANT_GLOBAL_LUT) {
         p->lut_ws_bytes = msgemm::lut_bytes_of(*p);
         e = hipMalloc((void**)&p->lut_ws, p->lut_ws_bytes);
@@ -180,12 +182,19 @@ extern "C" {
 int msgemm_plan(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtype, int y_dtype, int d,
                 int scale_group, const void* W_codes, const void* scales, int variant, void* stream)
 {
-    return plan_impl(out, m, k, b, x_dtype, y_dtype, d, scale_group, W_codes, scales, variant, stream, nullptr);
+    return plan_impl(out, m, k, b, x_dtype, y_dtype, d, scale_group, W_codes, scales, variant, stream, nullptr, nullptr);
+}
+
+int msgemm_plan_with_options(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtype, int y_dtype, int d,
+                             int scale_group, const void* W_codes, const void* scales, int variant,
+                             const msgemm_plan_options_t* options, void* stream)
+{
+    return plan_impl(out, m, k, b, x_dtype, y_dtype, d, scale_group, W_codes, scales, variant, stream, nullptr, options);
 }
 
 int msgemm_plan_codes8(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x_dtype, int y_dtype,
                        int scale_group, const void* W_codes8, const void* scales, const float* values256,
-                       void* stream)
+                       const msgemm_plan_options_t* options, void* stream)
 {
     if (!out) return MSGEMM_ERR_INVALID_ARG;
     *out = nullptr;
@@ -198,7 +207,7 @@ int msgemm_plan_codes8(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int
     // full-width tables for one or two columns and for fp32 activations, 16-bit tables for wider batches
     const int variant = (b <= 2 || x_dtype == MSGEMM_F32) ? MSGEMM_VARIANT_FUSED_LDS : MSGEMM_VARIANT_FUSED_LDS16;
     return plan_impl(out, m, 2 * k, b, x_dtype, y_dtype, 2, 2 * scale_group, W_codes8, scales, variant, stream,
-                     values256);
+                     values256, options);
 }
 
 int msgemm_plan_set_codebook(msgemm_plan_t* plan, const float* values16)

@@ -56,12 +56,12 @@ struct Plan {
     int64_t m_pad;        // row_blocks * tile_rows
     int col_passes;       // ceil(b / cols)
     int cus;              // compute units of the device
-    // tuning aids read from the environment once, when the plan is made (launches read none)
-    int xcd_map_allowed;  // MSGEMM_TUNE_XCD_MAP (default 1)
-    int forced_reduce;    // MSGEMM_TUNE_REDUCE: 0 none, 1 second pass, 2 in launch (single-column kernels)
-    int global_plain;     // MSGEMM_TUNE_GLOBAL_PLAIN: two-launch variant with the plain consumer
-    int global_chunk_kib; // MSGEMM_TUNE_GLOBAL_CHUNK_KIB (default 1024)
-    int build_mfma;       // MSGEMM_TUNE_BUILD_MFMA: phase 1 alone on the matrix cores (default: from 16 batch columns on)
+    msgemm_plan_options_t opt;  // the caller's requests (all zero: none), fixed when the plan is made
+    int xcd_map_allowed;  // !opt.no_xcd_map
+    int forced_reduce;    // opt.reduce_mode: 0 none, 1 second pass, 2 in launch (single-column kernels)
+    int global_plain;     // two-launch variant with the plain consumer
+    int global_chunk_kib; // two-launch variant: table KiB per chunk (default 1024)
+    int build_mfma;       // phase 1 alone on the matrix cores (default: from 16 batch columns on)
     int segments;         // batched kernel: k-segments (partial sums per output); 0 otherwise
     int tiles_per_segment; // batched kernel: k-tiles a workgroup runs through
     uint16_t* scales_ordered;  // device fp16 [nblocks][m_pad], rows in the order the lanes own outputs; nullptr without scales

@@ -79,7 +79,7 @@ def check(y_gpu_host, y_ref, xd, what="", bound=None):
     return err
 
 
-def run_gpu(codes, X, xd, scales, sg, d, variant, ldx_pad=0, ldy_pad=0, use_phases=False):
+def run_gpu(codes, X, xd, scales, sg, d, variant, ldx_pad=0, ldy_pad=0, use_phases=False, options=None):
     m, k = codes.shape[0], codes.shape[1] * 2
     b = X.shape[0]
     yd = Y_OF_X[xd]
@@ -92,7 +92,7 @@ def run_gpu(codes, X, xd, scales, sg, d, variant, ldx_pad=0, ldy_pad=0, use_phas
     dX = torch_io.to_device(X, xd)
     dC = torch_io.to_device(codes, "codes")
     dS = torch_io.to_device(scales, "scales")
-    plan = B.msgemm_plan(m, k, b, xd, yd, d, sg, dC, dS, variant)
+    plan = B.msgemm_plan(m, k, b, xd, yd, d, sg, dC, dS, variant, options=options)
     try:
         info = B.msgemm_plan_get_info(plan)
         Y = torch_io.empty_output(b, m, yd, ldy=m + ldy_pad)
@@ -338,20 +338,15 @@ PIPELINED_CASES = [
 
 
 @pytest.mark.parametrize("m,k,b,xd,sg,lb,ppw,segments", PIPELINED_CASES)
-def test_batched_pipelined_form(monkeypatch, m, k, b, xd, sg, lb, ppw, segments):
+def test_batched_pipelined_form(m, k, b, xd, sg, lb, ppw, segments):
     """The batched kernel that builds the next table while it gathers from the current one
     (chosen by itself only for large problems), forced on small shapes; twice on one plan."""
-    monkeypatch.setenv("MSGEMM_TUNE_BATCH_PIPE", "1")
-    monkeypatch.setenv("MSGEMM_TUNE_BATCH_LB", str(lb))
-    if ppw:
-        monkeypatch.setenv("MSGEMM_TUNE_PPW", str(ppw))
-    if segments:
-        monkeypatch.setenv("MSGEMM_TUNE_SEGMENTS", str(segments))
+    options = {"batched_form": 2, "rows_per_lane": lb, "panels_per_workgroup": ppw, "batched_segments": segments}
     codes = inputs.make_codes(m, k, seed=m + 5 * k)
     scales = inputs.make_scales(m, k, sg, seed=8) if sg else None
     dC = torch_io.to_device(codes, "codes")
     dS = torch_io.to_device(scales, "scales")
-    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS, B.VARIANT_FUSED_LDS16)
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS, B.VARIANT_FUSED_LDS16, options=options)
     try:
         info = B.msgemm_plan_get_info(plan)
         assert info["tile_groups"] == 16 and info["col_chunk"] == 8
@@ -415,16 +410,16 @@ REDUCE_CASES = [
 
 @pytest.mark.parametrize("mode", [1, 2])
 @pytest.mark.parametrize("m,k,b,xd,sg", REDUCE_CASES)
-def test_fused_k_tile_reduction_modes(monkeypatch, m, k, b, xd, sg, mode):
+def test_fused_k_tile_reduction_modes(m, k, b, xd, sg, mode):
     """Both ways of adding the k-tile partial sums (1: second launch, 2: trailing
     workgroups of the same launch) against the oracle, twice on the same plan:
     the arrival flags of the in-launch reduction must be down again after a launch."""
-    monkeypatch.setenv("MSGEMM_TUNE_REDUCE", str(mode))
     codes = inputs.make_codes(m, k, seed=m + k)
     scales = inputs.make_scales(m, k, sg, seed=4) if sg else None
     dC = torch_io.to_device(codes, "codes")
     dS = torch_io.to_device(scales, "scales")
-    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS, B.VARIANT_FUSED_LDS)
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS, B.VARIANT_FUSED_LDS,
+                         options={"reduce_mode": mode, "k_tiles_per_workgroup": 1})
     try:
         assert B.msgemm_plan_get_info(plan)["split_k"] == -(-(k // 2) // 64)
         for rep in range(2):
@@ -453,19 +448,16 @@ LONG_K_CASES = [
 
 @pytest.mark.parametrize("mode", [1, 2])
 @pytest.mark.parametrize("m,k,b,xd,sg,tps,ppw", LONG_K_CASES)
-def test_fused_long_k_form(monkeypatch, m, k, b, xd, sg, tps, ppw, mode):
+def test_fused_long_k_form(m, k, b, xd, sg, tps, ppw, mode):
     """The single-column kernel that runs through several k-tiles per workgroup
     (two table buffers, sums kept in registers), forced on small shapes; both
     reductions over the segments; twice on one plan."""
-    monkeypatch.setenv("MSGEMM_TUNE_LONGK", str(tps))
-    monkeypatch.setenv("MSGEMM_TUNE_REDUCE", str(mode))
-    if ppw:
-        monkeypatch.setenv("MSGEMM_TUNE_PPW", str(ppw))
     codes = inputs.make_codes(m, k, seed=m + k + tps)
     scales = inputs.make_scales(m, k, sg, seed=6) if sg else None
     dC = torch_io.to_device(codes, "codes")
     dS = torch_io.to_device(scales, "scales")
-    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS, B.VARIANT_FUSED_LDS)
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS, B.VARIANT_FUSED_LDS,
+                         options={"k_tiles_per_workgroup": tps, "reduce_mode": mode, "panels_per_workgroup": ppw})
     try:
         ktiles = -(-(k // 2) // 64)
         assert B.msgemm_plan_get_info(plan)["split_k"] == -(-ktiles // tps)
@@ -546,26 +538,23 @@ def test_extreme_aspect_ratios(m, k, xd, sg):
     (515, 1 << 17, 8, "bf16", 0),        # wide: 2048 (4096) k-tiles, long segments
     (259, 1 << 16, 16, "i8", 0),         # the same with integer tables and two column passes
 ])
-def test_extreme_aspect_ratios_batched(monkeypatch, m, k, b, xd, sg, pipelined):
+def test_extreme_aspect_ratios_batched(m, k, b, xd, sg, pipelined):
     """Very tall and very wide batched problems in both forms of the batched kernel, every row against the oracle."""
-    monkeypatch.setenv("MSGEMM_TUNE_BATCH_PIPE", str(pipelined))
     codes = inputs.make_codes(m, k, seed=23)
     X = inputs.make_x(k, b, xd, seed=24)
     if xd != "i8" and k > 4096:
         X = (X.astype(np.float32) / 8).astype(X.dtype) if xd == "f16" else X  # keep fp16 outputs in range
     scales = inputs.make_scales(m, k, sg, seed=25) if sg else None
-    out, info = run_gpu(codes, X, xd, scales, sg, 2, B.VARIANT_AUTO)
+    out, info = run_gpu(codes, X, xd, scales, sg, 2, B.VARIANT_AUTO, options={"batched_form": 1 + pipelined})
     assert info["variant"] == B.VARIANT_FUSED_LDS16 and info["tile_groups"] == (16 if pipelined else 32)
     check(out, oracle_y(codes, X, xd, scales, sg), xd, f"{m}x{k}x{b}", elem_bound(codes, X, xd, scales, sg, table16=True))
 
 
 @pytest.mark.parametrize("pipelined", [0, 1])
-def test_int8_batched_sums_stay_exact_on_long_segments(monkeypatch, pipelined):
+def test_int8_batched_sums_stay_exact_on_long_segments(pipelined):
     """The batched kernel adds int8 tables in fp32.  Worst case for that: the first half of k drives
     every sum to 2^25 (codes -8, activations -128), the second half adds ones, which fp32 could no longer
     hold if one segment ran through all of k.  A single segment is asked for; the library must cut it."""
-    monkeypatch.setenv("MSGEMM_TUNE_BATCH_PIPE", str(pipelined))
-    monkeypatch.setenv("MSGEMM_TUNE_SEGMENTS", "1")
     m, k, b = 300, 1 << 16, 8
     codes = np.empty((m, k // 2), dtype=np.uint8)
     codes[:, : k // 4] = 0x88           # two codes of -8
@@ -576,7 +565,8 @@ def test_int8_batched_sums_stay_exact_on_long_segments(monkeypatch, pipelined):
     X[3, k // 2:] = -1                  # one column counts down instead
     ref = oracle.gemm_i32(codes, X)
     assert ref[0, 0] == (1 << 25) + k // 4 and ref[3, 0] == (1 << 25) - k // 4
-    out, info = run_gpu(codes, X, "i8", None, 0, 2, B.VARIANT_FUSED_LDS16)
+    out, info = run_gpu(codes, X, "i8", None, 0, 2, B.VARIANT_FUSED_LDS16,
+                        options={"batched_form": 1 + pipelined, "batched_segments": 1})
     assert info["split_k"] >= (k // 2) // 8192  # at most 8192 groups per segment
     assert np.array_equal(out, ref)
 
@@ -606,18 +596,18 @@ def test_config2_full_size_two_launch_variant(d):
     (90, 512, 4, "i8", 0, 2),
     (64, 4096, 2, "f16", 0, 1),
 ])
-def test_two_launch_consumers_agree_with_oracle(monkeypatch, m, k, b, xd, sg, d):
+def test_two_launch_consumers_agree_with_oracle(m, k, b, xd, sg, d):
     """The tiled consumer and the plain one-thread-per-output consumer against the oracle."""
     codes = inputs.make_codes(m, k, seed=m + d)
     X = inputs.make_x(k, b, xd, seed=k + d)
     scales = inputs.make_scales(m, k, sg, seed=8) if sg else None
     ref = oracle_y(codes, X, xd, scales, sg)
-    monkeypatch.setenv("MSGEMM_TUNE_GLOBAL_CHUNK_KIB", "64")  # several chunks per block where the block is long
-    out_t, _ = run_gpu(codes, X, xd, scales, sg, d, B.VARIANT_GLOBAL_LUT, ldx_pad=2, ldy_pad=5)
+    chunks = {"global_chunk_kib": 64}  # several chunks per block where the block is long
+    out_t, _ = run_gpu(codes, X, xd, scales, sg, d, B.VARIANT_GLOBAL_LUT, ldx_pad=2, ldy_pad=5, options=chunks)
     bnd = elem_bound(codes, X, xd, scales, sg)
     check(out_t, ref, xd, "tiled consumer", bnd)
-    monkeypatch.setenv("MSGEMM_TUNE_GLOBAL_PLAIN", "1")
-    out_p, _ = run_gpu(codes, X, xd, scales, sg, d, B.VARIANT_GLOBAL_LUT, ldx_pad=2, ldy_pad=5)
+    out_p, _ = run_gpu(codes, X, xd, scales, sg, d, B.VARIANT_GLOBAL_LUT, ldx_pad=2, ldy_pad=5,
+                       options={"global_chunk_kib": 64, "global_plain_consumer": 1})
     check(out_p, ref, xd, "plain consumer", bnd)
     if xd == "i8":
         assert np.array_equal(out_t, out_p)
@@ -745,35 +735,33 @@ def e4m3_finite():
 
 
 CODES8_CASES = [
-    # m, k, b, xd, sg, env
+    # m, k, b, xd, sg, plan options
     (300, 520, 1, "f32", 0, {}),                       # ragged rows and a ragged last k-tile
     (2049, 512, 1, "f16", 128, {}),                    # 8 k-tiles, 9 panels, scales
     (700, 384, 2, "bf16", 64, {}),                     # two column passes, scale block = one k-tile
-    (515, 4096, 1, "f16", 0, {"MSGEMM_TUNE_LONGK": "5"}),   # the long-k form: runs of 5 k-tiles
-    (4100, 640, 1, "f16", 128, {"MSGEMM_TUNE_LONGK": "3", "MSGEMM_TUNE_PPW": "16"}),
+    (515, 4096, 1, "f16", 0, {"k_tiles_per_workgroup": 5}),   # the long-k form: runs of 5 k-tiles
+    (4100, 640, 1, "f16", 128, {"k_tiles_per_workgroup": 3, "panels_per_workgroup": 16}),
     (64, 64, 1, "f32", 64, {}),                        # a single k-tile: straight to Y
     (520, 512, 8, "f16", 128, {}),                     # batches: fp16 tables of 8 columns
     (300, 384, 5, "bf16", 0, {}),                      # a ragged column pass
     (1000, 1024, 16, "f16", 32, {}),                   # two column passes, scale block = one k-tile of 32 columns
     (257, 256, 4, "f32", 0, {}),                       # fp32 activations: four fp32 columns per entry
     (130, 320, 7, "f32", 64, {}),
-    (520, 512, 8, "f16", 128, {"MSGEMM_TUNE_BATCH_PIPE": "1"}),                        # the pipelined batched form
-    (1000, 1024, 16, "f16", 32, {"MSGEMM_TUNE_BATCH_PIPE": "1", "MSGEMM_TUNE_BATCH_LB": "4"}),
-    (300, 384, 5, "bf16", 0, {"MSGEMM_TUNE_BATCH_PIPE": "1", "MSGEMM_TUNE_SEGMENTS": "3"}),
+    (520, 512, 8, "f16", 128, {"batched_form": 2}),                        # the pipelined batched form
+    (1000, 1024, 16, "f16", 32, {"batched_form": 2, "rows_per_lane": 4}),
+    (300, 384, 5, "bf16", 0, {"batched_form": 2, "batched_segments": 3}),
 ]
 
 
-@pytest.mark.parametrize("m,k,b,xd,sg,env", CODES8_CASES)
-def test_codes8_against_oracle(monkeypatch, m, k, b, xd, sg, env):
-    for name, value in env.items():
-        monkeypatch.setenv(name, value)
+@pytest.mark.parametrize("m,k,b,xd,sg,options", CODES8_CASES)
+def test_codes8_against_oracle(m, k, b, xd, sg, options):
     codes = inputs.make_codes8(m, k, seed=m + k)
     X = inputs.make_x(k, b, xd, seed=k + 1)
     scales = inputs.make_scales(m, k, sg, seed=10) if sg else None
     values = e4m3_finite() / 16.0   # keeps fp16 outputs in range
     ref = oracle.gemm_f64_codes8(codes, x_to_f64(X, xd), values, scales, sg)
     dC, dS, dX = torch_io.to_device(codes, "codes"), torch_io.to_device(scales, "scales"), torch_io.to_device(X, xd)
-    plan = B.msgemm_plan_codes8(m, k, b, xd, Y_OF_X[xd], sg, dC, dS, values)
+    plan = B.msgemm_plan_codes8(m, k, b, xd, Y_OF_X[xd], sg, dC, dS, values, options=options or None)
     try:
         info = B.msgemm_plan_get_info(plan)
         assert (info["k"], info["d"], info["lut_groups"], info["scale_group"]) == (k, 1, k, sg)
@@ -925,15 +913,14 @@ CODEBOOK_CASES = [
 @pytest.mark.parametrize("pipelined", [0, 1])
 @pytest.mark.parametrize("table", [UINT4, NONUNIFORM])
 @pytest.mark.parametrize("m,k,b,xd,sg,d,variant", CODEBOOK_CASES)
-def test_codebook_against_oracle(monkeypatch, m, k, b, xd, sg, d, variant, table, pipelined):
+def test_codebook_against_oracle(m, k, b, xd, sg, d, variant, table, pipelined):
     if pipelined and variant != B.VARIANT_FUSED_LDS16:
         pytest.skip("only the batched kernel has a pipelined form")
-    monkeypatch.setenv("MSGEMM_TUNE_BATCH_PIPE", str(pipelined))
     codes = inputs.make_codes(m, k, seed=m + k + 1)
     X = inputs.make_x(k, b, xd, seed=k + b + 3)
     scales = inputs.make_scales(m, k, sg, seed=13) if sg else None
     dC, dS, dX = torch_io.to_device(codes, "codes"), torch_io.to_device(scales, "scales"), torch_io.to_device(X, xd)
-    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], d, sg, dC, dS, variant)
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], d, sg, dC, dS, variant, options={"batched_form": 1 + pipelined})
     try:
         assert B.msgemm_plan_get_info(plan)["variant"] == variant
         Y = torch_io.empty_output(b, m, Y_OF_X[xd])
@@ -1025,13 +1012,13 @@ def _random_cases(count, seed):
 
 
 @pytest.mark.parametrize("m,k,b,xd,sg,d,variant,pipe", _random_cases(160, seed=20231006))
-def test_random_shapes(monkeypatch, m, k, b, xd, sg, d, variant, pipe):
-    monkeypatch.setenv("MSGEMM_TUNE_BATCH_PIPE", str(pipe))
+def test_random_shapes(m, k, b, xd, sg, d, variant, pipe):
     codes = inputs.make_codes(m, k, seed=m * 31 + k)
     X = inputs.make_x(k, b, xd, seed=k * 7 + b)
     scales = inputs.make_scales(m, k, sg, seed=m + b) if sg else None
     ref = oracle_y(codes, X, xd, scales, sg)
-    out, info = run_gpu(codes, X, xd, scales, sg, 0 if variant == B.VARIANT_AUTO else d, variant, ldx_pad=2, ldy_pad=1)
+    out, info = run_gpu(codes, X, xd, scales, sg, 0 if variant == B.VARIANT_AUTO else d, variant, ldx_pad=2, ldy_pad=1,
+                        options={"batched_form": 1 + pipe})
     if variant != B.VARIANT_AUTO:
         assert info["variant"] == variant
     bnd = elem_bound(codes, X, xd, scales, sg, table16=info["variant"] == B.VARIANT_FUSED_LDS16)
