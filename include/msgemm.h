@@ -61,7 +61,8 @@ typedef enum {
     MSGEMM_ERR_INVALID_ARG = -1, /* null pointer, bad size, bad d, bad dtype pair */
     MSGEMM_ERR_ALLOC = -2,       /* host or device allocation failed */
     MSGEMM_ERR_HIP = -3,         /* a HIP call failed; see msgemm_last_hip_error */
-    MSGEMM_ERR_UNSUPPORTED = -4  /* valid request that the chosen variant cannot serve */
+    MSGEMM_ERR_UNSUPPORTED = -4, /* valid request that the chosen variant cannot serve */
+    MSGEMM_ERR_INCOMPLETE = -5   /* msgemm_plan_check: a reduction inside a launch gave up waiting */
 } msgemm_status_t;
 
 /* How phase 1 and phase 2 are scheduled on the GPU. */
@@ -236,6 +237,22 @@ int msgemm_consume_lut(const msgemm_plan_t* plan, const void* L,
  */
 int msgemm_run(const msgemm_plan_t* plan, const void* X, int64_t ldx,
                void* Y, int64_t ldy, void* stream);
+
+/*
+ * The single-column kernels add the partial sums of the k-tiles (the sum over
+ * j in Section 3.2, cut into pieces that different workgroups hold) inside the
+ * launch: wavefronts wait, for a bounded number of polls, until the partial
+ * sums they need have been announced.  A wavefront whose wait runs out cannot
+ * make msgemm_run fail (the call has long returned): it sets a sticky word in
+ * the plan's device memory, writes no valid output and leaves its flags up.
+ * This call waits for `stream`, reads that word and returns MSGEMM_OK if no
+ * wavefront has given up since the last check; otherwise it clears the word and
+ * the flags, so that the plan works again, and returns MSGEMM_ERR_INCOMPLETE:
+ * the outputs of the msgemm_run calls on this plan since the last check are not
+ * valid.  With the default poll bound (about a second of polling) a give-up
+ * means that the producing workgroups never ran.  Synchronises the stream.
+ */
+int msgemm_plan_check(const msgemm_plan_t* plan, void* stream);
 
 /*
  * Comparison point only, not msGeMM: the same Y computed as a dense

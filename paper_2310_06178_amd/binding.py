@@ -17,11 +17,11 @@ LIB_PATH = os.path.join(_HERE, "libmsgemm.so")
 F32, F16, BF16, I8, I32 = 0, 1, 2, 3, 4
 DTYPES = {"f32": F32, "f16": F16, "bf16": BF16, "i8": I8, "i32": I32}
 VARIANT_AUTO, VARIANT_GLOBAL_LUT, VARIANT_FUSED_LDS, VARIANT_FUSED_LDS16, VARIANT_GLOBAL_LUT_HALF = 0, 1, 2, 3, 4
-OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, -1, -2, -3, -4
+OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED, ERR_INCOMPLETE = 0, -1, -2, -3, -4, -5
 
 EXPORTS = (
     "msgemm_plan", "msgemm_plan_with_options", "msgemm_plan_codes8", "msgemm_plan_set_codebook", "msgemm_plan_get_info", "msgemm_lut_bytes", "msgemm_build_lut",
-    "msgemm_consume_lut", "msgemm_run", "msgemm_dequant_mfma_run", "msgemm_calib_stream_read", "msgemm_calib_lds_read", "msgemm_destroy",
+    "msgemm_consume_lut", "msgemm_run", "msgemm_plan_check", "msgemm_dequant_mfma_run", "msgemm_calib_stream_read", "msgemm_calib_lds_read", "msgemm_destroy",
     "msgemm_status_string", "msgemm_last_hip_error", "msgemm_version",
 )
 
@@ -109,6 +109,8 @@ def load():
     lib.msgemm_consume_lut.restype = ci
     lib.msgemm_run.argtypes = [vp, vp, i64, vp, i64, vp]
     lib.msgemm_run.restype = ci
+    lib.msgemm_plan_check.argtypes = [vp, vp]
+    lib.msgemm_plan_check.restype = ci
     lib.msgemm_dequant_mfma_run.argtypes = [vp, vp, i64, vp, i64, vp]
     lib.msgemm_dequant_mfma_run.restype = ci
     lib.msgemm_calib_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
@@ -244,6 +246,11 @@ def msgemm_run(plan, X, ldx, Y, ldy, stream=None):
     rc = load().msgemm_run(ctypes.c_void_p(plan), _ptr(X), int(ldx), _ptr(Y), int(ldy), _stream(stream))
     if rc != OK:
         raise MsgemmError(rc, "msgemm_run")
+
+
+def msgemm_plan_check(plan, stream=None) -> int:
+    """OK, or ERR_INCOMPLETE when a reduction inside a launch gave up since the last check (then cleared)."""
+    return int(load().msgemm_plan_check(ctypes.c_void_p(plan), _stream(stream)))
 
 
 def msgemm_dequant_mfma_run(plan, X, ldx, Y, ldy, stream=None):

@@ -77,7 +77,7 @@ namespace {
 #define MSGEMM_RING_BYTES 128
 #endif
 constexpr int kRingBytes = MSGEMM_RING_BYTES;  // code bytes per lane a wavefront keeps in flight (x64 lanes)
-constexpr unsigned kMaxFlagPolls = 1u << 22;  // safety bound of the in-launch reduction's wait (seconds)
+constexpr unsigned kMaxFlagPolls = 1u << 22;  // default bound of the in-launch reductions' waits (seconds)
 
 struct FusedArgs {
     const uint8_t* tiled;
@@ -104,13 +104,19 @@ struct FusedArgs {
     int tiles_per_segment;  // long-k form: k-tiles a workgroup runs through
     FastDiv div_slices;
     const float* values256; // 8-bit codes: the value of each of the 256 bit patterns (device), else nullptr
+    unsigned* epochs;       // wide form, resident reduction: launch count of every workgroup (each bumps its own)
+    unsigned* error;        // sticky word: set when a wavefront gave up waiting for partial sums (see msgemm_plan_check)
+    unsigned poll_limit;    // polls before a waiting wavefront gives up
+    int publish;            // 0 (test aid): producers never announce their partial sums
+    int red_chunk;          // resident reduction: partial sums (floats, a multiple of 4) each workgroup of a row group adds up
     ValueMap values;        // value of each 4-bit pattern; last, read only by the forms built for a custom map
 };
 
 enum ReduceMode {
     kReduceDirect = 0,    // a single k-tile: the fused kernel writes Y itself
     kReduceSecondPass = 1,  // partials to memory, a second small kernel adds them
-    kReduceInLaunch = 2   // partials to memory, the workgroup of the last k-tile adds them in the same launch
+    kReduceInLaunch = 2,  // partials to memory, trailing workgroups of the same launch add them
+    kReduceResident = 3   // partials to memory, the workgroups that wrote them add them (the whole grid is resident)
 };
 
 template <int LB> struct LaneLoad;
@@ -142,6 +148,13 @@ __device__ __forceinline__ float mul_add(float w, float x, float acc) { return f
 __device__ __forceinline__ int mul_add(int w, int x, int acc) { return w * x + acc; }
 
 template <typename ET, int C> struct alignas(C * sizeof(ET) >= 16 ? 16 : C * sizeof(ET)) EntryVec { ET v[C]; };
+
+// A partial sum and the parity of its launch in one word (wide form's resident reduction): floating point gives up
+// its last mantissa bit, integers move up by one bit.
+__device__ __forceinline__ unsigned tag_partial(float v, unsigned parity) { return (__float_as_uint(v) & ~1u) | parity; }
+__device__ __forceinline__ unsigned tag_partial(int v, unsigned parity) { return ((unsigned)v << 1) | parity; }
+__device__ __forceinline__ void untag_partial(float& d, unsigned u) { d = __uint_as_float(u & ~1u); }
+__device__ __forceinline__ void untag_partial(int& d, unsigned u) { d = (int)u >> 1; }
 
 // The single-column kernels can reduce inside the launch; the batched ones are
 // bound by the gather, not by launches, and have no registers to spare for it.
@@ -175,11 +188,21 @@ __device__ __forceinline__ void reduce_in_launch(const FusedArgs& a, int unit, i
             const int idx = base + lane;
             const bool need = idx < mine;
             unsigned* flag = flags + w + (int64_t)idx * kRedSplit;
-            for (unsigned spins = 0; spins < kMaxFlagPolls; ++spins) {
+            bool seen = false;
+            for (unsigned spins = 0; spins < a.poll_limit; ++spins) {
                 asm volatile("" ::: "memory");
                 const unsigned f = need ? __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1u;
-                if (__builtin_amdgcn_ballot_w64(f != 1u) == 0) break;
+                if (__builtin_amdgcn_ballot_w64(f != 1u) == 0) {
+                    seen = true;
+                    break;
+                }
                 __builtin_amdgcn_s_sleep(2);
+            }
+            if (!seen) {
+                // gave up: the sums below are not the result.  The plan's error word says so (msgemm_plan_check);
+                // the flags stay as they are, that call clears them.
+                if (lane == 0) __hip_atomic_store(a.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                continue;
             }
             // lowered again for the next launch (kernel boundaries order launches)
             if (need) __hip_atomic_store(flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -592,7 +615,7 @@ fused_kernel(FusedArgs a)
         if (!in_launch) continue;
         // publish: partials acknowledged at the point of coherence, then the flag goes up
         wait_vmem();
-        if (lane == 0)
+        if (lane == 0 && a.publish)
             __hip_atomic_store(a.flags + ((int64_t)panel_g * a.col_passes + cp) * a.ktiles + kt, 1u, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
         MSGEMM_TRACE(6);
@@ -868,10 +891,438 @@ fused_long_kernel(FusedArgs a)
         else store_partials<kFinal, 0>(part_rsrc, off, out);
         if (!in_launch) continue;
         wait_vmem();
-        if (lane == 0)
+        if (lane == 0 && a.publish)
             __hip_atomic_store(a.flags + ((int64_t)panel_g * a.col_passes + cp) * a.slices + sgm, 1u, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
     }
+}
+
+// ---------------------------------------------------------------------------
+// Wide form of the single-column kernel, for problems whose (k-tile, panel)
+// units are about as many as the device has streaming wavefronts (the 32 MiB
+// GEMV: 2048 units on 256 compute units x 8 wavefronts).  There one launch is a
+// single chain of latencies -- arguments, instructions, activations, tables,
+// codes, partial sums, reduction -- and the chain is what this form shortens:
+//   * every loop is kept rolled.  A wavefront runs through its part of the
+//     kernel once, so straight-line code is fetched from memory line by line
+//     behind the code stream (measured: about 0.2 us per KiB of code executed
+//     once); the look-ups of a unit are a loop of four passes over a body of
+//     kRing loads, the table build a loop over the high codes;
+//   * a workgroup holds the tables of kTables (1 or 2) consecutive k-tiles at
+//     once, 64 KiB each, nothing is reused: its streaming wavefronts are dealt
+//     over the tables (wavefront w gathers from table w / (8 / kTables)), a
+//     wavefront's work is one (k-tile, panel) unit, and with two tables half as
+//     many partial sums per output leave the workgroup;
+//   * the builders request the activations before any code load of the
+//     workgroup is issued (the streaming wavefronts wait for that request, not
+//     for its data), so the activations do not queue behind the codes;
+//   * a streaming wavefront keeps kRing loads in flight: eight wavefronts times
+//     four loads of 1 KiB is what a compute unit's memory pipeline holds; more
+//     only blocks the wavefront at the issue of a load while look-ups wait;
+//   * the wavefronts of the two tables that share rows are added through LDS;
+//   * the sums over the slices are added by the workgroups that produced them
+//     (kReduceResident): each workgroup of a row group adds 1/slices of the row
+//     group's outputs.  There are no flags, no acknowledgements and nothing to
+//     clear: every 32-bit partial sum carries, in its lowest bit, the parity of
+//     the launch that wrote it.  A workgroup keeps its own launch count in the
+//     plan's memory (it alone reads and bumps it, so the counts of all
+//     workgroups move in step and no count is shared), every slot is written in
+//     every launch, so a slot shows the current parity exactly when this
+//     launch's sum has arrived.  A workgroup writes its partial sums through to
+//     memory and is done; a reader -- the first builder wavefront, which has
+//     nothing else left to do -- reads its slots of all slices until all show
+//     the parity, adds them in a fixed order (reproducible) and writes Y: one
+//     trip through memory between the last partial sum and Y.  The bit costs a
+//     floating-point partial sum its last mantissa bit (cleared before the add:
+//     at most one unit in the last place of a partial sum, exact for sums that
+//     do not need the bit) and an integer one a bit of range (a slice of 256
+//     columns stays far inside).  A reader waits for workgroups of its own
+//     launch, so the host takes this mode only when the whole grid is resident
+//     at once; the wait is bounded all the same, and a wavefront that gives up
+//     sets the plan's error word.  Otherwise a second launch adds the slices.
+// Same code layout, look-up, fold and scale as fused_kernel with C = 1, G = 64,
+// LB = 16.
+constexpr int kWideWaves = 8, kWideBuilders = 4, kWideTableBytes = 65536;
+#ifndef MSGEMM_WIDE_RING
+#define MSGEMM_WIDE_RING 4
+#endif
+
+template <typename XT, typename YT, typename ET, int kValueMode, int kTables>
+__global__ void __launch_bounds__((kWideWaves + kWideBuilders) * 64)
+fused_wide_kernel(FusedArgs a)
+{
+    using AT = typename EntryAcc<ET>::type;
+    constexpr int G = 64, LB = 16, NQ = 4, kFinal = 4, kPanelRows = 256;
+    constexpr int kRing = MSGEMM_WIDE_RING;    // code loads a wavefront keeps in flight
+    constexpr int kSlots = kWideWaves / kTables;  // streaming wavefronts per table = panels per workgroup at most
+    static_assert(sizeof(ET) == 4 && (kTables == 1 || kTables == 2), "entries are 4 bytes; one or two tables");
+    static_assert(kLoadsPerPanel % kRing == 0 && kRing % 2 == 0, "whole passes over the ring; entries alternate between two sets");
+    using LoadT = uint4;
+
+    __shared__ __align__(16) unsigned char lds[kTables * kWideTableBytes];
+    __shared__ AT stage[kTables == 2 ? kSlots * kFinal * 64 : 1];  // sums of the second table's wavefronts
+    __shared__ unsigned x_requested, built[kTables], staged[kSlots], stored;
+    __shared__ unsigned launch_parity;  // 2 | parity of this workgroup's launch count, once known
+
+#define MSGEMM_ARG_NOW(x) asm volatile("" ::"s"(x))
+    MSGEMM_ARG_NOW((uint64_t)a.tiled); MSGEMM_ARG_NOW((uint64_t)a.X); MSGEMM_ARG_NOW(a.ldx);
+    MSGEMM_ARG_NOW((uint64_t)a.Y); MSGEMM_ARG_NOW(a.ldy); MSGEMM_ARG_NOW((uint64_t)a.scales);
+    MSGEMM_ARG_NOW((uint64_t)a.partials); MSGEMM_ARG_NOW((uint64_t)a.flags); MSGEMM_ARG_NOW(a.m); MSGEMM_ARG_NOW(a.k);
+    MSGEMM_ARG_NOW(a.b); MSGEMM_ARG_NOW(a.m_pad); MSGEMM_ARG_NOW(a.b_pad); MSGEMM_ARG_NOW(a.ktiles);
+    MSGEMM_ARG_NOW(a.panels_total); MSGEMM_ARG_NOW(a.panels_per_wg); MSGEMM_ARG_NOW(a.col_passes);
+    MSGEMM_ARG_NOW(a.row_groups); MSGEMM_ARG_NOW(a.xcd_map); MSGEMM_ARG_NOW(a.partial_span);
+    MSGEMM_ARG_NOW(a.reduce_mode); MSGEMM_ARG_NOW(a.slices); MSGEMM_ARG_NOW(a.red_chunk);
+    MSGEMM_ARG_NOW(a.poll_limit); MSGEMM_ARG_NOW(a.publish);
+#undef MSGEMM_ARG_NOW
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = (tid >> 6) - kWideBuilders;  // streaming wavefront index; negative: builder
+    const int q = lane >> 4, j = lane & 15;
+
+    int sgm, rg;
+    {
+        const uint32_t bid = blockIdx.x;
+        const uint32_t n = a.xcd_map ? bid / kXcds : bid;
+        const uint32_t nq = fast_div(n, a.div_slices);
+        sgm = (int)(n - nq * (uint32_t)a.slices);
+        rg = a.xcd_map ? (int)((bid % kXcds) + kXcds * nq) : (int)nq;
+        if (rg >= a.row_groups) return;
+    }
+    const int rb = (int)fast_div((uint32_t)rg, a.div_col_passes);
+    const int cp = rg - rb * a.col_passes;
+    const int64_t col0 = cp;
+    const int kt0 = sgm * kTables;
+    const int ntab = min(a.ktiles - kt0, kTables);  // >= 1: the host makes no empty slice
+
+    const int panel_first = rb * a.panels_per_wg;   // (the host keeps panels_per_wg <= kSlots)
+    int panels_here = a.panels_total - panel_first;
+    if (panels_here > a.panels_per_wg) panels_here = a.panels_per_wg;
+
+    if (tid < kTables) built[tid] = 0;
+    if (tid < kSlots) staged[tid] = 0;
+    if (tid == 0) {
+        x_requested = 0;
+        stored = 0;
+        launch_parity = 0;
+    }
+    __syncthreads();  // nothing is in flight yet
+
+    const uint32_t col_stride = (uint32_t)(a.m_pad * 4);            // bytes between columns of the partials
+    const uint32_t tile_stride = (uint32_t)(a.b_pad * a.m_pad * 4); // bytes between slices
+    __amdgpu_buffer_rsrc_t part_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)a.partials, 0, (int)a.partial_span, 0x00020000);
+
+    if (wave < 0) {
+        // ---- builders: activations first, then the tables of k-tiles kt0 .. kt0 + ntab - 1
+        const XT* __restrict__ X = (const XT*)a.X;
+        const int g = tid % G;
+        const int part = __builtin_amdgcn_readfirstlane(tid / G);  // 0..3: this wavefront's high codes are part, part + 4, ...
+        XT xr0[kTables], xr1[kTables];
+        bool live[kTables];
+#pragma unroll
+        for (int tb = 0; tb < kTables; ++tb) {
+            const int64_t kk = ((int64_t)(kt0 + tb) * G + g) * 2;
+            live[tb] = (col0 < a.b) && (kk < a.k) && tb < ntab;
+            const XT* px = X + (live[tb] ? col0 * a.ldx + (kValueMode == kValuesMap256 ? (kk >> 1) : kk) : 0);
+            xr0[tb] = px[0];
+            xr1[tb] = px[kValueMode == kValuesMap256 ? 0 : 1];
+        }
+        // this workgroup's launch count (resident reduction; the first builder wavefront alone reads and bumps it)
+        const bool counts = wave == -kWideBuilders && a.reduce_mode == kReduceResident;
+        unsigned launches = 0;
+        if (counts) launches = __hip_atomic_load(a.epochs + blockIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // the requests are out (their data is not): now the streaming wavefronts may queue their codes
+        __builtin_amdgcn_sched_barrier(0);
+        if (lane == 0) __hip_atomic_fetch_add(&x_requested, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __builtin_amdgcn_sched_barrier(0);
+        // a custom value map: lane i of the wavefront holds the value of pattern i, so that the value of a code
+        // known only at run time is one cross-lane read (the map itself sits in scalar registers)
+        float map_lane = 0.0f;
+        if constexpr (kValueMode == kValuesMap16) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) map_lane = (lane == i) ? a.values.v[i] : map_lane;
+        }
+        auto value_const = [&](unsigned nibble) -> AT {  // nibble known at compile time
+            if constexpr (kValueMode == kValuesMap16) return code_value(a.values, nibble, AT());
+            else return (AT)decode4(nibble);
+        };
+        auto value_uniform = [&](int nibble) -> AT {     // nibble the same in all lanes
+            if constexpr (kValueMode == kValuesMap16)
+                return (AT)__uint_as_float(__builtin_amdgcn_readlane((int)__float_as_uint(map_lane), nibble));
+            else
+                return (AT)decode4((unsigned)nibble);
+        };
+        // 8-bit codes: the 16 values behind each of this thread's high nibbles, requested before the activations are
+        // waited for (this form keeps the loop over the high nibbles unrolled: 64 values in registers)
+        float v256[kValueMode == kValuesMap256 ? 16 / kWideBuilders : 1][16];
+        if constexpr (kValueMode == kValuesMap256) {
+#pragma unroll
+            for (int u = 0; u < 16 / kWideBuilders; ++u) {
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    const float4 qv = *(const float4*)(a.values256 + (part + u * kWideBuilders) * 16 + v4 * 4);
+                    v256[u][v4 * 4 + 0] = qv.x; v256[u][v4 * 4 + 1] = qv.y;
+                    v256[u][v4 * 4 + 2] = qv.z; v256[u][v4 * 4 + 3] = qv.w;
+                }
+            }
+        }
+#pragma unroll 1
+        for (int tb = 0; tb < ntab; ++tb) {
+            AT x0, x1;
+            if constexpr (kTables == 2) {
+                const bool lv = tb ? live[1] : live[0];
+                const XT r0 = tb ? xr0[1] : xr0[0], r1 = tb ? xr1[1] : xr1[0];
+                x0 = lv ? (AT)XTraits<XT>::load(&r0) : (AT)0;
+                x1 = lv ? (AT)XTraits<XT>::load(&r1) : (AT)0;
+            } else {
+                x0 = live[0] ? (AT)XTraits<XT>::load(&xr0[0]) : (AT)0;
+                x1 = live[0] ? (AT)XTraits<XT>::load(&xr1[0]) : (AT)0;
+            }
+            unsigned char* dst = lds + tb * kWideTableBytes + (size_t)(part * 16) * 256 + g * 4;
+            if constexpr (kValueMode == kValuesMap256) {
+#pragma unroll
+                for (int u = 0; u < 16 / kWideBuilders; ++u)
+#pragma unroll
+                    for (int c0 = 0; c0 < 16; ++c0)
+                        *(ET*)(dst + (size_t)(u * kWideBuilders * 16 + c0) * 256) = EntryAcc<ET>::make((AT)v256[u][c0] * x0);
+            } else {
+#pragma unroll 1
+                for (int c1 = part; c1 < 16; c1 += kWideBuilders) {
+                    const AT hi = value_uniform(c1) * x1;
+#pragma unroll
+                    for (int c0 = 0; c0 < 16; ++c0)
+                        *(ET*)(dst + c0 * 256) = EntryAcc<ET>::make(mul_add(value_const((unsigned)c0), x0, hi));
+                    dst += (size_t)(kWideBuilders * 16) * 256;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            if (lane == 0) __hip_atomic_fetch_add(&built[tb], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        if (!counts) return;
+
+        // ---- the first builder wavefront turns reader: 1/slices of the row group's outputs
+        launches += 1;
+        const unsigned parity = launches & 1u;
+        if (lane == 0) {
+            __hip_atomic_store(a.epochs + blockIdx.x, launches, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&launch_parity, 2u | parity, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        const int S = a.slices;
+        const uint32_t rg_floats = (uint32_t)panels_here * kPanelRows;
+        const uint32_t f0 = (uint32_t)sgm * (uint32_t)a.red_chunk;
+        if (f0 >= rg_floats) return;
+        const uint32_t f1 = min(f0 + (uint32_t)a.red_chunk, rg_floats);
+        // this workgroup's own partial sums are on their way: the others' are about as far (polling from the start
+        // would only add traffic)
+        while (__hip_atomic_load(&stored, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < (unsigned)panels_here)
+            __builtin_amdgcn_s_sleep(2);
+        YT* __restrict__ Y = (YT*)a.Y;
+        const uint32_t base = (uint32_t)col0 * col_stride + ((uint32_t)panel_first * kPanelRows + f0) * 4u;
+        // lane (grp, pc): the 16-byte piece pc of a run of 16 pieces, the slices grp, grp + 4, grp + 8, ...
+        const int grp = lane >> 4, pc = lane & 15;
+        unsigned polls = 0;
+        bool gave_up = false;
+#pragma unroll 1
+        for (uint32_t p0 = 0; f0 + p0 < f1 && !gave_up; p0 += 64u) {
+            const uint32_t p = p0 + (uint32_t)pc * 4u;
+            const bool have = f0 + p < f1;
+            AT sum[4] = {0, 0, 0, 0};
+#pragma unroll 1
+            for (int sb = 0; sb < S; sb += 16) {
+                v4u v[4];
+                uint32_t off[4];
+                bool live[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int sl = sb + grp + 4 * u;
+                    live[u] = have && sl < S;
+                    off[u] = live[u] ? base + p * 4u + (uint32_t)sl * tile_stride : 0x7ffffff0u;  // (out of range: reads zero)
+                }
+#pragma unroll 1
+                for (;;) {
+                    asm volatile("" ::: "memory");
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) v[u] = __builtin_amdgcn_raw_buffer_load_b128(part_rsrc, (int)off[u], 0, kAuxSc1);
+                    bool arrived = true;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        arrived &= !live[u] || ((v[u].x & v[u].y & v[u].z & v[u].w & 1u) == parity &&
+                                                ((v[u].x | v[u].y | v[u].z | v[u].w) & 1u) == parity);
+                    if (__builtin_amdgcn_ballot_w64(!arrived) == 0) break;
+                    if (++polls >= a.poll_limit) {
+                        gave_up = true;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                if (gave_up) break;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {  // (what is not live read as zero and adds nothing)
+                    AT x;
+                    untag_partial(x, live[u] ? v[u].x : 0u); sum[0] += x;
+                    untag_partial(x, live[u] ? v[u].y : 0u); sum[1] += x;
+                    untag_partial(x, live[u] ? v[u].z : 0u); sum[2] += x;
+                    untag_partial(x, live[u] ? v[u].w : 0u); sum[3] += x;
+                }
+            }
+            if (gave_up) break;
+            // the four slice classes, in a fixed order; 16-lane row r ends with output ((r & 1) << 1) | (r >> 1) of its pieces
+            const AT total = fold16(fold32(sum[0], sum[1]), fold32(sum[2], sum[3]));
+            const int e = ((grp & 1) << 1) | (grp >> 1);
+            // partial sum f of a panel belongs to lane f / 4, output f % 4 of the producing wavefront: row 64 (f % 4) + f / 4
+            const uint32_t f = f0 + p;
+            const int64_t row = ((int64_t)panel_first + f / kPanelRows) * kPanelRows + (f % kPanelRows) / 4 + 64 * e;
+            if (have && row < a.m && col0 < a.b) Y[col0 * a.ldy + row] = to_output<YT, AT>(total);
+        }
+        // gave up: some partial sum never arrived.  The plan's error word says so (msgemm_plan_check).
+        if (gave_up && lane == 0) __hip_atomic_store(a.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+
+    // ---- streamers: wavefront `slot` of table `tb` takes panel `slot` of the row group at k-tile kt0 + tb
+    const int tb = wave / kSlots, slot = wave % kSlots;
+    if (tb >= ntab || slot >= panels_here) return;  // nothing to stream
+    const int kt = kt0 + tb;
+    const int panel_g = panel_first + slot;
+    const int64_t step_stride = (int64_t)a.ktiles * a.panels_total * 64;  // LoadT elements between loads
+    const LoadT* nxt = (const LoadT*)a.tiled + ((int64_t)kt * a.panels_total + panel_g) * 64 + lane;
+    // the activations are requested first (a handful of cycles: the builders do nothing before it)
+    while (__hip_atomic_load(&x_requested, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < (unsigned)kWideBuilders)
+        __builtin_amdgcn_s_sleep(0);
+    LoadT ring[kRing];
+#pragma unroll
+    for (int u = 0; u < kRing; ++u) {
+        ring[u] = *nxt;
+        nxt += step_stride;
+        __builtin_amdgcn_sched_barrier(0);  // loads return in issue order: keep slot 0 first
+    }
+    __amdgpu_buffer_rsrc_t scale_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(a.scales ? (const void*)a.scales : (const void*)a.tiled), 0, a.scales ? (int)a.scale_span : 0, 0x00020000);
+    struct alignas(8) PackedScales { __half h[kFinal]; };
+    PackedScales qraw;
+    if constexpr (__is_same(AT, float)) {
+        const int scale_block = (int)fast_div((uint32_t)kt, a.div_tiles_per_block);
+        const int64_t qat = (int64_t)scale_block * a.m_pad + (int64_t)panel_g * kPanelRows + lane * kFinal;
+        const v2u qv = __builtin_amdgcn_raw_buffer_load_b64(scale_rsrc, (int)(qat * 2), 0, 0);
+        __builtin_memcpy(&qraw, &qv, sizeof(qraw));
+    }
+    // LDS address of a look-up: code byte in bits 15:8, the lane's group (16 (q % 4) + (j + t) % 16) in bits 7:2,
+    // the table in bit 16
+    const uint32_t addr_fixed = ((uint32_t)(16 * (q % NQ)) * 4u) | ((uint32_t)tb << 16);
+
+    while (__hip_atomic_load(&built[tb], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < (unsigned)kWideBuilders)
+        __builtin_amdgcn_s_sleep(1);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+
+    AT acc[LB];
+    ET ent[2][LB];  // entries of the load being looked up and of the one before it, which is being added
+#pragma unroll
+    for (int s = 0; s < LB; ++s) {
+        acc[s] = 0;
+        ent[1][s] = 0;
+    }
+    // One pass over the ring: the look-ups of kRing loads.  The passes that refill the ring are a rolled loop in
+    // which every step issues its load unconditionally (a branch around a load makes the compiler lose count of
+    // the loads in flight and wait for all of them); the last pass, which has nothing left to request, is a
+    // second copy of the body.
+    auto ring_pass = [&](int t0, auto refill) {
+#pragma unroll
+        for (int u = 0; u < kRing; ++u) {
+            // look-ups of load t0 + u ...
+            const uint32_t lane_off = addr_fixed | ((uint32_t)((j + t0 + u) & 15) * 4u);
+            const LoadT d = ring[u];
+#pragma unroll
+            for (int s = 0; s < LB; ++s) {
+                const uint32_t w = load_word<LB>(d, s >> 2);
+                const uint32_t addr = __builtin_amdgcn_perm(w, lane_off, 0x0c020000u | ((4u + (s & 3)) << 8));
+                ent[u & 1][s] = *(const ET*)(lds + addr);
+            }
+            // ... its slot refilled with the load kRing ahead ...
+            if constexpr (decltype(refill)::value) {
+                ring[u] = *nxt;
+                nxt += step_stride;
+            }
+            // ... while the entries of the load before it are added (the first time round: zeros)
+#pragma unroll
+            for (int s = 0; s < LB; ++s) {
+                acc[s] += EntryAcc<ET>::widen(ent[(u & 1) ^ 1][s]);
+                asm volatile("" : "+v"(acc[s]));  // keep the adds in their stage
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+#pragma unroll 1
+    for (int t0 = 0; t0 < kLoadsPerPanel - kRing; t0 += kRing) ring_pass(t0, std::true_type());
+    ring_pass(kLoadsPerPanel - kRing, std::false_type());
+#pragma unroll
+    for (int s = 0; s < LB; ++s) acc[s] += EntryAcc<ET>::widen(ent[(kRing - 1) & 1][s]);
+
+    // fold the four group classes: each lane ends with rows 64 * i + lane; then the block scale (Section 3.3)
+    AT y_run[kFinal];
+    {
+        AT half[LB / 2];
+#pragma unroll
+        for (int s = 0; s < LB / 2; ++s) half[s] = fold32(acc[s], acc[s + LB / 2]);
+#pragma unroll
+        for (int i = 0; i < kFinal; ++i) {
+            AT fin = fold16(half[i], half[i + kFinal]);
+            if constexpr (__is_same(AT, float)) fin *= (a.scales ? __half2float(qraw.h[i]) : 1.0f);
+            y_run[i] = fin;
+        }
+    }
+
+    // ---- the two tables' wavefronts of a slot hold sums of the same rows: the second hands its to the first
+    if constexpr (kTables == 2) {
+        AT* mine = stage + slot * (kFinal * 64) + lane;
+        if (tb == 1) {
+#pragma unroll
+            for (int i = 0; i < kFinal; ++i) mine[i * 64] = y_run[i];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            if (lane == 0) __hip_atomic_fetch_add(&staged[slot], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            return;
+        }
+        if (ntab == 2) {
+            // (that wavefront runs to its increment without waiting on this one)
+            while (__hip_atomic_load(&staged[slot], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0)
+                __builtin_amdgcn_s_sleep(1);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+#pragma unroll
+            for (int i = 0; i < kFinal; ++i) y_run[i] += mine[i * 64];
+        }
+    }
+
+    // ---- one sum per (slice, row): Y, or a partial
+    if (a.reduce_mode == kReduceDirect) {
+        YT* __restrict__ Y = (YT*)a.Y;
+#pragma unroll
+        for (int i = 0; i < kFinal; ++i) {
+            const int64_t row = (int64_t)panel_g * kPanelRows + lane + 64 * i;
+            if (row < a.m && col0 < a.b) Y[col0 * a.ldy + row] = to_output<YT, AT>(y_run[i]);
+        }
+        return;
+    }
+    const bool resident = a.reduce_mode == kReduceResident;
+    if (!resident || a.publish) {  // (publish = 0, a test aid: the readers find nothing and give up)
+        unsigned out[kFinal];
+        if (resident) {
+            // (the launch count was read at the start of the kernel: long known by now)
+            unsigned par;
+            while ((par = __hip_atomic_load(&launch_parity, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) == 0)
+                __builtin_amdgcn_s_sleep(1);
+#pragma unroll
+            for (int i = 0; i < kFinal; ++i) out[i] = tag_partial(y_run[i], par & 1u);
+        } else {
+#pragma unroll
+            for (int i = 0; i < kFinal; ++i) out[i] = bits_of(y_run[i]);
+        }
+        const uint32_t off = (uint32_t)sgm * tile_stride + (uint32_t)col0 * col_stride +
+                             (uint32_t)(panel_g * kPanelRows + lane * kFinal) * 4u;
+        if (resident) store_partials<kFinal, kAuxSc1>(part_rsrc, off, out);
+        else store_partials<kFinal, 0>(part_rsrc, off, out);
+    }
+    // tell the workgroup's reader that these sums are on their way
+    if (resident && lane == 0) __hip_atomic_fetch_add(&stored, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 // Second pass of the k-tile reduction.  A workgroup of kReduceWaves wavefronts
@@ -1096,6 +1547,44 @@ int launch_long(const Plan& p, FusedArgs& a, hipStream_t s)
     return MSGEMM_OK;
 }
 
+// Workgroups of `kern` (block threads, static LDS only) that one compute unit holds at once.
+template <typename K> int resident_blocks_per_cu(K kern, int threads)
+{
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, threads, 0) != hipSuccess) return 0;
+    return n;
+}
+
+template <typename XT, typename YT, typename ET, int kValueMode, int kTables>
+int launch_wide(const Plan& p, FusedArgs& a, hipStream_t s)
+{
+    using AT = typename EntryAcc<ET>::type;
+    auto kern = fused_wide_kernel<XT, YT, ET, kValueMode, kTables>;
+    constexpr int kThreads = (kWideWaves + kWideBuilders) * 64;
+    a.fused_wgs = a.xcd_map ? (int)(a.slices * kXcds * ((a.row_groups + kXcds - 1) / kXcds)) : (int)(a.slices * a.row_groups);
+    if (a.reduce_mode == kReduceResident) {
+        // the readers wait for workgroups of their own launch: only when all of them run at once
+        static const int per_cu = resident_blocks_per_cu(kern, kThreads);  // once per instantiation
+        if ((int64_t)a.fused_wgs > (int64_t)per_cu * p.cus) a.reduce_mode = kReduceSecondPass;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)a.fused_wgs), dim3(kThreads), 0, s, a);
+    MSGEMM_HIP_TRY(hipGetLastError());
+    if (a.reduce_mode == kReduceSecondPass) {
+        const int64_t blocks = (a.m_pad / 64) * a.b;
+        hipLaunchKernelGGL((reduce_kernel<YT, AT, 4>), dim3((unsigned)blocks), dim3(kReduceWaves * 64), 0, s,
+                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.slices, a.partial_span);
+        MSGEMM_HIP_TRY(hipGetLastError());
+    }
+    return MSGEMM_OK;
+}
+
+template <typename XT, typename YT, typename ET, int kValueMode>
+int launch_wide_tables(const Plan& p, FusedArgs& a, hipStream_t s)
+{
+    if (p.wide_tables == 2) return launch_wide<XT, YT, ET, kValueMode, 2>(p, a, s);
+    return launch_wide<XT, YT, ET, kValueMode, 1>(p, a, s);
+}
+
 // integer tables have the one encoding; floating-point ones also a form that reads the plan's map
 template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves>
 int launch_for_values(const Plan& p, FusedArgs& a, hipStream_t s)
@@ -1103,6 +1592,7 @@ int launch_for_values(const Plan& p, FusedArgs& a, hipStream_t s)
     constexpr bool kFloatTables = !std::is_same<ET, int>::value;
     if (p.codes8) {  // 8-bit weights: the single-column kernels with 16 rows per lane, and the four-column fp32 one
         if constexpr (C == 1 && LB == 16 && kFloatTables) {
+            if (p.wide_tables > 0) return launch_wide_tables<XT, YT, ET, kValuesMap256>(p, a, s);
             if (p.segments > 0) return launch_long<XT, YT, ET, kValuesMap256>(p, a, s);
             return launch_one<XT, YT, ET, C, G, LB, kWaves, kValuesMap256>(p, a, s);
         }
@@ -1110,6 +1600,12 @@ int launch_for_values(const Plan& p, FusedArgs& a, hipStream_t s)
         return MSGEMM_ERR_UNSUPPORTED;
     }
     if constexpr (C == 1 && LB == 16) {
+        if (p.wide_tables > 0) {  // wide form: one or two tables per workgroup, a whole unit in flight per wavefront
+            if constexpr (kFloatTables) {
+                if (p.custom_values) return launch_wide_tables<XT, YT, ET, kValuesMap16>(p, a, s);
+            }
+            return launch_wide_tables<XT, YT, ET, kValuesDefault>(p, a, s);
+        }
         if (p.segments > 0) {  // long-k form
             if constexpr (kFloatTables) {
                 if (p.custom_values) return launch_long<XT, YT, ET, kValuesMap16>(p, a, s);
@@ -1220,8 +1716,17 @@ int fused_choose_shape(Plan& p, int requested_variant)
     if ((int64_t)p.ktiles * (row_groups + kXcds) + panels * p.col_passes > 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
     // the k-tile reduction addresses the partial buffer with 32-bit byte offsets
     if (batched16 && !batched_pipe) batched_choose_segments(p);
-    // (a streaming wavefront of the long-k form holds the sums of at most two panels)
-    if (can_run_long && ppw <= 2 * kLongWaves && tps >= 2) {
+    // The single-column kernel's forms: wide with one table (one k-tile, up to eight panels per workgroup), wide
+    // with two (two k-tiles, up to four panels), long-k (runs of k-tiles through two table buffers; a streaming
+    // wavefront holds the sums of at most two panels), and the plain one (one k-tile, up to sixteen panels).
+    p.wide_tables = 0;
+    if (can_run_long && tps == 1 && ppw <= kWideWaves) {
+        p.wide_tables = 1;
+    } else if (can_run_long && tps == 2 && ppw <= kWideWaves / 2 && p.ktiles >= 2) {
+        p.wide_tables = 2;
+        p.tiles_per_segment = 2;
+        p.segments = (int)((p.ktiles + 1) / 2);
+    } else if (can_run_long && ppw <= 2 * kLongWaves && tps >= 2) {
         p.tiles_per_segment = (int)tps;
         p.segments = (int)((p.ktiles + tps - 1) / tps);
     }
@@ -1330,6 +1835,10 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     a.scales = (const __half*)p.scales_ordered;
     a.partials = p.partials;
     a.flags = p.flags;
+    a.error = p.error_word;
+    a.epochs = p.epochs;
+    a.poll_limit = p.opt.poll_limit > 0 ? (unsigned)p.opt.poll_limit : kMaxFlagPolls;
+    a.publish = p.opt.skip_publish ? 0 : 1;
     a.m = p.m; a.k = p.k; a.b = p.b; a.m_pad = p.m_pad;
     a.b_pad = (int64_t)p.col_passes * p.fs.cols;
     a.ktiles = (int)p.ktiles;
@@ -1360,10 +1869,16 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     // pass.  The plan's option reduce_mode = 1 (second pass) or 2 (in launch) overrides the
     // choice for the single-column kernels.
     a.reduce_mode = kReduceDirect;
+    a.red_chunk = 0;
     if (a.slices > 1) {
-        a.reduce_mode = p.fs.cols == 1 ? kReduceInLaunch : kReduceSecondPass;
-        const int forced = p.forced_reduce;
-        if (p.fs.cols == 1 && (forced == kReduceSecondPass || forced == kReduceInLaunch)) a.reduce_mode = forced;
+        // (the wide form adds in its own workgroups, the others in trailing ones: requests for either in-launch
+        // mode get the one the kernel has)
+        const int in_launch = p.wide_tables > 0 ? kReduceResident : kReduceInLaunch;
+        a.reduce_mode = p.fs.cols == 1 ? in_launch : kReduceSecondPass;
+        if (p.fs.cols == 1 && p.forced_reduce == kReduceSecondPass) a.reduce_mode = kReduceSecondPass;
+        // outputs per reader of the resident reduction: the row group's, dealt evenly in whole 16-byte pieces
+        const int64_t rg_floats = (int64_t)p.fs.panels * p.fs.panel_rows;
+        a.red_chunk = (int)(((rg_floats + a.slices - 1) / a.slices + 3) / 4 * 4);
     }
 
     const int C = p.fs.cols, G = p.fs.groups, LB = p.fs.lane_bytes, EB = p.fs.entry_bytes;

@@ -31,6 +31,7 @@ void free_plan(Plan* p)
     if (p->scales_ordered) (void)hipFree(p->scales_ordered);
     if (p->partials) (void)hipFree(p->partials);
     if (p->flags) (void)hipFree(p->flags);
+    if (p->epochs) (void)hipFree(p->epochs);
     delete p;
 }
 
@@ -153,7 +154,10 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
         const size_t b_pad = (size_t)p->col_passes * (size_t)p->fs.cols;
         const size_t slices = p->segments > 0 ? (size_t)p->segments : (size_t)p->ktiles;
         const size_t part = slices * b_pad * (size_t)p->m_pad * 4u;
-        const size_t cnt = (size_t)(p->m_pad / p->fs.panel_rows) * (size_t)p->col_passes * (size_t)p->ktiles * sizeof(unsigned);
+        // arrival flags per (panel, column pass, slice) for trailing reducers; one more word for give-ups
+        const size_t words = (size_t)(p->m_pad / p->fs.panel_rows) * (size_t)p->col_passes * (size_t)p->ktiles;
+        p->flag_words = words;
+        const size_t cnt = (words + 1) * sizeof(unsigned);
         e = hipMalloc((void**)&p->codes_tiled, tiled);
         if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
         e = hipMalloc((void**)&p->partials, part);
@@ -162,6 +166,20 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
         if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
         e = hipMemsetAsync(p->flags, 0, cnt, s);
         if (e != hipSuccess) return hip_fail(e);
+        p->error_word = p->flags + words;
+        p->partial_bytes = part;
+        if (p->wide_tables > 0) {
+            // the wide form's resident reduction: every partial sum carries the parity of its launch, counted per
+            // workgroup; both start at zero
+            p->epoch_words = (size_t)slices * msgemm::kXcds * (((size_t)p->row_blocks * p->col_passes + msgemm::kXcds - 1) / msgemm::kXcds);
+            e = hipMalloc((void**)&p->epochs, p->epoch_words * sizeof(unsigned));
+            if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
+            e = hipMemsetAsync(p->epochs, 0, p->epoch_words * sizeof(unsigned), s);
+            if (e != hipSuccess) return hip_fail(e);
+            e = hipMemsetAsync(p->partials, 0, part, s);
+            if (e != hipSuccess) return hip_fail(e);
+            p->workspace_bytes += p->epoch_words * sizeof(unsigned);
+        }
         p->workspace_bytes = tiled + part + cnt;
         if (p->scales) {
             // (the batched kernel keeps one scale per look-up slot: twice the rows)
@@ -286,6 +304,26 @@ int msgemm_run(const msgemm_plan_t* plan, const void* X, int64_t ldx, void* Y, i
     return msgemm::launch_consume_lut(p, p.lut_ws, Y, ldy, s);
 }
 
+int msgemm_plan_check(const msgemm_plan_t* plan, void* stream)
+{
+    if (!plan) return MSGEMM_ERR_INVALID_ARG;
+    const Plan& p = *reinterpret_cast<const Plan*>(plan);
+    if (!p.flags) return MSGEMM_OK;  // no in-launch reduction in this plan's variant
+    hipStream_t s = (hipStream_t)stream;
+    unsigned err = 0;
+    MSGEMM_HIP_TRY(hipMemcpyAsync(&err, p.error_word, sizeof(err), hipMemcpyDeviceToHost, s));
+    MSGEMM_HIP_TRY(hipStreamSynchronize(s));
+    if (!err) return MSGEMM_OK;
+    // a reducer gave up: flags may be left up, outputs of that call are not the result.  Clear, so that the plan works again.
+    MSGEMM_HIP_TRY(hipMemsetAsync(p.flags, 0, (p.flag_words + 1) * sizeof(unsigned), s));
+    if (p.wide_tables > 0) {  // partial sums of the failed launch may be missing: parities and launch counts start over
+        MSGEMM_HIP_TRY(hipMemsetAsync(p.partials, 0, p.partial_bytes, s));
+        MSGEMM_HIP_TRY(hipMemsetAsync(p.epochs, 0, p.epoch_words * sizeof(unsigned), s));
+    }
+    MSGEMM_HIP_TRY(hipStreamSynchronize(s));
+    return MSGEMM_ERR_INCOMPLETE;
+}
+
 int msgemm_dequant_mfma_run(const msgemm_plan_t* plan, const void* X, int64_t ldx, void* Y, int64_t ldy,
                             void* stream)
 {
@@ -322,6 +360,7 @@ const char* msgemm_status_string(int status)
     case MSGEMM_ERR_ALLOC: return "allocation failed";
     case MSGEMM_ERR_HIP: return "HIP runtime error";
     case MSGEMM_ERR_UNSUPPORTED: return "not supported by the requested variant";
+    case MSGEMM_ERR_INCOMPLETE: return "a reduction inside a launch gave up waiting for partial sums; the outputs of the calls since the last check are not valid";
     default: return "unknown status";
     }
 }

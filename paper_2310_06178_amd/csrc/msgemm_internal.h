@@ -67,7 +67,14 @@ struct Plan {
     uint16_t* scales_ordered;  // device fp16 [nblocks][m_pad], rows in the order the lanes own outputs; nullptr without scales
     uint8_t* codes_tiled; // device, [ktiles][m_pad / panel_rows][16][64][lane_bytes]
     float* partials;      // device, [ktiles or segments][b_pad][m_pad] fp32 / int32
-    unsigned* flags;      // device, [panels][col_passes][ktiles] arrival flags of the in-launch reduction, zero between launches
+    unsigned* flags;      // device, [panels][col_passes][slices] arrival flags of the trailing-workgroup reduction, zero
+                          // between launches; then the error word
+    size_t partial_bytes; // size of `partials`
+    unsigned* epochs;     // device, wide form: launch count of every workgroup of the grid (resident reduction), or nullptr
+    size_t epoch_words;
+    size_t flag_words;    // flags in that buffer
+    unsigned* error_word; // device, flags + flag_words: set by a wavefront that gave up waiting (msgemm_plan_check)
+    int wide_tables;      // single-column kernel, wide form: tables a workgroup holds (1 or 2); 0 = another form
     size_t workspace_bytes;
 };
 

@@ -411,9 +411,9 @@ REDUCE_CASES = [
 @pytest.mark.parametrize("mode", [1, 2])
 @pytest.mark.parametrize("m,k,b,xd,sg", REDUCE_CASES)
 def test_fused_k_tile_reduction_modes(m, k, b, xd, sg, mode):
-    """Both ways of adding the k-tile partial sums (1: second launch, 2: trailing
-    workgroups of the same launch) against the oracle, twice on the same plan:
-    the arrival flags of the in-launch reduction must be down again after a launch."""
+    """Both ways of adding the k-tile partial sums (1: second launch, 2: inside the
+    launch) against the oracle, twice on the same plan: the arrival flags of the
+    in-launch reduction must be down again after a launch."""
     codes = inputs.make_codes(m, k, seed=m + k)
     scales = inputs.make_scales(m, k, sg, seed=4) if sg else None
     dC = torch_io.to_device(codes, "codes")
@@ -471,6 +471,89 @@ def test_fused_long_k_form(m, k, b, xd, sg, tps, ppw, mode):
             out = torch_io.to_host(Y)
             check(np.ascontiguousarray(out[:, :m]), oracle_y(codes, X, xd, scales, sg), xd,
                   f"long-k tps {tps} reduce mode {mode} call {rep}", elem_bound(codes, X, xd, scales, sg))
+    finally:
+        B.msgemm_destroy(plan)
+
+
+WIDE_CASES = [
+    # m, k, b, xd, sg, panels per workgroup (0: the library's choice)
+    (2049, 1024, 1, "f16", 128, 4),    # 8 k-tiles in pairs, 9 panels: three row groups, the last with one panel
+    (300, 8320, 1, "f32", 0, 0),       # 65 k-tiles: 33 slices, the last with one table only
+    (700, 768, 2, "i8", 0, 2),         # two column passes; two panels for four wavefronts per table: idle ones
+    (4100, 512, 1, "bf16", 256, 8),    # 17 panels, 8 per workgroup: two per wavefront; scale block = the two k-tiles
+    (515, 256, 1, "f16", 128, 1),      # one slice: written straight to Y
+    (1030, 640, 1, "f16", 128, 3),     # five k-tiles: three slices; row groups of three panels (768 outputs over 3 readers)
+]
+
+
+@pytest.mark.parametrize("mode", [1, 3])
+@pytest.mark.parametrize("m,k,b,xd,sg,ppw", WIDE_CASES)
+def test_fused_wide_form_two_tables(m, k, b, xd, sg, ppw, mode):
+    """The single-column kernel with the tables of two k-tiles per workgroup (a whole unit of codes in flight per
+    wavefront, the two tables' sums joined through LDS), forced on small shapes; the sums over the slices added by a
+    second launch (1) or by the workgroups that produced them (3); twice on one plan: flags must be down again."""
+    codes = inputs.make_codes(m, k, seed=m + k + ppw)
+    scales = inputs.make_scales(m, k, sg, seed=6) if sg else None
+    dC = torch_io.to_device(codes, "codes")
+    dS = torch_io.to_device(scales, "scales")
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS, B.VARIANT_FUSED_LDS,
+                         options={"k_tiles_per_workgroup": 2, "reduce_mode": mode, "panels_per_workgroup": ppw})
+    try:
+        ktiles = -(-(k // 2) // 64)
+        info = B.msgemm_plan_get_info(plan)
+        assert info["split_k"] == -(-ktiles // 2)
+        if ppw:
+            assert info["tile_rows"] == 256 * ppw
+        for rep in range(2):
+            X = inputs.make_x(k, b, xd, seed=91 + rep)
+            dX = torch_io.to_device(X, xd)
+            Y = torch_io.empty_output(b, m, Y_OF_X[xd], ldy=m + 3)
+            Y.fill_(-3)
+            B.msgemm_run(plan, dX, k, Y, m + 3)
+            torch.cuda.synchronize()
+            out = torch_io.to_host(Y)
+            check(np.ascontiguousarray(out[:, :m]), oracle_y(codes, X, xd, scales, sg), xd,
+                  f"wide form, reduce mode {mode}, call {rep}", elem_bound(codes, X, xd, scales, sg))
+            minus3 = torch_io.to_host(torch.full((1,), -3, dtype=Y.dtype))[0]
+            assert np.all(out[:, m:] == minus3), "output padding was written"
+        assert B.msgemm_plan_check(plan) == B.OK
+    finally:
+        B.msgemm_destroy(plan)
+
+
+@pytest.mark.parametrize("options", [
+    {"k_tiles_per_workgroup": 1},                               # wide form, one table: readers in the producing workgroups
+    {"k_tiles_per_workgroup": 2, "panels_per_workgroup": 4},    # wide form, two tables
+    {"k_tiles_per_workgroup": 3, "reduce_mode": 2},             # long-k form: trailing reducer workgroups
+])
+def test_in_launch_reduction_give_up_is_reported(options):
+    """A reduction inside the launch whose producers never announce their partial sums (forced from the host: the
+    announcement is skipped and the poll bound is tiny, so every kernel still runs to its end) must not pass for a
+    result: the plan's check reports it once, clears the state, and the next check is clean."""
+    m, k = 2049, 1024
+    codes = inputs.make_codes(m, k, seed=3)
+    X = inputs.make_x(k, 1, "f16", seed=4)
+    dC, dX = torch_io.to_device(codes, "codes"), torch_io.to_device(X, "f16")
+    Y = torch_io.empty_output(1, m, "f16")
+    plan = B.msgemm_plan(m, k, 1, "f16", "f16", 2, 0, dC, None, B.VARIANT_FUSED_LDS,
+                         options=dict(options, poll_limit=8, skip_publish=1))
+    try:
+        assert B.msgemm_plan_get_info(plan)["split_k"] > 1
+        assert B.msgemm_plan_check(plan) == B.OK       # nothing has run yet
+        B.msgemm_run(plan, dX, k, Y, m)
+        assert B.msgemm_plan_check(plan) == B.ERR_INCOMPLETE
+        assert B.msgemm_plan_check(plan) == B.OK       # reported once, then cleared
+        B.msgemm_run(plan, dX, k, Y, m)
+        assert B.msgemm_plan_check(plan) == B.ERR_INCOMPLETE
+    finally:
+        B.msgemm_destroy(plan)
+    # the same problem without the test aid is complete and right
+    plan = B.msgemm_plan(m, k, 1, "f16", "f16", 2, 0, dC, None, B.VARIANT_FUSED_LDS, options=dict(options))
+    try:
+        B.msgemm_run(plan, dX, k, Y, m)
+        assert B.msgemm_plan_check(plan) == B.OK
+        check(torch_io.to_host(Y), oracle_y(codes, X, "f16", None, 0), "f16", "after the give-up test",
+              elem_bound(codes, X, "f16", None, 0))
     finally:
         B.msgemm_destroy(plan)
 
