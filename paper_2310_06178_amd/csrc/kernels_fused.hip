@@ -1703,6 +1703,13 @@ int fused_choose_shape(Plan& p, int requested_variant)
     p.segments = 0;
     p.tiles_per_segment = 0;
     if (batched_pipe) batched_choose_rows_and_segments(p, panels, ppw);
+    // Eight panels of one k-tile per workgroup and four panels of two are the same workgroups with the same
+    // work; the second form halves the partial sums per output (measured on the 32 MiB GEMV: 10.8 -> 10.55 us).
+    if (can_run_long && tps == 1 && ppw == kWideWaves && p.ktiles >= 2 && p.opt.k_tiles_per_workgroup == 0 &&
+        p.opt.panels_per_workgroup == 0) {
+        ppw = kWideWaves / 2;
+        tps = 2;
+    }
     const int forced = p.opt.panels_per_workgroup;
     if (forced >= 1 && forced <= 64 && !batched_pipe) ppw = forced;
     // k_tiles_per_workgroup = 1 keeps one k-tile per workgroup, n > 1 forces runs of n.
