@@ -239,6 +239,24 @@ int msgemm_run(const msgemm_plan_t* plan, const void* X, int64_t ldx,
                void* Y, int64_t ldy, void* stream);
 
 /*
+ * msgemm_run for callers that cannot allocate or hold a workspace: code under
+ * HIP graph capture, serving loops and harnesses that forbid hipMalloc.  The
+ * same Y by the same kernels, but the partial sums over the k-tiles live in a
+ * static array in the library's device image (16 MiB on every device the
+ * library runs on, held until the process ends) instead of the plan's
+ * workspace, and are added by a second launch; the call allocates and frees
+ * nothing.  Plans of the fused variants only (MSGEMM_ERR_UNSUPPORTED for
+ * GLOBAL_LUT / GLOBAL_LUT_HALF) whose partial sums fit the array
+ * (split_k * b * m rounded up to whole panels * 4 bytes <= 16 MiB, else
+ * MSGEMM_ERR_UNSUPPORTED); the plan's device must be current
+ * (MSGEMM_ERR_INVALID_ARG).  All calls on one device share the array: calls
+ * that overlap on a device -- different streams, different plans -- race.
+ * Nothing in the array needs a particular value when a call starts.
+ */
+int msgemm_run_static(const msgemm_plan_t* plan, const void* X, int64_t ldx,
+                      void* Y, int64_t ldy, void* stream);
+
+/*
  * The single-column kernels add the partial sums of the k-tiles (the sum over
  * j in Section 3.2, cut into pieces that different workgroups hold) inside the
  * launch: wavefronts wait, for a bounded number of polls, until the partial

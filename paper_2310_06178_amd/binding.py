@@ -21,7 +21,7 @@ OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED, ERR_INCOMPLETE = 0, -1
 
 EXPORTS = (
     "msgemm_plan", "msgemm_plan_with_options", "msgemm_plan_codes8", "msgemm_plan_set_codebook", "msgemm_plan_get_info", "msgemm_lut_bytes", "msgemm_build_lut",
-    "msgemm_consume_lut", "msgemm_run", "msgemm_plan_check", "msgemm_dequant_mfma_run", "msgemm_calib_stream_read", "msgemm_calib_lds_read", "msgemm_destroy",
+    "msgemm_consume_lut", "msgemm_run", "msgemm_run_static", "msgemm_plan_check", "msgemm_dequant_mfma_run", "msgemm_calib_stream_read", "msgemm_calib_lds_read", "msgemm_destroy",
     "msgemm_status_string", "msgemm_last_hip_error", "msgemm_version",
 )
 
@@ -109,6 +109,8 @@ def load():
     lib.msgemm_consume_lut.restype = ci
     lib.msgemm_run.argtypes = [vp, vp, i64, vp, i64, vp]
     lib.msgemm_run.restype = ci
+    lib.msgemm_run_static.argtypes = [vp, vp, i64, vp, i64, vp]
+    lib.msgemm_run_static.restype = ci
     lib.msgemm_plan_check.argtypes = [vp, vp]
     lib.msgemm_plan_check.restype = ci
     lib.msgemm_dequant_mfma_run.argtypes = [vp, vp, i64, vp, i64, vp]
@@ -246,6 +248,13 @@ def msgemm_run(plan, X, ldx, Y, ldy, stream=None):
     rc = load().msgemm_run(ctypes.c_void_p(plan), _ptr(X), int(ldx), _ptr(Y), int(ldy), _stream(stream))
     if rc != OK:
         raise MsgemmError(rc, "msgemm_run")
+
+
+def msgemm_run_static(plan, X, ldx, Y, ldy, stream=None, check=True):
+    rc = load().msgemm_run_static(ctypes.c_void_p(plan), _ptr(X), int(ldx), _ptr(Y), int(ldy), _stream(stream))
+    if check and rc != OK:
+        raise MsgemmError(rc, "msgemm_run_static")
+    return rc
 
 
 def msgemm_plan_check(plan, stream=None) -> int:

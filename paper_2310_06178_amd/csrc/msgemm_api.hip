@@ -304,6 +304,57 @@ int msgemm_run(const msgemm_plan_t* plan, const void* X, int64_t ldx, void* Y, i
     return msgemm::launch_consume_lut(p, p.lut_ws, Y, ldy, s);
 }
 
+// Scratch memory of msgemm_run_static: one array per device for the life of the process.  In host code the
+// array's name is only a handle; its device address is looked up once per device (scratch_on_device).
+namespace {
+constexpr size_t kScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each device, once looked up
+bool g_scratch_known[kMaxDevices];
+
+// Address of this device's copy of `scratch` (the device must be current); nullptr and the HIP error kept on failure.
+void* scratch_on_device(int device)
+{
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    if (!g_scratch_known[device]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            msgemm::set_hip_error(e);
+            return nullptr;
+        }
+        g_scratch_ptr[device] = ptr;
+        g_scratch_known[device] = true;
+    }
+    return g_scratch_ptr[device];
+}
+}  // namespace
+
+int msgemm_run_static(const msgemm_plan_t* plan, const void* X, int64_t ldx, void* Y, int64_t ldy, void* stream)
+{
+    if (!plan || !X || !Y) return MSGEMM_ERR_INVALID_ARG;
+    const Plan& p = *reinterpret_cast<const Plan*>(plan);
+    if (ldx < (p.codes8 ? p.k / 2 : p.k) || ldy < p.m) return MSGEMM_ERR_INVALID_ARG;
+    if (p.variant == MSGEMM_VARIANT_GLOBAL_LUT) return MSGEMM_ERR_UNSUPPORTED;  // its table alone can be gigabytes
+    int device = -1;
+    MSGEMM_HIP_TRY(hipGetDevice(&device));
+    if (device != p.device) return MSGEMM_ERR_INVALID_ARG;
+    // the partial sums over the k-tiles (or k-segments) are the only memory the fused kernels need besides the
+    // plan's weights, X and Y when those sums are added by a second launch: no flag, count or table outlives a call
+    if (p.partial_bytes > kScratchBytes) return MSGEMM_ERR_UNSUPPORTED;
+    void* ptr = scratch_on_device(device);
+    if (!ptr) return MSGEMM_ERR_HIP;
+    Plan q = p;  // (a plain copy of pointers and numbers: nothing is owned twice, nothing is freed)
+    q.partials = (float*)ptr;
+    q.forced_reduce = 1;   // second launch: every partial sum is written before it is read, nothing needs clearing
+    q.flags = nullptr;
+    q.epochs = nullptr;
+    q.error_word = nullptr;
+    return msgemm::launch_fused(q, X, ldx, Y, ldy, (hipStream_t)stream);
+}
+
 int msgemm_plan_check(const msgemm_plan_t* plan, void* stream)
 {
     if (!plan) return MSGEMM_ERR_INVALID_ARG;
