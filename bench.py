@@ -190,6 +190,9 @@ def main() -> int:
                     help="time the dequantise + MFMA comparison kernel instead of the msGeMM path (labelled as such)")
     ap.add_argument("--no-ceiling", action="store_true",
                     help="skip the plain stream-read kernel that measures the practical HBM ceiling")
+    ap.add_argument("--lib", default=None,
+                    help="time another build of the library (a measurement build made with "
+                         "`python -m paper_2310_06178_amd.build -D... --out PATH`); implies --no-cpu when it computes nothing")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 64 MiB elementwise copy (untimed): gives hardware-counter runs a kernel of known traffic")
     args = ap.parse_args()
@@ -206,6 +209,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
+    if args.lib:
+        B.LIB_PATH = os.path.abspath(args.lib)
     B.load()
     torch.cuda.set_device(0)
 
@@ -305,6 +310,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": {"f32": "f32", "f16": "f32", "bf16": "f32", "i8": "int32"}[cfg["x"]],
         "data": "synthetic",
+        "library": os.path.relpath(B.LIB_PATH, ROOT),
         "config": {
             "workload": f"{args.config}: m={m} k={k} b={b} int4 W, {cfg['x']} X, {cfg['y']} Y, "
                         f"scale_group={cfg['scale_group']}, d={info['d']}",

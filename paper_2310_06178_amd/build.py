@@ -32,15 +32,22 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = True) -> str:
-    cmd = [hipcc(), *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           "-o", LIB, *sources()]
+def build(verbose: bool = True, defines=(), out: str = LIB) -> str:
+    """Compile the library.  `defines` / `out` make a measurement build beside the product (for instance
+    MSGEMM_WIDE_LEAVE_OUT=1, see csrc/kernels_fused.hip; bench.py --lib times such a build)."""
+    cmd = [hipcc(), *HIPCC_FLAGS, *[f"-D{d}" for d in defines], "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+           "-o", out, *sources()]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
-    build()
+    import argparse
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--define", "-D", action="append", default=[], help="preprocessor definition NAME or NAME=VALUE")
+    ap.add_argument("--out", default=LIB, help="output path (default: the product library)")
+    args = ap.parse_args()
+    build(defines=args.define, out=args.out)
     sys.exit(0)

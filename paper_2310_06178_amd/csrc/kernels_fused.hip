@@ -946,6 +946,13 @@ constexpr int kWideWaves = 8, kWideBuilders = 4, kWideTableBytes = 65536;
 #ifndef MSGEMM_WIDE_RING
 #define MSGEMM_WIDE_RING 4
 #endif
+// Measurement builds only (never the product): -DMSGEMM_WIDE_LEAVE_OUT=<bits> leaves parts of the wide form out, so that
+// the time each part adds to a launch can be read off as a difference (the results are then wrong, of course):
+// 1 the readers (nobody adds the partial sums), 2 the partial sums' stores, 4 the look-ups (their addresses are
+// still formed and added), 8 the wait for the tables, 16 the wait for the activations' request.
+#ifndef MSGEMM_WIDE_LEAVE_OUT
+#define MSGEMM_WIDE_LEAVE_OUT 0
+#endif
 
 template <typename XT, typename YT, typename ET, int kValueMode, int kTables>
 __global__ void __launch_bounds__((kWideWaves + kWideBuilders) * 64)
@@ -1100,6 +1107,7 @@ fused_wide_kernel(FusedArgs a)
             if (lane == 0) __hip_atomic_fetch_add(&built[tb], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
         if (!counts) return;
+        if (MSGEMM_WIDE_LEAVE_OUT & 1) return;
 
         // ---- the first builder wavefront turns reader: 1/slices of the row group's outputs
         launches += 1;
@@ -1188,7 +1196,8 @@ fused_wide_kernel(FusedArgs a)
     const int64_t step_stride = (int64_t)a.ktiles * a.panels_total * 64;  // LoadT elements between loads
     const LoadT* nxt = (const LoadT*)a.tiled + ((int64_t)kt * a.panels_total + panel_g) * 64 + lane;
     // the activations are requested first (a handful of cycles: the builders do nothing before it)
-    while (__hip_atomic_load(&x_requested, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < (unsigned)kWideBuilders)
+    while (!(MSGEMM_WIDE_LEAVE_OUT & 16) &&
+           __hip_atomic_load(&x_requested, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < (unsigned)kWideBuilders)
         __builtin_amdgcn_s_sleep(0);
     LoadT ring[kRing];
 #pragma unroll
@@ -1211,7 +1220,8 @@ fused_wide_kernel(FusedArgs a)
     // the table in bit 16
     const uint32_t addr_fixed = ((uint32_t)(16 * (q % NQ)) * 4u) | ((uint32_t)tb << 16);
 
-    while (__hip_atomic_load(&built[tb], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < (unsigned)kWideBuilders)
+    while (!(MSGEMM_WIDE_LEAVE_OUT & 8) &&
+           __hip_atomic_load(&built[tb], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < (unsigned)kWideBuilders)
         __builtin_amdgcn_s_sleep(1);
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 
@@ -1236,7 +1246,8 @@ fused_wide_kernel(FusedArgs a)
             for (int s = 0; s < LB; ++s) {
                 const uint32_t w = load_word<LB>(d, s >> 2);
                 const uint32_t addr = __builtin_amdgcn_perm(w, lane_off, 0x0c020000u | ((4u + (s & 3)) << 8));
-                ent[u & 1][s] = *(const ET*)(lds + addr);
+                if (MSGEMM_WIDE_LEAVE_OUT & 4) set_bits(ent[u & 1][s], addr);
+                else ent[u & 1][s] = *(const ET*)(lds + addr);
             }
             // ... its slot refilled with the load kRing ahead ...
             if constexpr (decltype(refill)::value) {
@@ -1303,7 +1314,7 @@ fused_wide_kernel(FusedArgs a)
         return;
     }
     const bool resident = a.reduce_mode == kReduceResident;
-    if (!resident || a.publish) {  // (publish = 0, a test aid: the readers find nothing and give up)
+    if ((!resident || a.publish) && !(MSGEMM_WIDE_LEAVE_OUT & 2)) {  // (publish = 0, a test aid: the readers find nothing and give up)
         unsigned out[kFinal];
         if (resident) {
             // (the launch count was read at the start of the kernel: long known by now)
