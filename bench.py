@@ -157,6 +157,45 @@ def stream_read_ceiling(B, torch, stream, nbytes, n_copies, steps):
     return {"bytes": nbytes, "us": us, "GB/s": nbytes / (us * 1e-6) / 1e9}
 
 
+def stream_read_sweep(B, torch, stream, nbytes, n_copies, steps):
+    """The read-only yardstick over launch shapes, loads in flight and cache policy, each timed like a step
+    (HIP graph, rotating cold buffers, events on the launch stream); also an empty launch."""
+    bufs = [torch.randint(0, 255, (nbytes,), dtype=torch.uint8, device="cuda:0") for _ in range(n_copies)]
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
+
+    def timed(launch):
+        for i in range(5):
+            launch(i)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for i in range(steps):
+                launch(i)
+        graph.replay()
+        torch.cuda.synchronize()
+        best = float("inf")
+        for _ in range(3):
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            with torch.cuda.stream(stream):
+                ev0.record(stream)
+                graph.replay()
+                ev1.record(stream)
+            torch.cuda.synchronize()
+            best = min(best, ev0.elapsed_time(ev1) * 1e3 / steps)
+        return best
+
+    rows = []
+    for waves, wgs, depth, nt in [(8, 1, 2, 0), (8, 1, 4, 0), (8, 1, 8, 0), (8, 1, 16, 0), (16, 1, 4, 0), (16, 1, 8, 0),
+                                  (8, 2, 4, 0), (8, 2, 8, 0), (4, 2, 8, 0), (4, 2, 16, 0), (4, 4, 4, 0), (4, 4, 8, 0),
+                                  (4, 8, 4, 0), (4, 8, 2, 0), (8, 1, 4, 1), (8, 1, 8, 1), (8, 1, 16, 1), (4, 8, 4, 1)]:
+        us = timed(lambda i: B.msgemm_calib_stream_read_shape(bufs[i % n_copies], nbytes, sink, waves, wgs, depth, nt))
+        rows.append({"waves_per_workgroup": waves, "workgroups_per_cu": wgs, "loads_in_flight": depth,
+                     "non_temporal": nt, "us": round(us, 3), "GB/s": round(nbytes / (us * 1e-6) / 1e9, 1)})
+    hot = timed(lambda i: B.msgemm_calib_stream_read_shape(bufs[0], nbytes, sink, 8, 1, 8, 0))
+    empty = timed(lambda i: B.msgemm_calib_lds_read(4, 8, sink))  # a launch that touches no memory at all
+    return {"bytes": nbytes, "rows": rows, "hot_same_buffer_us": round(hot, 3), "launch_without_memory_us": round(empty, 3)}
+
+
 def lds_read_ceiling(B, torch, stream, width=16, reads=4096, launches=20):
     """Measured LDS read bandwidth of the device: conflict-free `width`-byte reads by 16 wavefronts on
     every compute unit (msgemm_calib_lds_read), HIP events on the launch stream."""
@@ -193,6 +232,8 @@ def main() -> int:
     ap.add_argument("--lib", default=None,
                     help="time another build of the library (a measurement build made with "
                          "`python -m paper_2310_06178_amd.build -D... --out PATH`); implies --no-cpu when it computes nothing")
+    ap.add_argument("--ceiling-sweep", action="store_true",
+                    help="also time the read-only yardstick over launch shapes, loads in flight and cache policy")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 64 MiB elementwise copy (untimed): gives hardware-counter runs a kernel of known traffic")
     args = ap.parse_args()
@@ -354,6 +395,8 @@ def main() -> int:
             out["roofline"]["stream_read_kernel"] = stream_read_ceiling(B, torch, stream, code_bytes, n_copies, args.steps)
         except Exception as e:  # a device with another CU count: the figure is optional
             print(f"bench.py: stream-read ceiling not measured ({e})", file=sys.stderr)
+    if args.ceiling_sweep and graph is not None:
+        out["roofline"]["stream_read_sweep"] = stream_read_sweep(B, torch, stream, code_bytes, n_copies, min(args.steps, 400))
     if not args.no_cpu:
         out["parity_spot_check"] = spot
         out["cpu_baseline"] = cpu_baseline(cfg, codes, X, scales)

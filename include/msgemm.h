@@ -294,6 +294,18 @@ int msgemm_dequant_mfma_run(const msgemm_plan_t* plan, const void* X, int64_t ld
 int msgemm_calib_stream_read(const void* src, size_t bytes, void* sink, void* stream);
 
 /*
+ * The same read with its launch shape as parameters, for the sweep that shows
+ * what a launch that only reads can reach on this device: `workgroups_per_cu`
+ * (1..16) workgroups per compute unit of `waves_per_workgroup` (1..16)
+ * wavefronts, `depth` (1, 2, 4, 8 or 16) 16-byte loads per lane in flight per
+ * wavefront, `non_temporal` != 0 marks the loads as streaming.  bytes: below
+ * 2 GiB and such that every wavefront gets a multiple of `depth` loads of 1 KiB
+ * (else MSGEMM_ERR_INVALID_ARG).
+ */
+int msgemm_calib_stream_read_shape(const void* src, size_t bytes, void* sink, int waves_per_workgroup,
+                                   int workgroups_per_cu, int depth, int non_temporal, void* stream);
+
+/*
  * Measurement aid, not msGeMM: one workgroup of 16 wavefronts per compute unit
  * reads LDS and nothing else -- every lane `reads` times (a multiple of 8, at
  * most 2^20) `width_bytes` (4, 8 or 16) bytes, consecutive lanes consecutive

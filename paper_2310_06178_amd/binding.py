@@ -21,7 +21,7 @@ OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED, ERR_INCOMPLETE = 0, -1
 
 EXPORTS = (
     "msgemm_plan", "msgemm_plan_with_options", "msgemm_plan_codes8", "msgemm_plan_set_codebook", "msgemm_plan_get_info", "msgemm_lut_bytes", "msgemm_build_lut",
-    "msgemm_consume_lut", "msgemm_run", "msgemm_run_static", "msgemm_plan_check", "msgemm_dequant_mfma_run", "msgemm_calib_stream_read", "msgemm_calib_lds_read", "msgemm_destroy",
+    "msgemm_consume_lut", "msgemm_run", "msgemm_run_static", "msgemm_plan_check", "msgemm_dequant_mfma_run", "msgemm_calib_stream_read", "msgemm_calib_stream_read_shape", "msgemm_calib_lds_read", "msgemm_destroy",
     "msgemm_status_string", "msgemm_last_hip_error", "msgemm_version",
 )
 
@@ -117,6 +117,8 @@ def load():
     lib.msgemm_dequant_mfma_run.restype = ci
     lib.msgemm_calib_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     lib.msgemm_calib_stream_read.restype = ci
+    lib.msgemm_calib_stream_read_shape.argtypes = [vp, ctypes.c_size_t, vp, ci, ci, ci, ci, vp]
+    lib.msgemm_calib_stream_read_shape.restype = ci
     lib.msgemm_calib_lds_read.argtypes = [ci, ci, vp, ctypes.POINTER(ctypes.c_size_t), vp]
     lib.msgemm_calib_lds_read.restype = ci
     lib.msgemm_destroy.argtypes = [vp]
@@ -282,6 +284,15 @@ def msgemm_calib_stream_read(src, nbytes, sink, stream=None):
     rc = load().msgemm_calib_stream_read(_ptr(src), int(nbytes), _ptr(sink), _stream(stream))
     if rc != OK:
         raise MsgemmError(rc, "msgemm_calib_stream_read")
+
+
+def msgemm_calib_stream_read_shape(src, nbytes, sink, waves_per_workgroup, workgroups_per_cu, depth, non_temporal,
+                                   stream=None, check=True):
+    rc = load().msgemm_calib_stream_read_shape(_ptr(src), int(nbytes), _ptr(sink), int(waves_per_workgroup),
+                                               int(workgroups_per_cu), int(depth), int(non_temporal), _stream(stream))
+    if check and rc != OK:
+        raise MsgemmError(rc, "msgemm_calib_stream_read_shape")
+    return rc
 
 
 def msgemm_plan_set_codebook(plan, values16, check: bool = True):

@@ -45,6 +45,39 @@ stream_read_kernel(const uint4* __restrict__ src, uint32_t* sink, int64_t waves_
     if (acc == 0x12345678u) *sink = acc;
 }
 
+// The same read with the launch shape, the loads in flight and the cache policy as parameters: the sweep behind
+// the statement of what one launch that only reads can reach.  kDepth loads of 16 bytes per lane in flight per
+// wavefront; kNonTemporal marks the loads as streaming (they are not kept in the caches).
+template <int kDepth, bool kNonTemporal>
+__global__ void __launch_bounds__(1024)
+stream_read_shape_kernel(const void* src, uint32_t bytes, uint32_t* sink, int waves_total, int loads)
+{
+    const int lane = threadIdx.x & 63;
+    const int w = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)src, 0, (int)bytes, 0x00020000);
+    constexpr int kAux = kNonTemporal ? 2 : 0;
+    const uint32_t stride = (uint32_t)waves_total * 1024u;   // load t of all wavefronts is contiguous
+    const uint32_t base = (uint32_t)w * 1024u + (uint32_t)lane * 16u;
+    typedef unsigned v4 __attribute__((ext_vector_type(4)));
+    v4 v[kDepth];
+    uint32_t acc = 0;
+#pragma unroll
+    for (int t = 0; t < kDepth; ++t) v[t] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(base + (uint32_t)t * stride), 0, kAux);
+    for (int t0 = 0; t0 < loads; t0 += kDepth) {   // (loads is a multiple of kDepth)
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) {
+            const v4 x = v[u];
+            acc += x.x ^ x.y ^ x.z ^ x.w;
+            asm volatile("" : "+v"(acc));
+            // past the end the offset is out of the buffer's range: no memory access
+            v[u] = __builtin_amdgcn_raw_buffer_load_b128(
+                rsrc, t0 + u + kDepth < loads ? (int)(base + (uint32_t)(t0 + u + kDepth) * stride) : 0x7ffffff0, 0, kAux);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    if (acc == 0x12345678u) *sink = acc;
+}
+
 // Conflict-free LDS reads and nothing else: every lane reads `reads` times W bytes, consecutive lanes
 // consecutive W-byte slots (so the lanes served together cover all banks), eight reads in flight.
 constexpr int kLdsCalibWaves = 16;
@@ -102,6 +135,37 @@ int launch_calib_lds_read(int width_bytes, int reads, void* sink, size_t* bytes_
     MSGEMM_HIP_TRY(hipGetLastError());
     if (bytes_out) *bytes_out = (size_t)cus * kLdsCalibWaves * 64 * (size_t)reads * (size_t)width_bytes;
     return MSGEMM_OK;
+}
+
+int launch_calib_stream_read_shape(const void* src, size_t bytes, void* sink, int waves_per_workgroup,
+                                   int workgroups_per_cu, int depth, int non_temporal, hipStream_t s)
+{
+    int cus = 256, dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+        prop.multiProcessorCount > 0)
+        cus = prop.multiProcessorCount;
+    if (waves_per_workgroup < 1 || waves_per_workgroup > 16 || workgroups_per_cu < 1 || workgroups_per_cu > 16)
+        return MSGEMM_ERR_INVALID_ARG;
+    const int64_t waves = (int64_t)cus * workgroups_per_cu * waves_per_workgroup;
+    if (bytes == 0 || bytes >= ((size_t)1 << 31) || bytes % ((size_t)waves * 1024) != 0) return MSGEMM_ERR_INVALID_ARG;
+    const int64_t loads = (int64_t)(bytes / ((size_t)waves * 1024));
+    if (loads % depth != 0) return MSGEMM_ERR_INVALID_ARG;
+    const dim3 grid((unsigned)(cus * workgroups_per_cu)), blk((unsigned)(waves_per_workgroup * 64));
+#define MSGEMM_SHAPE(D)                                                                                              \
+    if (depth == D) {                                                                                                \
+        if (non_temporal)                                                                                            \
+            hipLaunchKernelGGL((stream_read_shape_kernel<D, true>), grid, blk, 0, s, src, (uint32_t)bytes,           \
+                               (uint32_t*)sink, (int)waves, (int)loads);                                             \
+        else                                                                                                         \
+            hipLaunchKernelGGL((stream_read_shape_kernel<D, false>), grid, blk, 0, s, src, (uint32_t)bytes,          \
+                               (uint32_t*)sink, (int)waves, (int)loads);                                             \
+        MSGEMM_HIP_TRY(hipGetLastError());                                                                           \
+        return MSGEMM_OK;                                                                                            \
+    }
+    MSGEMM_SHAPE(1) MSGEMM_SHAPE(2) MSGEMM_SHAPE(4) MSGEMM_SHAPE(8) MSGEMM_SHAPE(16)
+#undef MSGEMM_SHAPE
+    return MSGEMM_ERR_INVALID_ARG;
 }
 
 int launch_calib_stream_read(const void* src, size_t bytes, void* sink, hipStream_t s)

@@ -62,6 +62,39 @@ template <typename AT> __device__ __forceinline__ AT fold16(AT a, AT b)
     return x + y;
 }
 
+// A load from the code stream.  Every code byte is used once per column pass, so the loads are marked as
+// streaming (non-temporal: the bytes are not kept in the caches); on the 32 MiB GEMV that alone is worth a tenth
+// of the launch.  MSGEMM_STREAM_NT=0 builds with plain loads for comparison.
+#ifndef MSGEMM_STREAM_NT
+#define MSGEMM_STREAM_NT 1
+#endif
+__device__ __forceinline__ uint4 load_codes(const uint4* p)
+{
+#if MSGEMM_STREAM_NT
+    const v4u v = __builtin_nontemporal_load((const v4u*)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+#else
+    return *p;
+#endif
+}
+__device__ __forceinline__ uint2 load_codes(const uint2* p)
+{
+#if MSGEMM_STREAM_NT
+    const v2u v = __builtin_nontemporal_load((const v2u*)p);
+    return make_uint2(v.x, v.y);
+#else
+    return *p;
+#endif
+}
+__device__ __forceinline__ uint32_t load_codes(const uint32_t* p)
+{
+#if MSGEMM_STREAM_NT
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+
 // The partial sums of one output come from workgroups that may sit on different
 // XCDs, whose L2 slices are not coherent with each other.  When they are reduced
 // inside the launch, partials and flags are therefore only touched with

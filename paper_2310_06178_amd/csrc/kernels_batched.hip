@@ -228,7 +228,7 @@ batched_kernel(BatchedArgs a)
     if (active) {
 #pragma unroll
         for (int u = 0; u < kBRing; ++u) {
-            ring[u] = *code_at(kt_begin, u);
+            ring[u] = load_codes(code_at(kt_begin, u));
             __builtin_amdgcn_sched_barrier(0);  // loads return in issue order: keep slot 0 first
         }
     }
@@ -282,8 +282,8 @@ batched_kernel(BatchedArgs a)
                     dhi[s] = __builtin_amdgcn_mfma_f32_4x4x4f16(up, onehot, dhi[s], 0, 0, 0);
                 }
                 // the slot's bytes are now addresses: refill it with the load kBRing ahead
-                ring[t % kBRing] = (t + kBRing < kLoadsPerPanel) ? *code_at(kt, t + kBRing)
-                                                                   : *code_at(kt_next, t + kBRing - kLoadsPerPanel);
+                ring[t % kBRing] = load_codes((t + kBRing < kLoadsPerPanel) ? code_at(kt, t + kBRing)
+                                                                              : code_at(kt_next, t + kBRing - kLoadsPerPanel));
                 __builtin_amdgcn_sched_barrier(0);
             }
             if constexpr (kScaled) {
@@ -479,7 +479,7 @@ batched_pipe_kernel(BatchedArgs a)
     if (active) {
 #pragma unroll
         for (int u = 0; u < kBRing; ++u) {
-            ring[u] = *code_at(kt_begin, u);
+            ring[u] = load_codes(code_at(kt_begin, u));
             __builtin_amdgcn_sched_barrier(0);  // loads return in issue order: keep slot 0 first
         }
     }
@@ -547,8 +547,8 @@ batched_pipe_kernel(BatchedArgs a)
             };
             // once the addresses of load t are out, its ring slot takes the load kBRing ahead
             auto refill = [&](int t) {
-                ring[t % kBRing] = (t + kBRing < kLoadsPerPanel) ? *code_at(kt, t + kBRing)
-                                                                   : *code_at(kt_next, t + kBRing - kLoadsPerPanel);
+                ring[t % kBRing] = load_codes((t + kBRing < kLoadsPerPanel) ? code_at(kt, t + kBRing)
+                                                                              : code_at(kt_next, t + kBRing - kLoadsPerPanel));
             };
             if constexpr (kGather) {
 #pragma unroll

@@ -371,7 +371,7 @@ fused_kernel(FusedArgs a)
     auto fill_ring = [&](int from, int to) {
 #pragma unroll
         for (int u = from; u < to; ++u) {
-            ring[u] = first[u * step_stride];
+            ring[u] = load_codes(first + u * step_stride);
             __builtin_amdgcn_sched_barrier(0);  // loads return in issue order: keep slot 0 first
         }
     };
@@ -543,9 +543,9 @@ fused_kernel(FusedArgs a)
             }
             // the slot's bytes are now addresses: refill it with the load kRing ahead
             if (t + kRing < kLoadsPerPanel) {
-                ring[t % kRing] = cur[(t + kRing) * step_stride];
+                ring[t % kRing] = load_codes(cur + (t + kRing) * step_stride);
             } else if (more) {
-                ring[t % kRing] = cur[kWaves * 64 + (t + kRing - kLoadsPerPanel) * step_stride];
+                ring[t % kRing] = load_codes(cur + kWaves * 64 + (t + kRing - kLoadsPerPanel) * step_stride);
             }
         };
         auto consume = [&](int t, const Entry (&src)[LB]) {
@@ -770,7 +770,7 @@ fused_long_kernel(FusedArgs a)
     LoadT ring[kRing];
 #pragma unroll
     for (int u = 0; u < kRing; ++u) {
-        ring[u] = cur[u * step_stride];
+        ring[u] = load_codes(cur + u * step_stride);
         __builtin_amdgcn_sched_barrier(0);  // loads return in issue order: keep slot 0 first
     }
 
@@ -827,9 +827,9 @@ fused_long_kernel(FusedArgs a)
                     dst[s] = *(const ET*)(lds + addr);
                 }
                 if (t + kRing < kLoadsPerPanel) {
-                    ring[t % kRing] = cur[(t + kRing) * step_stride];
+                    ring[t % kRing] = load_codes(cur + (t + kRing) * step_stride);
                 } else if (more) {
-                    ring[t % kRing] = nxt[(t + kRing - kLoadsPerPanel) * step_stride];
+                    ring[t % kRing] = load_codes(nxt + (t + kRing - kLoadsPerPanel) * step_stride);
                 }
             };
             auto consume = [&](const ET (&src)[LB]) {
@@ -953,7 +953,6 @@ constexpr int kWideWaves = 8, kWideBuilders = 4, kWideTableBytes = 65536;
 #ifndef MSGEMM_WIDE_LEAVE_OUT
 #define MSGEMM_WIDE_LEAVE_OUT 0
 #endif
-
 template <typename XT, typename YT, typename ET, int kValueMode, int kTables>
 __global__ void __launch_bounds__((kWideWaves + kWideBuilders) * 64)
 fused_wide_kernel(FusedArgs a)
@@ -1107,15 +1106,16 @@ fused_wide_kernel(FusedArgs a)
             if (lane == 0) __hip_atomic_fetch_add(&built[tb], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
         if (!counts) return;
-        if (MSGEMM_WIDE_LEAVE_OUT & 1) return;
 
         // ---- the first builder wavefront turns reader: 1/slices of the row group's outputs
         launches += 1;
         const unsigned parity = launches & 1u;
         if (lane == 0) {
             __hip_atomic_store(a.epochs + blockIdx.x, launches, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // (the streaming wavefronts wait for this word before they store: nothing may come between the tables and it)
             __hip_atomic_store(&launch_parity, 2u | parity, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
+        if (MSGEMM_WIDE_LEAVE_OUT & 1) return;
         const int S = a.slices;
         const uint32_t rg_floats = (uint32_t)panels_here * kPanelRows;
         const uint32_t f0 = (uint32_t)sgm * (uint32_t)a.red_chunk;
@@ -1202,7 +1202,7 @@ fused_wide_kernel(FusedArgs a)
     LoadT ring[kRing];
 #pragma unroll
     for (int u = 0; u < kRing; ++u) {
-        ring[u] = *nxt;
+        ring[u] = load_codes(nxt);
         nxt += step_stride;
         __builtin_amdgcn_sched_barrier(0);  // loads return in issue order: keep slot 0 first
     }
@@ -1251,7 +1251,7 @@ fused_wide_kernel(FusedArgs a)
             }
             // ... its slot refilled with the load kRing ahead ...
             if constexpr (decltype(refill)::value) {
-                ring[u] = *nxt;
+                ring[u] = load_codes(nxt);
                 nxt += step_stride;
             }
             // ... while the entries of the load before it are added (the first time round: zeros)

@@ -391,6 +391,14 @@ int msgemm_calib_stream_read(const void* src, size_t bytes, void* sink, void* st
     return msgemm::launch_calib_stream_read(src, bytes, sink, (hipStream_t)stream);
 }
 
+int msgemm_calib_stream_read_shape(const void* src, size_t bytes, void* sink, int waves_per_workgroup,
+                                   int workgroups_per_cu, int depth, int non_temporal, void* stream)
+{
+    if (!src || !sink || ((uintptr_t)src & 15)) return MSGEMM_ERR_INVALID_ARG;
+    return msgemm::launch_calib_stream_read_shape(src, bytes, sink, waves_per_workgroup, workgroups_per_cu, depth,
+                                                  non_temporal, (hipStream_t)stream);
+}
+
 int msgemm_calib_lds_read(int width_bytes, int reads, void* sink, size_t* bytes_out, void* stream)
 {
     return msgemm::launch_calib_lds_read(width_bytes, reads, sink, bytes_out, (hipStream_t)stream);

@@ -113,6 +113,8 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
 
 // calibration.hip
 int launch_calib_stream_read(const void* src, size_t bytes, void* sink, hipStream_t s);
+int launch_calib_stream_read_shape(const void* src, size_t bytes, void* sink, int waves_per_workgroup,
+                                   int workgroups_per_cu, int depth, int non_temporal, hipStream_t s);
 int launch_calib_lds_read(int width_bytes, int reads, void* sink, size_t* bytes_out, hipStream_t s);
 
 // kernels_mfma.hip

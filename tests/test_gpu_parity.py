@@ -974,6 +974,23 @@ def test_calibration_stream_read_entry_point():
         B.msgemm_calib_stream_read(buf.data_ptr() + 4, unit, sink)
 
 
+def test_calibration_stream_read_shape_entry_point():
+    """The yardstick with its launch shape as parameters: whole loads per wavefront only, sink left alone."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    nbytes = cus * 16 * 1024 * 8            # 16 wavefronts per compute unit, 8 loads of 1 KiB each
+    buf = torch.zeros(nbytes, dtype=torch.uint8, device="cuda:0")
+    sink = torch.full((4,), 7, dtype=torch.int32, device="cuda:0")
+    for waves, wgs, depth, nt in ((8, 2, 4, 0), (16, 1, 8, 1), (4, 4, 2, 0), (8, 1, 16, 0), (4, 1, 1, 1)):
+        B.msgemm_calib_stream_read_shape(buf, nbytes, sink, waves, wgs, depth, nt)
+    torch.cuda.synchronize()
+    assert sink.cpu().tolist() == [7, 7, 7, 7]
+    bad = [(0, 1, 4), (17, 1, 4), (8, 0, 4), (8, 17, 4), (8, 2, 3), (8, 2, 16), (12, 1, 4)]  # (8, 2, 16): 8 loads, depth 16
+    for waves, wgs, depth in bad:
+        assert B.msgemm_calib_stream_read_shape(buf, nbytes, sink, waves, wgs, depth, 0, check=False) == B.ERR_INVALID_ARG
+    assert B.msgemm_calib_stream_read_shape(buf, nbytes - 1024, sink, 8, 2, 4, 0, check=False) == B.ERR_INVALID_ARG
+    assert B.msgemm_calib_stream_read_shape(None, nbytes, sink, 8, 2, 4, 0, check=False) == B.ERR_INVALID_ARG
+
+
 # ---------------------------------------------------------------------------
 # other 16-value encodings of the codes (only b(.) changes)
 
