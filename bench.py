@@ -224,6 +224,8 @@ def main() -> int:
     ap.add_argument("--hot", action="store_true", help="one weight copy (cache-resident), labelled as such")
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--d", type=int, default=None)
+    ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
+                    help="a field of msgemm_plan_options_t (a particular kernel form), e.g. batched_segments=16")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle legs (cpu_baseline and the parity spot check)")
     ap.add_argument("--mfma", action="store_true",
                     help="time the dequantise + MFMA comparison kernel instead of the msGeMM path (labelled as such)")
@@ -264,6 +266,7 @@ def main() -> int:
     n_copies = 1 if args.hot else (1 << 30) // code_bytes + 2
     n_copies = max(1, min(n_copies, 64))
 
+    plan_options = {n: int(v) for n, v in (o.split("=", 1) for o in args.option)} or None
     dX = torch_io.to_device(X, cfg["x"])
     dS = torch_io.to_device(scales, "scales")
     plans = []
@@ -272,7 +275,8 @@ def main() -> int:
         # independent weight bytes per copy (copy 0 is the seeded config itself)
         ci = codes if i == 0 else rng.integers(0, 256, size=codes.shape, dtype=np.uint8)
         dC = torch_io.to_device(ci, "codes")
-        plans.append(B.msgemm_plan(m, k, b, cfg["x"], cfg["y"], d, cfg["scale_group"], dC, dS, args.variant))
+        plans.append(B.msgemm_plan(m, k, b, cfg["x"], cfg["y"], d, cfg["scale_group"], dC, dS, args.variant,
+                                   options=plan_options))
         torch.cuda.synchronize()
         del dC
     info = B.msgemm_plan_get_info(plans[0])
@@ -362,6 +366,7 @@ def main() -> int:
             "weight_copies_rotated": n_copies,
             "cache_state": "hot (single weight copy)" if args.hot else "cold (rotating copies > 1 GiB)",
             "launch": mode,
+            "plan_options": plan_options,
             "paper_op_ratio": m * k / (16 ** info["d"] * k + (k / info["d"] - 1) * m),
         },
         "roofline": {

@@ -62,7 +62,8 @@ typedef enum {
     MSGEMM_ERR_ALLOC = -2,       /* host or device allocation failed */
     MSGEMM_ERR_HIP = -3,         /* a HIP call failed; see msgemm_last_hip_error */
     MSGEMM_ERR_UNSUPPORTED = -4, /* valid request that the chosen variant cannot serve */
-    MSGEMM_ERR_INCOMPLETE = -5   /* msgemm_plan_check: a reduction inside a launch gave up waiting */
+    MSGEMM_ERR_INCOMPLETE = -5,  /* msgemm_plan_check: a reduction inside a launch gave up waiting */
+    MSGEMM_ERR_RANGE = -6        /* msgemm_plan_check: an activation too large for 16-bit table entries was seen */
 } msgemm_status_t;
 
 /* How phase 1 and phase 2 are scheduled on the GPU. */
@@ -82,9 +83,14 @@ typedef enum {
     /* Same schedule with fp16 table entries, 8 batch columns per entry.  For
      * int8 X the entries are integers of magnitude <= 2048, exact in fp16, and
      * the sums are kept exact (result bit-exact); for fp16 / bf16 X each entry
-     * is rounded to fp16, which needs |16 x| inside the fp16 range; accumulation
-     * is fp32.  scale_group % 32 == 0.  Not available for fp32 X.  AUTO picks
-     * it for b > 2. */
+     * is rounded to fp16, which needs 2 max|value(code)| |x| (16 |x| for the
+     * paper's int4) inside the fp16 range.  A larger activation is detected by
+     * the kernel: the outputs may then hold infinities, and msgemm_plan_check
+     * returns MSGEMM_ERR_RANGE; such callers ask for FUSED_LDS.  Value maps
+     * (msgemm_plan_set_codebook, msgemm_plan_codes8) with a value beyond +-65504
+     * are refused on such a plan; values that fp16 cannot hold exactly are rounded
+     * to nearest.  Accumulation is fp32.  scale_group % 32 == 0.  Not available
+     * for fp32 X.  AUTO picks it for b > 2. */
     MSGEMM_VARIANT_FUSED_LDS16 = 3,
     /* GLOBAL_LUT with half of every table (the optimisation sketched in Section
      * 4.1): only the combinations whose last code has its top bit clear are
@@ -268,7 +274,10 @@ int msgemm_run_static(const msgemm_plan_t* plan, const void* X, int64_t ldx,
  * the flags, so that the plan works again, and returns MSGEMM_ERR_INCOMPLETE:
  * the outputs of the msgemm_run calls on this plan since the last check are not
  * valid.  With the default poll bound (about a second of polling) a give-up
- * means that the producing workgroups never ran.  Synchronises the stream.
+ * means that the producing workgroups never ran.  The same word records that
+ * a kernel with 16-bit table entries met an activation too large for them
+ * (see MSGEMM_VARIANT_FUSED_LDS16): then, and if no reduction gave up, the word
+ * is cleared and MSGEMM_ERR_RANGE is returned.  Synchronises the stream.
  */
 int msgemm_plan_check(const msgemm_plan_t* plan, void* stream);
 

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libmsgemm.so")
 F32, F16, BF16, I8, I32 = 0, 1, 2, 3, 4
 DTYPES = {"f32": F32, "f16": F16, "bf16": BF16, "i8": I8, "i32": I32}
 VARIANT_AUTO, VARIANT_GLOBAL_LUT, VARIANT_FUSED_LDS, VARIANT_FUSED_LDS16, VARIANT_GLOBAL_LUT_HALF = 0, 1, 2, 3, 4
-OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED, ERR_INCOMPLETE = 0, -1, -2, -3, -4, -5
+OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED, ERR_INCOMPLETE, ERR_RANGE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = (
     "msgemm_plan", "msgemm_plan_with_options", "msgemm_plan_codes8", "msgemm_plan_set_codebook", "msgemm_plan_get_info", "msgemm_lut_bytes", "msgemm_build_lut",

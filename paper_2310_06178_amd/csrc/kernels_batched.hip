@@ -91,12 +91,27 @@ struct BatchedArgs {
     int direct;              // 1: a single segment, the kernel writes Y itself
     int64_t partial_span;    // bytes of the partial buffer (< 2^31)
     FastDiv div_col_passes, div_segments, div_tiles_per_block;
+    float x_limit;           // floating-point activations beyond this magnitude can take a table entry out of the fp16 range
+    unsigned* error;         // the plan's sticky error word (bit 1: such an activation was seen), or nullptr
 };
 
 template <typename XT> __device__ __forceinline__ _Float16 to_half(XT v);
 template <> __device__ __forceinline__ _Float16 to_half<__half>(__half v) { return (_Float16)__half2float(v); }
 template <> __device__ __forceinline__ _Float16 to_half<bf16_t>(bf16_t v) { return (_Float16)XTraits<bf16_t>::load(&v); }
 template <> __device__ __forceinline__ _Float16 to_half<int8_t>(int8_t v) { return (_Float16)(float)v; }
+
+// 16-bit table entries hold value(c0) x0 + value(c1) x1 in fp16: an activation larger than x_limit (65504 over twice
+// the largest value of a code; int8 activations never are) can push an entry to infinity.  The result then holds
+// infinities or NaN where a full-width table would not; the kernel cannot fail the call, so it raises bit 1 of the
+// plan's error word (msgemm_plan_check reports MSGEMM_ERR_RANGE).  One comparison per staged activation.
+template <typename XT>
+__device__ __forceinline__ void flag_range(const BatchedArgs& a, bool live, XT raw)
+{
+    if constexpr (!__is_same(XT, int8_t)) {
+        const float x = fabsf(XTraits<XT>::load(&raw));
+        if (live && !(x <= a.x_limit) && a.error) __hip_atomic_fetch_or(a.error, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
 
 // all of this wavefront's LDS traffic has landed / returned, then the workgroup meets.
 // (Not __syncthreads(): its fence would also wait for the code loads in flight.)
@@ -162,6 +177,7 @@ batched_kernel(BatchedArgs a)
         const int64_t kk = (int64_t)kt * (2 * kBG) + xkc;
         const bool live = (col0 + xc < a.b) && (kk < a.k);
         if (tid < 2 * kBG * kBC) xs[buf][xkc][xc] = live ? to_half<XT>(raw) : (_Float16)0.0f;
+        flag_range<XT>(a, live, raw);
     };
 
     // ---- phase 1: L(c0 | c1 << 4, g, c) = b(c0) X(2g, c) + b(c1) X(2g + 1, c), in packed fp16
@@ -432,6 +448,7 @@ batched_pipe_kernel(BatchedArgs a)
         const int64_t kk = (int64_t)kt * (2 * kPG) + xkc;
         const bool live = (col0 + xc < a.b) && (kk < a.k);
         if (tid < 2 * kPG * kBC) xs[buf][xkc][xc] = live ? to_half<XT>(raw) : (_Float16)0.0f;
+        flag_range<XT>(a, live, raw);
     };
 
     // ---- phase 1: thread (g, c1, part) writes the entries c0 = kPEach part .. kPEach part + kPEach - 1 of its (g, c1):
@@ -829,6 +846,14 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
     a.values256 = p.values256;
     a.scales = (const __half*)p.scales_ordered;
     a.partials = p.partials;
+    a.error = p.error_word;
+    {
+        // the largest entry is value(c0) x0 + value(c1) x1 (one product for 8-bit weights)
+        float vmax = 0.0f;
+        for (int i = 0; i < 16; ++i) vmax = fmaxf(vmax, fabsf(p.values[i]));
+        if (p.codes8) vmax = 0.5f * p.values256_max;
+        a.x_limit = vmax > 0.0f ? 65504.0f / (2.0f * vmax) : 3.0e38f;
+    }
     a.m = p.m; a.k = p.k; a.b = p.b; a.m_pad = p.m_pad;
     a.b_pad = (int64_t)p.col_passes * kBC;
     a.ktiles = (int)p.ktiles;

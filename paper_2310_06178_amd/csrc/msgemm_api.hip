@@ -1,5 +1,6 @@
 // The C ABI of libmsgemm.so: argument checking, plan ownership, dispatch.
 // See include/msgemm.h for the contract of every entry point.
+#include <math.h>
 #include <new>
 
 #include "msgemm_internal.h"
@@ -121,6 +122,10 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
         if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
         e = hipMemcpy(p->values256, values256, 256 * sizeof(float), hipMemcpyHostToDevice);
         if (e != hipSuccess) return hip_fail(e);
+        p->values256_max = 0.0f;
+        for (int i = 0; i < 256; ++i) p->values256_max = fmaxf(p->values256_max, fabsf(values256[i]));
+        // 16-bit tables hold values256[code] * x in fp16: the values themselves must be inside its range
+        if (p->variant == MSGEMM_VARIANT_FUSED_LDS16 && p->values256_max > 65504.0f) return fail(MSGEMM_ERR_UNSUPPORTED);
     }
 
     // the value of each 4-bit pattern: b(.) of Section 3.1 until the caller installs another map
@@ -246,6 +251,10 @@ int msgemm_plan_set_codebook(msgemm_plan_t* plan, const float* values16)
             if (v[i] + v[15 - i] != c) return MSGEMM_ERR_UNSUPPORTED;
         p.half_c = c;
     }
+    // 16-bit tables keep the values in fp16 (rounded to nearest): outside its range they cannot be held at all
+    if (p.variant == MSGEMM_VARIANT_FUSED_LDS16)
+        for (int i = 0; i < 16; ++i)
+            if (v[i] > 65504.0f || v[i] < -65504.0f) return MSGEMM_ERR_UNSUPPORTED;
     for (int i = 0; i < 16; ++i) p.values[i] = v[i];  // travels in the arguments of every later launch
     p.custom_values = values16 != nullptr;
     return MSGEMM_OK;
@@ -365,6 +374,12 @@ int msgemm_plan_check(const msgemm_plan_t* plan, void* stream)
     MSGEMM_HIP_TRY(hipMemcpyAsync(&err, p.error_word, sizeof(err), hipMemcpyDeviceToHost, s));
     MSGEMM_HIP_TRY(hipStreamSynchronize(s));
     if (!err) return MSGEMM_OK;
+    if (!(err & 1u)) {
+        // only the range bit: an activation was too large for the 16-bit tables; nothing else is out of order
+        MSGEMM_HIP_TRY(hipMemsetAsync(p.error_word, 0, sizeof(unsigned), s));
+        MSGEMM_HIP_TRY(hipStreamSynchronize(s));
+        return MSGEMM_ERR_RANGE;
+    }
     // a reducer gave up: flags may be left up, outputs of that call are not the result.  Clear, so that the plan works again.
     MSGEMM_HIP_TRY(hipMemsetAsync(p.flags, 0, (p.flag_words + 1) * sizeof(unsigned), s));
     if (p.wide_tables > 0) {  // partial sums of the failed launch may be missing: parities and launch counts start over
@@ -419,6 +434,7 @@ const char* msgemm_status_string(int status)
     case MSGEMM_ERR_ALLOC: return "allocation failed";
     case MSGEMM_ERR_HIP: return "HIP runtime error";
     case MSGEMM_ERR_UNSUPPORTED: return "not supported by the requested variant";
+    case MSGEMM_ERR_RANGE: return "an activation was too large for 16-bit table entries; the outputs of the calls since the last check may hold infinities (use MSGEMM_VARIANT_FUSED_LDS)";
     case MSGEMM_ERR_INCOMPLETE: return "a reduction inside a launch gave up waiting for partial sums; the outputs of the calls since the last check are not valid";
     default: return "unknown status";
     }

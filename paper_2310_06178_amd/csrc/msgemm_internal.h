@@ -39,6 +39,7 @@ struct Plan {
     bool custom_values;   // another encoding has been installed with msgemm_plan_set_codebook
     bool codes8;          // 8-bit weights: k counts two per code byte internally, a table group is one real column
     float* values256;     // device, 256 floats: the value of each 8-bit pattern (codes8 plans), else nullptr
+    float values256_max;  // largest magnitude among them
     uint8_t* codes;       // device, [m][k/2], plan-owned copy
     uint16_t* scales;     // device fp16 [m][nblocks] or nullptr
     float* lut_ws;        // device workspace for the two-launch variant

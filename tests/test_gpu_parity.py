@@ -807,6 +807,67 @@ def test_power_of_two_block_scales_are_exact(m, k, b, variant):
         assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("pipelined", [0, 1])
+@pytest.mark.parametrize("xd", ["f16", "bf16"])
+def test_16_bit_tables_report_activations_out_of_their_range(xd, pipelined):
+    """A table entry of the batched kernels is b(c0) x0 + b(c1) x1 in fp16: |x| beyond 65504 / 16 = 4094 can push it
+    to infinity.  The library's own choice for a batch has such tables; it must say so (msgemm_plan_check), and the
+    variant with full-width entries must give the right answer on the same inputs."""
+    m, k, b = 600, 512, 8
+    codes = inputs.make_codes(m, k, seed=1)
+    X = inputs.make_x(k, b, "f32", seed=2)
+    X[3, 100] = 30000.0          # times -8 and more: beyond fp16
+    X[5, 7] = -5000.0
+    Xh = X.astype(np.float16) if xd == "f16" else inputs.f32_to_bf16_bits(X)
+    dC, dX = torch_io.to_device(codes, "codes"), torch_io.to_device(Xh, xd)
+    Y = torch_io.empty_output(b, m, xd)
+    plan = B.msgemm_plan(m, k, b, xd, xd, 2, 0, dC, None, B.VARIANT_AUTO, options={"batched_form": 1 + pipelined})
+    try:
+        assert B.msgemm_plan_get_info(plan)["variant"] == B.VARIANT_FUSED_LDS16
+        B.msgemm_run(plan, dX, k, Y, m)
+        assert B.msgemm_plan_check(plan) == B.ERR_RANGE
+        assert B.msgemm_plan_check(plan) == B.OK        # reported once
+        # the same plan with activations inside the range is clean again
+        Xok = np.clip(X, -4000.0, 4000.0)
+        Xokh = Xok.astype(np.float16) if xd == "f16" else inputs.f32_to_bf16_bits(Xok)
+        B.msgemm_run(plan, torch_io.to_device(Xokh, xd), k, Y, m)
+        assert B.msgemm_plan_check(plan) == B.OK
+        check(torch_io.to_host(Y), oracle_y(codes, Xokh, xd, None, 0), xd, "activations at the edge of the range",
+              elem_bound(codes, Xokh, xd, None, 0, table16=True))
+    finally:
+        B.msgemm_destroy(plan)
+    # full-width entries take the large activations (fp16 outputs of this size would overflow: bf16 only)
+    if xd == "bf16":
+        out, info = run_gpu(codes, Xh, xd, None, 0, 2, B.VARIANT_FUSED_LDS)
+        assert info["variant"] == B.VARIANT_FUSED_LDS
+        check(out, oracle_y(codes, Xh, xd, None, 0), xd, "full-width tables", elem_bound(codes, Xh, xd, None, 0))
+
+
+def test_16_bit_tables_refuse_value_maps_out_of_their_range():
+    dC = torch.zeros(128 * 64, dtype=torch.uint8, device="cuda:0")
+    plan = B.msgemm_plan(128, 128, 8, "f16", "f16", 2, 0, dC, None, B.VARIANT_FUSED_LDS16)
+    try:
+        big = list(UINT4)
+        big[9] = 1.0e5
+        assert B.msgemm_plan_set_codebook(plan, big, check=False) == B.ERR_UNSUPPORTED
+        assert B.msgemm_plan_set_codebook(plan, UINT4, check=False) == B.OK
+    finally:
+        B.msgemm_destroy(plan)
+    plan = B.msgemm_plan(128, 128, 8, "f32", "f32", 2, 0, dC, None, B.VARIANT_FUSED_LDS)
+    try:
+        big = list(UINT4)
+        big[9] = 1.0e5
+        assert B.msgemm_plan_set_codebook(plan, big, check=False) == B.OK   # full-width entries hold it
+    finally:
+        B.msgemm_destroy(plan)
+    v = e4m3_finite() * 1000.0    # up to 448000: beyond fp16
+    dC8 = torch.zeros(128 * 128, dtype=torch.uint8, device="cuda:0")
+    assert B.msgemm_plan_codes8(128, 128, 8, "f16", "f16", 0, dC8, None, v, check=False)[0] == B.ERR_UNSUPPORTED
+    rc, plan = B.msgemm_plan_codes8(128, 128, 1, "f16", "f16", 0, dC8, None, v, check=False)  # one column: full-width tables
+    assert rc == B.OK
+    B.msgemm_destroy(plan)
+
+
 # ---------------------------------------------------------------------------
 # 8-bit weights with a 256-entry value map (Section 2: an 8-bit floating-point
 # weight matrix is another datatype the method applies to)
