@@ -78,7 +78,12 @@ typedef enum {
      * workgroups of the same launch (b <= 2) or by a small second kernel.
      * Table entries are fp32 (int32 for int8 X).  A scale block must be a whole
      * number of k-tiles: scale_group % 128 == 0, or % 64 == 0 for fp32 X with
-     * b > 2; otherwise MSGEMM_ERR_UNSUPPORTED, and AUTO takes GLOBAL_LUT. */
+     * b > 2; otherwise MSGEMM_ERR_UNSUPPORTED, and AUTO takes GLOBAL_LUT.
+     * With d = 3 (on request only, never by AUTO; b <= 2, no scales, the paper's
+     * encoding): tables of 16 KiB per group, 8 groups = 24 columns per k-tile --
+     * the depth the paper's operation count prefers (Section 5), kept as the
+     * measured point beside d = 2; option half_tables_in_lds stores half of each
+     * table (Section 4.1) and holds 16 groups per k-tile. */
     MSGEMM_VARIANT_FUSED_LDS = 2,
     /* Same schedule with fp16 table entries, 8 batch columns per entry.  For
      * int8 X the entries are integers of magnitude <= 2048, exact in fp16, and
@@ -142,6 +147,8 @@ typedef struct {
     int global_chunk_kib;        /* two-launch variant: table KiB per chunk; 0 = 1024 */
     int global_segments;         /* two-launch variant: runs of chunks; 0 = library's choice */
     int build_on_matrix_cores;   /* msgemm_build_lut: 0 = from 16 columns on, 1 = never, 2 = always */
+    int half_tables_in_lds;      /* FUSED_LDS at d = 3: keep only the half of each table whose last code has its top
+                                    bit clear (Section 4.1): 16 instead of 8 groups per k-tile */
     int poll_limit;              /* in-launch reductions: polls before a waiting wavefront gives up; 0 = 2^22 */
     int skip_publish;            /* test aid: producers never announce their partial sums, so every waiting
                                     wavefront gives up after poll_limit polls (see msgemm_plan_check) */

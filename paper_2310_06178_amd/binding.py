@@ -57,7 +57,8 @@ class PlanOptions(ctypes.Structure):
         ("reduce_mode", ctypes.c_int), ("rows_per_lane", ctypes.c_int), ("no_xcd_map", ctypes.c_int),
         ("batched_form", ctypes.c_int), ("batched_segments", ctypes.c_int),
         ("global_plain_consumer", ctypes.c_int), ("global_chunk_kib", ctypes.c_int), ("global_segments", ctypes.c_int),
-        ("build_on_matrix_cores", ctypes.c_int), ("poll_limit", ctypes.c_int), ("skip_publish", ctypes.c_int),
+        ("build_on_matrix_cores", ctypes.c_int), ("half_tables_in_lds", ctypes.c_int), ("poll_limit", ctypes.c_int),
+        ("skip_publish", ctypes.c_int),
     ]
 
 

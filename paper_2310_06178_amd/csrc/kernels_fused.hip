@@ -1671,6 +1671,13 @@ void choose_rows_and_segments(int64_t panels, int64_t ktiles, int col_passes, in
 
 int fused_choose_shape(Plan& p, int requested_variant)
 {
+    p.d3 = false;
+    if (p.d == 3 && requested_variant == MSGEMM_VARIANT_FUSED_LDS) {
+        // depth 3 with the tables in LDS: on request only (the measured point beside d = 2; never the faster one)
+        const int rc = depth3_choose_shape(p);
+        if (rc == MSGEMM_OK) p.d3 = true;
+        return rc;
+    }
     if (p.d != 2) return MSGEMM_ERR_UNSUPPORTED;
     if (requested_variant == MSGEMM_VARIANT_FUSED_LDS16 && p.x_dtype == MSGEMM_F32) return MSGEMM_ERR_UNSUPPORTED;
     p.xcd_map_allowed = p.opt.no_xcd_map ? 0 : 1;
@@ -1844,6 +1851,7 @@ int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int
 
 int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s)
 {
+    if (p.d3) return launch_depth3(p, X, ldx, Y, ldy, s);
     if (p.fs.entry_bytes == 2) return launch_batched(p, X, ldx, Y, ldy, s);
     FusedArgs a;
     a.tiled = p.codes_tiled;

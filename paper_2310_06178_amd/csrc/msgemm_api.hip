@@ -154,6 +154,18 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
         p->workspace_bytes = p->lut_ws_bytes;
         rc = msgemm::global_plan_setup(*p, s);
         if (rc != MSGEMM_OK) return fail(rc);
+    } else if (p->d3) {
+        // depth-3 tables in LDS: the rotated code runs and one partial sum per (segment, column, row)
+        const size_t tiled = (size_t)p->ktiles * (size_t)(p->fs.groups / 8) * (size_t)p->m_pad * 12u;
+        const size_t part = (size_t)p->segments * (size_t)p->b * (size_t)p->m_pad * 4u;
+        e = hipMalloc((void**)&p->codes_tiled, tiled);
+        if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
+        e = hipMalloc((void**)&p->partials, part);
+        if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
+        p->partial_bytes = part;
+        p->workspace_bytes = tiled + part;
+        rc = msgemm::launch_repack3(*p, s);
+        if (rc != MSGEMM_OK) return fail(rc);
     } else {
         const size_t tiled = (size_t)p->ktiles * (size_t)p->m_pad * (size_t)(p->fs.groups);
         const size_t b_pad = (size_t)p->col_passes * (size_t)p->fs.cols;
@@ -238,6 +250,7 @@ int msgemm_plan_set_codebook(msgemm_plan_t* plan, const float* values16)
     if (!plan) return MSGEMM_ERR_INVALID_ARG;
     Plan& p = *reinterpret_cast<Plan*>(plan);
     if (p.codes8) return MSGEMM_ERR_UNSUPPORTED;  // its value map is given when the plan is made
+    if (p.d3 && values16) return MSGEMM_ERR_UNSUPPORTED;  // the depth-3 LDS kernel builds its tables from b(.) only
     float v[16];
     for (int i = 0; i < 16; ++i) v[i] = values16 ? values16[i] : (float)(((i ^ 8) & 15) - 8);
     for (int i = 0; i < 16; ++i)

@@ -75,6 +75,9 @@ struct Plan {
     size_t epoch_words;
     size_t flag_words;    // flags in that buffer
     unsigned* error_word; // device, flags + flag_words: set by a wavefront that gave up waiting (msgemm_plan_check)
+    bool d3;              // depth-3 tables in LDS (kernels_depth3.hip): codes_tiled holds its rotated 96-bit runs
+    bool d3_half;         // ... with half tables (Section 4.1)
+    int d3_sub;           // ... sub-panels of 64 rows per wavefront
     int wide_tables;      // single-column kernel, wide form: tables a workgroup holds (1 or 2); 0 = another form
     size_t workspace_bytes;
 };
@@ -102,6 +105,11 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
 // adds `slices` partial-sum slices ([slice][b_pad][m_pad], output order) and writes Y in the plan's output type
 int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int64_t ldy, int slices,
                               int64_t span, hipStream_t s);
+
+// kernels_depth3.hip (d = 3, tables in LDS, single column)
+int depth3_choose_shape(Plan& p);  // fills row_blocks, m_pad, ktiles, segments, fs; MSGEMM_ERR_UNSUPPORTED if not applicable
+int launch_repack3(const Plan& p, hipStream_t s);
+int launch_depth3(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s);
 
 // kernels_batched.hip (16-bit table entries, 8 batch columns per pass)
 void batched_choose_segments(Plan& p);  // needs ktiles, row_blocks, col_passes, cus; fills segments, tiles_per_segment

@@ -246,7 +246,8 @@ def test_plan_rejects_bad_arguments():
     assert rc(64, 64, 1, "f32", "f32", 4, 2, dC, dS) == B.ERR_INVALID_ARG   # group < d
     assert rc(64, 64, 1, "f32", "f32", 2, 32, dC, None) == B.ERR_INVALID_ARG  # scales missing
     assert rc(64, 64, 1, "i8", "i32", 2, 32, dC, dS) == B.ERR_INVALID_ARG   # int8 has no scales
-    assert rc(64, 64, 1, "f32", "f32", 3, 0, dC, None, B.VARIANT_FUSED_LDS) == B.ERR_UNSUPPORTED
+    assert rc(64, 64, 1, "f32", "f32", 4, 0, dC, None, B.VARIANT_FUSED_LDS) == B.ERR_UNSUPPORTED
+    assert rc(64, 64, 3, "f32", "f32", 3, 0, dC, None, B.VARIANT_FUSED_LDS) == B.ERR_UNSUPPORTED   # d = 3 in LDS: b <= 2
 
     plan = B.msgemm_plan(64, 64, 1, "f32", "f32", 2, 0, dC)
     try:
@@ -556,6 +557,61 @@ def test_in_launch_reduction_give_up_is_reported(options):
               elem_bound(codes, X, "f16", None, 0))
     finally:
         B.msgemm_destroy(plan)
+
+
+DEPTH3_CASES = [
+    # m, k, b, xd, segments (0: the library's choice)
+    (12, 4, 1, "f32", 0),          # the worked example's shape: one full group and one of a single column
+    (300, 520, 1, "f32", 0),       # 174 groups: the last of one column; ragged rows
+    (2049, 1024, 1, "f16", 0),     # four sub-panels per wavefront, two row blocks
+    (700, 4096, 2, "bf16", 5),     # config 2's k (1366 groups, short last group), two columns, five segments
+    (131, 130, 1, "i8", 0),        # integer tables
+    (600, 768, 2, "i8", 3),
+    (515, 98, 1, "f16", 1),        # a single segment: written straight to Y
+]
+
+
+@pytest.mark.parametrize("half", [0, 1])
+@pytest.mark.parametrize("m,k,b,xd,segments", DEPTH3_CASES)
+def test_depth_three_tables_in_lds(m, k, b, xd, segments, half):
+    """d = 3 with the tables in LDS (16 KiB per group, 8 groups per k-tile; with half tables, Section 4.1, 16 groups):
+    on request only.  Against the oracle, twice on one plan."""
+    codes = inputs.make_codes(m, k, seed=m + k + half)
+    dC = torch_io.to_device(codes, "codes")
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 3, 0, dC, None, B.VARIANT_FUSED_LDS,
+                         options={"half_tables_in_lds": half, "batched_segments": segments})
+    try:
+        info = B.msgemm_plan_get_info(plan)
+        assert info["variant"] == B.VARIANT_FUSED_LDS and info["d"] == 3 and info["tile_groups"] == (16 if half else 8)
+        assert info["lut_groups"] == -(-k // 3)
+        if segments:
+            assert info["split_k"] == segments
+        assert B.msgemm_plan_set_codebook(plan, UINT4, check=False) == B.ERR_UNSUPPORTED
+        for rep in range(2):
+            X = inputs.make_x(k, b, xd, seed=17 + rep)
+            dX = torch_io.to_device(X, xd)
+            Y = torch_io.empty_output(b, m, Y_OF_X[xd], ldy=m + 2)
+            Y.fill_(-3)
+            B.msgemm_run(plan, dX, k, Y, m + 2)
+            torch.cuda.synchronize()
+            out = torch_io.to_host(Y)
+            bnd = elem_bound(codes, X, xd, None, 0)
+            check(np.ascontiguousarray(out[:, :m]), oracle_y(codes, X, xd, None, 0), xd, f"d = 3 in LDS, half {half}, call {rep}",
+                  None if bnd is None else (2 * bnd if half else bnd))
+            minus3 = torch_io.to_host(torch.full((1,), -3, dtype=Y.dtype))[0]
+            assert np.all(out[:, m:] == minus3), "output padding was written"
+    finally:
+        B.msgemm_destroy(plan)
+
+
+def test_depth_three_in_lds_full_size_config2():
+    """Config 2 asks for the sweep d in {2, 3}: d = 3 with the tables in LDS at full size, every row."""
+    cfg, codes, X, _ = inputs.make_config("cfg2")
+    for half in (0, 1):
+        out, info = run_gpu(codes, X, "f16", None, 0, 3, B.VARIANT_FUSED_LDS, options={"half_tables_in_lds": half})
+        assert info["d"] == 3 and info["variant"] == B.VARIANT_FUSED_LDS
+        bnd = elem_bound(codes, X, "f16", None, 0)
+        check(out, oracle_y(codes, X, "f16", None, 0), "f16", f"cfg2 d=3 in LDS half={half}", 2 * bnd if half else bnd)
 
 
 def test_fused_repeated_calls_reuse_workspace():
