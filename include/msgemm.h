@@ -120,7 +120,7 @@ typedef struct {
     int tile_groups;     /* table groups of a k-tile (one table in LDS), else 0 */
     int split_k;         /* partial sums reduced per output: k-tiles, or runs of k-tiles (long k, batches) */
     int col_chunk;       /* batch columns handled per pass over the codes */
-    int64_t workspace_bytes; /* device memory the plan owns besides the codes */
+    int64_t workspace_bytes; /* device memory the plan owns besides the codes in its kernels' order */
 } msgemm_plan_info_t;
 
 /*
@@ -239,6 +239,10 @@ int msgemm_build_lut(const msgemm_plan_t* plan, const void* X, int64_t ldx,
  * 3.3): Y(i,c) = sum_blocks q(i,block) * sum_{groups j of the block}
  * L(codes of row i at group j, j, c).  L: device, as written by
  * msgemm_build_lut for the same plan.  Y: device, ldy >= m.
+ * This kernel reads the codes row by row.  A fused plan keeps them in its
+ * streaming order only: the first call on such a plan allocates m*k/2 bytes
+ * (MSGEMM_ERR_ALLOC if that fails) and fills them on `stream`; it must not run
+ * at the same time as another first call on that plan.
  */
 int msgemm_consume_lut(const msgemm_plan_t* plan, const void* L,
                        void* Y, int64_t ldy, void* stream);
@@ -294,6 +298,7 @@ int msgemm_plan_check(const msgemm_plan_t* plan, void* stream);
  * registers, MFMA per scale block, fp32 accumulate).  Floating-point dtypes
  * only.  Exists so the LUT path can be timed against it on equal inputs
  * (Section 6 argues the matrix units are what a table-add has to compete with).
+ * Reads rows like msgemm_consume_lut: the same first-call allocation applies.
  */
 int msgemm_dequant_mfma_run(const msgemm_plan_t* plan, const void* X, int64_t ldx,
                             void* Y, int64_t ldy, void* stream);

@@ -212,14 +212,32 @@ depth3_reduce_kernel(const float* __restrict__ partials, YT* __restrict__ Y, int
 }
 
 // [m][k/2] row-major code bytes -> [k-tile][run][row][3 words], each row's 96 bits of a run rotated right by
-// 12 (row % 64 % 8) bits; rows past m and bytes past k/2 are zero
+// 12 (row % 64 % 8) bits; rows past m and bytes past k/2 are zero.  kInverse: back to row-major.
+template <bool kInverse>
 __global__ void __launch_bounds__(256)
-repack3_kernel(const uint8_t* __restrict__ codes, uint32_t* __restrict__ out, int64_t m, int64_t m_pad, int64_t kbytes,
+repack3_kernel(uint8_t* __restrict__ codes, uint32_t* __restrict__ out, int64_t m, int64_t m_pad, int64_t kbytes,
                int64_t runs_total)
 {
     const int64_t total = runs_total * m_pad;
     for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < total; o += (int64_t)gridDim.x * blockDim.x) {
         const int64_t run = o / m_pad, row = o % m_pad;
+        if constexpr (kInverse) {
+            if (row >= m) continue;
+            const uint32_t r[3] = {out[o * 3], out[o * 3 + 1], out[o * 3 + 2]};
+            const int rot = 12 * (int)(row & 7);
+            for (int bt = 0; bt < 12; ++bt) {
+                const int64_t byte = run * 12 + bt;
+                if (byte >= kbytes) break;
+                uint32_t v = 0;
+                for (int bit = 0; bit < 8; ++bit) {
+                    // source bit j sits at result bit (j - rot) mod 96
+                    const int dst = (bt * 8 + bit - rot + 96) % 96;
+                    v |= ((r[dst >> 5] >> (dst & 31)) & 1u) << bit;
+                }
+                codes[row * kbytes + byte] = (uint8_t)v;
+            }
+            continue;
+        }
         uint32_t w[3] = {0, 0, 0};
         if (row < m) {
             for (int bt = 0; bt < 12; ++bt) {
@@ -283,13 +301,17 @@ int depth3_choose_shape(Plan& p)
     return MSGEMM_OK;
 }
 
-int launch_repack3(const Plan& p, hipStream_t s)
+int launch_repack3(const Plan& p, uint8_t* row_major, bool inverse, hipStream_t s)
 {
     const int64_t runs = p.ktiles * (p.fs.groups / 8);
     int64_t blocks = (runs * p.m_pad + 255) / 256;
     if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(repack3_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p.codes, (uint32_t*)p.codes_tiled, p.m, p.m_pad,
-                       p.k / 2, runs);
+    if (inverse)
+        hipLaunchKernelGGL(repack3_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, row_major, (uint32_t*)p.codes_tiled,
+                           p.m, p.m_pad, p.k / 2, runs);
+    else
+        hipLaunchKernelGGL(repack3_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, row_major, (uint32_t*)p.codes_tiled,
+                           p.m, p.m_pad, p.k / 2, runs);
     MSGEMM_HIP_TRY(hipGetLastError());
     return MSGEMM_OK;
 }

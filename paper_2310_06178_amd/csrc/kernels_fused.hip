@@ -1434,9 +1434,11 @@ reduce_few_kernel(const float* __restrict__ partials, YT* __restrict__ Y, int64_
 // [load t][k-tile][panel][lane][LB], or, kPanelMajor, [panel][k-tile][load t][lane][LB]
 // (a wavefront that runs through the k-tiles of its panel then reads one
 // sequential stream).
-template <int G, int LB, bool kPanelMajor = false>
+// kInverse: the other way round, streaming order back to row-major (for the entry points that read the
+// weights row by row: the plan keeps no row-major copy of its own until one of them is called).
+template <int G, int LB, bool kPanelMajor = false, bool kInverse = false>
 __global__ void __launch_bounds__(256)
-repack_kernel(const uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled, int64_t m, int64_t kbytes,
+repack_kernel(uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled, int64_t m, int64_t kbytes,
               int ktiles, int panels_total)
 {
     constexpr int NQ = G / 16;
@@ -1462,7 +1464,11 @@ repack_kernel(const uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled, in
         const int qg = q % NQ;
         const int64_t row = panel * kPanelRows + panel_row<NQ, LB>(q, j, s);
         const int64_t byte = kt * G + 16 * qg + ((j + t) & 15);
-        tiled[o] = (row < m && byte < kbytes) ? codes[row * kbytes + byte] : (uint8_t)0;
+        if constexpr (kInverse) {
+            if (row < m && byte < kbytes) codes[row * kbytes + byte] = tiled[o];
+        } else {
+            tiled[o] = (row < m && byte < kbytes) ? codes[row * kbytes + byte] : (uint8_t)0;
+        }
     }
 }
 
@@ -1761,12 +1767,36 @@ int fused_choose_shape(Plan& p, int requested_variant)
     return MSGEMM_OK;
 }
 
-int launch_repack(const Plan& p, hipStream_t s)
+// Row-major code bytes -> the plan's streaming order (inverse: back again, without touching scales).
+static int repack_codes(const Plan& p, uint8_t* row_major, bool inverse, hipStream_t s)
 {
     const int64_t panels = p.m_pad / p.fs.panel_rows;
     const int64_t total = (int64_t)p.ktiles * p.m_pad * p.fs.groups;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
+#define MSGEMM_REPACK(GG, LL, PM)                                                                                  \
+    if (p.fs.groups == GG && p.fs.lane_bytes == LL) {                                                              \
+        if (inverse)                                                                                               \
+            hipLaunchKernelGGL((repack_kernel<GG, LL, PM, true>), dim3((unsigned)blocks), dim3(256), 0, s, row_major, \
+                               p.codes_tiled, p.m, p.k / 2, (int)p.ktiles, (int)panels);                           \
+        else                                                                                                       \
+            hipLaunchKernelGGL((repack_kernel<GG, LL, PM, false>), dim3((unsigned)blocks), dim3(256), 0, s, row_major, \
+                               p.codes_tiled, p.m, p.k / 2, (int)p.ktiles, (int)panels);                           \
+        MSGEMM_HIP_TRY(hipGetLastError());                                                                         \
+        return MSGEMM_OK;                                                                                          \
+    }
+    MSGEMM_REPACK(64, 16, false)
+    MSGEMM_REPACK(64, 8, false)
+    MSGEMM_REPACK(32, 8, false)
+    MSGEMM_REPACK(32, 4, false)
+    MSGEMM_REPACK(16, 8, true)
+    MSGEMM_REPACK(16, 4, true)
+#undef MSGEMM_REPACK
+    return MSGEMM_ERR_UNSUPPORTED;
+}
+
+int launch_repack(const Plan& p, const void* W_codes, hipStream_t s)
+{
     if (p.scales && p.fs.entry_bytes == 2) {
         const int rc = launch_repack_scales_batched(p, s);
         if (rc != MSGEMM_OK) return rc;
@@ -1777,30 +1807,10 @@ int launch_repack(const Plan& p, hipStream_t s)
                            (__half*)p.scales_ordered, p.m, p.m_pad, p.nblocks, p.fs.panel_rows);
         MSGEMM_HIP_TRY(hipGetLastError());
     }
-#define MSGEMM_REPACK(GG, LL)                                                                          \
-    if (p.fs.groups == GG && p.fs.lane_bytes == LL) {                                                  \
-        hipLaunchKernelGGL((repack_kernel<GG, LL>), dim3((unsigned)blocks), dim3(256), 0, s, p.codes, \
-                           p.codes_tiled, p.m, p.k / 2, (int)p.ktiles, (int)panels);                   \
-        MSGEMM_HIP_TRY(hipGetLastError());                                                             \
-        return MSGEMM_OK;                                                                              \
-    }
-    MSGEMM_REPACK(64, 16)
-    MSGEMM_REPACK(64, 8)
-    MSGEMM_REPACK(32, 8)
-    MSGEMM_REPACK(32, 4)
-    if (p.fs.groups == 16 && (p.fs.lane_bytes == 8 || p.fs.lane_bytes == 4)) {
-        if (p.fs.lane_bytes == 8)
-            hipLaunchKernelGGL((repack_kernel<16, 8, true>), dim3((unsigned)blocks), dim3(256), 0, s, p.codes,
-                               p.codes_tiled, p.m, p.k / 2, (int)p.ktiles, (int)panels);
-        else
-            hipLaunchKernelGGL((repack_kernel<16, 4, true>), dim3((unsigned)blocks), dim3(256), 0, s, p.codes,
-                               p.codes_tiled, p.m, p.k / 2, (int)p.ktiles, (int)panels);
-        MSGEMM_HIP_TRY(hipGetLastError());
-        return MSGEMM_OK;
-    }
-#undef MSGEMM_REPACK
-    return MSGEMM_ERR_UNSUPPORTED;
+    return repack_codes(p, (uint8_t*)W_codes, false, s);  // (read only in this direction)
 }
+
+int launch_unpack(const Plan& p, uint8_t* row_major, hipStream_t s) { return repack_codes(p, row_major, true, s); }
 
 int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int64_t ldy, int slices,
                               int64_t span, hipStream_t s)

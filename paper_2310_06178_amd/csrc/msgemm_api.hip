@@ -48,6 +48,24 @@ size_t lut_bytes_of(const Plan& p)
 
 using msgemm::Plan;
 
+// The entry points that read the weights row by row (the phase-2-alone consumer on a fused plan, the dense
+// comparison kernel) need the row-major codes, which a fused plan does not keep: made here, once, from the
+// streaming order.  Allocates on first use; not safe against two first uses of one plan at the same time.
+static int ensure_row_major(const Plan& cp, hipStream_t s)
+{
+    if (cp.codes) return MSGEMM_OK;
+    Plan& p = const_cast<Plan&>(cp);
+    const size_t code_bytes = (size_t)p.m * (size_t)(p.k / 2);
+    uint8_t* buf = nullptr;
+    hipError_t e = hipMalloc((void**)&buf, code_bytes);
+    if (e != hipSuccess) { msgemm::set_hip_error(e); return MSGEMM_ERR_ALLOC; }
+    const int rc = p.d3 ? msgemm::launch_repack3(p, buf, true, s) : msgemm::launch_unpack(p, buf, s);
+    if (rc != MSGEMM_OK) { (void)hipFree(buf); return rc; }
+    p.codes = buf;
+    p.workspace_bytes += code_bytes;
+    return MSGEMM_OK;
+}
+
 // values256 != nullptr: 8-bit weights.  k and scale_group then count two per code
 // byte (the kernels see a code byte as the pair of 4-bit codes it would be for
 // int4 weights; only the table build knows better), d is 2, the variant FUSED_LDS.
@@ -132,12 +150,15 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
     for (int i = 0; i < 16; ++i) p->values[i] = (float)(((i ^ 8) & 15) - 8);
     p->custom_values = false;
 
-    // the plan's own copies of the weights
+    // the plan's own copies of the weights: row-major for the two-launch variant; the fused variants keep the
+    // codes in their streaming order only (made straight from W_codes below)
     const size_t code_bytes = (size_t)m * (size_t)(k / 2);
-    e = hipMalloc((void**)&p->codes, code_bytes);
-    if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
-    e = hipMemcpyAsync(p->codes, W_codes, code_bytes, hipMemcpyDeviceToDevice, s);
-    if (e != hipSuccess) return hip_fail(e);
+    if (p->variant == MSGEMM_VARIANT_GLOBAL_LUT) {
+        e = hipMalloc((void**)&p->codes, code_bytes);
+        if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
+        e = hipMemcpyAsync(p->codes, W_codes, code_bytes, hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return hip_fail(e);
+    }
     if (scale_group > 0) {
         const size_t sb = (size_t)m * (size_t)p->nblocks * 2u;
         e = hipMalloc((void**)&p->scales, sb);
@@ -164,7 +185,7 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
         if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
         p->partial_bytes = part;
         p->workspace_bytes = tiled + part;
-        rc = msgemm::launch_repack3(*p, s);
+        rc = msgemm::launch_repack3(*p, (uint8_t*)W_codes, false, s);  // (read only in this direction)
         if (rc != MSGEMM_OK) return fail(rc);
     } else {
         const size_t tiled = (size_t)p->ktiles * (size_t)p->m_pad * (size_t)(p->fs.groups);
@@ -205,7 +226,7 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
             if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
             p->workspace_bytes += so;
         }
-        rc = msgemm::launch_repack(*p, s);
+        rc = msgemm::launch_repack(*p, W_codes, s);
         if (rc != MSGEMM_OK) return fail(rc);
     }
     *out = reinterpret_cast<msgemm_plan_t*>(p);
@@ -311,6 +332,8 @@ int msgemm_consume_lut(const msgemm_plan_t* plan, const void* L, void* Y, int64_
     const Plan& p = *reinterpret_cast<const Plan*>(plan);
     if (p.codes8) return MSGEMM_ERR_UNSUPPORTED;
     if (ldy < p.m) return MSGEMM_ERR_INVALID_ARG;
+    const int rc = ensure_row_major(p, (hipStream_t)stream);
+    if (rc != MSGEMM_OK) return rc;
     return msgemm::launch_consume_lut(p, L, Y, ldy, (hipStream_t)stream);
 }
 
@@ -410,6 +433,8 @@ int msgemm_dequant_mfma_run(const msgemm_plan_t* plan, const void* X, int64_t ld
     const Plan& p = *reinterpret_cast<const Plan*>(plan);
     if (ldx < p.k || ldy < p.m) return MSGEMM_ERR_INVALID_ARG;
     if (p.x_dtype == MSGEMM_I8 || p.custom_values || p.codes8) return MSGEMM_ERR_UNSUPPORTED;  // it dequantises with b(.) only
+    const int rc = ensure_row_major(p, (hipStream_t)stream);
+    if (rc != MSGEMM_OK) return rc;
     return msgemm::launch_dequant_mfma(p, X, ldx, Y, ldy, (hipStream_t)stream);
 }
 

@@ -40,7 +40,8 @@ struct Plan {
     bool codes8;          // 8-bit weights: k counts two per code byte internally, a table group is one real column
     float* values256;     // device, 256 floats: the value of each 8-bit pattern (codes8 plans), else nullptr
     float values256_max;  // largest magnitude among them
-    uint8_t* codes;       // device, [m][k/2], plan-owned copy
+    uint8_t* codes;       // device, [m][k/2] row-major, plan-owned: always for the two-launch variant; for the fused ones
+                          // made from the streaming order when an entry point that reads rows is first called
     uint16_t* scales;     // device fp16 [m][nblocks] or nullptr
     float* lut_ws;        // device workspace for the two-launch variant
     size_t lut_ws_bytes;
@@ -100,7 +101,8 @@ int global_plan_setup(Plan& p, hipStream_t s);  // transposed codes and partial 
 
 // kernels_fused.hip
 int fused_choose_shape(Plan& p, int requested_variant);  // fills p.fs, ktiles, ...; MSGEMM_ERR_UNSUPPORTED if not applicable
-int launch_repack(const Plan& p, hipStream_t s);
+int launch_repack(const Plan& p, const void* W_codes, hipStream_t s);  // scales and codes into the kernels' order
+int launch_unpack(const Plan& p, uint8_t* row_major, hipStream_t s);   // the codes back to row-major
 int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s);
 // adds `slices` partial-sum slices ([slice][b_pad][m_pad], output order) and writes Y in the plan's output type
 int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int64_t ldy, int slices,
@@ -108,7 +110,7 @@ int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int
 
 // kernels_depth3.hip (d = 3, tables in LDS, single column)
 int depth3_choose_shape(Plan& p);  // fills row_blocks, m_pad, ktiles, segments, fs; MSGEMM_ERR_UNSUPPORTED if not applicable
-int launch_repack3(const Plan& p, hipStream_t s);
+int launch_repack3(const Plan& p, uint8_t* row_major, bool inverse, hipStream_t s);
 int launch_depth3(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s);
 
 // kernels_batched.hip (16-bit table entries, 8 batch columns per pass)

@@ -600,6 +600,15 @@ def test_depth_three_tables_in_lds(m, k, b, xd, segments, half):
                   None if bnd is None else (2 * bnd if half else bnd))
             minus3 = torch_io.to_host(torch.full((1,), -3, dtype=Y.dtype))[0]
             assert np.all(out[:, m:] == minus3), "output padding was written"
+        if xd != "i8" and k % 64 == 0:
+            # the dense comparison kernel reads rows: the plan makes its row-major copy from the run layout on this
+            # first call (the workspace grows by exactly that copy), so this also checks that layout's inverse
+            before = B.msgemm_plan_get_info(plan)["workspace_bytes"]
+            Y = torch_io.empty_output(b, m, Y_OF_X[xd], ldy=m)
+            B.msgemm_dequant_mfma_run(plan, dX, k, Y, m)
+            torch.cuda.synchronize()
+            assert B.msgemm_plan_get_info(plan)["workspace_bytes"] == before + m * (k // 2)
+            check(torch_io.to_host(Y), oracle_y(codes, X, xd, None, 0), xd, "dense comparison on a d = 3 plan", bnd)
     finally:
         B.msgemm_destroy(plan)
 
