@@ -199,14 +199,22 @@ __global__ void __launch_bounds__(256)
 depth3_reduce_kernel(const float* __restrict__ partials, YT* __restrict__ Y, int64_t ldy, int64_t m, int64_t m_pad, int b,
                      int segments)
 {
-    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t row = (int64_t)blockIdx.x * 64 + threadIdx.x;  // one wavefront per workgroup: m / 64 workgroups
     const int cp = blockIdx.y;
     if (row >= m) return;
     AT sum = 0;
-    for (int s = 0; s < segments; ++s) {
-        AT x;
-        set_bits(x, ((const unsigned*)partials)[((int64_t)s * b + cp) * m_pad + row]);
-        sum += x;
+    const unsigned* src = (const unsigned*)partials + (int64_t)cp * m_pad + row;
+    const int64_t step = (int64_t)b * m_pad;
+    for (int s0 = 0; s0 < segments; s0 += 8) {  // eight loads in flight, added in segment order
+        unsigned w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i] = s0 + i < segments ? src[(s0 + i) * step] : 0u;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            AT x;
+            set_bits(x, w[i]);
+            sum += x;
+        }
     }
     Y[(int64_t)cp * ldy + row] = to_output<YT, AT>(sum);
 }
@@ -329,7 +337,7 @@ static int launch_depth3_typed(const Plan& p, Depth3Args& a, hipStream_t s)
 #undef MSGEMM_D3
     MSGEMM_HIP_TRY(hipGetLastError());
     if (p.segments > 1) {
-        hipLaunchKernelGGL((depth3_reduce_kernel<YT, ET>), dim3((unsigned)((p.m + 255) / 256), (unsigned)p.b), dim3(256), 0, s,
+        hipLaunchKernelGGL((depth3_reduce_kernel<YT, ET>), dim3((unsigned)((p.m + 63) / 64), (unsigned)p.b), dim3(64), 0, s,
                            a.partials, (YT*)a.Y, a.ldy, a.m, a.m_pad, a.b, a.segments);
         MSGEMM_HIP_TRY(hipGetLastError());
     }
