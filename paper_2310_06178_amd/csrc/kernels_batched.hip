@@ -57,6 +57,17 @@ template <int LB> constexpr int batched_waves() { return LB == 8 ? 8 : 12; }
 constexpr int kBCodeStride = 256;        // bytes between the entries of consecutive codes within a half
 constexpr int kBHalfBytes = 256 * kBCodeStride;
 constexpr int kBRing = 8;                // code loads a wavefront keeps in flight
+// table look-ups issued ahead of the adds that use them (a power of two, at most the rows per load)
+#ifndef MSGEMM_BATCHED_LOOKAHEAD
+#define MSGEMM_BATCHED_LOOKAHEAD 8
+#endif
+// Measurement builds only (the result is then wrong): parts of batched_kernel left out, to time what remains.
+// Bits: 1 the matrix-core adds (an xor consumes the entries), 2 the table look-ups, 4 the table build (the barriers
+// stay), 8 the code loads after the first ring, 16 the partial-sum / output stores, 32 the table builds after a
+// workgroup's first.
+#ifndef MSGEMM_BATCHED_LEAVE_OUT
+#define MSGEMM_BATCHED_LEAVE_OUT 0
+#endif
 static_assert(kLoadsPerPanel % kBRing == 0, "ring slots are reused with a period dividing the panel");
 
 template <int LB> struct LaneLoad;
@@ -136,6 +147,8 @@ batched_kernel(BatchedArgs a)
     constexpr int kBWaves = batched_waves<kBLB>();  // wavefronts per workgroup, one row panel each
     constexpr int kBPanelRows = 32 * kBLB;          // 64 lanes x LB rows / 2 lanes per row
     constexpr int kBFinal = kBLB / 2;               // rows a lane owns after the fold
+    // look-ups per chunk (with scales the second set of accumulators leaves registers for half as many)
+    constexpr int kLook = (MSGEMM_BATCHED_LOOKAHEAD < kBLB ? MSGEMM_BATCHED_LOOKAHEAD : kBLB) / (kScaled ? 2 : 1);
     constexpr int kThreads = kBWaves * 64;
     using LoadT = typename LaneLoad<kBLB>::type;
     __shared__ __align__(16) unsigned char lds[2 * kBHalfBytes];
@@ -197,6 +210,7 @@ batched_kernel(BatchedArgs a)
     auto build_tables = [&](int buf) {
         const int g = tid & (kBG - 1), c1 = (tid >> 5) & 15, part = tid >> 9;
         if (part >= kBuildParts) return;  // (a thread count that is no multiple of 512: the rest sits the build out)
+        if constexpr (MSGEMM_BATCHED_LEAVE_OUT & 4) return;
         h2 x0[4], x1[4], top[4];
         __builtin_memcpy(x0, &xs[buf][2 * g][0], 16);
         __builtin_memcpy(x1, &xs[buf][2 * g + 1][0], 16);
@@ -280,26 +294,62 @@ batched_kernel(BatchedArgs a)
                 qraw = *(const LaneScales*)(a.scales + (((int64_t)blk * a.panels_total + panel) * 64 + lane) * kBLB);
             }
             const int kt_next = more ? kt + 1 : kt;  // (the last tile re-requests its own tail: harmless, and branch-free)
-#pragma unroll
-            for (int t = 0; t < kLoadsPerPanel; ++t) {
+            // The look-ups run one chunk ahead of the table-adds: the reads of chunk c + 1 are issued between the
+            // matrix-core adds of chunk c, so a read has a whole chunk's adds to land in and the LDS and the matrix
+            // cores work at the same time (left to itself the compiler keeps two reads in flight and waits for each).
+            constexpr int kChunks = kLoadsPerPanel * kBLB / kLook;
+            uint4 ent[2][kLook];
+            auto look = [&](int c, uint4 (&e)[kLook]) {
+                const int t = c * kLook / kBLB, s0 = c * kLook % kBLB;
                 // byte 0: the slot of this lane's group within a code's 256 bytes; byte 2: the half
                 const uint32_t lane_off = (uint32_t)((j + t) & 15) * 16u | ((uint32_t)qg << 16);
                 const LoadT d = ring[t % kBRing];
 #pragma unroll
-                for (int s = 0; s < kBLB; ++s) {
+                for (int i = 0; i < kLook; ++i) {
+                    const int s = s0 + i;
                     const uint32_t w = load_word<kBLB>(d, s >> 2);
                     // address bytes (3..0) = (0, half, code, slot)
                     const uint32_t addr = __builtin_amdgcn_perm(w, lane_off, 0x0c020000u | ((4u + (s & 3)) << 8));
-                    const uint4 e = *(const uint4*)(lds + addr);
+                    if constexpr (MSGEMM_BATCHED_LEAVE_OUT & 2) e[i] = uint4{addr, addr, addr, addr};
+                    else e[i] = *(const uint4*)(lds + addr);
+                }
+            };
+            auto add = [&](int c, const uint4 (&e)[kLook]) {
+                const int s0 = c * kLook % kBLB;
+#pragma unroll
+                for (int i = 0; i < kLook; ++i) {
+                    const int s = s0 + i;
+                    if constexpr (MSGEMM_BATCHED_LEAVE_OUT & 1) {
+                        asm volatile("" ::"v"(e[i].x), "v"(e[i].y), "v"(e[i].z), "v"(e[i].w));  // demanded, by no instruction
+                        continue;
+                    }
                     h4 lo, up;
-                    __builtin_memcpy(&lo, &e.x, 8);
-                    __builtin_memcpy(&up, &e.z, 8);
+                    __builtin_memcpy(&lo, &e[i].x, 8);
+                    __builtin_memcpy(&up, &e[i].z, 8);
                     dlo[s] = __builtin_amdgcn_mfma_f32_4x4x4f16(lo, onehot, dlo[s], 0, 0, 0);
                     dhi[s] = __builtin_amdgcn_mfma_f32_4x4x4f16(up, onehot, dhi[s], 0, 0, 0);
                 }
-                // the slot's bytes are now addresses: refill it with the load kBRing ahead
-                ring[t % kBRing] = load_codes((t + kBRing < kLoadsPerPanel) ? code_at(kt, t + kBRing)
-                                                                              : code_at(kt_next, t + kBRing - kLoadsPerPanel));
+            };
+            look(0, ent[0]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int c = 0; c < kChunks; ++c) {
+                if (c + 1 < kChunks) look(c + 1, ent[(c + 1) & 1]);
+                add(c, ent[c & 1]);
+                if ((c + 1) * kLook % kBLB == 0) {
+                    // load t is all addresses now: refill its slot with the load kBRing ahead
+                    const int t = c * kLook / kBLB;
+                    if constexpr (!(MSGEMM_BATCHED_LEAVE_OUT & 8))
+                    ring[t % kBRing] = load_codes((t + kBRing < kLoadsPerPanel) ? code_at(kt, t + kBRing)
+                                                                                  : code_at(kt_next, t + kBRing - kLoadsPerPanel));
+                }
+                if (c + 1 < kChunks) {
+#pragma unroll
+                    for (int i = 0; i < kLook; ++i) {  // one look-up, then two adds, kLook times
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
             if constexpr (kScaled) {
@@ -326,11 +376,14 @@ batched_kernel(BatchedArgs a)
             const int buf = (kt + 1 - kt_begin) & 1;
             x_store(buf, kt + 1, xraw);
             lds_barrier();  // every wavefront is done with the old tables; the new activations are in place
-            build_tables(buf);
+            if constexpr (!(MSGEMM_BATCHED_LEAVE_OUT & 32)) build_tables(buf);
             lds_barrier();
         }
     }
     if (!active) return;
+    if constexpr (MSGEMM_BATCHED_LEAVE_OUT & 16) {
+        if (dlo[0][0] != 1234.5f) return;  // (keeps the sums alive)
+    }
 
     // ---- lanes 16 apart looked up the same rows (in different groups): fold them.
     // Afterwards lane (quad b, j'), register (s, i) holds row 64 s + 4 b + i of the
