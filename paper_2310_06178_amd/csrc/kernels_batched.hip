@@ -65,6 +65,10 @@ constexpr int kBRing = 8;                // code loads a wavefront keeps in flig
 // Bits: 1 the matrix-core adds (an xor consumes the entries), 2 the table look-ups, 4 the table build (the barriers
 // stay), 8 the code loads after the first ring, 16 the partial-sum / output stores, 32 the table builds after a
 // workgroup's first.
+// schedule of the pipelined form's look-ups: 0 every look-up fenced off, 1 the order given as groups, 2 the compiler's
+#ifndef MSGEMM_PIPE_SCHED
+#define MSGEMM_PIPE_SCHED 1
+#endif
 #ifndef MSGEMM_BATCHED_LEAVE_OUT
 #define MSGEMM_BATCHED_LEAVE_OUT 0
 #endif
@@ -640,7 +644,16 @@ batched_pipe_kernel(BatchedArgs a)
                         dlo[s] = __builtin_amdgcn_mfma_f32_4x4x4f16(lo, onehot, dlo[s], 0, 0, 0);
                         dhi[s] = __builtin_amdgcn_mfma_f32_4x4x4f16(up, onehot, dhi[s], 0, 0, 0);
                         if (t + 1 < kLoadsPerPanel) look_up(t + 1, s);
-                        __builtin_amdgcn_sched_barrier(0);
+                        if constexpr (MSGEMM_PIPE_SCHED == 0) __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if constexpr (MSGEMM_PIPE_SCHED == 1) {
+                        if (t + 1 < kLoadsPerPanel) {
+#pragma unroll
+                            for (int s = 0; s < kPLB; ++s) {  // two adds, then the look-up that takes their register
+                                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                            }
+                        }
                     }
                     if (t + 1 < kLoadsPerPanel) refill(t + 1);
                     next_slot();
@@ -800,12 +813,13 @@ static double pipe_form_choice(int64_t panels, int64_t ktiles, int tpb, int col_
     double best = 1e300;
     best_ppw = waves;
     best_per = blocks;
-    // Measured: a k-tile takes a workgroup 3.0 us + 0.125 us per active wavefront (8 rows per
+    // Measured: a k-tile takes a workgroup 2.75 us + 0.12 us per active wavefront (8 rows per
     // lane; 1.9 + 0.085 with 4): what bounds it is the rate at which a wavefront issues its
     // look-ups, and wavefronts that share a SIMD overlap almost completely.  Start-up, launch
-    // and tail of a workgroup: 6.5 us.
-    const double tile_base_us = lane_bytes == 8 ? 3.0 : 1.9, tile_wave_us = lane_bytes == 8 ? 0.125 : 0.085;
-    for (int ppw = waves; ppw >= 1; ppw >>= 1) {
+    // and tail of a workgroup: 6.5 us.  Every panel count is tried: one wavefront less per
+    // workgroup can turn a grid that leaves compute units idle into one that fills them.
+    const double tile_base_us = lane_bytes == 8 ? 2.75 : 1.9, tile_wave_us = lane_bytes == 8 ? 0.12 : 0.085;
+    for (int ppw = waves; ppw >= 1; --ppw) {
         const int64_t row_blocks = (panels + ppw - 1) / ppw;
         const double tile_us = tile_base_us + tile_wave_us * ppw;
         for (int64_t per = blocks; per >= 1; --per) {
