@@ -135,9 +135,10 @@ typedef struct {
     int panels_per_workgroup;    /* fused kernels: panels of rows per workgroup (1..64); 0 = library's choice */
     int k_tiles_per_workgroup;   /* single-column kernels: consecutive k-tiles a workgroup runs through
                                     (1 = one k-tile per workgroup, n > 2 = the long-k form); 0 = library's choice */
-    int reduce_mode;             /* single-column kernels, sums over k-tiles: 0 = library's choice, 1 = a second
-                                    launch, 2 = trailing workgroups of the same launch, 3 = the workgroups that
-                                    produced them (needs the whole grid resident; else 1 is taken) */
+    int reduce_mode;             /* sums over k-tiles / k-segments: 0 = library's choice, 1 = a second launch,
+                                    2 = trailing workgroups of the same launch (single-column kernels), 3 = the
+                                    workgroups that produced them (needs the whole grid resident; else 1 is
+                                    taken; the batched kernels do it on request only: it measured slower) */
     int rows_per_lane;           /* single-column kernel: 16 (default) or 8 (its 16-wavefront form);
                                     batched kernel: 8 (default) or 4 */
     int no_xcd_map;              /* 1: workgroup ids in k-tile-major order instead of grouped per L2 */

@@ -106,6 +106,15 @@ __device__ __forceinline__ void wait_vmem()
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
+constexpr unsigned kMaxFlagPolls = 1u << 22;  // default bound of the in-launch reductions' waits (seconds)
+
+// A partial sum and the parity of its launch in one word (the reductions done by the workgroups of the launch that
+// wrote the sums): floating point gives up its last mantissa bit, integers move up by one bit.
+__device__ __forceinline__ unsigned tag_partial(float v, unsigned parity) { return (__float_as_uint(v) & ~1u) | parity; }
+__device__ __forceinline__ unsigned tag_partial(int v, unsigned parity) { return ((unsigned)v << 1) | parity; }
+__device__ __forceinline__ void untag_partial(float& d, unsigned u) { d = __uint_as_float(u & ~1u); }
+__device__ __forceinline__ void untag_partial(int& d, unsigned u) { d = (int)u >> 1; }
+
 template <int N, int AUX>
 __device__ __forceinline__ void store_partials(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, const unsigned (&v)[N])
 {

@@ -107,7 +107,14 @@ struct BatchedArgs {
     int64_t partial_span;    // bytes of the partial buffer (< 2^31)
     FastDiv div_col_passes, div_segments, div_tiles_per_block;
     float x_limit;           // floating-point activations beyond this magnitude can take a table entry out of the fp16 range
-    unsigned* error;         // the plan's sticky error word (bit 1: such an activation was seen), or nullptr
+    unsigned* error;         // the plan's sticky error word (bit 0: a reduction gave up; bit 1: such an activation was seen), or nullptr
+    // the segments' sums added by the workgroups of this launch (every workgroup resident at once), not by a second one
+    int resident;            // 1: on
+    int publish;             // 0 (a test aid): the partial sums are not stored, the readers find nothing and give up
+    unsigned* epochs;        // launch count of every workgroup (each bumps its own)
+    unsigned poll_limit;     // polls before a waiting lane gives up
+    int red_pieces;          // 16-byte pieces of the outputs one workgroup adds
+    int red_groups;          // lanes that share a piece, each taking every red_groups-th segment
 };
 
 template <typename XT> __device__ __forceinline__ _Float16 to_half(XT v);
@@ -141,6 +148,141 @@ template <int I> __device__ __forceinline__ float quad_broadcast(float v)
     return __uint_as_float((unsigned)__builtin_amdgcn_mov_dpp((int)__float_as_uint(v), I * 0x55, 0xf, 0xf, true));
 }
 
+// The sums over the k-segments, inside the launch that made them.  Every partial sum carries the parity of the launch
+// in its last bit (tag_partial), so a reader knows a word of this launch from one of the launch before without flags:
+// every launch rewrites every word, and the parity alternates.  When a workgroup has stored its own sums it turns
+// reader of 1 / readers of the outputs: lane (piece, g) loads the 16-byte piece of the segments g, g + groups, ...,
+// eight loads at a time, again until all carry this launch's parity (at most poll_limit times: then bit 0 of the
+// plan's error word is set and msgemm_plan_check reports it), adds them in segment order; the groups' sums meet in
+// LDS and are added in group order: a fixed order.  Needs every workgroup of the grid resident at the same time
+// (one per compute unit: the host checks) -- a reader waits for sums of workgroups that must be running.
+// Called by every thread of the workgroup (it holds workgroup barriers); `scratch` is LDS nobody reads any more once
+// all have arrived here, 16 bytes per thread.
+template <typename YT, typename AT, int kFinal>
+__device__ __forceinline__ void reduce_segments_resident(const BatchedArgs& a, unsigned parity, int reader, unsigned char* scratch)
+{
+    constexpr int kPanelRowsR = 64 * kFinal;
+    const int tid = threadIdx.x;
+    const int G = a.red_groups;
+    const int per_round = (int)blockDim.x / G;   // pieces a round of the workgroup covers
+    const int pl = tid % per_round, g = tid / per_round;
+    const uint32_t seg_bytes = (uint32_t)(a.b_pad * a.m_pad * 4);
+    const int64_t p0 = (int64_t)reader * a.red_pieces;
+    const int64_t p_end = min(p0 + a.red_pieces, a.b_pad * a.m_pad / 4);
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)a.partials, 0, (int)a.partial_span, 0x00020000);
+    YT* __restrict__ Y = (YT*)a.Y;
+    unsigned polls = 0;
+    bool gave_up = false;
+    // One wavefront watches a single piece of every segment (the first of this workgroup's share) until it carries
+    // this launch's parity, at a leisurely pace; the others sleep at the barrier.  Workgroups finish at different
+    // times: were every lane to poll all of its pieces, the early ones would take memory bandwidth from the late.
+    if (tid < 64) {
+        const int64_t piece = min(p0, p_end - 1);
+#pragma unroll 1
+        for (int s0 = 0; s0 < a.segments && !gave_up; s0 += 64) {
+            const bool live = s0 + tid < a.segments && p0 < p_end;
+            const uint32_t off = live ? (uint32_t)(s0 + tid) * seg_bytes + (uint32_t)piece * 16u : 0x7ffffff0u;
+#pragma unroll 1
+            for (;;) {
+                asm volatile("" ::: "memory");
+                const v4u v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, kAuxSc1);
+                const bool here = !live || ((v.x & v.y & v.z & v.w & 1u) == parity && ((v.x | v.y | v.z | v.w) & 1u) == parity);
+                if (__builtin_amdgcn_ballot_w64(!here) == 0) break;
+                if (++polls >= a.poll_limit) {
+                    gave_up = true;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(32);
+            }
+        }
+    }
+    lds_barrier();  // every wavefront has left the tables (their memory is scratch now), and the sums are about there
+#pragma unroll 1
+    for (int r0 = 0; r0 < a.red_pieces; r0 += per_round) {
+        const int64_t piece = p0 + r0 + pl;
+        const bool have = g < G && r0 + pl < a.red_pieces && piece < p_end;
+        AT sum[4] = {0, 0, 0, 0};
+#pragma unroll 1
+        for (int s0 = g; s0 < a.segments && have && !gave_up; s0 += 8 * G) {
+            v4u v[8];
+            uint32_t off[8];
+            bool live[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int sl = s0 + u * G;
+                live[u] = sl < a.segments;
+                off[u] = live[u] ? (uint32_t)sl * seg_bytes + (uint32_t)piece * 16u : 0x7ffffff0u;  // (out of range: reads zero)
+            }
+#pragma unroll 1
+            for (;;) {
+                asm volatile("" ::: "memory");
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off[u], 0, kAuxSc1);
+                bool arrived = true;
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    arrived &= !live[u] || ((v[u].x & v[u].y & v[u].z & v[u].w & 1u) == parity &&
+                                            ((v[u].x | v[u].y | v[u].z | v[u].w) & 1u) == parity);
+                if (arrived) break;
+                if (++polls >= a.poll_limit) {
+                    gave_up = true;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(16);
+            }
+            if (gave_up) break;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {  // (what is not live read as zero and adds nothing)
+                AT x;
+                untag_partial(x, live[u] ? v[u].x : 0u); sum[0] += x;
+                untag_partial(x, live[u] ? v[u].y : 0u); sum[1] += x;
+                untag_partial(x, live[u] ? v[u].z : 0u); sum[2] += x;
+                untag_partial(x, live[u] ? v[u].w : 0u); sum[3] += x;
+            }
+        }
+        // the groups' sums of a piece meet in LDS
+        AT* mine = (AT*)(scratch + (size_t)tid * 16);
+        if (G > 1) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mine[e] = sum[e];
+            lds_barrier();
+        }
+        if (have && g == 0 && !gave_up) {
+            for (int og = 1; og < G; ++og) {
+                const AT* other = (const AT*)(scratch + (size_t)(og * per_round + pl) * 16);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sum[e] += other[e];
+            }
+            // piece -> (column, partial-sum slots of a panel); slot f of a panel belongs to lane f / kFinal of the
+            // wavefront that made it, output f % kFinal: row 64 (f % kFinal) + f / kFinal
+            const int64_t f = piece * 4;
+            const int64_t col = f / a.m_pad, rr = f % a.m_pad;
+            const int64_t panel = rr / kPanelRowsR;
+            const int q0 = (int)(rr % kPanelRowsR);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int qe = q0 + e;
+                const int64_t row = panel * kPanelRowsR + 64 * (qe % kFinal) + qe / kFinal;
+                if (row < a.m && col < a.b) Y[col * a.ldy + row] = to_output<YT, AT>(sum[e]);
+            }
+        }
+        if (G > 1) lds_barrier();  // the scratch is read: the next round may write it
+    }
+    // gave up: some partial sum never arrived.  The plan's error word says so (msgemm_plan_check).
+    if (gave_up && a.error) __hip_atomic_fetch_or(a.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// This workgroup's launch count goes up by one (one lane); its parity tags the partial sums of this launch.
+// The caller's next workgroup barrier makes `*slot` (LDS) visible to the other lanes.
+__device__ __forceinline__ void count_launch(const BatchedArgs& a, unsigned* slot)
+{
+    if (a.resident && threadIdx.x == 0) {
+        const unsigned n = __hip_atomic_load(a.epochs + blockIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
+        __hip_atomic_store(a.epochs + blockIdx.x, n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *slot = n & 1u;
+    }
+}
+
 // kCodes8: 8-bit weights.  A code byte is one element, a table group one k-column
 // (a.k counts two per byte), an entry values256[code] * x; only the table build
 // and the activations it reads differ.
@@ -157,6 +299,7 @@ batched_kernel(BatchedArgs a)
     using LoadT = typename LaneLoad<kBLB>::type;
     __shared__ __align__(16) unsigned char lds[2 * kBHalfBytes];
     __shared__ __align__(16) _Float16 xs[2][2 * kBG][kBC];            // activations of a k-tile: [k-column][batch column]
+    __shared__ unsigned launch_parity;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -266,6 +409,7 @@ batched_kernel(BatchedArgs a)
             __builtin_amdgcn_sched_barrier(0);  // loads return in issue order: keep slot 0 first
         }
     }
+    count_launch(a, &launch_parity);
     x_store(0, kt_begin, xraw);
     lds_barrier();
     build_tables(0);
@@ -384,10 +528,8 @@ batched_kernel(BatchedArgs a)
             lds_barrier();
         }
     }
-    if (!active) return;
-    if constexpr (MSGEMM_BATCHED_LEAVE_OUT & 16) {
-        if (dlo[0][0] != 1234.5f) return;  // (keeps the sums alive)
-    }
+    const unsigned parity = a.resident ? launch_parity : 0u;
+    if (active && !((MSGEMM_BATCHED_LEAVE_OUT & 16) && dlo[0][0] != 1234.5f)) {
 
     // ---- lanes 16 apart looked up the same rows (in different groups): fold them.
     // Afterwards lane (quad b, j'), register (s, i) holds row 64 s + 4 b + i of the
@@ -428,15 +570,20 @@ batched_kernel(BatchedArgs a)
                 unsigned out[kBFinal];
 #pragma unroll
                 for (int s = 0; s < kBFinal; ++s) {
-                    if constexpr (__is_same(AT, int)) out[s] = (unsigned)__float2int_rn(fin[s]);
-                    else out[s] = __float_as_uint(fin[s]);
+                    AT v;
+                    if constexpr (__is_same(AT, int)) v = __float2int_rn(fin[s]);
+                    else v = fin[s];
+                    out[s] = a.resident ? tag_partial(v, parity) : bits_of(v);
                 }
                 const uint32_t off =
                     (uint32_t)((((int64_t)seg * a.b_pad + col) * a.m_pad + (int64_t)panel * kBPanelRows + owner * kBFinal) * 4);
-                store_partials<kBFinal, 0>(part_rsrc, off, out);
+                if (!a.resident) store_partials<kBFinal, 0>(part_rsrc, off, out);
+                else if (a.publish) store_partials<kBFinal, kAuxSc1>(part_rsrc, off, out);
             }
         }
     }
+    }
+    if (a.resident) reduce_segments_resident<YT, AT, kBFinal>(a, parity, unit * a.col_passes + cp, lds);
 }
 
 // Pipelined form: the table of the next k-tile is built while the current one is
@@ -470,6 +617,7 @@ batched_pipe_kernel(BatchedArgs a)
     using LoadT = typename LaneLoad<kPLB>::type;
     __shared__ __align__(16) unsigned char lds[2 * kPTableBytes];
     __shared__ __align__(16) _Float16 xs[2][2 * kPG][kBC];  // activations of a k-tile: [k-column][batch column]
+    __shared__ unsigned launch_parity;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -557,6 +705,7 @@ batched_pipe_kernel(BatchedArgs a)
             __builtin_amdgcn_sched_barrier(0);  // loads return in issue order: keep slot 0 first
         }
     }
+    count_launch(a, &launch_parity);
     x_store(0, kt_begin, xraw);
     if (ngen > 1) x_store(1, kt_begin + 1, xraw1);
     lds_barrier();
@@ -692,8 +841,8 @@ batched_pipe_kernel(BatchedArgs a)
         // everyone has finished reading table gen & 1 and writing the other one (and the activations)
         if (more) lds_barrier();
     }
-    if (!active) return;
-
+    const unsigned parity = a.resident ? launch_parity : 0u;
+    if (active) {
     // ---- lane (quad b, j'), register (s, i) holds row 64 s + 4 b + i of the panel,
     // column 4 h + j' of the pass (the matrix cores hand the sums back transposed within a quad)
     const int quad = lane >> 2, jq = lane & 3;
@@ -725,15 +874,20 @@ batched_pipe_kernel(BatchedArgs a)
                 unsigned out[kPLB];
 #pragma unroll
                 for (int s = 0; s < kPLB; ++s) {
-                    if constexpr (__is_same(AT, int)) out[s] = (unsigned)__float2int_rn(fin[s]);
-                    else out[s] = __float_as_uint(fin[s]);
+                    AT v;
+                    if constexpr (__is_same(AT, int)) v = __float2int_rn(fin[s]);
+                    else v = fin[s];
+                    out[s] = a.resident ? tag_partial(v, parity) : bits_of(v);
                 }
                 const uint32_t off =
                     (uint32_t)((((int64_t)seg * a.b_pad + col) * a.m_pad + (int64_t)panel * kPanelRows + owner * kPLB) * 4);
-                store_partials<kPLB, 0>(part_rsrc, off, out);
+                if (!a.resident) store_partials<kPLB, 0>(part_rsrc, off, out);
+                else if (a.publish) store_partials<kPLB, kAuxSc1>(part_rsrc, off, out);
             }
         }
     }
+    }
+    if (a.resident) reduce_segments_resident<YT, AT, kPLB>(a, parity, unit * a.col_passes + cp, lds);
 }
 
 // One-off reorder of the block scales ([m][nblocks]) for the batched kernel:
@@ -938,6 +1092,23 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
     a.div_segments = make_fastdiv((uint32_t)a.segments);
     a.div_tiles_per_block = make_fastdiv((uint32_t)a.tiles_per_block);
     const int64_t grid = (int64_t)kXcds * a.col_passes * ((a.units + kXcds - 1) / kXcds);
+    // On request (reduce_mode 3) the segments are added inside the launch, if every workgroup is resident at once:
+    // each needs more than half of a compute unit's LDS, so that is one workgroup per compute unit.  Not the default:
+    // the partial sums of a batch are tens of megabytes, and reading them with loads that are coherent across the
+    // device inside the launch measured slower than the second launch (config 3a 30.8 against 24.7 us, config 5
+    // 263 against 242), unlike the single-column forms whose sums are a megabyte.
+    const int threads = (p.fs.groups == kPG) ? (64 / p.fs.lane_bytes) * 64 : (p.fs.lane_bytes == 8 ? 8 : 12) * 64;
+    a.resident = (!a.direct && p.epochs && p.forced_reduce == 3 && grid <= p.cus) ? 1 : 0;
+    a.publish = p.opt.skip_publish ? 0 : 1;
+    a.epochs = p.epochs;
+    a.poll_limit = p.opt.poll_limit > 0 ? (unsigned)p.opt.poll_limit : kMaxFlagPolls;
+    {
+        const int64_t pieces = a.b_pad * p.m_pad / 4, readers = (int64_t)a.units * a.col_passes;
+        a.red_pieces = (int)((pieces + readers - 1) / readers);
+        int g = 1;
+        while (g < 8 && 2 * g <= a.segments && (int64_t)a.red_pieces * (2 * g) <= threads) g *= 2;
+        a.red_groups = g;
+    }
     const int lb = p.fs.lane_bytes;
     const dim3 g((unsigned)grid), blk((unsigned)(lb == 8 ? 8 : 12) * 64);
     const bool scaled = p.scales != nullptr;
@@ -959,7 +1130,7 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
         else if (scaled) MSGEMM_PIPE_LB(XT, YT, AT, true, false);                                   \
         else MSGEMM_PIPE_LB(XT, YT, AT, false, false);                                              \
         MSGEMM_HIP_TRY(hipGetLastError());                                                          \
-        if (!a.direct) return launch_reduce_second_pass(p, a.partials, Y, ldy, a.segments, a.partial_span, s); \
+        if (!a.direct && !a.resident) return launch_reduce_second_pass(p, a.partials, Y, ldy, a.segments, a.partial_span, s); \
         return MSGEMM_OK;                                                                           \
     }
     if (!pipe && p.codes8 && (lb != 8 || p.x_dtype == MSGEMM_I8)) return MSGEMM_ERR_UNSUPPORTED;
@@ -975,7 +1146,7 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
         else if (lb == 8) hipLaunchKernelGGL((batched_kernel<XT, YT, AT, false, 8, false>), g, blk, 0, s, a);            \
         else hipLaunchKernelGGL((batched_kernel<XT, YT, AT, false, 4, false>), g, blk, 0, s, a);                         \
         MSGEMM_HIP_TRY(hipGetLastError());                                                          \
-        if (!a.direct) return launch_reduce_second_pass(p, a.partials, Y, ldy, a.segments, a.partial_span, s); \
+        if (!a.direct && !a.resident) return launch_reduce_second_pass(p, a.partials, Y, ldy, a.segments, a.partial_span, s); \
         return MSGEMM_OK;                                                                           \
     }
     MSGEMM_BATCHED_PIPE(MSGEMM_F16, __half, __half, float)

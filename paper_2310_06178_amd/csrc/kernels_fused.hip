@@ -77,7 +77,6 @@ namespace {
 #define MSGEMM_RING_BYTES 128
 #endif
 constexpr int kRingBytes = MSGEMM_RING_BYTES;  // code bytes per lane a wavefront keeps in flight (x64 lanes)
-constexpr unsigned kMaxFlagPolls = 1u << 22;  // default bound of the in-launch reductions' waits (seconds)
 
 struct FusedArgs {
     const uint8_t* tiled;
@@ -148,13 +147,6 @@ __device__ __forceinline__ float mul_add(float w, float x, float acc) { return f
 __device__ __forceinline__ int mul_add(int w, int x, int acc) { return w * x + acc; }
 
 template <typename ET, int C> struct alignas(C * sizeof(ET) >= 16 ? 16 : C * sizeof(ET)) EntryVec { ET v[C]; };
-
-// A partial sum and the parity of its launch in one word (wide form's resident reduction): floating point gives up
-// its last mantissa bit, integers move up by one bit.
-__device__ __forceinline__ unsigned tag_partial(float v, unsigned parity) { return (__float_as_uint(v) & ~1u) | parity; }
-__device__ __forceinline__ unsigned tag_partial(int v, unsigned parity) { return ((unsigned)v << 1) | parity; }
-__device__ __forceinline__ void untag_partial(float& d, unsigned u) { d = __uint_as_float(u & ~1u); }
-__device__ __forceinline__ void untag_partial(int& d, unsigned u) { d = (int)u >> 1; }
 
 // The single-column kernels can reduce inside the launch; the batched ones are
 // bound by the gather, not by launches, and have no registers to spare for it.

@@ -206,10 +206,16 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
         if (e != hipSuccess) return hip_fail(e);
         p->error_word = p->flags + words;
         p->partial_bytes = part;
-        if (p->wide_tables > 0) {
-            // the wide form's resident reduction: every partial sum carries the parity of its launch, counted per
-            // workgroup; both start at zero
-            p->epoch_words = (size_t)slices * msgemm::kXcds * (((size_t)p->row_blocks * p->col_passes + msgemm::kXcds - 1) / msgemm::kXcds);
+        p->workspace_bytes = tiled + part + cnt;
+        const bool batched = p->fs.entry_bytes == 2 && p->segments > 1;
+        if (p->wide_tables > 0 || batched) {
+            // reductions by the workgroups of the launch itself: every partial sum carries the parity of its launch,
+            // counted per workgroup; both start at zero
+            if (batched)
+                p->epoch_words = (size_t)msgemm::kXcds * (size_t)p->col_passes *
+                                 (((size_t)p->segments * (size_t)p->row_blocks + msgemm::kXcds - 1) / msgemm::kXcds);
+            else
+                p->epoch_words = (size_t)slices * msgemm::kXcds * (((size_t)p->row_blocks * p->col_passes + msgemm::kXcds - 1) / msgemm::kXcds);
             e = hipMalloc((void**)&p->epochs, p->epoch_words * sizeof(unsigned));
             if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
             e = hipMemsetAsync(p->epochs, 0, p->epoch_words * sizeof(unsigned), s);
@@ -218,7 +224,6 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
             if (e != hipSuccess) return hip_fail(e);
             p->workspace_bytes += p->epoch_words * sizeof(unsigned);
         }
-        p->workspace_bytes = tiled + part + cnt;
         if (p->scales) {
             // (the batched kernel keeps one scale per look-up slot: twice the rows)
             const size_t so = (size_t)p->nblocks * (size_t)p->m_pad * (p->fs.entry_bytes == 2 ? 4u : 2u);
@@ -418,7 +423,7 @@ int msgemm_plan_check(const msgemm_plan_t* plan, void* stream)
     }
     // a reducer gave up: flags may be left up, outputs of that call are not the result.  Clear, so that the plan works again.
     MSGEMM_HIP_TRY(hipMemsetAsync(p.flags, 0, (p.flag_words + 1) * sizeof(unsigned), s));
-    if (p.wide_tables > 0) {  // partial sums of the failed launch may be missing: parities and launch counts start over
+    if (p.epochs) {  // partial sums of the failed launch may be missing: parities and launch counts start over
         MSGEMM_HIP_TRY(hipMemsetAsync(p.partials, 0, p.partial_bytes, s));
         MSGEMM_HIP_TRY(hipMemsetAsync(p.epochs, 0, p.epoch_words * sizeof(unsigned), s));
     }

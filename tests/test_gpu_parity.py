@@ -559,6 +559,51 @@ def test_in_launch_reduction_give_up_is_reported(options):
         B.msgemm_destroy(plan)
 
 
+@pytest.mark.parametrize("form,xd", [(1, "f16"), (2, "bf16"), (1, "i8")])
+def test_batched_segments_added_in_the_launch(form, xd):
+    """Batches, on request (reduce_mode 3): the k-segments' sums are added by the workgroups of the launch that made
+    them (the grid fits the device at once).  Against the oracle over repeated calls on one plan (the parity of a
+    launch tags its sums), beside the default second launch, and the host-forced give-up is reported."""
+    m, k, b, sg = 1300, 2048, 11, (0 if xd == "i8" else 128)
+    codes = inputs.make_codes(m, k, seed=21)
+    scales = inputs.make_scales(m, k, sg, seed=5) if sg else None
+    dC, dS = torch_io.to_device(codes, "codes"), torch_io.to_device(scales, "scales")
+    base = {"batched_form": form, "batched_segments": 4}
+    outs = {}
+    for mode in (3, 0):
+        plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS, options=dict(base, reduce_mode=mode))
+        try:
+            assert B.msgemm_plan_get_info(plan)["split_k"] == 4
+            for rep in range(3):
+                X = inputs.make_x(k, b, xd, seed=30 + rep)
+                dX = torch_io.to_device(X, xd)
+                Y = torch_io.empty_output(b, m, Y_OF_X[xd], ldy=m + 1)
+                Y.fill_(-3)
+                B.msgemm_run(plan, dX, k, Y, m + 1)
+                torch.cuda.synchronize()
+                assert B.msgemm_plan_check(plan) == B.OK
+                out = torch_io.to_host(Y)
+                check(np.ascontiguousarray(out[:, :m]), oracle_y(codes, X, xd, scales, sg), xd,
+                      f"batched, reduce mode {mode}, call {rep}", elem_bound(codes, X, xd, scales, sg, table16=True))
+                minus3 = torch_io.to_host(torch.full((1,), -3, dtype=Y.dtype))[0]
+                assert np.all(out[:, m:] == minus3), "output padding was written"
+            outs[mode] = out
+        finally:
+            B.msgemm_destroy(plan)
+    if xd == "i8":
+        assert np.array_equal(outs[0], outs[3])
+    # the give-up: partial sums are never stored, the poll bound is tiny
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS,
+                         options=dict(base, reduce_mode=3, poll_limit=8, skip_publish=1))
+    try:
+        assert B.msgemm_plan_check(plan) == B.OK
+        B.msgemm_run(plan, dX, k, Y, m + 1)
+        assert B.msgemm_plan_check(plan) == B.ERR_INCOMPLETE
+        assert B.msgemm_plan_check(plan) == B.OK
+    finally:
+        B.msgemm_destroy(plan)
+
+
 DEPTH3_CASES = [
     # m, k, b, xd, segments (0: the library's choice)
     (12, 4, 1, "f32", 0),          # the worked example's shape: one full group and one of a single column
