@@ -214,6 +214,24 @@ def lds_read_ceiling(B, torch, stream, width=16, reads=4096, launches=20):
     return {"width_bytes": width, "bytes": nbytes, "us": us, "GB/s": nbytes / (us * 1e-6) / 1e9}
 
 
+def lookup_add_ceiling(B, torch, stream, tiles=64, launches=10):
+    """Measured rate of the batched kernels' inner loop alone (msgemm_calib_lookup_add: a 16-byte look-up and its
+    two matrix-core adds, 8 wavefronts per compute unit, no code stream, no table build): lane look-ups per second."""
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
+    n = 0
+    with torch.cuda.stream(stream):
+        for _ in range(2):
+            n = B.msgemm_calib_lookup_add(tiles, sink, stream)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record(stream)
+        for _ in range(launches):
+            B.msgemm_calib_lookup_add(tiles, sink, stream)
+        ev1.record(stream)
+    torch.cuda.synchronize()
+    us = ev0.elapsed_time(ev1) * 1e3 / launches
+    return {"lane_lookups": n, "us": us, "Glookups/s": n / (us * 1e-6) / 1e9}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -395,6 +413,11 @@ def main() -> int:
             measured = lds_read_ceiling(B, torch, stream)
             out["roofline"]["lds"]["measured_read_kernel"] = measured
             out["roofline"]["lds"]["frac_of_measured"] = out["roofline"]["lds"]["achieved"] / measured["GB/s"]
+            # and the look-up + add instruction mix without anything else: the practical ceiling of the gather
+            mix = lookup_add_ceiling(B, torch, stream)
+            lookups = lds_bytes / 16.0
+            out["roofline"]["lds"]["measured_lookup_add_kernel"] = mix
+            out["roofline"]["lds"]["frac_of_lookup_add"] = lookups / (kernel_us * 1e-6) / 1e9 / mix["Glookups/s"]
     if graph is not None and not args.no_ceiling and not args.hot:
         try:
             out["roofline"]["stream_read_kernel"] = stream_read_ceiling(B, torch, stream, code_bytes, n_copies, args.steps)

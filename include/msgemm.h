@@ -340,6 +340,21 @@ int msgemm_calib_stream_read_shape(const void* src, size_t bytes, void* sink, in
  */
 int msgemm_calib_lds_read(int width_bytes, int reads, void* sink, size_t* bytes_out, void* stream);
 
+/*
+ * Measurement aid, not msGeMM: the inner loop of the batched kernels and
+ * nothing else.  One workgroup of 8 wavefronts per compute unit; every lane
+ * makes 128 * tiles look-ups (tiles in 1 .. 65536) of 16 bytes in a 128 KiB
+ * table at addresses formed from code bytes as the kernels form them, and adds
+ * each entry's eight fp16 columns to fp32 sums with two matrix-core
+ * instructions against the identity, the look-ups eight ahead of the adds.
+ * Timed like msgemm_run it gives the rate at which the device sustains that
+ * instruction mix: the practical ceiling of phase 2 for batches (Section 6
+ * expects phase 2 to be bound by the look-ups; here the adds cost as much).
+ * *lookups_out (host, may be NULL) receives the lane look-ups of one launch;
+ * `sink` (device, >= 4 bytes) is never written in practice.
+ */
+int msgemm_calib_lookup_add(int tiles, void* sink, size_t* lookups_out, void* stream);
+
 /* Synchronise the device, free everything the plan owns.  NULL is allowed. */
 void msgemm_destroy(msgemm_plan_t* plan);
 

@@ -21,7 +21,7 @@ OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED, ERR_INCOMPLETE, ERR_RA
 
 EXPORTS = (
     "msgemm_plan", "msgemm_plan_with_options", "msgemm_plan_codes8", "msgemm_plan_set_codebook", "msgemm_plan_get_info", "msgemm_lut_bytes", "msgemm_build_lut",
-    "msgemm_consume_lut", "msgemm_run", "msgemm_run_static", "msgemm_plan_check", "msgemm_dequant_mfma_run", "msgemm_calib_stream_read", "msgemm_calib_stream_read_shape", "msgemm_calib_lds_read", "msgemm_destroy",
+    "msgemm_consume_lut", "msgemm_run", "msgemm_run_static", "msgemm_plan_check", "msgemm_dequant_mfma_run", "msgemm_calib_stream_read", "msgemm_calib_stream_read_shape", "msgemm_calib_lds_read", "msgemm_calib_lookup_add", "msgemm_destroy",
     "msgemm_status_string", "msgemm_last_hip_error", "msgemm_version",
 )
 
@@ -122,6 +122,8 @@ def load():
     lib.msgemm_calib_stream_read_shape.restype = ci
     lib.msgemm_calib_lds_read.argtypes = [ci, ci, vp, ctypes.POINTER(ctypes.c_size_t), vp]
     lib.msgemm_calib_lds_read.restype = ci
+    lib.msgemm_calib_lookup_add.argtypes = [ci, vp, ctypes.POINTER(ctypes.c_size_t), vp]
+    lib.msgemm_calib_lookup_add.restype = ci
     lib.msgemm_destroy.argtypes = [vp]
     lib.msgemm_destroy.restype = None
     lib.msgemm_status_string.argtypes = [ci]
@@ -278,6 +280,15 @@ def msgemm_calib_lds_read(width_bytes, reads, sink, stream=None):
     rc = load().msgemm_calib_lds_read(int(width_bytes), int(reads), _ptr(sink), ctypes.byref(out), _stream(stream))
     if rc != OK:
         raise MsgemmError(rc, "msgemm_calib_lds_read")
+    return out.value
+
+
+def msgemm_calib_lookup_add(tiles, sink, stream=None):
+    """Returns the lane look-ups one launch makes."""
+    out = ctypes.c_size_t(0)
+    rc = load().msgemm_calib_lookup_add(int(tiles), _ptr(sink), ctypes.byref(out), _stream(stream))
+    if rc != OK:
+        raise MsgemmError(rc, "msgemm_calib_lookup_add")
     return out.value
 
 

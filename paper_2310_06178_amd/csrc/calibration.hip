@@ -117,7 +117,89 @@ lds_read_kernel(uint32_t* sink, int reads)
     if (all == 0x12345678u) *sink = all;
 }
 
+// The batched kernels' inner loop and nothing else: a 16-byte table look-up at an address a v_perm_b32 makes from a
+// code byte, and the two matrix-core adds (v_mfma_f32_4x4x4_16b_f16 against the identity) that put its eight fp16
+// columns into fp32 sums; eight wavefronts per compute unit over a 128 KiB table, the look-ups one chunk of eight
+// ahead of the adds, the order left to the compiler.  No code stream, no table build, no barriers: the rate at which
+// this device sustains the instruction mix, which is what bounds those kernels (LDS and matrix cores are both near
+// their limit at 256 bytes per clock per compute unit).
+constexpr int kMixWaves = 8;
+typedef _Float16 mix_h4 __attribute__((ext_vector_type(4)));
+typedef float mix_f4 __attribute__((ext_vector_type(4)));
+
+__global__ void __launch_bounds__(kMixWaves * 64)
+lookup_add_kernel(uint32_t* sink, int tiles)
+{
+    __shared__ __align__(16) unsigned char lds[2 * 65536];
+    for (int i = threadIdx.x; i < 2 * 65536 / 4; i += blockDim.x) ((uint32_t*)lds)[i] = 0x3c003800u;  // (1.0, 0.5)
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int j = lane & 15, half = (lane >> 4) & 1;
+    // sixteen "code loads" of eight code bytes each, as a wavefront holds them for one k-tile
+    uint32_t codes[16][2];
+    uint32_t h = (uint32_t)threadIdx.x * 2654435761u + 12345u;
+    for (int t = 0; t < 16; ++t)
+        for (int w = 0; w < 2; ++w) {
+            h = h * 1664525u + 1013904223u;
+            codes[t][w] = h;
+        }
+    mix_h4 onehot;
+    for (int e = 0; e < 4; ++e) onehot[e] = (_Float16)((lane & 3) == e ? 1.0f : 0.0f);
+    mix_f4 dlo[8], dhi[8];
+    for (int s = 0; s < 8; ++s) {
+        dlo[s] = mix_f4{0, 0, 0, 0};
+        dhi[s] = mix_f4{0, 0, 0, 0};
+    }
+    uint4 ent[2][8];
+    auto look = [&](int t, uint4 (&e)[8]) {
+        const uint32_t lane_off = (uint32_t)((j + t) & 15) * 16u | ((uint32_t)half << 16);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const uint32_t addr = __builtin_amdgcn_perm(codes[t][s >> 2], lane_off, 0x0c020000u | ((4u + (s & 3)) << 8));
+            e[s] = *(const uint4*)(lds + addr);
+        }
+    };
+    auto add = [&](const uint4 (&e)[8]) {
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            mix_h4 lo, up;
+            __builtin_memcpy(&lo, &e[s].x, 8);
+            __builtin_memcpy(&up, &e[s].z, 8);
+            dlo[s] = __builtin_amdgcn_mfma_f32_4x4x4f16(lo, onehot, dlo[s], 0, 0, 0);
+            dhi[s] = __builtin_amdgcn_mfma_f32_4x4x4f16(up, onehot, dhi[s], 0, 0, 0);
+        }
+    };
+    for (int it = 0; it < tiles; ++it) {
+        look(0, ent[0]);
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            if (t + 1 < 16) look(t + 1, ent[(t + 1) & 1]);
+            add(ent[t & 1]);
+        }
+        // the codes are opaque again: nothing of a k-tile is hoisted out of the loop
+#pragma unroll
+        for (int t = 0; t < 16; ++t) asm volatile("" : "+v"(codes[t][0]), "+v"(codes[t][1]));
+    }
+    float total = 0.0f;
+    for (int s = 0; s < 8; ++s) total += dlo[s][0] + dhi[s][3];
+    if (total == -1.0f) *sink = 1u;  // (the sums are positive)
+}
+
 }  // namespace
+
+int launch_calib_lookup_add(int tiles, void* sink, size_t* lookups_out, hipStream_t s)
+{
+    int cus = 256, dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+        prop.multiProcessorCount > 0)
+        cus = prop.multiProcessorCount;
+    if (!sink || tiles < 1 || tiles > (1 << 16)) return MSGEMM_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(lookup_add_kernel, dim3((unsigned)cus), dim3(kMixWaves * 64), 0, s, (uint32_t*)sink, tiles);
+    MSGEMM_HIP_TRY(hipGetLastError());
+    if (lookups_out) *lookups_out = (size_t)cus * kMixWaves * 64 * 128 * (size_t)tiles;
+    return MSGEMM_OK;
+}
 
 int launch_calib_lds_read(int width_bytes, int reads, void* sink, size_t* bytes_out, hipStream_t s)
 {

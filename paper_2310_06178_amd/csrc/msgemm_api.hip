@@ -457,6 +457,11 @@ int msgemm_calib_stream_read_shape(const void* src, size_t bytes, void* sink, in
                                                   non_temporal, (hipStream_t)stream);
 }
 
+int msgemm_calib_lookup_add(int tiles, void* sink, size_t* lookups_out, void* stream)
+{
+    return msgemm::launch_calib_lookup_add(tiles, sink, lookups_out, (hipStream_t)stream);
+}
+
 int msgemm_calib_lds_read(int width_bytes, int reads, void* sink, size_t* bytes_out, void* stream)
 {
     return msgemm::launch_calib_lds_read(width_bytes, reads, sink, bytes_out, (hipStream_t)stream);

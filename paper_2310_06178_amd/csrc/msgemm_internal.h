@@ -127,6 +127,7 @@ int launch_calib_stream_read(const void* src, size_t bytes, void* sink, hipStrea
 int launch_calib_stream_read_shape(const void* src, size_t bytes, void* sink, int waves_per_workgroup,
                                    int workgroups_per_cu, int depth, int non_temporal, hipStream_t s);
 int launch_calib_lds_read(int width_bytes, int reads, void* sink, size_t* bytes_out, hipStream_t s);
+int launch_calib_lookup_add(int tiles, void* sink, size_t* lookups_out, hipStream_t s);
 
 // kernels_mfma.hip
 int launch_dequant_mfma(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s);

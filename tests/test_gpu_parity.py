@@ -1128,6 +1128,19 @@ def test_calibration_lds_read_entry_point():
         B.msgemm_calib_lds_read(16, 64, None)
 
 
+def test_calibration_lookup_add_entry_point():
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert B.msgemm_calib_lookup_add(3, sink) == cus * 8 * 64 * 128 * 3
+    torch.cuda.synchronize()
+    assert int(sink[0]) == 0
+    for tiles in (0, -1, (1 << 16) + 1):
+        with pytest.raises(B.MsgemmError):
+            B.msgemm_calib_lookup_add(tiles, sink)
+    with pytest.raises(B.MsgemmError):
+        B.msgemm_calib_lookup_add(1, None)
+
+
 def test_calibration_stream_read_entry_point():
     """The measurement aid accepts whole multiples of its launch footprint only and leaves the sink alone."""
     cus = torch.cuda.get_device_properties(0).multi_processor_count
