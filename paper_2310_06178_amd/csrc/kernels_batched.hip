@@ -56,7 +56,7 @@ template <int LB> constexpr int batched_waves() { return LB == 8 ? 8 : 12; }
 // an address.  Lanes served together hold different g % 16, i.e. different banks.
 constexpr int kBCodeStride = 256;        // bytes between the entries of consecutive codes within a half
 constexpr int kBHalfBytes = 256 * kBCodeStride;
-constexpr int kBRing = 8;                // code loads a wavefront keeps in flight
+constexpr int kBRing = 8;                // code loads a wavefront keeps in flight (16 measured no faster)
 // table look-ups issued ahead of the adds that use them (a power of two, at most the rows per load)
 #ifndef MSGEMM_BATCHED_LOOKAHEAD
 #define MSGEMM_BATCHED_LOOKAHEAD 8
