@@ -115,6 +115,13 @@ __device__ __forceinline__ unsigned tag_partial(int v, unsigned parity) { return
 __device__ __forceinline__ void untag_partial(float& d, unsigned u) { d = __uint_as_float(u & ~1u); }
 __device__ __forceinline__ void untag_partial(int& d, unsigned u) { d = (int)u >> 1; }
 
+// Which lane's rows the partial sums of slot group l (= slot / sums per lane) of a panel belong to.  The
+// single-column kernels store lane by lane (owner = l).  The batched kernels get their sums from the matrix cores
+// transposed within quads of lanes -- register i of lane (quad, j) belongs to the rows of lane 4 quad + i -- and
+// store them quad-major, slot group 16 i + quad: the 16 quads of one store instruction then write one contiguous
+// run per batch column instead of 16-byte pieces 64 bytes apart.
+__device__ __forceinline__ int slot_owner(int l, int quad_major) { return quad_major ? 4 * (l & 15) + (l >> 4) : l; }
+
 template <int N, int AUX>
 __device__ __forceinline__ void store_partials(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, const unsigned (&v)[N])
 {

@@ -253,8 +253,8 @@ __device__ __forceinline__ void reduce_segments_resident(const BatchedArgs& a, u
 #pragma unroll
                 for (int e = 0; e < 4; ++e) sum[e] += other[e];
             }
-            // piece -> (column, partial-sum slots of a panel); slot f of a panel belongs to lane f / kFinal of the
-            // wavefront that made it, output f % kFinal: row 64 (f % kFinal) + f / kFinal
+            // piece -> (column, partial-sum slots of a panel); slot f of a panel belongs to lane slot_owner(f / kFinal)
+            // of the wavefront that made it, output f % kFinal: row 64 (f % kFinal) + that lane
             const int64_t f = piece * 4;
             const int64_t col = f / a.m_pad, rr = f % a.m_pad;
             const int64_t panel = rr / kPanelRowsR;
@@ -262,7 +262,7 @@ __device__ __forceinline__ void reduce_segments_resident(const BatchedArgs& a, u
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int qe = q0 + e;
-                const int64_t row = panel * kPanelRowsR + 64 * (qe % kFinal) + qe / kFinal;
+                const int64_t row = panel * kPanelRowsR + 64 * (qe % kFinal) + slot_owner(qe / kFinal, 1);
                 if (row < a.m && col < a.b) Y[col * a.ldy + row] = to_output<YT, AT>(sum[e]);
             }
         }
@@ -575,8 +575,9 @@ batched_kernel(BatchedArgs a)
                     else v = fin[s];
                     out[s] = a.resident ? tag_partial(v, parity) : bits_of(v);
                 }
+                // (slot group 16 i + quad: the quads of this store are neighbours in memory, see slot_owner)
                 const uint32_t off =
-                    (uint32_t)((((int64_t)seg * a.b_pad + col) * a.m_pad + (int64_t)panel * kBPanelRows + owner * kBFinal) * 4);
+                    (uint32_t)((((int64_t)seg * a.b_pad + col) * a.m_pad + (int64_t)panel * kBPanelRows + (16 * i + quad) * kBFinal) * 4);
                 if (!a.resident) store_partials<kBFinal, 0>(part_rsrc, off, out);
                 else if (a.publish) store_partials<kBFinal, kAuxSc1>(part_rsrc, off, out);
             }
@@ -879,8 +880,9 @@ batched_pipe_kernel(BatchedArgs a)
                     else v = fin[s];
                     out[s] = a.resident ? tag_partial(v, parity) : bits_of(v);
                 }
+                // (slot group 16 i + quad: the quads of this store are neighbours in memory, see slot_owner)
                 const uint32_t off =
-                    (uint32_t)((((int64_t)seg * a.b_pad + col) * a.m_pad + (int64_t)panel * kPanelRows + owner * kPLB) * 4);
+                    (uint32_t)((((int64_t)seg * a.b_pad + col) * a.m_pad + (int64_t)panel * kPanelRows + (16 * i + quad) * kPLB) * 4);
                 if (!a.resident) store_partials<kPLB, 0>(part_rsrc, off, out);
                 else if (a.publish) store_partials<kPLB, kAuxSc1>(part_rsrc, off, out);
             }

@@ -1338,7 +1338,7 @@ constexpr int kReduceWaves = 4;
 template <typename YT, typename AT, int F>
 __global__ void __launch_bounds__(kReduceWaves * 64)
 reduce_kernel(const float* __restrict__ partials, YT* __restrict__ Y, int64_t ldy, int64_t m, int64_t b,
-              int64_t m_pad, int64_t b_pad, int ktiles, int64_t span)
+              int64_t m_pad, int64_t b_pad, int ktiles, int64_t span, int quad_major)
 {
     __shared__ AT wave_sum[kReduceWaves][64];
     const int lane = threadIdx.x & 63;
@@ -1376,7 +1376,7 @@ reduce_kernel(const float* __restrict__ partials, YT* __restrict__ Y, int64_t ld
         const int64_t f = chunk * 64 + lane;
         const int64_t panel = f / (64 * F);
         const int in_panel = (int)(f % (64 * F));
-        const int64_t row = panel * (64 * F) + 64 * (in_panel % F) + in_panel / F;
+        const int64_t row = panel * (64 * F) + 64 * (in_panel % F) + slot_owner(in_panel / F, quad_major);
         if (row < m) Y[col * ldy + row] = to_output<YT, AT>(total);
     }
 }
@@ -1389,7 +1389,7 @@ constexpr int kFewSlices = 16;
 template <typename YT, typename AT, int F, int kMax>
 __global__ void __launch_bounds__(64)
 reduce_few_kernel(const float* __restrict__ partials, YT* __restrict__ Y, int64_t ldy, int64_t m, int64_t b,
-                  int64_t m_pad, int64_t b_pad, int slices, int64_t span)
+                  int64_t m_pad, int64_t b_pad, int slices, int64_t span, int quad_major)
 {
     const int lane = threadIdx.x;
     const int64_t chunks_per_col = m_pad / 256;
@@ -1417,7 +1417,7 @@ reduce_few_kernel(const float* __restrict__ partials, YT* __restrict__ Y, int64_
         const int64_t f = chunk * 256 + lane * 4 + e;
         const int64_t panel = f / (64 * F);
         const int in_panel = (int)(f % (64 * F));
-        const int64_t row = panel * (64 * F) + 64 * (in_panel % F) + in_panel / F;
+        const int64_t row = panel * (64 * F) + 64 * (in_panel % F) + slot_owner(in_panel / F, quad_major);
         if (row < m) Y[col * ldy + row] = to_output<YT, AT>(sum[e]);
     }
 }
@@ -1530,7 +1530,7 @@ int launch_one(const Plan& p, FusedArgs& a, hipStream_t s)
     if (a.reduce_mode == kReduceSecondPass) {
         const int64_t blocks = (a.m_pad / 64) * a.b;
         hipLaunchKernelGGL((reduce_kernel<YT, AT, kFinal>), dim3((unsigned)blocks), dim3(kReduceWaves * 64), 0, s,
-                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.slices, a.partial_span);
+                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.slices, a.partial_span, 0);
         MSGEMM_HIP_TRY(hipGetLastError());
     }
     return MSGEMM_OK;
@@ -1550,7 +1550,7 @@ int launch_long(const Plan& p, FusedArgs& a, hipStream_t s)
     if (a.reduce_mode == kReduceSecondPass) {
         const int64_t blocks = (a.m_pad / 64) * a.b;
         hipLaunchKernelGGL((reduce_kernel<YT, AT, 4>), dim3((unsigned)blocks), dim3(kReduceWaves * 64), 0, s,
-                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.slices, a.partial_span);
+                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.slices, a.partial_span, 0);
         MSGEMM_HIP_TRY(hipGetLastError());
     }
     return MSGEMM_OK;
@@ -1581,7 +1581,7 @@ int launch_wide(const Plan& p, FusedArgs& a, hipStream_t s)
     if (a.reduce_mode == kReduceSecondPass) {
         const int64_t blocks = (a.m_pad / 64) * a.b;
         hipLaunchKernelGGL((reduce_kernel<YT, AT, 4>), dim3((unsigned)blocks), dim3(kReduceWaves * 64), 0, s,
-                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.slices, a.partial_span);
+                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.slices, a.partial_span, 0);
         MSGEMM_HIP_TRY(hipGetLastError());
     }
     return MSGEMM_OK;
@@ -1810,19 +1810,20 @@ int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int
     const int64_t b_pad = (int64_t)p.col_passes * p.fs.cols;
     const dim3 grid((unsigned)((p.m_pad / 64) * p.b)), blk(kReduceWaves * 64);
     const int f = p.fs.panel_rows / 64;  // outputs per lane of the producing kernel: 8, 4 or 2
+    const int qm = p.fs.entry_bytes == 2;  // the batched kernels store their sums quad-major (slot_owner)
     const bool few = slices <= kFewSlices && p.m_pad % 256 == 0;
     const dim3 fgrid((unsigned)((p.m_pad / 256) * p.b)), fblk(64);
 #define MSGEMM_REDUCE_FEW(YT, AT, FF)                                                                           \
     do {                                                                                                        \
         if (slices <= 4)                                                                                        \
             hipLaunchKernelGGL((reduce_few_kernel<YT, AT, FF, 4>), fgrid, fblk, 0, s, partials, (YT*)Y, ldy, p.m, p.b,  \
-                               p.m_pad, b_pad, slices, span);                                                   \
+                               p.m_pad, b_pad, slices, span, qm);                                               \
         else if (slices <= 8)                                                                                   \
             hipLaunchKernelGGL((reduce_few_kernel<YT, AT, FF, 8>), fgrid, fblk, 0, s, partials, (YT*)Y, ldy, p.m, p.b,  \
-                               p.m_pad, b_pad, slices, span);                                                   \
+                               p.m_pad, b_pad, slices, span, qm);                                               \
         else                                                                                                    \
             hipLaunchKernelGGL((reduce_few_kernel<YT, AT, FF, 16>), fgrid, fblk, 0, s, partials, (YT*)Y, ldy, p.m, p.b, \
-                               p.m_pad, b_pad, slices, span);                                                   \
+                               p.m_pad, b_pad, slices, span, qm);                                               \
     } while (0)
 #define MSGEMM_REDUCE(YT, AT)                                                                                   \
     if (few && f == 8) MSGEMM_REDUCE_FEW(YT, AT, 8);                                                            \
@@ -1830,13 +1831,13 @@ int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int
     else if (few) MSGEMM_REDUCE_FEW(YT, AT, 2);                                                                 \
     else if (f == 8)                                                                                            \
         hipLaunchKernelGGL((reduce_kernel<YT, AT, 8>), grid, blk, 0, s, partials, (YT*)Y, ldy, p.m, p.b, p.m_pad, \
-                           b_pad, slices, span);                                                                \
+                           b_pad, slices, span, qm);                                                      \
     else if (f == 4)                                                                                            \
         hipLaunchKernelGGL((reduce_kernel<YT, AT, 4>), grid, blk, 0, s, partials, (YT*)Y, ldy, p.m, p.b, p.m_pad, \
-                           b_pad, slices, span);                                                                \
+                           b_pad, slices, span, qm);                                                      \
     else                                                                                                        \
         hipLaunchKernelGGL((reduce_kernel<YT, AT, 2>), grid, blk, 0, s, partials, (YT*)Y, ldy, p.m, p.b, p.m_pad, \
-                           b_pad, slices, span);
+                           b_pad, slices, span, qm);
     switch (p.y_dtype) {
     case MSGEMM_F32: MSGEMM_REDUCE(float, float) break;
     case MSGEMM_F16: MSGEMM_REDUCE(__half, float) break;
