@@ -1,6 +1,6 @@
 """ctypes binding of libmsgemm.so -- argument marshalling only.
 
-The functions carry the names of the C ABI (``include/msgemm.h``); every step of
+The functions carry the names of the C ABI (``include/msgemm.h``, ``include/msgemm_measure.h``); every step of
 the msGeMM path runs in the library's HIP kernels.  Device memory and streams
 come from PyTorch: a tensor argument is passed as its ``data_ptr()``, the stream
 defaults to torch's current stream.  There is no CPU fallback: if the library

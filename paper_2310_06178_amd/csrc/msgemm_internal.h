@@ -1,11 +1,12 @@
 // Internal declarations shared by the translation units of libmsgemm.so.
-// Nothing here is part of the public ABI (see include/msgemm.h).
+// Nothing here is part of the public ABI (see include/msgemm.h and include/msgemm_measure.h).
 #pragma once
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "msgemm.h"
+#include "msgemm_measure.h"
 
 namespace msgemm {
 

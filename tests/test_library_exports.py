@@ -1,5 +1,6 @@
 """Host-side checks that need no GPU: the C-ABI library loads and exports every
-symbol the public header declares, and the binding mirrors the header."""
+symbol the public headers declare (msgemm.h: the library; msgemm_measure.h: the
+comparison kernel and the yardsticks), and the binding mirrors the headers."""
 import ctypes
 import os
 import re
@@ -9,19 +10,26 @@ import pytest
 from paper_2310_06178_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "msgemm.h")
+INCLUDE = os.path.join(ROOT, "include")
+HEADERS = sorted(f for f in os.listdir(INCLUDE) if f.endswith(".h"))
 
 
-def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(msgemm_[a-z0-9_]+)\s*\(", text)))
+def declared_functions(headers=None):
+    names = set()
+    for h in headers or HEADERS:
+        text = open(os.path.join(INCLUDE, h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(msgemm_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_declares_the_three_named_entry_points():
-    names = declared_functions()
+    assert HEADERS == ["msgemm.h", "msgemm_measure.h"]
+    names = declared_functions(["msgemm.h"])
     for must in ("msgemm_plan", "msgemm_build_lut", "msgemm_run"):
         assert must in names
+    # the library's own header holds no measurement aid
+    assert not [n for n in names if n.startswith("msgemm_calib_") or n == "msgemm_dequant_mfma_run"]
 
 
 def test_library_exports_every_declared_symbol():
@@ -29,7 +37,7 @@ def test_library_exports_every_declared_symbol():
         pytest.fail("libmsgemm.so has not been built (python -m paper_2310_06178_amd.build)")
     lib = ctypes.CDLL(binding.LIB_PATH)
     for name in declared_functions():
-        assert hasattr(lib, name), f"{name} is declared in msgemm.h but not exported"
+        assert hasattr(lib, name), f"{name} is declared under include/ but not exported"
 
 
 def test_binding_mirrors_header():
