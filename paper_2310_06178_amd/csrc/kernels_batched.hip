@@ -56,7 +56,10 @@ template <int LB> constexpr int batched_waves() { return LB == 8 ? 8 : 12; }
 // an address.  Lanes served together hold different g % 16, i.e. different banks.
 constexpr int kBCodeStride = 256;        // bytes between the entries of consecutive codes within a half
 constexpr int kBHalfBytes = 256 * kBCodeStride;
-constexpr int kBRing = 8;                // code loads a wavefront keeps in flight (16 measured no faster)
+#ifndef MSGEMM_BATCHED_RING
+#define MSGEMM_BATCHED_RING 8
+#endif
+constexpr int kBRing = MSGEMM_BATCHED_RING;  // code loads a wavefront keeps in flight (4 and 16 measure the same on every configuration)
 // table look-ups issued ahead of the adds that use them (a power of two, at most the rows per load)
 #ifndef MSGEMM_BATCHED_LOOKAHEAD
 #define MSGEMM_BATCHED_LOOKAHEAD 8
@@ -71,6 +74,13 @@ constexpr int kBRing = 8;                // code loads a wavefront keeps in flig
 #endif
 #ifndef MSGEMM_BATCHED_LEAVE_OUT
 #define MSGEMM_BATCHED_LEAVE_OUT 0
+#endif
+// The same for batched_pipe_kernel.  Bits: 1 the matrix-core adds, 2 the table look-ups (addresses are still formed),
+// 4 the entries of the next table, 8 the barrier between k-tiles (every address stays inside LDS whatever the tables
+// hold, and no wait depends on the barrier), 32 the code loads after the first ring, 128 the activations after the
+// first two k-tiles.
+#ifndef MSGEMM_PIPE_LEAVE_OUT
+#define MSGEMM_PIPE_LEAVE_OUT 0
 #endif
 static_assert(kLoadsPerPanel % kBRing == 0, "ring slots are reused with a period dividing the panel");
 
@@ -734,7 +744,7 @@ batched_pipe_kernel(BatchedArgs a)
         const int kt = kt_begin + gen;
         const bool more = gen + 1 < ngen;   // a table to build during this k-tile
         const bool more2 = gen + 2 < ngen;  // activations to fetch for the one after it
-        if (more2) xraw = x_fetch(kt + 2);
+        if (more2 && !(MSGEMM_PIPE_LEAVE_OUT & 128)) xraw = x_fetch(kt + 2);
         if (more) build_operands((gen + 1) & 1);
         unsigned char* next_table = lds + ((gen + 1) & 1) * kPTableBytes;
         const uint32_t table_bit = (uint32_t)(gen & 1) << 16;
@@ -767,10 +777,12 @@ batched_pipe_kernel(BatchedArgs a)
                 const LoadT d = ring[t % kBRing];
                 const uint32_t addr =
                     __builtin_amdgcn_perm(load_word<kPLB>(d, s >> 2), lane_off, 0x0c020000u | ((4u + (s & 3)) << 8));
-                e[s] = *(const uint4*)(lds + addr);
+                if constexpr (MSGEMM_PIPE_LEAVE_OUT & 2) e[s] = uint4{addr, addr, addr, addr};
+                else e[s] = *(const uint4*)(lds + addr);
             };
             // once the addresses of load t are out, its ring slot takes the load kBRing ahead
             auto refill = [&](int t) {
+                if constexpr (MSGEMM_PIPE_LEAVE_OUT & 32) return;
                 ring[t % kBRing] = load_codes((t + kBRing < kLoadsPerPanel) ? code_at(kt, t + kBRing)
                                                                               : code_at(kt_next, t + kBRing - kLoadsPerPanel));
             };
@@ -788,11 +800,15 @@ batched_pipe_kernel(BatchedArgs a)
                     // load: kPLB look-ups stay in flight
 #pragma unroll
                     for (int s = 0; s < kPLB; ++s) {
-                        h4 lo, up;
-                        __builtin_memcpy(&lo, &e[s].x, 8);
-                        __builtin_memcpy(&up, &e[s].z, 8);
-                        dlo[s] = __builtin_amdgcn_mfma_f32_4x4x4f16(lo, onehot, dlo[s], 0, 0, 0);
-                        dhi[s] = __builtin_amdgcn_mfma_f32_4x4x4f16(up, onehot, dhi[s], 0, 0, 0);
+                        if constexpr (MSGEMM_PIPE_LEAVE_OUT & 1) {
+                            asm volatile("" ::"v"(e[s].x), "v"(e[s].y), "v"(e[s].z), "v"(e[s].w));  // demanded, by no instruction
+                        } else {
+                            h4 lo, up;
+                            __builtin_memcpy(&lo, &e[s].x, 8);
+                            __builtin_memcpy(&up, &e[s].z, 8);
+                            dlo[s] = __builtin_amdgcn_mfma_f32_4x4x4f16(lo, onehot, dlo[s], 0, 0, 0);
+                            dhi[s] = __builtin_amdgcn_mfma_f32_4x4x4f16(up, onehot, dhi[s], 0, 0, 0);
+                        }
                         if (t + 1 < kLoadsPerPanel) look_up(t + 1, s);
                         if constexpr (MSGEMM_PIPE_SCHED == 0) __builtin_amdgcn_sched_barrier(0);
                     }
@@ -809,6 +825,7 @@ batched_pipe_kernel(BatchedArgs a)
                     next_slot();
                 }
                 if constexpr (kBuild) {
+                    if constexpr (!(MSGEMM_PIPE_LEAVE_OUT & 4))
                     if (t % kBuildEvery == 0) build_entry(next_table, t / kBuildEvery);
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -838,9 +855,9 @@ batched_pipe_kernel(BatchedArgs a)
                 }
             }
         }
-        if (more2) x_store(gen & 1, kt + 2, xraw);
+        if (more2 && !(MSGEMM_PIPE_LEAVE_OUT & 128)) x_store(gen & 1, kt + 2, xraw);
         // everyone has finished reading table gen & 1 and writing the other one (and the activations)
-        if (more) lds_barrier();
+        if (more && !(MSGEMM_PIPE_LEAVE_OUT & 8)) lds_barrier();
     }
     const unsigned parity = a.resident ? launch_parity : 0u;
     if (active) {
