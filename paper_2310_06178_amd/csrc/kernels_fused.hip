@@ -90,7 +90,7 @@ struct FusedArgs {
     int64_t m, k, b, m_pad, b_pad;
     int ktiles, panels_total, panels_per_wg, row_blocks, col_passes;
     int row_groups;         // row_blocks * col_passes
-    int xcd_map;            // 1: workgroups that share outputs get ids congruent modulo kXcds
+    int xcd_map;            // 1: workgroups that share outputs get ids congruent modulo kXcds; 2: see column_pass_order
     int64_t nblocks;        // scale blocks per row
     int64_t partial_span;   // bytes of the partial buffer (< 2^31)
     int64_t scale_span;     // bytes of the ordered scales (< 2^31)
@@ -110,6 +110,26 @@ struct FusedArgs {
     int red_chunk;          // resident reduction: partial sums (floats, a multiple of 4) each workgroup of a row group adds up
     ValueMap values;        // value of each 4-bit pattern; last, read only by the forms built for a custom map
 };
+
+// Order of the workgroup ids when a plan has several column passes (b = 2; fp32 activations with b > 4): the passes
+// of one (row block, k-slice) unit stream the same codes, so they get ids that are congruent modulo the XCD count and
+// follow each other there -- they start together on one XCD and the second finds in that L2 what the first has
+// fetched (in any other order every pass streams its codes from memory again: 2.0x the bytes on a 300 MB GeMV).
+// Units are dealt over the XCDs; ids past the last unit do nothing.  Returns false for such an id.
+constexpr int kXcdMapColumnPasses = 2;
+__device__ __forceinline__ bool column_pass_order(const FusedArgs& a, uint32_t bid, FastDiv div_slices, int slices,
+                                                  int& slice, int& rg)
+{
+    const uint32_t n = bid / kXcds;
+    const uint32_t hi = fast_div(n, a.div_col_passes);
+    const uint32_t cp = n - hi * (uint32_t)a.col_passes;
+    const uint32_t unit = (bid % kXcds) + kXcds * hi;
+    if (unit >= (uint32_t)(slices * a.row_blocks)) return false;
+    const uint32_t rb = fast_div(unit, div_slices);
+    slice = (int)(unit - rb * (uint32_t)slices);
+    rg = (int)(rb * (uint32_t)a.col_passes + cp);
+    return true;
+}
 
 enum ReduceMode {
     kReduceDirect = 0,    // a single k-tile: the fused kernel writes Y itself
@@ -326,11 +346,15 @@ fused_kernel(FusedArgs a)
     int kt, rg;
     {
         const uint32_t bid = blockIdx.x;
-        const uint32_t n = a.xcd_map ? bid / kXcds : bid;
-        const uint32_t nq = fast_div(n, a.div_ktiles);
-        kt = (int)(n - nq * (uint32_t)a.ktiles);
-        rg = a.xcd_map ? (int)((bid % kXcds) + kXcds * nq) : (int)nq;
-        if (rg >= a.row_groups) return;
+        if (a.xcd_map == kXcdMapColumnPasses) {
+            if (!column_pass_order(a, bid, a.div_ktiles, a.ktiles, kt, rg)) return;
+        } else {
+            const uint32_t n = a.xcd_map ? bid / kXcds : bid;
+            const uint32_t nq = fast_div(n, a.div_ktiles);
+            kt = (int)(n - nq * (uint32_t)a.ktiles);
+            rg = a.xcd_map ? (int)((bid % kXcds) + kXcds * nq) : (int)nq;
+            if (rg >= a.row_groups) return;
+        }
     }
     const int rb = (int)fast_div((uint32_t)rg, a.div_col_passes);
     const int cp = rg - rb * a.col_passes;  // column passes of one row block are neighbours: the codes stay cached
@@ -669,11 +693,15 @@ fused_long_kernel(FusedArgs a)
     int sgm, rg;
     {
         const uint32_t bid = blockIdx.x;
-        const uint32_t n = a.xcd_map ? bid / kXcds : bid;
-        const uint32_t nq = fast_div(n, a.div_slices);
-        sgm = (int)(n - nq * (uint32_t)a.slices);
-        rg = a.xcd_map ? (int)((bid % kXcds) + kXcds * nq) : (int)nq;
-        if (rg >= a.row_groups) return;
+        if (a.xcd_map == kXcdMapColumnPasses) {
+            if (!column_pass_order(a, bid, a.div_slices, a.slices, sgm, rg)) return;
+        } else {
+            const uint32_t n = a.xcd_map ? bid / kXcds : bid;
+            const uint32_t nq = fast_div(n, a.div_slices);
+            sgm = (int)(n - nq * (uint32_t)a.slices);
+            rg = a.xcd_map ? (int)((bid % kXcds) + kXcds * nq) : (int)nq;
+            if (rg >= a.row_groups) return;
+        }
     }
     const int rb = (int)fast_div((uint32_t)rg, a.div_col_passes);
     const int cp = rg - rb * a.col_passes;
@@ -981,11 +1009,15 @@ fused_wide_kernel(FusedArgs a)
     int sgm, rg;
     {
         const uint32_t bid = blockIdx.x;
-        const uint32_t n = a.xcd_map ? bid / kXcds : bid;
-        const uint32_t nq = fast_div(n, a.div_slices);
-        sgm = (int)(n - nq * (uint32_t)a.slices);
-        rg = a.xcd_map ? (int)((bid % kXcds) + kXcds * nq) : (int)nq;
-        if (rg >= a.row_groups) return;
+        if (a.xcd_map == kXcdMapColumnPasses) {
+            if (!column_pass_order(a, bid, a.div_slices, a.slices, sgm, rg)) return;
+        } else {
+            const uint32_t n = a.xcd_map ? bid / kXcds : bid;
+            const uint32_t nq = fast_div(n, a.div_slices);
+            sgm = (int)(n - nq * (uint32_t)a.slices);
+            rg = a.xcd_map ? (int)((bid % kXcds) + kXcds * nq) : (int)nq;
+            if (rg >= a.row_groups) return;
+        }
     }
     const int rb = (int)fast_div((uint32_t)rg, a.div_col_passes);
     const int cp = rg - rb * a.col_passes;
@@ -1515,13 +1547,22 @@ ShapeChoice pick_shape(const Plan& p, int requested_variant)
     return lb1 == 8 ? ShapeChoice{1, 64, 8, 4, 16} : ShapeChoice{1, 64, 16, 4, 8};
 }
 
+// Workgroups that do the fused work, by the order of their ids (ids past the last unit return at once).
+static int fused_workgroups(const FusedArgs& a, int64_t slices)
+{
+    if (a.xcd_map == kXcdMapColumnPasses)
+        return (int)(kXcds * a.col_passes * ((slices * a.row_blocks + kXcds - 1) / kXcds));
+    if (a.xcd_map) return (int)(slices * kXcds * ((a.row_groups + kXcds - 1) / kXcds));
+    return (int)(slices * a.row_groups);
+}
+
 template <typename XT, typename YT, typename ET, int C, int G, int LB, int kWaves, int kValueMode>
 int launch_one(const Plan& p, FusedArgs& a, hipStream_t s)
 {
     using AT = typename EntryAcc<ET>::type;
     constexpr int kFinal = LB / (G / 16);
     auto kern = fused_kernel<XT, YT, ET, C, G, LB, kWaves, kValueMode>;
-    a.fused_wgs = a.xcd_map ? (int)(p.ktiles * kXcds * ((a.row_groups + kXcds - 1) / kXcds)) : (int)(p.ktiles * a.row_groups);
+    a.fused_wgs = fused_workgroups(a, (int64_t)p.ktiles);
     a.red_units = a.panels_total * a.col_passes;
     int64_t grid = a.fused_wgs;
     if (a.reduce_mode == kReduceInLaunch) grid += a.red_units;
@@ -1541,7 +1582,7 @@ int launch_long(const Plan& p, FusedArgs& a, hipStream_t s)
 {
     using AT = typename EntryAcc<ET>::type;
     auto kern = fused_long_kernel<XT, YT, ET, kValueMode>;
-    a.fused_wgs = a.xcd_map ? (int)(a.slices * kXcds * ((a.row_groups + kXcds - 1) / kXcds)) : (int)(a.slices * a.row_groups);
+    a.fused_wgs = fused_workgroups(a, (int64_t)a.slices);
     a.red_units = a.panels_total * a.col_passes;
     int64_t grid = a.fused_wgs;
     if (a.reduce_mode == kReduceInLaunch) grid += a.red_units;
@@ -1570,7 +1611,7 @@ int launch_wide(const Plan& p, FusedArgs& a, hipStream_t s)
     using AT = typename EntryAcc<ET>::type;
     auto kern = fused_wide_kernel<XT, YT, ET, kValueMode, kTables>;
     constexpr int kThreads = (kWideWaves + kWideBuilders) * 64;
-    a.fused_wgs = a.xcd_map ? (int)(a.slices * kXcds * ((a.row_groups + kXcds - 1) / kXcds)) : (int)(a.slices * a.row_groups);
+    a.fused_wgs = fused_workgroups(a, (int64_t)a.slices);
     if (a.reduce_mode == kReduceResident) {
         // the readers wait for workgroups of their own launch: only when all of them run at once
         static const int per_cu = resident_blocks_per_cu(kern, kThreads);  // once per instantiation
@@ -1736,7 +1777,7 @@ int fused_choose_shape(Plan& p, int requested_variant)
     p.row_blocks = (panels + ppw - 1) / ppw;
     p.m_pad = panels * fs.panel_rows;
     const int64_t row_groups = p.row_blocks * p.col_passes;
-    if ((int64_t)p.ktiles * (row_groups + kXcds) + panels * p.col_passes > 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
+    if ((int64_t)p.ktiles * (row_groups + kXcds) + (panels + kXcds) * p.col_passes > 0x7fffffffLL) return MSGEMM_ERR_UNSUPPORTED;
     // the k-tile reduction addresses the partial buffer with 32-bit byte offsets
     if (batched16 && !batched_pipe) batched_choose_segments(p);
     // The single-column kernel's forms: wide with one table (one k-tile, up to eight panels per workgroup), wide
@@ -1883,6 +1924,7 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     // (Only when the row groups divide evenly over the XCDs: otherwise some XCDs
     // would get twice the workgroups of others.)
     a.xcd_map = (a.row_groups % kXcds == 0 && p.xcd_map_allowed) ? 1 : 0;
+    if (a.col_passes > 1 && p.xcd_map_allowed) a.xcd_map = kXcdMapColumnPasses;  // (any shape: units, not row groups, are dealt)
     a.nblocks = p.nblocks;
     a.slices = p.segments > 0 ? p.segments : (int)p.ktiles;
     a.tiles_per_segment = p.segments > 0 ? p.tiles_per_segment : 1;

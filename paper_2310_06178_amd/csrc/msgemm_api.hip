@@ -214,8 +214,12 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
             if (batched)
                 p->epoch_words = (size_t)msgemm::kXcds * (size_t)p->col_passes *
                                  (((size_t)p->segments * (size_t)p->row_blocks + msgemm::kXcds - 1) / msgemm::kXcds);
-            else
-                p->epoch_words = (size_t)slices * msgemm::kXcds * (((size_t)p->row_blocks * p->col_passes + msgemm::kXcds - 1) / msgemm::kXcds);
+            else {
+                // one word per workgroup id of the grid, in either order of the ids (row groups or units dealt over the XCDs)
+                const size_t by_row_groups = (size_t)slices * msgemm::kXcds * (((size_t)p->row_blocks * p->col_passes + msgemm::kXcds - 1) / msgemm::kXcds);
+                const size_t by_units = (size_t)msgemm::kXcds * (size_t)p->col_passes * (((size_t)slices * (size_t)p->row_blocks + msgemm::kXcds - 1) / msgemm::kXcds);
+                p->epoch_words = by_row_groups > by_units ? by_row_groups : by_units;
+            }
             e = hipMalloc((void**)&p->epochs, p->epoch_words * sizeof(unsigned));
             if (e != hipSuccess) { msgemm::set_hip_error(e); return fail(MSGEMM_ERR_ALLOC); }
             e = hipMemsetAsync(p->epochs, 0, p->epoch_words * sizeof(unsigned), s);
