@@ -196,9 +196,10 @@ def stream_read_sweep(B, torch, stream, nbytes, n_copies, steps):
     return {"bytes": nbytes, "rows": rows, "hot_same_buffer_us": round(hot, 3), "launch_without_memory_us": round(empty, 3)}
 
 
-def lds_read_ceiling(B, torch, stream, width=16, reads=4096, launches=20):
+def lds_read_ceiling(B, torch, stream, width=16, reads=4096, launches=400):
     """Measured LDS read bandwidth of the device: conflict-free `width`-byte reads by 16 wavefronts on
-    every compute unit (msgemm_calib_lds_read), HIP events on the launch stream."""
+    every compute unit (msgemm_calib_lds_read), HIP events on the launch stream; some 50 ms of launches, like a
+    batched configuration's timed region (the clocks settle over the first 10 ms of sustained load)."""
     sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
     nbytes = 0
     with torch.cuda.stream(stream):
@@ -214,9 +215,10 @@ def lds_read_ceiling(B, torch, stream, width=16, reads=4096, launches=20):
     return {"width_bytes": width, "bytes": nbytes, "us": us, "GB/s": nbytes / (us * 1e-6) / 1e9}
 
 
-def lookup_add_ceiling(B, torch, stream, tiles=64, launches=10):
+def lookup_add_ceiling(B, torch, stream, tiles=64, launches=300):
     """Measured rate of the batched kernels' inner loop alone (msgemm_calib_lookup_add: a 16-byte look-up and its
-    two matrix-core adds, 8 wavefronts per compute unit, no code stream, no table build): lane look-ups per second."""
+    two matrix-core adds, 8 wavefronts per compute unit, no code stream, no table build): lane look-ups per second,
+    over some 50 ms of launches like the timed region it is compared with."""
     sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
     n = 0
     with torch.cuda.stream(stream):
@@ -277,8 +279,9 @@ def main() -> int:
 
     cfg, codes, X, scales = inputs.make_config(args.config)
     m, k, b = cfg["m"], cfg["k"], cfg["b"]
+    steps_from_warmup = args.steps is None and b > 1
     if args.steps is None:
-        args.steps = 2000 if b == 1 else 100
+        args.steps = 2000  # (batches: replaced below by a count that makes the timed region about 60 ms)
     d = cfg["d"] if args.d is None else args.d
     code_bytes = m * k // 2
     n_copies = 1 if args.hot else (1 << 30) // code_bytes + 2
@@ -305,9 +308,17 @@ def main() -> int:
     def step(i):
         run(plans[i % n_copies], dX, k, Y, m)
 
+    torch.cuda.synchronize()
+    t_warm = time.perf_counter()
     for i in range(max(args.warmup, 1)):
         step(i)
     torch.cuda.synchronize()
+    if steps_from_warmup:
+        # The device's clocks take some 10 ms of sustained load to settle after an idle gap (a step measures up to a
+        # tenth slower inside that transient), so the timed region of a batched configuration is made about 60 ms
+        # long: K from the warm-up's time per step, between 100 and 4000.  --steps overrides.
+        per_step = (time.perf_counter() - t_warm) / max(args.warmup, 1)
+        args.steps = int(min(4000, max(100, round(0.06 / max(per_step, 1e-6)))))
     if args.calib_copy:
         src = torch.ones(64 << 20, dtype=torch.uint8, device="cuda:0")
         dst = torch.empty_like(src)
