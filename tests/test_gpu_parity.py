@@ -686,6 +686,60 @@ def test_fused_repeated_calls_reuse_workspace():
         B.msgemm_destroy(plan)
 
 
+COLUMN_PASS_CASES = [
+    # m, k, b, xd, sg, options: several column passes through each form of the single-column kernels, with unit
+    # counts (row blocks x k-slices) that are no multiple of the XCD count, so ids past the last unit exist
+    (700, 768, 2, "f16", 128, {"k_tiles_per_workgroup": 1, "reduce_mode": 2}),                      # plain form, 3 units
+    (2300, 1280, 3, "bf16", 256, {"k_tiles_per_workgroup": 1, "reduce_mode": 1, "panels_per_workgroup": 4}),  # 3 x 10 units, 3 passes
+    (1030, 640, 3, "f16", 128, {"k_tiles_per_workgroup": 2, "reduce_mode": 3, "panels_per_workgroup": 3}),    # wide, two tables: 2 x 3 units
+    (515, 1024, 2, "f32", 0, {"k_tiles_per_workgroup": 1, "reduce_mode": 3, "panels_per_workgroup": 8}),      # wide, one table: 8 units, resident
+    (4100, 1280, 2, "i8", 0, {"k_tiles_per_workgroup": 4, "reduce_mode": 2, "panels_per_workgroup": 16}),     # long-k: 2 x 3 units
+    (300, 8320, 5, "f16", 0, {"k_tiles_per_workgroup": 7, "reduce_mode": 1}),                                # long-k, 10 units, 5 passes
+    (1500, 640, 10, "f32", 64, {}),                                                                          # four fp32 columns per entry: 3 passes
+]
+
+
+@pytest.mark.parametrize("m,k,b,xd,sg,options", COLUMN_PASS_CASES)
+def test_column_passes_of_the_single_column_kernels(m, k, b, xd, sg, options):
+    """Plans with several column passes (b = 2, full-width tables requested for wider batches, fp32 activations
+    beyond four columns): the passes of one (row block, k-slice) unit get neighbouring workgroup ids on one XCD.
+    Every form and reduction mode of the single-column kernels, twice on one plan."""
+    codes = inputs.make_codes(m, k, seed=m + 3 * k + b)
+    scales = inputs.make_scales(m, k, sg, seed=8) if sg else None
+    dC = torch_io.to_device(codes, "codes")
+    dS = torch_io.to_device(scales, "scales")
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS, B.VARIANT_FUSED_LDS, options=options or None)
+    try:
+        info = B.msgemm_plan_get_info(plan)
+        assert info["variant"] == B.VARIANT_FUSED_LDS and -(-b // info["col_chunk"]) > 1
+        for rep in range(2):
+            X = inputs.make_x(k, b, xd, seed=57 + rep)
+            dX = torch_io.to_device(X, xd)
+            Y = torch_io.empty_output(b, m, Y_OF_X[xd], ldy=m + 5)
+            Y.fill_(-3)
+            B.msgemm_run(plan, dX, k, Y, m + 5)
+            torch.cuda.synchronize()
+            out = torch_io.to_host(Y)
+            check(np.ascontiguousarray(out[:, :m]), oracle_y(codes, X, xd, scales, sg), xd,
+                  f"column passes {options} call {rep}", elem_bound(codes, X, xd, scales, sg))
+            minus3 = torch_io.to_host(torch.full((1,), -3, dtype=Y.dtype))[0]
+            assert np.all(out[:, m:] == minus3), "output padding was written"
+        assert B.msgemm_plan_check(plan) == B.OK
+    finally:
+        B.msgemm_destroy(plan)
+
+
+def test_two_columns_at_full_size():
+    """The paper's 12288 x 49152 GeMM (Section 5) with two activation vectors: two column passes through the long-k
+    form, 234 units over 8 XCDs, every row against the oracle."""
+    m, k, b, xd = 12288, 49152, 2, "f16"
+    codes = inputs.make_codes(m, k, seed=41)
+    X = inputs.make_x(k, b, xd, seed=42)
+    out, info = run_gpu(codes, X, xd, None, 0, 2, B.VARIANT_AUTO)
+    assert info["variant"] == B.VARIANT_FUSED_LDS and info["col_chunk"] == 1
+    check(out, oracle_y(codes, X, xd, None, 0), xd, "mlp1 shape, b = 2", elem_bound(codes, X, xd, None, 0))
+
+
 # ---------------------------------------------------------------------------
 # the benchmark configurations at full size, library's own choice of variant
 
