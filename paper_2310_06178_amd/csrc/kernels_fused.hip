@@ -1457,7 +1457,7 @@ reduce_few_kernel(const float* __restrict__ partials, YT* __restrict__ Y, int64_
 // One-off reorder of the row-major code bytes into streaming order:
 // [load t][k-tile][panel][lane][LB], or, kPanelMajor, [panel][k-tile][load t][lane][LB]
 // (a wavefront that runs through the k-tiles of its panel then reads one
-// sequential stream).
+// sequential stream; with LB = 8 the loads t and t + 1 of a lane sit side by side).
 // kInverse: the other way round, streaming order back to row-major (for the entry points that read the
 // weights row by row: the plan keeps no row-major copy of its own until one of them is called).
 template <int G, int LB, bool kPanelMajor = false, bool kInverse = false>
@@ -1472,14 +1472,23 @@ repack_kernel(uint8_t* __restrict__ codes, uint8_t* __restrict__ tiled, int64_t 
          o += (int64_t)gridDim.x * blockDim.x) {
         int64_t r = o;
         const int s = (int)(r % LB); r /= LB;
-        const int lane = (int)(r % 64); r /= 64;
         int64_t panel, kt;
-        int t;
-        if constexpr (kPanelMajor) {
+        int t, lane;
+        if constexpr (kPanelMajor && LB == 8) {
+            // (the pipelined batched form with 8 rows per lane fetches two loads of a lane at once:
+            // [panel][k-tile][load / 2][lane][load % 2][8])
+            const int tp = (int)(r % 2); r /= 2;
+            lane = (int)(r % 64); r /= 64;
+            t = 2 * (int)(r % (kLoadsPerPanel / 2)) + tp; r /= kLoadsPerPanel / 2;
+            kt = r % ktiles;
+            panel = r / ktiles;
+        } else if constexpr (kPanelMajor) {
+            lane = (int)(r % 64); r /= 64;
             t = (int)(r % kLoadsPerPanel); r /= kLoadsPerPanel;
             kt = r % ktiles;
             panel = r / ktiles;
         } else {
+            lane = (int)(r % 64); r /= 64;
             panel = r % panels_total; r /= panels_total;
             kt = r % ktiles;
             t = (int)(r / ktiles);
