@@ -1031,10 +1031,42 @@ static double pipe_form_choice(int64_t panels, int64_t ktiles, int tpb, int col_
     return best;
 }
 
-// Which of the two forms a problem gets: the one the models above predict to be faster, the
-// pipelined one only when by more than a tenth (the models are good to about that).  The form
-// with a build phase: 5 us of start-up, then 2.3 us of table build and 0.44 us of look-ups per
-// active wavefront for every k-tile of 64 columns.
+// The form with a build phase, modelled (microseconds): 5 us of start-up, then 2.3 us of table build and 0.44 us of
+// look-ups per active wavefront for every k-tile of 64 columns; workgroups in rounds of one per compute unit; the
+// second pass reads one partial sum per segment and output.  `ppw` panels of 256 rows per workgroup.
+static double phase_form_cost(int64_t panels, int64_t ktiles, int tpb, int col_passes, int64_t cus, int ppw)
+{
+    const int64_t row_blocks = (panels + ppw - 1) / ppw;
+    const int64_t blocks = (ktiles + tpb - 1) / tpb;  // indivisible runs of k-tiles
+    const int64_t segs = phase_form_segments(blocks, row_blocks * col_passes, cus);
+    const int64_t tiles_per_seg = ((blocks + segs - 1) / segs) * tpb;
+    const int64_t wgs = segs * row_blocks * col_passes;
+    double us = (double)((wgs + cus - 1) / cus) * (5.0 + (double)tiles_per_seg * (2.3 + 0.44 * ppw));
+    if (segs > 1) us += 3.0 + (double)segs * (double)(panels * 256) * col_passes * kBC * 4.0 / 3.0e6;
+    return us;
+}
+
+// Panels per workgroup of that form.  As many as its wavefronts while that still gives every compute unit a
+// workgroup, else half, a quarter, ...; between such a count and the next lower one the model above decides: one
+// panel less per workgroup can turn a grid that leaves compute units idle into one that fills them (56 panels:
+// 7 row blocks of 8 are 224 workgroups on 256 compute units, 8 of 7 are 256 -- measured 2 % faster).
+int batched_phase_form_panels(int64_t panels, int64_t ktiles, int64_t scale_group, int col_passes, int64_t cus)
+{
+    int ppw = 8;
+    while (ppw > 1 && ktiles * col_passes * ((panels + ppw - 1) / ppw) < cus) ppw >>= 1;
+    const int tpb = scale_group > 0 ? (int)(scale_group / (2 * kBG)) : 1;
+    if (tpb < 1) return ppw;
+    int best = ppw;
+    double best_us = phase_form_cost(panels, ktiles, tpb, col_passes, cus, ppw);
+    for (int c = ppw - 1; c > ppw / 2 && c >= 1; --c) {
+        const double us = phase_form_cost(panels, ktiles, tpb, col_passes, cus, c);
+        if (us < best_us - 1e-9) { best_us = us; best = c; }
+    }
+    return best;
+}
+
+// Which of the two forms a problem gets: the one the models predict to be faster, the pipelined
+// one only when by more than a tenth (the models are good to about that).
 bool batched_pipelined_is_faster(int64_t m, int64_t k, int64_t b, int64_t scale_group, int cus)
 {
     const int col_passes = (int)((b + kBC - 1) / kBC);
@@ -1045,17 +1077,10 @@ bool batched_pipelined_is_faster(int64_t m, int64_t k, int64_t b, int64_t scale_
                                             col_passes, cus, 8, 8, ppw, per);
     // form with a build phase: 256-row panels, k-tiles of 64 columns
     const int64_t panels = (m + 255) / 256, ktiles = (k / 2 + kBG - 1) / kBG;
-    int ppw0 = 8;
-    while (ppw0 > 1 && ktiles * col_passes * ((panels + ppw0 - 1) / ppw0) < cus) ppw0 >>= 1;
-    const int64_t row_blocks = (panels + ppw0 - 1) / ppw0;
     const int tpb = scale_group > 0 ? (int)(scale_group / (2 * kBG)) : 1;
     if (tpb < 1) return true;  // scale blocks of 32 columns: only the pipelined form has k-tiles that small
-    const int64_t blocks = (ktiles + tpb - 1) / tpb;
-    const int64_t segs = phase_form_segments(blocks, row_blocks * col_passes, cus);
-    const int64_t tiles_per_seg = ((blocks + segs - 1) / segs) * tpb;
-    const int64_t wgs = segs * row_blocks * col_passes;
-    double phase_us = (double)((wgs + cus - 1) / cus) * (5.0 + (double)tiles_per_seg * (2.3 + 0.44 * ppw0));
-    if (segs > 1) phase_us += 3.0 + (double)segs * (double)(panels * 256) * col_passes * kBC * 4.0 / 3.0e6;
+    const int ppw0 = batched_phase_form_panels(panels, ktiles, scale_group, col_passes, cus);
+    const double phase_us = phase_form_cost(panels, ktiles, tpb, col_passes, cus, ppw0);
     return pipe_us < 0.9 * phase_us;
 }
 

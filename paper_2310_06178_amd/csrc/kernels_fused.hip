@@ -1769,6 +1769,9 @@ int fused_choose_shape(Plan& p, int requested_variant)
     p.segments = 0;
     p.tiles_per_segment = 0;
     if (batched_pipe) batched_choose_rows_and_segments(p, panels, ppw);
+    // (the batched form with a build phase, 8 rows per lane: the count between two halvings that its time model prefers)
+    if (batched16 && !batched_pipe && sc.LB == 8)
+        ppw = batched_phase_form_panels(panels, p.ktiles, p.scale_group, p.col_passes, cus);
     // Eight panels of one k-tile per workgroup and four panels of two are the same workgroups with the same
     // work; the second form halves the partial sums per output (measured on the 32 MiB GEMV: 10.8 -> 10.55 us).
     if (can_run_long && tps == 1 && ppw == kWideWaves && p.ktiles >= 2 && p.opt.k_tiles_per_workgroup == 0 &&

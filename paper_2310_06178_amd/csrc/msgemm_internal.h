@@ -120,6 +120,8 @@ void batched_choose_segments(Plan& p);  // needs ktiles, row_blocks, col_passes,
 void batched_choose_rows_and_segments(Plan& p, int64_t panels, int& ppw_out);
 // which form of the batched kernel the time models predict to be faster for a problem
 bool batched_pipelined_is_faster(int64_t m, int64_t k, int64_t b, int64_t scale_group, int cus);
+// panels of 256 rows per workgroup of the batched form with a build phase (8 rows per lane)
+int batched_phase_form_panels(int64_t panels, int64_t ktiles, int64_t scale_group, int col_passes, int64_t cus);
 int launch_repack_scales_batched(const Plan& p, hipStream_t s);
 int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s);
 
