@@ -72,10 +72,11 @@ typedef enum {
     /* Two launches: L is written to device memory once and shared by all rows
      * (the paper's "L kept in cache", Section 4); any d in 1..4. */
     MSGEMM_VARIANT_GLOBAL_LUT = 1,
-    /* One launch, d = 2: each workgroup builds the tables of its k-tile in LDS
+    /* One launch, d = 2: each workgroup builds the tables of its k-tiles in LDS
      * (phase 1 and 2 pipelined over the last dimension of L, Section 4), streams
-     * its repacked code tile; partial sums over k-tiles are added by trailing
-     * workgroups of the same launch (b <= 2) or by a small second kernel.
+     * its repacked code tiles; partial sums over k-tiles are added inside the
+     * launch (b <= 2: by the workgroups that produced them, or by trailing
+     * workgroups) or by a small second kernel.
      * Table entries are fp32 (int32 for int8 X).  A scale block must be a whole
      * number of k-tiles: scale_group % 128 == 0, or % 64 == 0 for fp32 X with
      * b > 2; otherwise MSGEMM_ERR_UNSUPPORTED, and AUTO takes GLOBAL_LUT.
@@ -157,10 +158,11 @@ typedef struct {
 
 /*
  * Validate an m x k x b problem (Section 2), choose the kernel variant and
- * tile shape, and make the plan's own device copies of the weights: the
- * row-major codes, the scales and, for the fused variant, the codes reordered
- * into the order the kernel streams them.  M is a static model weight
- * (Section 1), so this is one-off work outside the hot path.
+ * tile shape, and make the plan's own device copies of the weights: the scales
+ * and the codes -- row-major for the two-launch variants, reordered into the
+ * order the kernels stream them for the fused ones (which keep no row-major
+ * copy: see msgemm_consume_lut).  M is a static model weight (Section 1), so
+ * this is one-off work outside the hot path.
  *
  *   d            1..4 (Section 5: larger d is never useful), or 0 = library's choice
  *   scale_group  0 = no scales; else the number r of consecutive row elements
