@@ -70,7 +70,7 @@ typedef enum {
 typedef enum {
     MSGEMM_VARIANT_AUTO = 0,
     /* Two launches: L is written to device memory once and shared by all rows
-     * (the paper's "L kept in cache", Section 4); any d in 1..4. */
+     * (the arrangement of Section 4: one L, kept in cache between the phases); any d in 1..4. */
     MSGEMM_VARIANT_GLOBAL_LUT = 1,
     /* One launch, d = 2: each workgroup builds the tables of its k-tiles in LDS
      * (phase 1 and 2 pipelined over the last dimension of L, Section 4), streams
