@@ -686,6 +686,46 @@ def test_fused_repeated_calls_reuse_workspace():
         B.msgemm_destroy(plan)
 
 
+BACK_TO_BACK_CASES = [
+    # m, k, b, xd, sg, variant, options: the reductions that hand partial sums over inside a launch
+    (2049, 1024, 1, "f16", 128, B.VARIANT_FUSED_LDS, {"k_tiles_per_workgroup": 2, "reduce_mode": 3}),   # wide form, parity-tagged sums
+    (1024, 1024, 1, "f32", 0, B.VARIANT_FUSED_LDS, None),                                                 # config 1's own choice
+    (700, 1024, 1, "f16", 128, B.VARIANT_FUSED_LDS, {"k_tiles_per_workgroup": 3, "reduce_mode": 2}),      # long-k form, flags
+    (2300, 768, 2, "i8", 0, B.VARIANT_FUSED_LDS, {"k_tiles_per_workgroup": 1, "reduce_mode": 2}),         # plain form, flags, two column passes
+    (2100, 512, 8, "bf16", 128, B.VARIANT_FUSED_LDS16, {"batched_form": 1, "reduce_mode": 3}),            # batched, sums added in the launch
+]
+
+
+@pytest.mark.parametrize("m,k,b,xd,sg,variant,options", BACK_TO_BACK_CASES)
+def test_many_launches_back_to_back_on_one_plan(m, k, b, xd, sg, variant, options):
+    """48 launches on one plan enqueued without a wait in between, each with activations and an output buffer of its
+    own, all checked afterwards: a launch must never take a partial sum, a flag or a launch parity of its
+    predecessor for its own (the benchmark's pattern: thousands of launches, one stream, no host in between)."""
+    n = 48
+    codes = inputs.make_codes(m, k, seed=5 * m + k)
+    scales = inputs.make_scales(m, k, sg, seed=9) if sg else None
+    dC = torch_io.to_device(codes, "codes")
+    dS = torch_io.to_device(scales, "scales")
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS, variant, options=options)
+    try:
+        Xs = [inputs.make_x(k, b, xd, seed=1000 + i) for i in range(n)]
+        dXs = [torch_io.to_device(X, xd) for X in Xs]
+        Ys = [torch_io.empty_output(b, m, Y_OF_X[xd]) for _ in range(n)]
+        for Y in Ys:
+            Y.fill_(-3)
+        torch.cuda.synchronize()
+        for i in range(n):
+            B.msgemm_run(plan, dXs[i], k, Ys[i], m)
+        torch.cuda.synchronize()
+        assert B.msgemm_plan_check(plan) == B.OK
+        table16 = B.msgemm_plan_get_info(plan)["variant"] == B.VARIANT_FUSED_LDS16
+        for i in range(n):
+            check(torch_io.to_host(Ys[i]), oracle_y(codes, Xs[i], xd, scales, sg), xd, f"launch {i} of {n}",
+                  elem_bound(codes, Xs[i], xd, scales, sg, table16=table16))
+    finally:
+        B.msgemm_destroy(plan)
+
+
 COLUMN_PASS_CASES = [
     # m, k, b, xd, sg, options: several column passes through each form of the single-column kernels, with unit
     # counts (row blocks x k-slices) that are no multiple of the XCD count, so ids past the last unit exist
