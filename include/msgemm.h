@@ -288,7 +288,12 @@ int msgemm_run_static(const msgemm_plan_t* plan, const void* X, int64_t ldx,
  * the flags, so that the plan works again, and returns MSGEMM_ERR_INCOMPLETE:
  * the outputs of the msgemm_run calls on this plan since the last check are not
  * valid.  With the default poll bound (about a second of polling) a give-up
- * means that the producing workgroups never ran.  The same word records that
+ * means that the producing workgroups never ran -- which can also happen
+ * when kernels of other streams occupy the device so that the workgroups of
+ * one launch are not all resident together (the library checks that the grid
+ * fits an otherwise idle device, not what else runs); a plan made with option
+ * reduce_mode = 1 adds its partial sums in a second launch and waits for
+ * nothing inside a launch.  The same word records that
  * a kernel with 16-bit table entries met an activation too large for them
  * (see MSGEMM_VARIANT_FUSED_LDS16): then, and if no reduction gave up, the word
  * is cleared and MSGEMM_ERR_RANGE is returned.  Synchronises the stream.
