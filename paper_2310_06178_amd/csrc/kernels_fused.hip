@@ -938,7 +938,11 @@ fused_long_kernel(FusedArgs a)
 //     for its data), so the activations do not queue behind the codes;
 //   * a streaming wavefront keeps kRing loads in flight: eight wavefronts times
 //     four loads of 1 KiB is what a compute unit's memory pipeline holds; more
-//     only blocks the wavefront at the issue of a load while look-ups wait;
+//     only blocks the wavefront at the issue of a load while look-ups wait.  A
+//     workgroup with at most four streaming wavefronts (small problems: a 4096 x
+//     4096 GEMV has two) keeps eight loads in flight per wavefront instead
+//     (measured: 1024 x 1024 6.27 -> 5.76 us, 4096 x 4096 7.31 -> 6.89, 8192 x 2048
+//     6.80 -> 6.41; with eight wavefronts 9.6 -> 10.0);
 //   * the wavefronts of the two tables that share rows are added through LDS;
 //   * the sums over the slices are added by the workgroups that produced them
 //     (kReduceResident): each workgroup of a row group adds 1/slices of the row
@@ -966,6 +970,11 @@ constexpr int kWideWaves = 8, kWideBuilders = 4, kWideTableBytes = 65536;
 #ifndef MSGEMM_WIDE_RING
 #define MSGEMM_WIDE_RING 4
 #endif
+#ifndef MSGEMM_WIDE_RING_SPARSE
+#define MSGEMM_WIDE_RING_SPARSE 8
+#endif
+// code loads in flight per streaming wavefront: of a workgroup with more than four of them, and of one with fewer
+constexpr int kWideRing = MSGEMM_WIDE_RING, kWideRingSparse = MSGEMM_WIDE_RING_SPARSE;
 // Measurement builds only (never the product): -DMSGEMM_WIDE_LEAVE_OUT=<bits> leaves parts of the wide form out, so that
 // the time each part adds to a launch can be read off as a difference (the results are then wrong, of course):
 // 1 the readers (nobody adds the partial sums), 2 the partial sums' stores, 4 the look-ups (their addresses are
@@ -973,13 +982,13 @@ constexpr int kWideWaves = 8, kWideBuilders = 4, kWideTableBytes = 65536;
 #ifndef MSGEMM_WIDE_LEAVE_OUT
 #define MSGEMM_WIDE_LEAVE_OUT 0
 #endif
-template <typename XT, typename YT, typename ET, int kValueMode, int kTables>
+template <typename XT, typename YT, typename ET, int kValueMode, int kTables, int kRing>
 __global__ void __launch_bounds__((kWideWaves + kWideBuilders) * 64)
 fused_wide_kernel(FusedArgs a)
 {
     using AT = typename EntryAcc<ET>::type;
     constexpr int G = 64, LB = 16, NQ = 4, kFinal = 4, kPanelRows = 256;
-    constexpr int kRing = MSGEMM_WIDE_RING;    // code loads a wavefront keeps in flight
+    // (kRing: code loads a wavefront keeps in flight)
     constexpr int kSlots = kWideWaves / kTables;  // streaming wavefronts per table = panels per workgroup at most
     static_assert(sizeof(ET) == 4 && (kTables == 1 || kTables == 2), "entries are 4 bytes; one or two tables");
     static_assert(kLoadsPerPanel % kRing == 0 && kRing % 2 == 0, "whole passes over the ring; entries alternate between two sets");
@@ -1614,11 +1623,11 @@ template <typename K> int resident_blocks_per_cu(K kern, int threads)
     return n;
 }
 
-template <typename XT, typename YT, typename ET, int kValueMode, int kTables>
+template <typename XT, typename YT, typename ET, int kValueMode, int kTables, int kRing>
 int launch_wide(const Plan& p, FusedArgs& a, hipStream_t s)
 {
     using AT = typename EntryAcc<ET>::type;
-    auto kern = fused_wide_kernel<XT, YT, ET, kValueMode, kTables>;
+    auto kern = fused_wide_kernel<XT, YT, ET, kValueMode, kTables, kRing>;
     constexpr int kThreads = (kWideWaves + kWideBuilders) * 64;
     a.fused_wgs = fused_workgroups(a, (int64_t)a.slices);
     if (a.reduce_mode == kReduceResident) {
@@ -1640,8 +1649,15 @@ int launch_wide(const Plan& p, FusedArgs& a, hipStream_t s)
 template <typename XT, typename YT, typename ET, int kValueMode>
 int launch_wide_tables(const Plan& p, FusedArgs& a, hipStream_t s)
 {
-    if (p.wide_tables == 2) return launch_wide<XT, YT, ET, kValueMode, 2>(p, a, s);
-    return launch_wide<XT, YT, ET, kValueMode, 1>(p, a, s);
+    // streaming wavefronts of a workgroup that have a unit: panels x tables
+    const int tables = p.wide_tables == 2 ? 2 : 1;
+    const bool sparse = p.fs.panels * tables <= kWideWaves / 2;
+    if (p.wide_tables == 2) {
+        if (sparse) return launch_wide<XT, YT, ET, kValueMode, 2, kWideRingSparse>(p, a, s);
+        return launch_wide<XT, YT, ET, kValueMode, 2, kWideRing>(p, a, s);
+    }
+    if (sparse) return launch_wide<XT, YT, ET, kValueMode, 1, kWideRingSparse>(p, a, s);
+    return launch_wide<XT, YT, ET, kValueMode, 1, kWideRing>(p, a, s);
 }
 
 // integer tables have the one encoding; floating-point ones also a form that reads the plan's map
