@@ -1790,9 +1790,12 @@ int fused_choose_shape(Plan& p, int requested_variant)
         ppw = batched_phase_form_panels(panels, p.ktiles, p.scale_group, p.col_passes, cus);
     // Eight panels of one k-tile per workgroup and four panels of two are the same workgroups with the same
     // work; the second form halves the partial sums per output (measured on the 32 MiB GEMV: 10.8 -> 10.55 us).
-    if (can_run_long && tps == 1 && ppw == kWideWaves && p.ktiles >= 2 && p.opt.k_tiles_per_workgroup == 0 &&
-        p.opt.panels_per_workgroup == 0) {
-        ppw = kWideWaves / 2;
+    // The same for four panels (8192 x 4096: 7.73 -> 7.50 us); for two only when the sum runs over many k-tiles
+    // (2048 x 8192, 64 k-tiles: 8.27 -> 7.6; 4096 x 4096, 32 k-tiles: 6.89 -> 7.1, so not there): a table built
+    // for a single panel is on the critical path of a short launch.
+    if (can_run_long && tps == 1 && ppw <= kWideWaves && ppw % 2 == 0 && (ppw >= 4 || p.ktiles >= 64) && p.ktiles >= 2 &&
+        p.opt.k_tiles_per_workgroup == 0 && p.opt.panels_per_workgroup == 0) {
+        ppw /= 2;
         tps = 2;
     }
     const int forced = p.opt.panels_per_workgroup;
