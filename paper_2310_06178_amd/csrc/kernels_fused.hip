@@ -975,6 +975,11 @@ constexpr int kWideWaves = 8, kWideBuilders = 4, kWideTableBytes = 65536;
 #endif
 // code loads in flight per streaming wavefront: of a workgroup with more than four of them, and of one with fewer
 constexpr int kWideRing = MSGEMM_WIDE_RING, kWideRingSparse = MSGEMM_WIDE_RING_SPARSE;
+// rounds of 16 slices that a reader of the resident reduction requests at once
+#ifndef MSGEMM_WIDE_READ_ROUNDS
+#define MSGEMM_WIDE_READ_ROUNDS 4
+#endif
+constexpr int kReadRounds = MSGEMM_WIDE_READ_ROUNDS;
 // Measurement builds only (never the product): -DMSGEMM_WIDE_LEAVE_OUT=<bits> leaves parts of the wide form out, so that
 // the time each part adds to a launch can be read off as a difference (the results are then wrong, of course):
 // 1 the readers (nobody adds the partial sums), 2 the partial sums' stores, 4 the look-ups (their addresses are
@@ -1169,28 +1174,51 @@ fused_wide_kernel(FusedArgs a)
             const uint32_t p = p0 + (uint32_t)pc * 4u;
             const bool have = f0 + p < f1;
             AT sum[4] = {0, 0, 0, 0};
+            // kRounds x 16 slices are requested at once (a sum over 56 slices is one trip through memory, not four
+            // in a row); a round that has arrived is not requested again.  The sums are added in slice order whatever
+            // order they arrive in.  Up to 16 slices take the single-round instance: code that a wavefront runs
+            // through once is fetched from memory as it goes, and the longer instance costs a short launch 0.3 us.
+            auto add_slices = [&](auto rounds_c) {
+            constexpr int kRounds = decltype(rounds_c)::value;
 #pragma unroll 1
-            for (int sb = 0; sb < S; sb += 16) {
-                v4u v[4];
-                uint32_t off[4];
-                bool live[4];
+            for (int sb = 0; sb < S; sb += 16 * kRounds) {
+                v4u v[kRounds][4];
+                uint32_t off[kRounds][4];
+                bool live[kRounds][4];
+                bool done[kRounds];  // (the same in all lanes)
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int sl = sb + grp + 4 * u;
-                    live[u] = have && sl < S;
-                    off[u] = live[u] ? base + p * 4u + (uint32_t)sl * tile_stride : 0x7ffffff0u;  // (out of range: reads zero)
+                for (int r = 0; r < kRounds; ++r) {
+                    done[r] = sb + 16 * r >= S;  // nothing to read: no slice of this round exists
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int sl = sb + 16 * r + grp + 4 * u;
+                        live[r][u] = have && sl < S;
+                        off[r][u] = live[r][u] ? base + p * 4u + (uint32_t)sl * tile_stride : 0x7ffffff0u;  // (out of range: reads zero)
+                        v[r][u] = v4u{0u, 0u, 0u, 0u};
+                    }
                 }
 #pragma unroll 1
                 for (;;) {
                     asm volatile("" ::: "memory");
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) v[u] = __builtin_amdgcn_raw_buffer_load_b128(part_rsrc, (int)off[u], 0, kAuxSc1);
-                    bool arrived = true;
+                    for (int r = 0; r < kRounds; ++r) {
+                        if (done[r]) continue;
 #pragma unroll
-                    for (int u = 0; u < 4; ++u)
-                        arrived &= !live[u] || ((v[u].x & v[u].y & v[u].z & v[u].w & 1u) == parity &&
-                                                ((v[u].x | v[u].y | v[u].z | v[u].w) & 1u) == parity);
-                    if (__builtin_amdgcn_ballot_w64(!arrived) == 0) break;
+                        for (int u = 0; u < 4; ++u) v[r][u] = __builtin_amdgcn_raw_buffer_load_b128(part_rsrc, (int)off[r][u], 0, kAuxSc1);
+                    }
+                    bool all = true;
+#pragma unroll
+                    for (int r = 0; r < kRounds; ++r) {
+                        if (done[r]) continue;
+                        bool arrived = true;
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+                            arrived &= !live[r][u] || ((v[r][u].x & v[r][u].y & v[r][u].z & v[r][u].w & 1u) == parity &&
+                                                       ((v[r][u].x | v[r][u].y | v[r][u].z | v[r][u].w) & 1u) == parity);
+                        done[r] = __builtin_amdgcn_ballot_w64(!arrived) == 0;
+                        all &= done[r];
+                    }
+                    if (all) break;
                     if (++polls >= a.poll_limit) {
                         gave_up = true;
                         break;
@@ -1199,14 +1227,20 @@ fused_wide_kernel(FusedArgs a)
                 }
                 if (gave_up) break;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {  // (what is not live read as zero and adds nothing)
-                    AT x;
-                    untag_partial(x, live[u] ? v[u].x : 0u); sum[0] += x;
-                    untag_partial(x, live[u] ? v[u].y : 0u); sum[1] += x;
-                    untag_partial(x, live[u] ? v[u].z : 0u); sum[2] += x;
-                    untag_partial(x, live[u] ? v[u].w : 0u); sum[3] += x;
+                for (int r = 0; r < kRounds; ++r) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {  // (what is not live read as zero and adds nothing)
+                        AT x;
+                        untag_partial(x, live[r][u] ? v[r][u].x : 0u); sum[0] += x;
+                        untag_partial(x, live[r][u] ? v[r][u].y : 0u); sum[1] += x;
+                        untag_partial(x, live[r][u] ? v[r][u].z : 0u); sum[2] += x;
+                        untag_partial(x, live[r][u] ? v[r][u].w : 0u); sum[3] += x;
+                    }
                 }
             }
+            };
+            if (S <= 16) add_slices(std::integral_constant<int, 1>());
+            else add_slices(std::integral_constant<int, kReadRounds>());
             if (gave_up) break;
             // the four slice classes, in a fixed order; 16-lane row r ends with output ((r & 1) << 1) | (r >> 1) of its pieces
             const AT total = fold16(fold32(sum[0], sum[1]), fold32(sum[2], sum[3]));
