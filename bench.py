@@ -240,6 +240,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--shape", default=None, metavar="M,K,B,X,Y,SG",
+                    help="an ad-hoc problem instead of a named configuration, e.g. 4096,4096,1,f16,f16,0 "
+                         "(x / y: f32, f16, bf16, i8 / i32; SG: scale block or 0; same input recipe, seed 21)")
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph")
     ap.add_argument("--hot", action="store_true", help="one weight copy (cache-resident), labelled as such")
     ap.add_argument("--variant", type=int, default=0)
@@ -277,6 +280,10 @@ def main() -> int:
     B.load()
     torch.cuda.set_device(0)
 
+    if args.shape:
+        sm, sk, sb, sx, sy, ssg = args.shape.split(",")
+        args.config = "shape " + args.shape
+        inputs.CONFIGS[args.config] = dict(m=int(sm), k=int(sk), b=int(sb), x=sx, y=sy, scale_group=int(ssg), d=2, seed=21)
     cfg, codes, X, scales = inputs.make_config(args.config)
     m, k, b = cfg["m"], cfg["k"], cfg["b"]
     steps_from_warmup = args.steps is None and b > 1
