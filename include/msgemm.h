@@ -96,7 +96,9 @@ typedef enum {
      * (msgemm_plan_set_codebook, msgemm_plan_codes8) with a value beyond +-65504
      * are refused on such a plan; values that fp16 cannot hold exactly are rounded
      * to nearest.  Accumulation is fp32.  scale_group % 32 == 0.  Not available
-     * for fp32 X.  AUTO picks it for b > 2. */
+     * for fp32 X.  AUTO picks it for b > 2 unless the problem is small (columns
+     * times code bytes up to 64 MiB, scale blocks of whole k-tiles): then
+     * FUSED_LDS runs one pass per column, which is faster there. */
     MSGEMM_VARIANT_FUSED_LDS16 = 3,
     /* GLOBAL_LUT with half of every table (the optimisation sketched in Section
      * 4.1): only the combinations whose last code has its top bit clear are

@@ -1575,14 +1575,24 @@ struct ShapeChoice { int C, G, LB, entry_bytes, waves; };
 // is small) and 16 bits wide (fp16 / int16) with 8 columns per entry for wider
 // batches, where the gather is bound by LDS bytes and VALU adds.  int16 holds
 // the int8 table values exactly (|entry| <= 2048); fp16 entries round.
+constexpr int64_t kColumnPassBytes = 64ll << 20;  // AUTO: up to this many code bytes x columns, one pass per column
+
 ShapeChoice pick_shape(const Plan& p, int requested_variant)
 {
     // rows_per_lane = 8 selects the 16-wavefront, 128-row-panel form of the single-column kernel (an option of the
     // plan; measured within 3 % of the default on the b = 1 GEMV)
     const int lb1 = p.opt.rows_per_lane == 8 ? 8 : 16;
     const bool narrow_ok = p.x_dtype != MSGEMM_F32;
+    // A small batch on a small matrix runs the single-column kernels once per column (the passes of a unit side by
+    // side on one XCD, full-width entries): the batched kernels cost two launches and a start-up that such a problem
+    // never earns back.  Measured cross-over (fp16, scale blocks of 128; 3 to 8 columns on 1024 x 1024 to 16384 x
+    // 4096): the passes win while columns x code bytes stay below some 70 MB -- 4096 x 4096 x 4 takes 8.3 us against
+    // 14.2, 8192 x 4096 x 4 12.8 against 17.1, 8192 x 4096 x 6 20.0 against 17.4.
+    const bool by_passes = requested_variant == MSGEMM_VARIANT_AUTO && p.b > 2 &&
+                           (p.scale_group == 0 || p.scale_group % 128 == 0) &&
+                           p.b * p.m * (p.k / 2) <= kColumnPassBytes;
     const bool narrow = requested_variant == MSGEMM_VARIANT_FUSED_LDS16 ||
-                        (requested_variant == MSGEMM_VARIANT_AUTO && p.b > 2);
+                        (requested_variant == MSGEMM_VARIANT_AUTO && p.b > 2 && !by_passes);
     // (plan options: rows_per_lane = 4, the 12- resp. 16-wavefront form of the batched kernel; batched_form = 1, its
     // form with one 32-group table and a build phase per k-tile, 2 the pipelined one)
     if (narrow && narrow_ok) {
@@ -1595,7 +1605,7 @@ ShapeChoice pick_shape(const Plan& p, int requested_variant)
             return lb == 4 ? ShapeChoice{8, 16, 4, 2, 16} : ShapeChoice{8, 16, 8, 2, 8};
         return lb == 4 ? ShapeChoice{8, 32, 4, 2, 12} : ShapeChoice{8, 32, 8, 2, 8};
     }
-    if (p.b > 2 && p.x_dtype == MSGEMM_F32) return ShapeChoice{4, 32, 8, 4, 8};
+    if (p.b > 2 && p.x_dtype == MSGEMM_F32 && !by_passes) return ShapeChoice{4, 32, 8, 4, 8};
     return lb1 == 8 ? ShapeChoice{1, 64, 8, 4, 16} : ShapeChoice{1, 64, 16, 4, 8};
 }
 
