@@ -658,6 +658,123 @@ fused_kernel(FusedArgs a)
 // C = 1, G = 64, LB = 16.
 constexpr int kLongWaves = 8, kLongBuilders = 4, kLongTableBytes = 65536;
 
+// rounds of 16 slices that a reader of the resident reduction requests at once
+#ifndef MSGEMM_WIDE_READ_ROUNDS
+#define MSGEMM_WIDE_READ_ROUNDS 4
+#endif
+constexpr int kReadRounds = MSGEMM_WIDE_READ_ROUNDS;
+
+// The resident reduction's reader (see fused_wide_kernel): this workgroup's share -- 1 / slices -- of its row group's
+// outputs, read from all slices until every sum shows the launch's parity, added in slice order, written to Y.
+// `reader` of `readers` wavefronts of the workgroup share the share, 64 outputs at a time.  Waits first until the
+// workgroup's own streaming wavefronts have stored (`*stored` reaches `stored_target`).
+template <typename YT, typename AT>
+__device__ __forceinline__ void resident_reader(const FusedArgs& a, __amdgpu_buffer_rsrc_t part_rsrc, int sgm, int panel_first,
+                                                int panels_here, int64_t col0, unsigned parity, int lane, unsigned* stored,
+                                                unsigned stored_target, uint32_t col_stride, uint32_t tile_stride,
+                                                int reader, int readers)
+{
+    constexpr int kPanelRows = 256;
+    const int S = a.slices;
+    const uint32_t rg_floats = (uint32_t)panels_here * kPanelRows;
+    const uint32_t f0 = (uint32_t)sgm * (uint32_t)a.red_chunk;
+    if (f0 >= rg_floats) return;
+    const uint32_t f1 = min(f0 + (uint32_t)a.red_chunk, rg_floats);
+    // this workgroup's own partial sums are on their way: the others' are about as far (polling from the start
+    // would only add traffic)
+    while (__hip_atomic_load(stored, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < stored_target)
+        __builtin_amdgcn_s_sleep(2);
+    YT* __restrict__ Y = (YT*)a.Y;
+    const uint32_t base = (uint32_t)col0 * col_stride + ((uint32_t)panel_first * kPanelRows + f0) * 4u;
+    // lane (grp, pc): the 16-byte piece pc of a run of 16 pieces, the slices grp, grp + 4, grp + 8, ...
+    const int grp = lane >> 4, pc = lane & 15;
+    unsigned polls = 0;
+    bool gave_up = false;
+#pragma unroll 1
+    for (uint32_t p0 = 64u * (uint32_t)reader; f0 + p0 < f1 && !gave_up; p0 += 64u * (uint32_t)readers) {
+        const uint32_t p = p0 + (uint32_t)pc * 4u;
+        const bool have = f0 + p < f1;
+        AT sum[4] = {0, 0, 0, 0};
+        // kRounds x 16 slices are requested at once (a sum over 56 slices is one trip through memory, not four
+        // in a row); a round that has arrived is not requested again.  The sums are added in slice order whatever
+        // order they arrive in.  Up to 16 slices take the single-round instance: code that a wavefront runs
+        // through once is fetched from memory as it goes, and the longer instance costs a short launch 0.3 us.
+        auto add_slices = [&](auto rounds_c) {
+        constexpr int kRounds = decltype(rounds_c)::value;
+#pragma unroll 1
+        for (int sb = 0; sb < S; sb += 16 * kRounds) {
+            v4u v[kRounds][4];
+            uint32_t off[kRounds][4];
+            bool live[kRounds][4];
+            bool done[kRounds];  // (the same in all lanes)
+#pragma unroll
+            for (int r = 0; r < kRounds; ++r) {
+                done[r] = sb + 16 * r >= S;  // nothing to read: no slice of this round exists
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int sl = sb + 16 * r + grp + 4 * u;
+                    live[r][u] = have && sl < S;
+                    off[r][u] = live[r][u] ? base + p * 4u + (uint32_t)sl * tile_stride : 0x7ffffff0u;  // (out of range: reads zero)
+                    v[r][u] = v4u{0u, 0u, 0u, 0u};
+                }
+            }
+#pragma unroll 1
+            for (;;) {
+                asm volatile("" ::: "memory");
+#pragma unroll
+                for (int r = 0; r < kRounds; ++r) {
+                    if (done[r]) continue;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) v[r][u] = __builtin_amdgcn_raw_buffer_load_b128(part_rsrc, (int)off[r][u], 0, kAuxSc1);
+                }
+                bool all = true;
+#pragma unroll
+                for (int r = 0; r < kRounds; ++r) {
+                    if (done[r]) continue;
+                    bool arrived = true;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        arrived &= !live[r][u] || ((v[r][u].x & v[r][u].y & v[r][u].z & v[r][u].w & 1u) == parity &&
+                                                   ((v[r][u].x | v[r][u].y | v[r][u].z | v[r][u].w) & 1u) == parity);
+                    done[r] = __builtin_amdgcn_ballot_w64(!arrived) == 0;
+                    all &= done[r];
+                }
+                if (all) break;
+                if (++polls >= a.poll_limit) {
+                    gave_up = true;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+            }
+            if (gave_up) break;
+#pragma unroll
+            for (int r = 0; r < kRounds; ++r) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {  // (what is not live read as zero and adds nothing)
+                    AT x;
+                    untag_partial(x, live[r][u] ? v[r][u].x : 0u); sum[0] += x;
+                    untag_partial(x, live[r][u] ? v[r][u].y : 0u); sum[1] += x;
+                    untag_partial(x, live[r][u] ? v[r][u].z : 0u); sum[2] += x;
+                    untag_partial(x, live[r][u] ? v[r][u].w : 0u); sum[3] += x;
+                }
+            }
+        }
+        };
+        if (S <= 16) add_slices(std::integral_constant<int, 1>());
+        else add_slices(std::integral_constant<int, kReadRounds>());
+        if (gave_up) break;
+        // the four slice classes, in a fixed order; 16-lane row r ends with output ((r & 1) << 1) | (r >> 1) of its pieces
+        const AT total = fold16(fold32(sum[0], sum[1]), fold32(sum[2], sum[3]));
+        const int e = ((grp & 1) << 1) | (grp >> 1);
+        // partial sum f of a panel belongs to lane f / 4, output f % 4 of the producing wavefront: row 64 (f % 4) + f / 4
+        const uint32_t f = f0 + p;
+        const int64_t row = ((int64_t)panel_first + f / kPanelRows) * kPanelRows + (f % kPanelRows) / 4 + 64 * e;
+        if (have && row < a.m && col0 < a.b) Y[col0 * a.ldy + row] = to_output<YT, AT>(total);
+    }
+    // gave up: some partial sum never arrived.  The plan's error word says so (msgemm_plan_check).
+    if (gave_up && lane == 0) __hip_atomic_store(a.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 template <typename XT, typename YT, typename ET, int kValueMode>
 __global__ void __launch_bounds__((kLongWaves + kLongBuilders) * 64)
 fused_long_kernel(FusedArgs a)
@@ -670,6 +787,8 @@ fused_long_kernel(FusedArgs a)
 
     __shared__ __align__(16) unsigned char lds[2 * kLongTableBytes];
     __shared__ unsigned built[2], done[2];  // per table buffer: generations i with i & 1 == index
+    __shared__ unsigned stored;         // resident reduction: streaming wavefronts whose partial sums are on their way
+    __shared__ unsigned launch_parity;  // resident reduction: 2 | parity of this workgroup's launch count, once known
 
 #define MSGEMM_ARG_NOW(x) asm volatile("" ::"s"(x))
     MSGEMM_ARG_NOW((uint64_t)a.tiled); MSGEMM_ARG_NOW((uint64_t)a.X); MSGEMM_ARG_NOW(a.ldx);
@@ -718,7 +837,18 @@ fused_long_kernel(FusedArgs a)
         built[tid] = 0;
         done[tid] = 0;
     }
+    if (tid == 0) {
+        stored = 0;
+        launch_parity = 0;
+    }
     __syncthreads();
+
+    const uint32_t col_stride = (uint32_t)(a.m_pad * 4);
+    const uint32_t tile_stride = (uint32_t)(a.b_pad * a.m_pad * 4);
+    __amdgpu_buffer_rsrc_t part_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)a.partials, 0, (int)a.partial_span, 0x00020000);
+    // the sums over the segments added by the workgroups of this launch (fused_wide_kernel describes the scheme)
+    const bool resident = a.reduce_mode == kReduceResident;
 
     if (wave < 0) {
         // ---- builders: the tables of k-tile kt0 + i into buffer i & 1
@@ -742,6 +872,10 @@ fused_long_kernel(FusedArgs a)
                 }
             }
         }
+        // resident reduction: this workgroup's launch count (the first builder wavefront alone reads and bumps it)
+        const bool counts = resident && wave == -kLongBuilders;
+        unsigned launches = 0;
+        if (counts) launches = __hip_atomic_load(a.epochs + blockIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         for (int i = 0; i < ngen; ++i) {
             const int64_t kk = ((int64_t)(kt0 + i) * G + g) * 2;
             const bool live = (col0 < a.b) && (kk < a.k);
@@ -775,9 +909,26 @@ fused_long_kernel(FusedArgs a)
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             if (lane == 0) __hip_atomic_fetch_add(&built[i & 1], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
+        if (!resident) return;
+        // ---- the builders turn readers: together 1 / slices of the row group's outputs
+        unsigned par;
+        if (counts) {
+            launches += 1;
+            par = 2u | (launches & 1u);
+            if (lane == 0) {
+                __hip_atomic_store(a.epochs + blockIdx.x, launches, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&launch_parity, par, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        } else {
+            // (the first builder publishes it without waiting on anyone)
+            while ((par = __hip_atomic_load(&launch_parity, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) == 0)
+                __builtin_amdgcn_s_sleep(1);
+        }
+        resident_reader<YT, AT>(a, part_rsrc, sgm, panel_first, panels_here, col0, par & 1u, lane, &stored, (unsigned)active,
+                                col_stride, tile_stride, wave + kLongBuilders, kLongBuilders);
         return;
     }
-    if (wave >= active) return;  // nothing to stream; `done` does not count this wavefront
+    if (wave >= active) return;  // nothing to stream; `done` and `stored` do not count this wavefront
 
     // ---- streamers
     YT* __restrict__ Y = (YT*)a.Y;
@@ -794,8 +945,6 @@ fused_long_kernel(FusedArgs a)
         __builtin_amdgcn_sched_barrier(0);  // loads return in issue order: keep slot 0 first
     }
 
-    __amdgpu_buffer_rsrc_t part_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void*)a.partials, 0, (int)a.partial_span, 0x00020000);
     __amdgpu_buffer_rsrc_t scale_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void*)(a.scales ? (const void*)a.scales : (const void*)a.tiled), 0, a.scales ? (int)a.scale_span : 0, 0x00020000);
     const uint32_t class_base = (uint32_t)(16 * (q % NQ)) * 4u;
@@ -886,10 +1035,14 @@ fused_long_kernel(FusedArgs a)
         if (lane == 0) __hip_atomic_fetch_add(&done[gen & 1], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
 
-    // ---- one sum per (segment, row): Y, or a partial with its flag
-    const uint32_t col_stride = (uint32_t)(a.m_pad * 4);
-    const uint32_t tile_stride = (uint32_t)(a.b_pad * a.m_pad * 4);
+    // ---- one sum per (segment, row): Y, or a partial (with its flag, or tagged with the launch's parity)
     const bool in_launch = a.reduce_mode == kReduceInLaunch;
+    unsigned par = 0;
+    if (resident) {
+        // (the first builder wavefront sets it when its last table is built: long before this point)
+        while ((par = __hip_atomic_load(&launch_parity, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) == 0)
+            __builtin_amdgcn_s_sleep(1);
+    }
 #pragma unroll
     for (int pi = 0; pi < 2; ++pi) {
         if (pi >= npan) break;
@@ -904,9 +1057,13 @@ fused_long_kernel(FusedArgs a)
         }
         unsigned out[kFinal];
 #pragma unroll
-        for (int i = 0; i < kFinal; ++i) out[i] = bits_of(y_run[pi][i]);
+        for (int i = 0; i < kFinal; ++i) out[i] = resident ? tag_partial(y_run[pi][i], par & 1u) : bits_of(y_run[pi][i]);
         const uint32_t off = (uint32_t)sgm * tile_stride + (uint32_t)col0 * col_stride +
                              (uint32_t)(panel_g * kPanelRows + lane * kFinal) * 4u;
+        if (resident) {
+            if (a.publish) store_partials<kFinal, kAuxSc1>(part_rsrc, off, out);  // (publish = 0, a test aid: the readers give up)
+            continue;
+        }
         if (in_launch) store_partials<kFinal, kAuxSc1>(part_rsrc, off, out);
         else store_partials<kFinal, 0>(part_rsrc, off, out);
         if (!in_launch) continue;
@@ -915,6 +1072,8 @@ fused_long_kernel(FusedArgs a)
             __hip_atomic_store(a.flags + ((int64_t)panel_g * a.col_passes + cp) * a.slices + sgm, 1u, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
     }
+    // tell the workgroup's readers that this wavefront's sums are on their way
+    if (resident && lane == 0) __hip_atomic_fetch_add(&stored, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 // ---------------------------------------------------------------------------
@@ -975,11 +1134,6 @@ constexpr int kWideWaves = 8, kWideBuilders = 4, kWideTableBytes = 65536;
 #endif
 // code loads in flight per streaming wavefront: of a workgroup with more than four of them, and of one with fewer
 constexpr int kWideRing = MSGEMM_WIDE_RING, kWideRingSparse = MSGEMM_WIDE_RING_SPARSE;
-// rounds of 16 slices that a reader of the resident reduction requests at once
-#ifndef MSGEMM_WIDE_READ_ROUNDS
-#define MSGEMM_WIDE_READ_ROUNDS 4
-#endif
-constexpr int kReadRounds = MSGEMM_WIDE_READ_ROUNDS;
 // Measurement builds only (never the product): -DMSGEMM_WIDE_LEAVE_OUT=<bits> leaves parts of the wide form out, so that
 // the time each part adds to a launch can be read off as a difference (the results are then wrong, of course):
 // 1 the readers (nobody adds the partial sums), 2 the partial sums' stores, 4 the look-ups (their addresses are
@@ -1154,104 +1308,8 @@ fused_wide_kernel(FusedArgs a)
             __hip_atomic_store(&launch_parity, 2u | parity, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
         if (MSGEMM_WIDE_LEAVE_OUT & 1) return;
-        const int S = a.slices;
-        const uint32_t rg_floats = (uint32_t)panels_here * kPanelRows;
-        const uint32_t f0 = (uint32_t)sgm * (uint32_t)a.red_chunk;
-        if (f0 >= rg_floats) return;
-        const uint32_t f1 = min(f0 + (uint32_t)a.red_chunk, rg_floats);
-        // this workgroup's own partial sums are on their way: the others' are about as far (polling from the start
-        // would only add traffic)
-        while (__hip_atomic_load(&stored, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < (unsigned)panels_here)
-            __builtin_amdgcn_s_sleep(2);
-        YT* __restrict__ Y = (YT*)a.Y;
-        const uint32_t base = (uint32_t)col0 * col_stride + ((uint32_t)panel_first * kPanelRows + f0) * 4u;
-        // lane (grp, pc): the 16-byte piece pc of a run of 16 pieces, the slices grp, grp + 4, grp + 8, ...
-        const int grp = lane >> 4, pc = lane & 15;
-        unsigned polls = 0;
-        bool gave_up = false;
-#pragma unroll 1
-        for (uint32_t p0 = 0; f0 + p0 < f1 && !gave_up; p0 += 64u) {
-            const uint32_t p = p0 + (uint32_t)pc * 4u;
-            const bool have = f0 + p < f1;
-            AT sum[4] = {0, 0, 0, 0};
-            // kRounds x 16 slices are requested at once (a sum over 56 slices is one trip through memory, not four
-            // in a row); a round that has arrived is not requested again.  The sums are added in slice order whatever
-            // order they arrive in.  Up to 16 slices take the single-round instance: code that a wavefront runs
-            // through once is fetched from memory as it goes, and the longer instance costs a short launch 0.3 us.
-            auto add_slices = [&](auto rounds_c) {
-            constexpr int kRounds = decltype(rounds_c)::value;
-#pragma unroll 1
-            for (int sb = 0; sb < S; sb += 16 * kRounds) {
-                v4u v[kRounds][4];
-                uint32_t off[kRounds][4];
-                bool live[kRounds][4];
-                bool done[kRounds];  // (the same in all lanes)
-#pragma unroll
-                for (int r = 0; r < kRounds; ++r) {
-                    done[r] = sb + 16 * r >= S;  // nothing to read: no slice of this round exists
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int sl = sb + 16 * r + grp + 4 * u;
-                        live[r][u] = have && sl < S;
-                        off[r][u] = live[r][u] ? base + p * 4u + (uint32_t)sl * tile_stride : 0x7ffffff0u;  // (out of range: reads zero)
-                        v[r][u] = v4u{0u, 0u, 0u, 0u};
-                    }
-                }
-#pragma unroll 1
-                for (;;) {
-                    asm volatile("" ::: "memory");
-#pragma unroll
-                    for (int r = 0; r < kRounds; ++r) {
-                        if (done[r]) continue;
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) v[r][u] = __builtin_amdgcn_raw_buffer_load_b128(part_rsrc, (int)off[r][u], 0, kAuxSc1);
-                    }
-                    bool all = true;
-#pragma unroll
-                    for (int r = 0; r < kRounds; ++r) {
-                        if (done[r]) continue;
-                        bool arrived = true;
-#pragma unroll
-                        for (int u = 0; u < 4; ++u)
-                            arrived &= !live[r][u] || ((v[r][u].x & v[r][u].y & v[r][u].z & v[r][u].w & 1u) == parity &&
-                                                       ((v[r][u].x | v[r][u].y | v[r][u].z | v[r][u].w) & 1u) == parity);
-                        done[r] = __builtin_amdgcn_ballot_w64(!arrived) == 0;
-                        all &= done[r];
-                    }
-                    if (all) break;
-                    if (++polls >= a.poll_limit) {
-                        gave_up = true;
-                        break;
-                    }
-                    __builtin_amdgcn_s_sleep(1);
-                }
-                if (gave_up) break;
-#pragma unroll
-                for (int r = 0; r < kRounds; ++r) {
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {  // (what is not live read as zero and adds nothing)
-                        AT x;
-                        untag_partial(x, live[r][u] ? v[r][u].x : 0u); sum[0] += x;
-                        untag_partial(x, live[r][u] ? v[r][u].y : 0u); sum[1] += x;
-                        untag_partial(x, live[r][u] ? v[r][u].z : 0u); sum[2] += x;
-                        untag_partial(x, live[r][u] ? v[r][u].w : 0u); sum[3] += x;
-                    }
-                }
-            }
-            };
-            if (S <= 16) add_slices(std::integral_constant<int, 1>());
-            else add_slices(std::integral_constant<int, kReadRounds>());
-            if (gave_up) break;
-            // the four slice classes, in a fixed order; 16-lane row r ends with output ((r & 1) << 1) | (r >> 1) of its pieces
-            const AT total = fold16(fold32(sum[0], sum[1]), fold32(sum[2], sum[3]));
-            const int e = ((grp & 1) << 1) | (grp >> 1);
-            // partial sum f of a panel belongs to lane f / 4, output f % 4 of the producing wavefront: row 64 (f % 4) + f / 4
-            const uint32_t f = f0 + p;
-            const int64_t row = ((int64_t)panel_first + f / kPanelRows) * kPanelRows + (f % kPanelRows) / 4 + 64 * e;
-            if (have && row < a.m && col0 < a.b) Y[col0 * a.ldy + row] = to_output<YT, AT>(total);
-        }
-        // gave up: some partial sum never arrived.  The plan's error word says so (msgemm_plan_check).
-        if (gave_up && lane == 0) __hip_atomic_store(a.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        resident_reader<YT, AT>(a, part_rsrc, sgm, panel_first, panels_here, col0, parity, lane, &stored,
+                                (unsigned)panels_here, col_stride, tile_stride, 0, 1);
         return;
     }
 
@@ -1609,6 +1667,14 @@ ShapeChoice pick_shape(const Plan& p, int requested_variant)
     return lb1 == 8 ? ShapeChoice{1, 64, 8, 4, 16} : ShapeChoice{1, 64, 16, 4, 8};
 }
 
+// Workgroups of `kern` (block threads, static LDS only) that one compute unit holds at once.
+template <typename K> int resident_blocks_per_cu(K kern, int threads)
+{
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, threads, 0) != hipSuccess) return 0;
+    return n;
+}
+
 // Workgroups that do the fused work, by the order of their ids (ids past the last unit return at once).
 static int fused_workgroups(const FusedArgs& a, int64_t slices)
 {
@@ -1645,6 +1711,11 @@ int launch_long(const Plan& p, FusedArgs& a, hipStream_t s)
     using AT = typename EntryAcc<ET>::type;
     auto kern = fused_long_kernel<XT, YT, ET, kValueMode>;
     a.fused_wgs = fused_workgroups(a, (int64_t)a.slices);
+    if (a.reduce_mode == kReduceResident) {
+        // the readers wait for workgroups of their own launch: only when all of them run at once; else trailing ones
+        static const int per_cu = resident_blocks_per_cu(kern, (kLongWaves + kLongBuilders) * 64);  // once per instantiation
+        if ((int64_t)a.fused_wgs > (int64_t)per_cu * p.cus) a.reduce_mode = kReduceInLaunch;
+    }
     a.red_units = a.panels_total * a.col_passes;
     int64_t grid = a.fused_wgs;
     if (a.reduce_mode == kReduceInLaunch) grid += a.red_units;
@@ -1657,14 +1728,6 @@ int launch_long(const Plan& p, FusedArgs& a, hipStream_t s)
         MSGEMM_HIP_TRY(hipGetLastError());
     }
     return MSGEMM_OK;
-}
-
-// Workgroups of `kern` (block threads, static LDS only) that one compute unit holds at once.
-template <typename K> int resident_blocks_per_cu(K kern, int threads)
-{
-    int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, threads, 0) != hipSuccess) return 0;
-    return n;
 }
 
 template <typename XT, typename YT, typename ET, int kValueMode, int kTables, int kRing>
@@ -2024,7 +2087,15 @@ int launch_fused(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy
     if (a.slices > 1) {
         // (the wide form adds in its own workgroups, the others in trailing ones: requests for either in-launch
         // mode get the one the kernel has)
-        const int in_launch = p.wide_tables > 0 ? kReduceResident : kReduceInLaunch;
+        // (the long-k form has both in-launch modes.  Its own workgroups add sums of up to 24 slices -- measured:
+        // 28672 x 4096, 16 slices, 15.2 -> 14.6 us, 22016 x 4096 14.3 -> 13.2, 24576 x 6144 18.8 -> 17.9, 13824 x 5120,
+        // 20 slices, 14.1 -> 13.4 -- and trailing workgroups longer ones: 8192 x 16384, 64 slices, 16.3 against 17.0,
+        // 16384 x 16384, 32 slices, 26.2 against 26.7.  reduce_mode = 2 or 3 asks for one of them.)
+        const bool long_form = p.wide_tables == 0 && p.segments > 0 && p.fs.cols == 1 && p.fs.lane_bytes == 16;
+        int in_launch = p.wide_tables > 0 ? kReduceResident : kReduceInLaunch;
+        if (long_form && p.epochs && p.forced_reduce != kReduceInLaunch &&
+            (p.forced_reduce == kReduceResident || a.slices <= 24))
+            in_launch = kReduceResident;
         a.reduce_mode = p.fs.cols == 1 ? in_launch : kReduceSecondPass;
         if (p.fs.cols == 1 && p.forced_reduce == kReduceSecondPass) a.reduce_mode = kReduceSecondPass;
         // outputs per reader of the resident reduction: the row group's, dealt evenly in whole 16-byte pieces

@@ -208,7 +208,9 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
         p->partial_bytes = part;
         p->workspace_bytes = tiled + part + cnt;
         const bool batched = p->fs.entry_bytes == 2 && p->segments > 1;
-        if (p->wide_tables > 0 || batched) {
+        const bool long_form = p->wide_tables == 0 && p->segments > 0 && p->fs.cols == 1 && p->fs.lane_bytes == 16 &&
+                               p->fs.entry_bytes == 4;
+        if (p->wide_tables > 0 || batched || long_form) {
             // reductions by the workgroups of the launch itself: every partial sum carries the parity of its launch,
             // counted per workgroup; both start at zero
             if (batched)

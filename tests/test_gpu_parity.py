@@ -453,12 +453,13 @@ LONG_K_CASES = [
 ]
 
 
-@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("mode", [1, 2, 3])
 @pytest.mark.parametrize("m,k,b,xd,sg,tps,ppw", LONG_K_CASES)
 def test_fused_long_k_form(m, k, b, xd, sg, tps, ppw, mode):
     """The single-column kernel that runs through several k-tiles per workgroup
-    (two table buffers, sums kept in registers), forced on small shapes; both
-    reductions over the segments; twice on one plan."""
+    (two table buffers, sums kept in registers), forced on small shapes; the three
+    reductions over the segments (second launch, trailing workgroups, the producing
+    workgroups themselves); twice on one plan."""
     codes = inputs.make_codes(m, k, seed=m + k + tps)
     scales = inputs.make_scales(m, k, sg, seed=6) if sg else None
     dC = torch_io.to_device(codes, "codes")
@@ -532,6 +533,7 @@ def test_fused_wide_form_two_tables(m, k, b, xd, sg, ppw, mode):
     {"k_tiles_per_workgroup": 1},                               # wide form, one table: readers in the producing workgroups
     {"k_tiles_per_workgroup": 2, "panels_per_workgroup": 4},    # wide form, two tables
     {"k_tiles_per_workgroup": 3, "reduce_mode": 2},             # long-k form: trailing reducer workgroups
+    {"k_tiles_per_workgroup": 3, "reduce_mode": 3},             # long-k form: readers in the producing workgroups
 ])
 def test_in_launch_reduction_give_up_is_reported(options):
     """A reduction inside the launch whose producers never announce their partial sums (forced from the host: the
@@ -697,6 +699,7 @@ BACK_TO_BACK_CASES = [
     (2049, 1024, 1, "f16", 128, B.VARIANT_FUSED_LDS, {"k_tiles_per_workgroup": 2, "reduce_mode": 3}),   # wide form, parity-tagged sums
     (1024, 1024, 1, "f32", 0, B.VARIANT_FUSED_LDS, None),                                                 # config 1's own choice
     (700, 1024, 1, "f16", 128, B.VARIANT_FUSED_LDS, {"k_tiles_per_workgroup": 3, "reduce_mode": 2}),      # long-k form, flags
+    (4100, 1280, 2, "bf16", 128, B.VARIANT_FUSED_LDS, {"k_tiles_per_workgroup": 4, "reduce_mode": 3, "panels_per_workgroup": 16}),  # long-k form, parity-tagged sums
     (2300, 768, 2, "i8", 0, B.VARIANT_FUSED_LDS, {"k_tiles_per_workgroup": 1, "reduce_mode": 2}),         # plain form, flags, two column passes
     (2100, 512, 8, "bf16", 128, B.VARIANT_FUSED_LDS16, {"batched_form": 1, "reduce_mode": 3}),            # batched, sums added in the launch
 ]
