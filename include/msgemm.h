@@ -141,7 +141,11 @@ typedef struct {
     int reduce_mode;             /* sums over k-tiles / k-segments: 0 = library's choice, 1 = a second launch,
                                     2 = trailing workgroups of the same launch (single-column kernels), 3 = the
                                     workgroups that produced them (needs the whole grid resident; else 1 is
-                                    taken; the batched kernels do it on request only: it measured slower) */
+                                    taken; the batched kernels do it on request only: it measured slower),
+                                    4 = batched kernels: the producing workgroups, with all workgroups of a (row
+                                    block, column pass) placed on one XCD and the sums handed over through its L2
+                                    (needs the whole grid resident, the pairs to divide evenly over the XCDs and a
+                                    device seen to deal workgroup ids over its XCDs in turn; else as 0) */
     int rows_per_lane;           /* single-column kernel: 16 (default) or 8 (its 16-wavefront form);
                                     batched kernel: 8 (default) or 4 */
     int no_xcd_map;              /* 1: workgroup ids in k-tile-major order instead of grouped per L2 */

@@ -83,6 +83,16 @@ constexpr int kBRing = MSGEMM_BATCHED_RING;  // code loads a wavefront keeps in 
 #ifndef MSGEMM_PIPE_LEAVE_OUT
 #define MSGEMM_PIPE_LEAVE_OUT 0
 #endif
+// The sums over the k-segments handed over inside an XCD: on request only (reduce_mode 4).  Measured slower than the
+// second launch on every mid-size configuration (14336 x 4096 x 8: 29.6 against 22.3 us; 8192 x 8192 x 16: 39.8 against
+// 29.8; level at 28672 x 8192 x 64): the partial sums just written do not come back from the L2 any faster than
+// from memory, and a workgroup that waits keeps its compute unit.
+constexpr bool kLocalByDefault = false;
+// Measurement builds only (the result is then wrong): parts of the XCD-local reduction left out.  Bits: 1 all of it
+// (the workgroups keep its order of ids), 2 the wait for the other workgroups, 4 the reads and adds.
+#ifndef MSGEMM_LOCAL_LEAVE_OUT
+#define MSGEMM_LOCAL_LEAVE_OUT 0
+#endif
 static_assert(kLoadsPerPanel % kBRing == 0, "ring slots are reused with a period dividing the panel");
 
 template <int LB> struct LaneLoad;
@@ -127,6 +137,10 @@ struct BatchedArgs {
     unsigned poll_limit;     // polls before a waiting lane gives up
     int red_pieces;          // 16-byte pieces of the outputs one workgroup adds
     int red_groups;          // lanes that share a piece, each taking every red_groups-th segment
+    // resident = 2: the workgroups of one (row block, column pass) run on one XCD and hand their sums over through its L2
+    int local_inner;         // column passes of a row block that share an XCD (col_passes, or 1: pairs are dealt instead)
+    unsigned* arrivals;      // per (row block, column pass): workgroups that have stored their sums, all launches together
+    FastDiv div_local_inner;
 };
 
 template <typename XT> __device__ __forceinline__ _Float16 to_half(XT v);
@@ -284,14 +298,159 @@ __device__ __forceinline__ void reduce_segments_resident(const BatchedArgs& a, u
     if (gave_up && a.error) __hip_atomic_fetch_or(a.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// This workgroup's launch count goes up by one (one lane); its parity tags the partial sums of this launch.
+template <typename AT> __device__ __forceinline__ AT partial_of(unsigned u);
+template <> __device__ __forceinline__ float partial_of<float>(unsigned u) { return __uint_as_float(u); }
+template <> __device__ __forceinline__ int partial_of<int>(unsigned u) { return (int)u; }
+
+// Id of the XCD (one of the device's eight dies, each with an L2 of its own) that this wavefront runs on.
+__device__ __forceinline__ unsigned xcc_id()
+{
+    unsigned x;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(x));
+    return x & 15u;
+}
+
+// *p as the L2 of this XCD holds it: a read-modify-write that changes nothing is carried out in the L2 itself, where a
+// load may be answered by the compute unit's own cache (and the compiler turns an atomic add of a constant 0 into one).
+__device__ __forceinline__ unsigned l2_read(unsigned* p)
+{
+    unsigned v;
+    asm volatile("global_atomic_or %0, %1, %2, off sc0\n\ts_waitcnt vmcnt(0)" : "=&v"(v) : "v"(p), "v"(0u) : "memory");
+    return v;
+}
+
+// all of this wavefront's stores have been taken by the L2, its LDS traffic has landed, then the workgroup meets
+__device__ __forceinline__ void store_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// block id -> (row block, k-segment, column pass) when the sums are handed over inside an XCD (resident = 2).
+// Workgroup ids are dealt over the XCDs in turn, so id % 8 is the XCD.  XCD x takes the row blocks x, x + 8, ... with
+// all their column passes (local_inner = col_passes; the passes of a segment follow each other and share the codes in
+// the L2), or, when the row blocks do not divide by eight, the (row block, column pass) pairs x, x + 8, ...
+__device__ __forceinline__ void local_block(const BatchedArgs& a, uint32_t bid, int& rb, int& seg, int& cp)
+{
+    const uint32_t x = bid % kXcds, n = bid / kXcds;
+    const uint32_t t = fast_div(n, a.div_local_inner);
+    const int li = (int)(n - t * (uint32_t)a.local_inner);
+    const uint32_t lp = fast_div(t, a.div_segments);
+    seg = (int)(t - lp * (uint32_t)a.segments);
+    const uint32_t pr = x + kXcds * lp;
+    if (a.local_inner > 1 || a.col_passes == 1) {
+        rb = (int)pr;
+        cp = li;
+    } else {
+        rb = (int)fast_div(pr, a.div_col_passes);
+        cp = (int)(pr - (uint32_t)rb * (uint32_t)a.col_passes);
+    }
+}
+
+// The sums over the k-segments inside the launch, handed over through one L2 (resident = 2).  All workgroups of a
+// (row block, column pass) run on one XCD at the same time (the host checks the grid against the compute units and,
+// once per device, that ids are dealt over the XCDs in turn; every workgroup checks its own XCD id again).  Their
+// partial sums are ordinary stores: they go through the compute unit's cache into that L2.  When a wavefront's stores
+// have been taken and the workgroup has met, one lane counts the workgroup in (an atomic add in the L2) and waits
+// until the count has grown by one for every segment -- the count runs on over the launches, `target` is this launch's
+// -- then everybody reads: workgroup `seg` adds share `seg` of the pair's outputs in segment order, from lines this
+// compute unit has not touched since the launch began, which therefore come from the L2.  A wait that runs out
+// (poll_limit) or a workgroup on an unexpected XCD sets bit 0 of the plan's error word, and nothing is written.
+template <typename YT, typename AT, int kFinal>
+__device__ __forceinline__ void reduce_segments_local(const BatchedArgs& a, int rb, int cp, int seg, unsigned target,
+                                                      bool xcd_as_expected, unsigned char* scratch)
+{
+    constexpr int kPanelRowsR = 64 * kFinal;
+    const int tid = threadIdx.x;
+    if constexpr (MSGEMM_LOCAL_LEAVE_OUT & 1) return;
+    store_barrier();  // this workgroup's sums are in the L2, and nobody gathers from the tables any more
+    if (tid == 0) {
+        unsigned* cnt = a.arrivals + ((int64_t)rb * a.col_passes + cp);
+        if (a.publish) __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        unsigned polls = 0;
+        bool ok = xcd_as_expected;
+        while (!(MSGEMM_LOCAL_LEAVE_OUT & 2) && ok && (int)(l2_read(cnt) - target) < 0) {
+            if (++polls >= a.poll_limit) ok = false;
+            else __builtin_amdgcn_s_sleep(8);
+        }
+        *(volatile unsigned*)scratch = ok ? 1u : 0u;
+    }
+    lds_barrier();
+    const bool gave_up = *(volatile unsigned*)scratch == 0u;
+    lds_barrier();  // (the word is read: the scratch is free for the sums below)
+    if (gave_up) {
+        if (tid == 0 && a.error) __hip_atomic_fetch_or(a.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+    if constexpr (MSGEMM_LOCAL_LEAVE_OUT & 4) return;
+    const int panels_here = min(a.panels_per_wg, a.panels_total - rb * a.panels_per_wg);
+    const int per_col = panels_here * (kPanelRowsR / 4);  // 16-byte pieces of one column of this row block
+    const int total = kBC * per_col;
+    const int q_begin = seg * a.red_pieces, q_end = min(q_begin + a.red_pieces, total);
+    const int64_t f_rb = (int64_t)rb * a.panels_per_wg * kPanelRowsR;  // first partial-sum slot of the row block within a column
+    const int G = a.red_groups;
+    const int per_round = (int)blockDim.x / G;
+    const int pl = tid % per_round, g = tid / per_round;
+    const uint32_t seg_bytes = (uint32_t)(a.b_pad * a.m_pad * 4);
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)a.partials, 0, (int)a.partial_span, 0x00020000);
+    YT* __restrict__ Y = (YT*)a.Y;
+#pragma unroll 1
+    for (int r0 = q_begin; r0 < q_end; r0 += per_round) {
+        const int qi = r0 + pl;
+        const bool have = g < G && qi < q_end;
+        const int c = have ? qi / per_col : 0;
+        const int64_t f = ((int64_t)cp * kBC + c) * a.m_pad + f_rb + (int64_t)(have ? qi - c * per_col : 0) * 4;  // slot within a segment
+        AT sum[4] = {0, 0, 0, 0};
+#pragma unroll 1
+        for (int s0 = g; s0 < a.segments && have; s0 += 8 * G) {
+            v4u v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int sl = s0 + u * G;
+                const uint32_t off = sl < a.segments ? (uint32_t)sl * seg_bytes + (uint32_t)f * 4u : 0x7ffffff0u;  // (out of range: reads zero)
+                v[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                sum[0] += partial_of<AT>(v[u].x); sum[1] += partial_of<AT>(v[u].y);
+                sum[2] += partial_of<AT>(v[u].z); sum[3] += partial_of<AT>(v[u].w);
+            }
+        }
+        AT* mine = (AT*)(scratch + (size_t)tid * 16);
+        if (G > 1) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mine[e] = sum[e];
+            lds_barrier();
+        }
+        if (have && g == 0) {
+            for (int og = 1; og < G; ++og) {
+                const AT* other = (const AT*)(scratch + (size_t)(og * per_round + pl) * 16);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sum[e] += other[e];
+            }
+            // slot f of a column belongs to lane slot_owner(f / kFinal) of the wavefront that made it, output f % kFinal
+            const int64_t col = (int64_t)cp * kBC + c, rr = f - col * a.m_pad;
+            const int64_t panel = rr / kPanelRowsR;
+            const int q0 = (int)(rr % kPanelRowsR);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int qe = q0 + e;
+                const int64_t row = panel * kPanelRowsR + 64 * (qe % kFinal) + slot_owner(qe / kFinal, 1);
+                if (row < a.m && col < a.b) Y[col * a.ldy + row] = to_output<YT, AT>(sum[e]);
+            }
+        }
+        if (G > 1) lds_barrier();  // the scratch is read: the next round may write it
+    }
+}
+
+// This workgroup's launch count goes up by one (one lane); its parity tags the partial sums of this launch (the count
+// itself, times the segments, is what the arrival count of an XCD-local reduction has to reach).
 // The caller's next workgroup barrier makes `*slot` (LDS) visible to the other lanes.
 __device__ __forceinline__ void count_launch(const BatchedArgs& a, unsigned* slot)
 {
     if (a.resident && threadIdx.x == 0) {
         const unsigned n = __hip_atomic_load(a.epochs + blockIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
         __hip_atomic_store(a.epochs + blockIdx.x, n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *slot = n & 1u;
+        *slot = n;
     }
 }
 
@@ -311,7 +470,7 @@ batched_kernel(BatchedArgs a)
     using LoadT = typename LaneLoad<kBLB>::type;
     __shared__ __align__(16) unsigned char lds[2 * kBHalfBytes];
     __shared__ __align__(16) _Float16 xs[2][2 * kBG][kBC];            // activations of a k-tile: [k-column][batch column]
-    __shared__ unsigned launch_parity;
+    __shared__ unsigned launch_count;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -322,13 +481,20 @@ batched_kernel(BatchedArgs a)
     // unit (same codes) get ids that are congruent modulo the XCD count and close
     // together: they run on one XCD around the same time and share its L2.
     const uint32_t bid = blockIdx.x;
-    const uint32_t n = bid / kXcds;
-    const uint32_t hi = fast_div(n, a.div_col_passes);
-    const int cp = (int)(n - hi * (uint32_t)a.col_passes);
-    const int unit = (int)((bid % kXcds) + kXcds * hi);
-    if (unit >= a.units) return;
-    const int rb = (int)fast_div((uint32_t)unit, a.div_segments);
-    const int seg = unit - rb * a.segments;
+    int rb, seg, cp, unit;
+    if (a.resident == 2) {
+        local_block(a, bid, rb, seg, cp);  // (the grid is exactly the workgroups there are)
+        unit = rb * a.segments + seg;
+    } else {
+        const uint32_t n = bid / kXcds;
+        const uint32_t hi = fast_div(n, a.div_col_passes);
+        cp = (int)(n - hi * (uint32_t)a.col_passes);
+        unit = (int)((bid % kXcds) + kXcds * hi);
+        if (unit >= a.units) return;
+        rb = (int)fast_div((uint32_t)unit, a.div_segments);
+        seg = unit - rb * a.segments;
+    }
+    const bool xcd_as_expected = a.resident != 2 || xcc_id() == bid % kXcds;
     const int kt_begin = seg * a.tiles_per_segment;
     const int kt_end = min(kt_begin + a.tiles_per_segment, a.ktiles);
     const int64_t col0 = (int64_t)cp * kBC;
@@ -421,7 +587,7 @@ batched_kernel(BatchedArgs a)
             __builtin_amdgcn_sched_barrier(0);  // loads return in issue order: keep slot 0 first
         }
     }
-    count_launch(a, &launch_parity);
+    count_launch(a, &launch_count);
     x_store(0, kt_begin, xraw);
     lds_barrier();
     build_tables(0);
@@ -540,7 +706,7 @@ batched_kernel(BatchedArgs a)
             lds_barrier();
         }
     }
-    const unsigned parity = a.resident ? launch_parity : 0u;
+    const unsigned launches = a.resident ? launch_count : 0u, parity = launches & 1u;
     if (active && !((MSGEMM_BATCHED_LEAVE_OUT & 16) && dlo[0][0] != 1234.5f)) {
 
     // ---- lanes 16 apart looked up the same rows (in different groups): fold them.
@@ -585,18 +751,19 @@ batched_kernel(BatchedArgs a)
                     AT v;
                     if constexpr (__is_same(AT, int)) v = __float2int_rn(fin[s]);
                     else v = fin[s];
-                    out[s] = a.resident ? tag_partial(v, parity) : bits_of(v);
+                    out[s] = a.resident == 1 ? tag_partial(v, parity) : bits_of(v);
                 }
                 // (slot group 16 i + quad: the quads of this store are neighbours in memory, see slot_owner)
                 const uint32_t off =
                     (uint32_t)((((int64_t)seg * a.b_pad + col) * a.m_pad + (int64_t)panel * kBPanelRows + (16 * i + quad) * kBFinal) * 4);
-                if (!a.resident) store_partials<kBFinal, 0>(part_rsrc, off, out);
+                if (a.resident != 1) store_partials<kBFinal, 0>(part_rsrc, off, out);
                 else if (a.publish) store_partials<kBFinal, kAuxSc1>(part_rsrc, off, out);
             }
         }
     }
     }
-    if (a.resident) reduce_segments_resident<YT, AT, kBFinal>(a, parity, unit * a.col_passes + cp, lds);
+    if (a.resident == 2) reduce_segments_local<YT, AT, kBFinal>(a, rb, cp, seg, launches * (unsigned)a.segments, xcd_as_expected, lds);
+    else if (a.resident) reduce_segments_resident<YT, AT, kBFinal>(a, parity, unit * a.col_passes + cp, lds);
 }
 
 // Pipelined form: the table of the next k-tile is built while the current one is
@@ -630,7 +797,7 @@ batched_pipe_kernel(BatchedArgs a)
     using LoadT = typename LaneLoad<kPLB>::type;
     __shared__ __align__(16) unsigned char lds[2 * kPTableBytes];
     __shared__ __align__(16) _Float16 xs[2][2 * kPG][kBC];  // activations of a k-tile: [k-column][batch column]
-    __shared__ unsigned launch_parity;
+    __shared__ unsigned launch_count;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -639,13 +806,20 @@ batched_pipe_kernel(BatchedArgs a)
 
     // block id -> (k-segment, row block, column pass), as in batched_kernel
     const uint32_t bid = blockIdx.x;
-    const uint32_t n = bid / kXcds;
-    const uint32_t hi = fast_div(n, a.div_col_passes);
-    const int cp = (int)(n - hi * (uint32_t)a.col_passes);
-    const int unit = (int)((bid % kXcds) + kXcds * hi);
-    if (unit >= a.units) return;
-    const int rb = (int)fast_div((uint32_t)unit, a.div_segments);
-    const int seg = unit - rb * a.segments;
+    int rb, seg, cp, unit;
+    if (a.resident == 2) {
+        local_block(a, bid, rb, seg, cp);  // (the grid is exactly the workgroups there are)
+        unit = rb * a.segments + seg;
+    } else {
+        const uint32_t n = bid / kXcds;
+        const uint32_t hi = fast_div(n, a.div_col_passes);
+        cp = (int)(n - hi * (uint32_t)a.col_passes);
+        unit = (int)((bid % kXcds) + kXcds * hi);
+        if (unit >= a.units) return;
+        rb = (int)fast_div((uint32_t)unit, a.div_segments);
+        seg = unit - rb * a.segments;
+    }
+    const bool xcd_as_expected = a.resident != 2 || xcc_id() == bid % kXcds;
     const int kt_begin = seg * a.tiles_per_segment;
     const int ngen = min(a.tiles_per_segment, a.ktiles - kt_begin);  // >= 1: the host makes no empty segment
     const int64_t col0 = (int64_t)cp * kBC;
@@ -727,7 +901,7 @@ batched_pipe_kernel(BatchedArgs a)
             __builtin_amdgcn_sched_barrier(0);  // loads return in issue order: keep slot 0 first
         }
     }
-    count_launch(a, &launch_parity);
+    count_launch(a, &launch_count);
     x_store(0, kt_begin, xraw);
     if (ngen > 1) x_store(1, kt_begin + 1, xraw1);
     lds_barrier();
@@ -881,7 +1055,7 @@ batched_pipe_kernel(BatchedArgs a)
         // everyone has finished reading table gen & 1 and writing the other one (and the activations)
         if (more && !(MSGEMM_PIPE_LEAVE_OUT & 8)) lds_barrier();
     }
-    const unsigned parity = a.resident ? launch_parity : 0u;
+    const unsigned launches = a.resident ? launch_count : 0u, parity = launches & 1u;
     if (active) {
     // ---- lane (quad b, j'), register (s, i) holds row 64 s + 4 b + i of the panel,
     // column 4 h + j' of the pass (the matrix cores hand the sums back transposed within a quad)
@@ -917,18 +1091,19 @@ batched_pipe_kernel(BatchedArgs a)
                     AT v;
                     if constexpr (__is_same(AT, int)) v = __float2int_rn(fin[s]);
                     else v = fin[s];
-                    out[s] = a.resident ? tag_partial(v, parity) : bits_of(v);
+                    out[s] = a.resident == 1 ? tag_partial(v, parity) : bits_of(v);
                 }
                 // (slot group 16 i + quad: the quads of this store are neighbours in memory, see slot_owner)
                 const uint32_t off =
                     (uint32_t)((((int64_t)seg * a.b_pad + col) * a.m_pad + (int64_t)panel * kPanelRows + (16 * i + quad) * kPLB) * 4);
-                if (!a.resident) store_partials<kPLB, 0>(part_rsrc, off, out);
+                if (a.resident != 1) store_partials<kPLB, 0>(part_rsrc, off, out);
                 else if (a.publish) store_partials<kPLB, kAuxSc1>(part_rsrc, off, out);
             }
         }
     }
     }
-    if (a.resident) reduce_segments_resident<YT, AT, kPLB>(a, parity, unit * a.col_passes + cp, lds);
+    if (a.resident == 2) reduce_segments_local<YT, AT, kPLB>(a, rb, cp, seg, launches * (unsigned)a.segments, xcd_as_expected, lds);
+    else if (a.resident) reduce_segments_resident<YT, AT, kPLB>(a, parity, unit * a.col_passes + cp, lds);
 }
 
 // One-off reorder of the block scales ([m][nblocks]) for the batched kernel:
@@ -1124,6 +1299,35 @@ int launch_repack_scales_batched(const Plan& p, hipStream_t s)
     return MSGEMM_OK;
 }
 
+// Does this device deal the workgroups of a launch over its XCDs in turn (id % 8 = XCD)?  The XCD-local reduction
+// places its workgroups by that rule; it is how these devices are known to dispatch, but no interface promises it, so
+// it is looked at once per device: a launch of 2048 small workgroups, each recording the XCD id it finds itself on.
+// Called when a plan is made (it allocates and waits), never from a launch.
+__global__ void xcd_probe_kernel(unsigned* out)
+{
+    if (threadIdx.x == 0) out[blockIdx.x] = xcc_id();
+}
+
+bool xcd_round_robin(int device, hipStream_t s)
+{
+    constexpr int kMaxDevices = 64, kProbe = 2048;
+    static int known[kMaxDevices];  // 0 not looked at, 1 yes, 2 no
+    if (device < 0 || device >= kMaxDevices) return false;
+    if (known[device]) return known[device] == 1;
+    unsigned* d = nullptr;
+    if (hipMalloc((void**)&d, kProbe * sizeof(unsigned)) != hipSuccess) return false;
+    bool ok = true;
+    unsigned h[kProbe];
+    for (int rep = 0; rep < 2 && ok; ++rep) {
+        hipLaunchKernelGGL(xcd_probe_kernel, dim3(kProbe), dim3(64), 0, s, d);
+        ok = hipMemcpyAsync(h, d, sizeof(h), hipMemcpyDeviceToHost, s) == hipSuccess && hipStreamSynchronize(s) == hipSuccess;
+        for (int i = 0; i < kProbe && ok; ++i) ok = h[i] == (unsigned)(i % kXcds);
+    }
+    (void)hipFree(d);
+    known[device] = ok ? 1 : 2;
+    return ok;
+}
+
 int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s)
 {
     BatchedArgs a;
@@ -1157,7 +1361,7 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
     a.div_col_passes = make_fastdiv((uint32_t)a.col_passes);
     a.div_segments = make_fastdiv((uint32_t)a.segments);
     a.div_tiles_per_block = make_fastdiv((uint32_t)a.tiles_per_block);
-    const int64_t grid = (int64_t)kXcds * a.col_passes * ((a.units + kXcds - 1) / kXcds);
+    int64_t grid = (int64_t)kXcds * a.col_passes * ((a.units + kXcds - 1) / kXcds);
     // On request (reduce_mode 3) the segments are added inside the launch, if every workgroup is resident at once:
     // each needs more than half of a compute unit's LDS, so that is one workgroup per compute unit.  Not the default:
     // the partial sums of a batch are tens of megabytes, and reading them with loads that are coherent across the
@@ -1165,11 +1369,33 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
     // 263 against 242), unlike the single-column forms whose sums are a megabyte.
     const int threads = (p.fs.groups == kPG) ? (64 / p.fs.lane_bytes) * 64 : (p.fs.lane_bytes == 8 ? 8 : 12) * 64;
     a.resident = (!a.direct && p.epochs && p.forced_reduce == 3 && grid <= p.cus) ? 1 : 0;
+    // The hand-over inside an XCD (resident = 2; reduce_mode 4 asks for it): every (row block, column pass) gets all
+    // its segments onto one XCD, which needs the pairs -- or, with the passes of a row block kept together for the
+    // codes they share, the row blocks -- to divide evenly over the XCDs, a workgroup per compute unit at most, and a
+    // device that deals workgroup ids over its XCDs in turn (probed once, at the first plan).
+    a.local_inner = 1;
+    a.arrivals = nullptr;
+    if (!a.direct && p.epochs && p.xcd_round_robin && (p.forced_reduce == 4 || (p.forced_reduce == 0 && kLocalByDefault))) {
+        const int64_t RB = p.row_blocks, CP = p.col_passes, S = p.segments;
+        const int inner = (RB % kXcds == 0) ? (int)CP : 1;
+        const int64_t dealt = RB * CP / inner;
+        if (dealt % kXcds == 0 && RB * CP * S <= p.cus && p.cus % kXcds == 0 && (dealt / kXcds) * inner * S <= p.cus / kXcds) {
+            a.resident = 2;
+            a.local_inner = inner;
+            a.arrivals = p.epochs + (p.epoch_words - (size_t)(RB * CP));
+            grid = RB * CP * S;
+        }
+    }
+    a.div_local_inner = make_fastdiv((uint32_t)a.local_inner);
     a.publish = p.opt.skip_publish ? 0 : 1;
     a.epochs = p.epochs;
     a.poll_limit = p.opt.poll_limit > 0 ? (unsigned)p.opt.poll_limit : kMaxFlagPolls;
     {
-        const int64_t pieces = a.b_pad * p.m_pad / 4, readers = (int64_t)a.units * a.col_passes;
+        int64_t pieces = a.b_pad * p.m_pad / 4, readers = (int64_t)a.units * a.col_passes;
+        if (a.resident == 2) {  // the pieces of one (row block, column pass), over its segments
+            pieces = (int64_t)kBC * p.fs.panels * p.fs.panel_rows / 4;
+            readers = a.segments;
+        }
         a.red_pieces = (int)((pieces + readers - 1) / readers);
         int g = 1;
         while (g < 8 && 2 * g <= a.segments && (int64_t)a.red_pieces * (2 * g) <= threads) g *= 2;

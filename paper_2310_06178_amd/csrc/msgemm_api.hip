@@ -213,9 +213,12 @@ static int plan_impl(msgemm_plan_t** out, int64_t m, int64_t k, int64_t b, int x
         if (p->wide_tables > 0 || batched || long_form) {
             // reductions by the workgroups of the launch itself: every partial sum carries the parity of its launch,
             // counted per workgroup; both start at zero
-            if (batched)
+            if (batched) {
                 p->epoch_words = (size_t)msgemm::kXcds * (size_t)p->col_passes *
                                  (((size_t)p->segments * (size_t)p->row_blocks + msgemm::kXcds - 1) / msgemm::kXcds);
+                p->epoch_words += (size_t)p->row_blocks * (size_t)p->col_passes;  // arrival counts (XCD-local reduction)
+                p->xcd_round_robin = msgemm::xcd_round_robin(p->device, s) ? 1 : 0;
+            }
             else {
                 // one word per workgroup id of the grid, in either order of the ids (row groups or units dealt over the XCDs)
                 const size_t by_row_groups = (size_t)slices * msgemm::kXcds * (((size_t)p->row_blocks * p->col_passes + msgemm::kXcds - 1) / msgemm::kXcds);

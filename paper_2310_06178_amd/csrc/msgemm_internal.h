@@ -74,7 +74,8 @@ struct Plan {
                           // between launches; then the error word
     size_t partial_bytes; // size of `partials`
     unsigned* epochs;     // device, wide form: launch count of every workgroup of the grid (resident reduction), or nullptr
-    size_t epoch_words;
+    size_t epoch_words;   // (batched kernels: the last row_blocks * col_passes words are the arrival counts of the XCD-local reduction)
+    int xcd_round_robin;  // 1: the device was seen to deal workgroup ids over its XCDs in turn (probed at the first batched plan)
     size_t flag_words;    // flags in that buffer
     unsigned* error_word; // device, flags + flag_words: set by a wavefront that gave up waiting (msgemm_plan_check)
     bool d3;              // depth-3 tables in LDS (kernels_depth3.hip): codes_tiled holds its rotated 96-bit runs
@@ -123,6 +124,7 @@ bool batched_pipelined_is_faster(int64_t m, int64_t k, int64_t b, int64_t scale_
 // panels of 256 rows per workgroup of the batched form with a build phase (8 rows per lane)
 int batched_phase_form_panels(int64_t panels, int64_t ktiles, int64_t scale_group, int col_passes, int64_t cus);
 int launch_repack_scales_batched(const Plan& p, hipStream_t s);
+bool xcd_round_robin(int device, hipStream_t s);
 int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t ldy, hipStream_t s);
 
 // calibration.hip

@@ -612,6 +612,65 @@ def test_batched_segments_added_in_the_launch(form, xd):
         B.msgemm_destroy(plan)
 
 
+XCD_LOCAL_CASES = [
+    # form, m, k, b, xd, panels per workgroup, segments
+    (1, 2000, 2048, 11, "f16", 1, 4),     # 8 row blocks x 2 column passes: a row block's passes share an XCD
+    (1, 3700, 1024, 8, "bf16", 2, 8),     # 15 panels in 8 row blocks: the last one has a single panel
+    (1, 1000, 2048, 13, "i8", 1, 4),      # 4 row blocks x 2 passes: the pairs are dealt over the XCDs
+    (1, 1300, 1536, 27, "f16", 1, 3),     # 6 row blocks x 4 passes = 24 pairs, ragged rows, ragged last pass
+    (2, 3700, 2048, 16, "bf16", 1, 4),    # pipelined form, 8 panels of 512 rows
+    (2, 2500, 1024, 5, "i8", 1, 16),      # 5 row blocks: no even deal, the second launch adds
+]
+
+
+@pytest.mark.parametrize("form,m,k,b,xd,ppw,segments", XCD_LOCAL_CASES)
+def test_batched_segments_added_inside_an_xcd(form, m, k, b, xd, ppw, segments):
+    """Batches, reduce_mode 4: all workgroups of a (row block, column pass) run on one XCD and hand their sums over
+    through its L2 (plain stores, an arrival count kept by L2 atomics).  Against the oracle over repeated calls on one
+    plan (the count runs on over the launches); integer results equal the second launch's; the host-forced give-up
+    is reported where the mode applies -- which also shows that it was taken -- and the plan works again afterwards."""
+    sg = 0 if xd == "i8" else 128
+    codes = inputs.make_codes(m, k, seed=m + b)
+    scales = inputs.make_scales(m, k, sg, seed=5) if sg else None
+    dC, dS = torch_io.to_device(codes, "codes"), torch_io.to_device(scales, "scales")
+    base = {"batched_form": form, "batched_segments": segments, "panels_per_workgroup": ppw}
+    panel_rows = 256 if form == 1 else 512
+    row_blocks, passes = -(-(-(-m // panel_rows)) // ppw), -(-b // 8)
+    applies = (row_blocks % 8 == 0) or (row_blocks * passes) % 8 == 0
+    outs = {}
+    for mode in (4, 1):
+        plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS, B.VARIANT_FUSED_LDS16, options=dict(base, reduce_mode=mode))
+        try:
+            assert B.msgemm_plan_get_info(plan)["split_k"] == segments
+            for rep in range(4):
+                X = inputs.make_x(k, b, xd, seed=40 + rep)
+                dX = torch_io.to_device(X, xd)
+                Y = torch_io.empty_output(b, m, Y_OF_X[xd], ldy=m + 3)
+                Y.fill_(-3)
+                B.msgemm_run(plan, dX, k, Y, m + 3)
+                torch.cuda.synchronize()
+                assert B.msgemm_plan_check(plan) == B.OK
+                out = torch_io.to_host(Y)
+                check(np.ascontiguousarray(out[:, :m]), oracle_y(codes, X, xd, scales, sg), xd,
+                      f"batched, reduce mode {mode}, call {rep}", elem_bound(codes, X, xd, scales, sg, table16=True))
+                minus3 = torch_io.to_host(torch.full((1,), -3, dtype=Y.dtype))[0]
+                assert np.all(out[:, m:] == minus3), "output padding was written"
+            outs[mode] = out
+        finally:
+            B.msgemm_destroy(plan)
+    if xd == "i8":
+        assert np.array_equal(outs[1], outs[4])
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS, B.VARIANT_FUSED_LDS16,
+                         options=dict(base, reduce_mode=4, poll_limit=8, skip_publish=1))
+    try:
+        assert B.msgemm_plan_check(plan) == B.OK
+        B.msgemm_run(plan, dX, k, Y, m + 3)
+        assert B.msgemm_plan_check(plan) == (B.ERR_INCOMPLETE if applies else B.OK)
+        assert B.msgemm_plan_check(plan) == B.OK
+    finally:
+        B.msgemm_destroy(plan)
+
+
 DEPTH3_CASES = [
     # m, k, b, xd, segments (0: the library's choice)
     (12, 4, 1, "f32", 0),          # the worked example's shape: one full group and one of a single column
