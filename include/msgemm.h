@@ -160,6 +160,9 @@ typedef struct {
     int poll_limit;              /* in-launch reductions: polls before a waiting wavefront gives up; 0 = 2^22 */
     int skip_publish;            /* test aid: producers never announce their partial sums, so every waiting
                                     wavefront gives up after poll_limit polls (see msgemm_plan_check) */
+    int batched_deal;            /* batched kernel, pipelined form: the k-tiles of all row blocks dealt evenly over the
+                                    workgroups (a workgroup may end one row block and begin the next); 0 = library's
+                                    choice, 1 = never, 2 = whenever the problem allows */
 } msgemm_plan_options_t;
 
 /*

@@ -58,7 +58,7 @@ class PlanOptions(ctypes.Structure):
         ("batched_form", ctypes.c_int), ("batched_segments", ctypes.c_int),
         ("global_plain_consumer", ctypes.c_int), ("global_chunk_kib", ctypes.c_int), ("global_segments", ctypes.c_int),
         ("build_on_matrix_cores", ctypes.c_int), ("half_tables_in_lds", ctypes.c_int), ("poll_limit", ctypes.c_int),
-        ("skip_publish", ctypes.c_int),
+        ("skip_publish", ctypes.c_int), ("batched_deal", ctypes.c_int),
     ]
 
 

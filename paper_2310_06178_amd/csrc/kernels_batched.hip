@@ -141,6 +141,14 @@ struct BatchedArgs {
     int local_inner;         // column passes of a row block that share an XCD (col_passes, or 1: pairs are dealt instead)
     unsigned* arrivals;      // per (row block, column pass): workgroups that have stored their sums, all launches together
     FastDiv div_local_inner;
+    // pipelined form, k-tiles dealt evenly (dealt = 1): for one column pass the scale blocks of all row blocks form one
+    // sequence, row block after row block; workgroup `unit` takes deal_blocks consecutive ones, which may run from the
+    // end of one row block into the start of the next (two runs, a partial sum each)
+    int dealt;
+    int deal_blocks;         // scale blocks (tiles_per_block k-tiles each) per workgroup
+    int blocks_per_rb;       // scale blocks of one row block (all of k)
+    int deal_total;          // row_blocks * blocks_per_rb
+    FastDiv div_blocks_per_rb, div_deal_blocks;
 };
 
 template <typename XT> __device__ __forceinline__ _Float16 to_half(XT v);
@@ -820,11 +828,29 @@ batched_pipe_kernel(BatchedArgs a)
         seg = unit - rb * a.segments;
     }
     const bool xcd_as_expected = a.resident != 2 || xcc_id() == bid % kXcds;
-    const int kt_begin = seg * a.tiles_per_segment;
-    const int ngen = min(a.tiles_per_segment, a.ktiles - kt_begin);  // >= 1: the host makes no empty segment
     const int64_t col0 = (int64_t)cp * kBC;
-    const int panel = rb * a.panels_per_wg + wave;
-    const bool active = wave < a.panels_per_wg && panel < a.panels_total;
+    // The k-tiles this workgroup runs through: a segment of its row block -- or, with the k-tiles dealt evenly, a run
+    // of scale blocks of the row-block-major sequence of its column pass, which may go from the end of one row block
+    // (its last k-tiles) into the start of the next (k-tile 0 of the panels 8 further on): the tables depend on the
+    // column pass and the k-tile alone, so the pipeline of activations, table builds and code loads runs across that
+    // border like across any other k-tile border; only the sums are stored and cleared there.
+    int kt_begin = seg * a.tiles_per_segment;
+    int ngen = min(a.tiles_per_segment, a.ktiles - kt_begin);  // >= 1: the host makes no empty segment
+    if (a.dealt) {
+        // scale block B of the sequence -> its first k-tile, counted through the row blocks
+        auto first_tile = [&](int B) -> int {
+            const int r = (int)fast_div((uint32_t)B, a.div_blocks_per_rb);
+            return r * a.ktiles + min((B - r * a.blocks_per_rb) * a.tiles_per_block, a.ktiles);
+        };
+        const int b0 = unit * a.deal_blocks, b1 = min(b0 + a.deal_blocks, a.deal_total);
+        rb = (int)fast_div((uint32_t)b0, a.div_blocks_per_rb);
+        seg = unit - (int)fast_div((uint32_t)(rb * a.blocks_per_rb), a.div_deal_blocks);
+        const int t0 = first_tile(b0);
+        kt_begin = t0 - rb * a.ktiles;
+        ngen = first_tile(b1) - t0;
+    }
+    const int panel_first = rb * a.panels_per_wg + wave;
+    const bool active_first = wave < a.panels_per_wg && panel_first < a.panels_total;
 
     const XT* __restrict__ X = (const XT*)a.X;
 
@@ -885,16 +911,19 @@ batched_pipe_kernel(BatchedArgs a)
     using RingT = typename std::conditional<kPair, uint4, LoadT>::type;
     constexpr int kSlots = kPair ? kBRing / 2 : kBRing;                     // ring slots (the same bytes in flight)
     constexpr int kSlotsPerTile = kPair ? kLoadsPerPanel / 2 : kLoadsPerPanel;
-    const RingT* __restrict__ tiled = (const RingT*)a.tiled + (int64_t)panel * a.ktiles * (kSlotsPerTile * 64) + lane;
+    // (k-tile kt of the panel 8 r further on is k-tile kt + 8 r ktiles of this one)
+    const RingT* __restrict__ tiled = (const RingT*)a.tiled + (int64_t)panel_first * a.ktiles * (kSlotsPerTile * 64) + lane;
     auto code_at = [&](int kt, int u) -> const RingT* {
         if constexpr (MSGEMM_PIPE_LEAVE_OUT & 64) kt = kt_begin;  // (every k-tile re-reads the first one's codes: cache hits)
         return tiled + ((int64_t)kt * kSlotsPerTile + u) * 64;
     };
     RingT ring[kSlots];
 
+    // k-tile that follows kt in the sequence (the next row block starts at its k-tile 0 again)
+    auto tile_after = [&](int kt) -> int { return kt + 1 == a.ktiles ? 0 : kt + 1; };
     XT xraw = x_fetch(kt_begin);
-    XT xraw1 = x_fetch(ngen > 1 ? kt_begin + 1 : kt_begin);
-    if (active) {
+    XT xraw1 = x_fetch(ngen > 1 ? tile_after(kt_begin) : kt_begin);
+    if (active_first) {
 #pragma unroll
         for (int u = 0; u < kSlots; ++u) {
             ring[u] = load_codes(code_at(kt_begin, u));
@@ -903,7 +932,7 @@ batched_pipe_kernel(BatchedArgs a)
     }
     count_launch(a, &launch_count);
     x_store(0, kt_begin, xraw);
-    if (ngen > 1) x_store(1, kt_begin + 1, xraw1);
+    if (ngen > 1) x_store(1, tile_after(kt_begin), xraw1);
     lds_barrier();
     build_operands(0);
 #pragma unroll
@@ -925,11 +954,19 @@ batched_pipe_kernel(BatchedArgs a)
         }
     }
 
+    const unsigned launches = a.resident ? launch_count : 0u, parity = launches & 1u;
+    int kt = kt_begin;     // k-tile within the row block
+    int rb_now = rb, seg_now = seg;
+    int kt_code = kt_begin;  // the same k-tile as the code stream counts it (from the first row block's panel on)
     for (int gen = 0; gen < ngen; ++gen) {
-        const int kt = kt_begin + gen;
         const bool more = gen + 1 < ngen;   // a table to build during this k-tile
         const bool more2 = gen + 2 < ngen;  // activations to fetch for the one after it
-        if (more2 && !(MSGEMM_PIPE_LEAVE_OUT & 128)) xraw = x_fetch(kt + 2);
+        const bool last_of_row_block = kt + 1 == a.ktiles;
+        const int panel = rb_now * a.panels_per_wg + wave;
+        const bool active = wave < a.panels_per_wg && panel < a.panels_total;
+        // (a wavefront without a panel in the next row block stays with its own codes: every address it forms is valid)
+        const bool active_next = !last_of_row_block || panel + a.panels_per_wg < a.panels_total;
+        if (more2 && !(MSGEMM_PIPE_LEAVE_OUT & 128)) xraw = x_fetch(tile_after(tile_after(kt)));
         if (more) build_operands((gen + 1) & 1);
         unsigned char* next_table = lds + ((gen + 1) & 1) * kPTableBytes;
         const uint32_t table_bit = (uint32_t)(gen & 1) << 16;
@@ -941,7 +978,9 @@ batched_pipe_kernel(BatchedArgs a)
                 qraw = *(const LaneScales*)(a.scales + (((int64_t)blk * a.panels_total + panel) * 64 + lane) * kPLB);
             }
         }
-        const int kt_next = more ? kt + 1 : kt;  // (the last tile re-requests its own tail: harmless, and branch-free)
+        // (the last tile re-requests its own tail: harmless, and branch-free)
+        const int kt_here = kt_code;
+        const int kt_next = (more && active_next) ? (last_of_row_block ? kt_code + (a.panels_per_wg - 1) * a.ktiles + 1 : kt_code + 1) : kt_code;
         // One k-tile as straight-line code (no branch inside, so the counters of the
         // code loads in flight stay known to the compiler): look-ups if this
         // wavefront has a panel, an entry of the next table after every second load
@@ -979,7 +1018,7 @@ batched_pipe_kernel(BatchedArgs a)
                 if constexpr (MSGEMM_PIPE_LEAVE_OUT & 32) return;
                 if (kPair && (t & 1) == 0) return;
                 const int u = kPair ? t / 2 : t;
-                ring[u % kSlots] = load_codes((u + kSlots < kSlotsPerTile) ? code_at(kt, u + kSlots)
+                ring[u % kSlots] = load_codes((u + kSlots < kSlotsPerTile) ? code_at(kt_here, u + kSlots)
                                                                            : code_at(kt_next, u + kSlots - kSlotsPerTile));
             };
             if constexpr (kGather) {
@@ -1036,7 +1075,7 @@ batched_pipe_kernel(BatchedArgs a)
             // a scale block ends with this k-tile: y += q(row) * block sum (Section 3.3).
             // Register i of the accumulators belongs to the row of quad lane i.
             const int blk = (int)fast_div((uint32_t)kt, a.div_tiles_per_block);
-            if (active && (!more || (kt + 1) == (blk + 1) * a.tiles_per_block)) {
+            if (active && (!more || last_of_row_block || (kt + 1) == (blk + 1) * a.tiles_per_block)) {
 #pragma unroll
                 for (int s = 0; s < kPLB; ++s) {
                     const float qf = __half2float(qraw.h[s]);
@@ -1051,15 +1090,18 @@ batched_pipe_kernel(BatchedArgs a)
                 }
             }
         }
-        if (more2 && !(MSGEMM_PIPE_LEAVE_OUT & 128)) x_store(gen & 1, kt + 2, xraw);
-        // everyone has finished reading table gen & 1 and writing the other one (and the activations)
-        if (more && !(MSGEMM_PIPE_LEAVE_OUT & 8)) lds_barrier();
-    }
-    const unsigned launches = a.resident ? launch_count : 0u, parity = launches & 1u;
-    if (active) {
+        // ---- the last k-tile of the share, or of a row block: the sums leave
+        if (!more || last_of_row_block) {
+        const bool ends_row_block = a.dealt && last_of_row_block;  // (it clears the slots of the segments this row block does not have)
+        const int seg = seg_now;
+        if (active) {
     // ---- lane (quad b, j'), register (s, i) holds row 64 s + 4 b + i of the panel,
     // column 4 h + j' of the pass (the matrix cores hand the sums back transposed within a quad)
-    const int quad = lane >> 2, jq = lane & 3;
+    // (computed here, from a lane id the compiler cannot see through: hoisted out of the k-tile loop, the addresses of
+    // these stores would occupy registers that the look-ups need)
+    int lane_here = lane;
+    asm volatile("" : "+v"(lane_here));
+    const int quad = lane_here >> 2, jq = lane_here & 3;
     YT* __restrict__ Y = (YT*)a.Y;
     __amdgpu_buffer_rsrc_t part_rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void*)a.partials, 0, (int)a.partial_span, 0x00020000);
@@ -1098,10 +1140,44 @@ batched_pipe_kernel(BatchedArgs a)
                     (uint32_t)((((int64_t)seg * a.b_pad + col) * a.m_pad + (int64_t)panel * kPanelRows + (16 * i + quad) * kPLB) * 4);
                 if (a.resident != 1) store_partials<kPLB, 0>(part_rsrc, off, out);
                 else if (a.publish) store_partials<kPLB, kAuxSc1>(part_rsrc, off, out);
+                if (ends_row_block) {
+                    // row blocks are cut into different numbers of runs: the slots of the segments this one does not
+                    // have read as zero for the second launch, whatever the buffer held
+                    unsigned zero[kPLB];
+#pragma unroll
+                    for (int s = 0; s < kPLB; ++s) zero[s] = 0u;
+                    for (int sl = seg + 1; sl < a.segments; ++sl)
+                        store_partials<kPLB, 0>(part_rsrc, off + (uint32_t)(sl - seg) * (uint32_t)(a.b_pad * a.m_pad * 4), zero);
+                }
             }
         }
     }
+        // the sums of the next row block start at zero
+#pragma unroll
+        for (int s = 0; s < kPLB; ++s) {
+            dlo[s] = f4{0, 0, 0, 0};
+            dhi[s] = f4{0, 0, 0, 0};
+            if constexpr (kScaled) {
+                ylo[s] = f4{0, 0, 0, 0};
+                yhi[s] = f4{0, 0, 0, 0};
+            }
+        }
+        }
+        }
+        if (more2 && !(MSGEMM_PIPE_LEAVE_OUT & 128)) x_store(gen & 1, tile_after(tile_after(kt)), xraw);
+        // everyone has finished reading table gen & 1 and writing the other one (and the activations)
+        if (more && !(MSGEMM_PIPE_LEAVE_OUT & 8)) lds_barrier();
+        if (last_of_row_block) {
+            kt = 0;
+            rb_now += 1;
+            seg_now = 0;  // (this workgroup is the first to touch the next row block)
+            kt_code += (a.panels_per_wg - 1) * a.ktiles + 1;
+        } else {
+            kt += 1;
+            kt_code += 1;
+        }
     }
+    // (the sums are added inside the launch only when the k-tiles are not dealt)
     if (a.resident == 2) reduce_segments_local<YT, AT, kPLB>(a, rb, cp, seg, launches * (unsigned)a.segments, xcd_as_expected, lds);
     else if (a.resident) reduce_segments_resident<YT, AT, kPLB>(a, parity, unit * a.col_passes + cp, lds);
 }
@@ -1259,13 +1335,61 @@ bool batched_pipelined_is_faster(int64_t m, int64_t k, int64_t b, int64_t scale_
     return pipe_us < 0.9 * phase_us;
 }
 
+// The pipelined form with its k-tiles dealt evenly (8 rows per lane): every workgroup has all its wavefronts busy
+// (row blocks of `waves` panels) and as many scale blocks as any other, taken from the row-block-major sequence of
+// one column pass -- so a workgroup's share may end one row block and begin the next (two runs, a partial sum each),
+// and row blocks are cut into different numbers of runs.  Worth it where equal segments cannot fill the device:
+// 56 panels x 8 passes are 224 workgroups of 8 wavefronts or 256 of 7 (4 segments, 64 k-tiles each); dealt, 256
+// workgroups of 8 run through 56 k-tiles (measured: 245 -> 233 us).  Modelled like the other grids.
+// Returns the modelled time (1e300: not possible); `deal_blocks` scale blocks per workgroup, `max_runs` the most
+// runs a row block is cut into (the partial sums per output).
+static double pipe_form_dealt(int64_t panels, int64_t ktiles, int tpb, int col_passes, int64_t cus, int waves,
+                              int64_t max_tiles, int64_t& deal_blocks, int& max_runs)
+{
+    const int64_t blocks = (ktiles + tpb - 1) / tpb;
+    const int64_t row_blocks = (panels + waves - 1) / waves;
+    // workgroups per column pass: one round, and no XCD with more workgroups than compute units (the column passes of
+    // a share run on one XCD, for the codes they have in common)
+    const int64_t chunks = kXcds * ((cus / kXcds) / col_passes);
+    if (chunks < 2 || row_blocks * blocks < 2 * chunks) return 1e300;
+    const int64_t total = row_blocks * blocks;
+    deal_blocks = (total + chunks - 1) / chunks;
+    if (deal_blocks > blocks || deal_blocks * tpb > max_tiles) return 1e300;  // (a share spans two row blocks at most)
+    max_runs = 0;
+    for (int64_t rb = 0; rb < row_blocks; ++rb) {
+        const int runs = (int)(((rb + 1) * blocks - 1) / deal_blocks - (rb * blocks) / deal_blocks + 1);
+        if (runs > max_runs) max_runs = runs;
+    }
+    if (max_runs < 2) return 1e300;
+    const double outputs = (double)panels * 512 * col_passes * kBC;
+    // (a share that crosses a row-block border stores its sums in mid-stream: about 6 us, measured on 20480 x 5120 x 64,
+    // where equal segments are as long as the shares)
+    return 6.5 + 6.0 + (double)(deal_blocks * tpb) * (2.75 + 0.12 * waves) + 3.0 + (double)max_runs * outputs * 4.0 / 3.0e6;
+}
+
 void batched_choose_rows_and_segments(Plan& p, int64_t panels, int& ppw_out)
 {
     const int tpb = p.scale_group > 0 ? (int)(p.scale_group / (2 * p.fs.groups)) : 1;
     const int64_t blocks = (p.ktiles + tpb - 1) / tpb;  // indivisible runs of k-tiles
     int best_ppw;
     int64_t best_per;
-    pipe_form_choice(panels, p.ktiles, tpb, p.col_passes, p.cus, p.fs.lane_bytes, p.fs.waves, best_ppw, best_per);
+    const double regular_us =
+        pipe_form_choice(panels, p.ktiles, tpb, p.col_passes, p.cus, p.fs.lane_bytes, p.fs.waves, best_ppw, best_per);
+    p.deal_blocks = 0;
+    // k-tiles dealt evenly: when the model sees 3 % or more in it (option batched_deal: 1 never, 2 whenever possible)
+    if (p.fs.lane_bytes == 8 && p.opt.batched_deal != 1 && p.opt.panels_per_workgroup == 0 && p.opt.batched_segments == 0) {
+        int64_t deal_blocks = 0;
+        int max_runs = 0;
+        const int64_t max_tiles = p.x_dtype == MSGEMM_I8 ? 8192 / p.fs.groups : (int64_t)1 << 40;
+        const double dealt_us = pipe_form_dealt(panels, p.ktiles, tpb, p.col_passes, p.cus, p.fs.waves, max_tiles, deal_blocks, max_runs);
+        if (dealt_us < 1e299 && (p.opt.batched_deal == 2 || dealt_us < 0.97 * regular_us)) {
+            ppw_out = p.fs.waves;
+            p.deal_blocks = (int)deal_blocks;
+            p.tiles_per_segment = (int)(deal_blocks * tpb);
+            p.segments = max_runs;
+            return;
+        }
+    }
     const int forced_ppw = p.opt.panels_per_workgroup;
     if (forced_ppw >= 1 && forced_ppw <= p.fs.waves) best_ppw = forced_ppw;
     int64_t segs = (blocks + best_per - 1) / best_per;
@@ -1357,6 +1481,13 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
     a.tiles_per_block = p.scale_group > 0 ? (int)(p.scale_group / (2 * p.fs.groups)) : 1;
     a.units = (int)(p.segments * p.row_blocks);
     a.direct = p.segments == 1;
+    a.dealt = p.deal_blocks > 0 ? 1 : 0;
+    a.deal_blocks = p.deal_blocks;
+    a.blocks_per_rb = (int)((p.ktiles + a.tiles_per_block - 1) / a.tiles_per_block);
+    a.deal_total = (int)(p.row_blocks * a.blocks_per_rb);
+    if (a.dealt) a.units = (a.deal_total + a.deal_blocks - 1) / a.deal_blocks;  // workgroups per column pass
+    a.div_blocks_per_rb = make_fastdiv((uint32_t)a.blocks_per_rb);
+    a.div_deal_blocks = make_fastdiv((uint32_t)(a.dealt ? a.deal_blocks : 1));
     a.partial_span = (int64_t)p.segments * a.b_pad * p.m_pad * 4;
     a.div_col_passes = make_fastdiv((uint32_t)a.col_passes);
     a.div_segments = make_fastdiv((uint32_t)a.segments);
@@ -1368,14 +1499,14 @@ int launch_batched(const Plan& p, const void* X, int64_t ldx, void* Y, int64_t l
     // device inside the launch measured slower than the second launch (config 3a 30.8 against 24.7 us, config 5
     // 263 against 242), unlike the single-column forms whose sums are a megabyte.
     const int threads = (p.fs.groups == kPG) ? (64 / p.fs.lane_bytes) * 64 : (p.fs.lane_bytes == 8 ? 8 : 12) * 64;
-    a.resident = (!a.direct && p.epochs && p.forced_reduce == 3 && grid <= p.cus) ? 1 : 0;
+    a.resident = (!a.direct && !a.dealt && p.epochs && p.forced_reduce == 3 && grid <= p.cus) ? 1 : 0;
     // The hand-over inside an XCD (resident = 2; reduce_mode 4 asks for it): every (row block, column pass) gets all
     // its segments onto one XCD, which needs the pairs -- or, with the passes of a row block kept together for the
     // codes they share, the row blocks -- to divide evenly over the XCDs, a workgroup per compute unit at most, and a
     // device that deals workgroup ids over its XCDs in turn (probed once, at the first plan).
     a.local_inner = 1;
     a.arrivals = nullptr;
-    if (!a.direct && p.epochs && p.xcd_round_robin && (p.forced_reduce == 4 || (p.forced_reduce == 0 && kLocalByDefault))) {
+    if (!a.direct && !a.dealt && p.epochs && p.xcd_round_robin && (p.forced_reduce == 4 || (p.forced_reduce == 0 && kLocalByDefault))) {
         const int64_t RB = p.row_blocks, CP = p.col_passes, S = p.segments;
         const int inner = (RB % kXcds == 0) ? (int)CP : 1;
         const int64_t dealt = RB * CP / inner;

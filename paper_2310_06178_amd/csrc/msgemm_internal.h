@@ -67,6 +67,7 @@ struct Plan {
     int build_mfma;       // phase 1 alone on the matrix cores (default: from 16 batch columns on)
     int segments;         // batched kernel: k-segments (partial sums per output); 0 otherwise
     int tiles_per_segment; // batched kernel: k-tiles a workgroup runs through
+    int deal_blocks;      // batched kernel, pipelined form with its k-tiles dealt evenly: scale blocks per workgroup (0: equal segments)
     uint16_t* scales_ordered;  // device fp16 [nblocks][m_pad], rows in the order the lanes own outputs; nullptr without scales
     uint8_t* codes_tiled; // device, [ktiles][m_pad / panel_rows][16][64][lane_bytes]
     float* partials;      // device, [ktiles or segments][b_pad][m_pad] fp32 / int32

@@ -379,6 +379,54 @@ def test_batched_pipelined_form(m, k, b, xd, sg, lb, ppw, segments):
         B.msgemm_destroy(plan)
 
 
+DEALT_CASES = [
+    # m, k, b, xd, sg, partial sums per output expected (the most runs a row block is cut into)
+    (12288, 3200, 16, "f16", 0, 34),     # 3 row blocks x 100 k-tiles over 128 workgroups a pass: shares of 3 cross row blocks
+    (9000, 3840, 60, "bf16", 128, 10),   # scale blocks of 4 k-tiles, last row block of 2 panels, ragged last pass
+    (8292, 4096, 16, "i8", 0, 44),       # integer sums; 17 panels: the third row block has one
+    (4097, 4096, 64, "f16", 128, 16),    # 2 row blocks x 32 scale blocks over 32 workgroups: shares of 2, no crossing
+    (4500, 5120, 30, "bf16", 64, 0),     # partial sums small enough for the static array (scale blocks of 2 k-tiles)
+]
+
+
+@pytest.mark.parametrize("m,k,b,xd,sg,runs", DEALT_CASES)
+def test_batched_pipelined_k_tiles_dealt(m, k, b, xd, sg, runs):
+    """The pipelined batched kernel with the k-tiles of all row blocks dealt evenly over the workgroups (option
+    batched_deal = 2): a workgroup's share may end one row block and begin the next.  Against the oracle, twice on one
+    plan, and through the entry point that keeps its partial sums in the shared static array (whose unused slots hold
+    whatever the last call left)."""
+    options = {"batched_form": 2, "batched_deal": 2}
+    codes = inputs.make_codes(m, k, seed=m + 3 * k)
+    scales = inputs.make_scales(m, k, sg, seed=9) if sg else None
+    dC = torch_io.to_device(codes, "codes")
+    dS = torch_io.to_device(scales, "scales")
+    plan = B.msgemm_plan(m, k, b, xd, Y_OF_X[xd], 2, sg, dC, dS, B.VARIANT_FUSED_LDS16, options=options)
+    try:
+        info = B.msgemm_plan_get_info(plan)
+        assert info["tile_groups"] == 16 and info["tile_rows"] == 4096
+        if runs:
+            assert info["split_k"] == runs
+        static_fits = info["split_k"] * -(-b // 8) * 8 * -(-m // 512) * 512 * 4 <= 16 << 20
+        assert static_fits == (runs == 0)
+        for rep in range(3 if static_fits else 2):
+            X = inputs.make_x(k, b, xd, seed=51 + rep)
+            dX = torch_io.to_device(X, xd)
+            Y = torch_io.empty_output(b, m, Y_OF_X[xd], ldy=m + 3)
+            Y.fill_(-3)
+            if rep == 2:
+                B.msgemm_run_static(plan, dX, k, Y, m + 3)
+            else:
+                B.msgemm_run(plan, dX, k, Y, m + 3)
+            torch.cuda.synchronize()
+            out = torch_io.to_host(Y)
+            check(np.ascontiguousarray(out[:, :m]), oracle_y(codes, X, xd, scales, sg), xd, f"dealt, call {rep}",
+                  elem_bound(codes, X, xd, scales, sg, table16=True))
+            minus3 = torch_io.to_host(torch.full((1,), -3, dtype=Y.dtype))[0]
+            assert np.all(out[:, m:] == minus3), "output padding was written"
+    finally:
+        B.msgemm_destroy(plan)
+
+
 def test_fused_lds16_not_for_fp32():
     dC = torch.zeros(64 * 32, dtype=torch.uint8, device="cuda:0")
     status, handle = B.msgemm_plan(64, 64, 4, "f32", "f32", 2, 0, dC, None, B.VARIANT_FUSED_LDS16, check=False)
