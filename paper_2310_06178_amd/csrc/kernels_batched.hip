@@ -833,7 +833,8 @@ batched_pipe_kernel(BatchedArgs a)
     // of scale blocks of the row-block-major sequence of its column pass, which may go from the end of one row block
     // (its last k-tiles) into the start of the next (k-tile 0 of the panels 8 further on): the tables depend on the
     // column pass and the k-tile alone, so the pipeline of activations, table builds and code loads runs across that
-    // border like across any other k-tile border; only the sums are stored and cleared there.
+    // border like across any other k-tile border; only the sums are stored and cleared there.  (Row blocks are cut
+    // into different numbers of shares: the second launch works out how many sums each row block has.)
     int kt_begin = seg * a.tiles_per_segment;
     int ngen = min(a.tiles_per_segment, a.ktiles - kt_begin);  // >= 1: the host makes no empty segment
     if (a.dealt) {
@@ -1092,7 +1093,6 @@ batched_pipe_kernel(BatchedArgs a)
         }
         // ---- the last k-tile of the share, or of a row block: the sums leave
         if (!more || last_of_row_block) {
-        const bool ends_row_block = a.dealt && last_of_row_block;  // (it clears the slots of the segments this row block does not have)
         const int seg = seg_now;
         if (active) {
     // ---- lane (quad b, j'), register (s, i) holds row 64 s + 4 b + i of the panel,
@@ -1140,15 +1140,6 @@ batched_pipe_kernel(BatchedArgs a)
                     (uint32_t)((((int64_t)seg * a.b_pad + col) * a.m_pad + (int64_t)panel * kPanelRows + (16 * i + quad) * kPLB) * 4);
                 if (a.resident != 1) store_partials<kPLB, 0>(part_rsrc, off, out);
                 else if (a.publish) store_partials<kPLB, kAuxSc1>(part_rsrc, off, out);
-                if (ends_row_block) {
-                    // row blocks are cut into different numbers of runs: the slots of the segments this one does not
-                    // have read as zero for the second launch, whatever the buffer held
-                    unsigned zero[kPLB];
-#pragma unroll
-                    for (int s = 0; s < kPLB; ++s) zero[s] = 0u;
-                    for (int sl = seg + 1; sl < a.segments; ++sl)
-                        store_partials<kPLB, 0>(part_rsrc, off + (uint32_t)(sl - seg) * (uint32_t)(a.b_pad * a.m_pad * 4), zero);
-                }
             }
         }
     }

@@ -1468,10 +1468,23 @@ fused_wide_kernel(FusedArgs a)
 // Many small workgroups keep the loads of the whole pass in flight at once.
 constexpr int kReduceWaves = 4;
 
+// Slices a row has when the k-tiles were dealt evenly (batched pipelined form): row block r = row / rows was cut into
+// the shares floor(r blocks / share) .. floor(((r + 1) blocks - 1) / share), and only that many of the `slices` slots
+// were written.  rows = 0: every row has all slices.
+struct DealtSlices {
+    int rows, blocks, share;
+};
+__device__ __forceinline__ int slices_of_row(const DealtSlices& d, int64_t row, int slices)
+{
+    if (d.rows == 0) return slices;
+    const int r = (int)(row / d.rows);
+    return ((r + 1) * d.blocks - 1) / d.share - (r * d.blocks) / d.share + 1;
+}
+
 template <typename YT, typename AT, int F>
 __global__ void __launch_bounds__(kReduceWaves * 64)
 reduce_kernel(const float* __restrict__ partials, YT* __restrict__ Y, int64_t ldy, int64_t m, int64_t b,
-              int64_t m_pad, int64_t b_pad, int ktiles, int64_t span, int quad_major)
+              int64_t m_pad, int64_t b_pad, int ktiles, int64_t span, int quad_major, DealtSlices dealt)
 {
     __shared__ AT wave_sum[kReduceWaves][64];
     const int lane = threadIdx.x & 63;
@@ -1482,6 +1495,7 @@ reduce_kernel(const float* __restrict__ partials, YT* __restrict__ Y, int64_t ld
     __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)partials, 0, (int)span, 0x00020000);
     const uint32_t tile_stride = (uint32_t)(b_pad * m_pad * 4);
     const uint32_t off0 = (uint32_t)(col * m_pad + chunk * 64 + lane) * 4u;
+    ktiles = slices_of_row(dealt, chunk * 64, ktiles);  // (the 64 sums of a chunk belong to one panel, hence one row block)
     AT sum = 0;
     constexpr int kBatch = 8;
     for (int t0 = w; t0 < ktiles; t0 += kBatch * kReduceWaves) {
@@ -1522,7 +1536,7 @@ constexpr int kFewSlices = 16;
 template <typename YT, typename AT, int F, int kMax>
 __global__ void __launch_bounds__(64)
 reduce_few_kernel(const float* __restrict__ partials, YT* __restrict__ Y, int64_t ldy, int64_t m, int64_t b,
-                  int64_t m_pad, int64_t b_pad, int slices, int64_t span, int quad_major)
+                  int64_t m_pad, int64_t b_pad, int slices, int64_t span, int quad_major, DealtSlices dealt)
 {
     const int lane = threadIdx.x;
     const int64_t chunks_per_col = m_pad / 256;
@@ -1531,6 +1545,7 @@ reduce_few_kernel(const float* __restrict__ partials, YT* __restrict__ Y, int64_
     __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)partials, 0, (int)span, 0x00020000);
     const uint32_t tile_stride = (uint32_t)(b_pad * m_pad * 4);
     const uint32_t off0 = (uint32_t)(col * m_pad + chunk * 256 + lane * 4) * 4u;
+    slices = slices_of_row(dealt, chunk * 256, slices);  // (256 consecutive sums belong to one row block)
     v4u v[kMax];  // kMax = 4, 8 or 16: the smallest that holds the segments
 #pragma unroll
     for (int t = 0; t < kMax; ++t)
@@ -1699,7 +1714,7 @@ int launch_one(const Plan& p, FusedArgs& a, hipStream_t s)
     if (a.reduce_mode == kReduceSecondPass) {
         const int64_t blocks = (a.m_pad / 64) * a.b;
         hipLaunchKernelGGL((reduce_kernel<YT, AT, kFinal>), dim3((unsigned)blocks), dim3(kReduceWaves * 64), 0, s,
-                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.slices, a.partial_span, 0);
+                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.slices, a.partial_span, 0, DealtSlices{0, 0, 0});
         MSGEMM_HIP_TRY(hipGetLastError());
     }
     return MSGEMM_OK;
@@ -1724,7 +1739,7 @@ int launch_long(const Plan& p, FusedArgs& a, hipStream_t s)
     if (a.reduce_mode == kReduceSecondPass) {
         const int64_t blocks = (a.m_pad / 64) * a.b;
         hipLaunchKernelGGL((reduce_kernel<YT, AT, 4>), dim3((unsigned)blocks), dim3(kReduceWaves * 64), 0, s,
-                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.slices, a.partial_span, 0);
+                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.slices, a.partial_span, 0, DealtSlices{0, 0, 0});
         MSGEMM_HIP_TRY(hipGetLastError());
     }
     return MSGEMM_OK;
@@ -1747,7 +1762,7 @@ int launch_wide(const Plan& p, FusedArgs& a, hipStream_t s)
     if (a.reduce_mode == kReduceSecondPass) {
         const int64_t blocks = (a.m_pad / 64) * a.b;
         hipLaunchKernelGGL((reduce_kernel<YT, AT, 4>), dim3((unsigned)blocks), dim3(kReduceWaves * 64), 0, s,
-                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.slices, a.partial_span, 0);
+                           a.partials, (YT*)a.Y, a.ldy, a.m, a.b, a.m_pad, a.b_pad, a.slices, a.partial_span, 0, DealtSlices{0, 0, 0});
         MSGEMM_HIP_TRY(hipGetLastError());
     }
     return MSGEMM_OK;
@@ -1991,6 +2006,11 @@ int launch_unpack(const Plan& p, uint8_t* row_major, hipStream_t s) { return rep
 int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int64_t ldy, int slices,
                               int64_t span, hipStream_t s)
 {
+    DealtSlices dealt{0, 0, 0};
+    if (p.deal_blocks > 0) {
+        const int tpb = p.scale_group > 0 ? (int)(p.scale_group / (2 * p.fs.groups)) : 1;
+        dealt = DealtSlices{p.fs.tile_rows, (int)((p.ktiles + tpb - 1) / tpb), p.deal_blocks};
+    }
     const int64_t b_pad = (int64_t)p.col_passes * p.fs.cols;
     const dim3 grid((unsigned)((p.m_pad / 64) * p.b)), blk(kReduceWaves * 64);
     const int f = p.fs.panel_rows / 64;  // outputs per lane of the producing kernel: 8, 4 or 2
@@ -2001,13 +2021,13 @@ int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int
     do {                                                                                                        \
         if (slices <= 4)                                                                                        \
             hipLaunchKernelGGL((reduce_few_kernel<YT, AT, FF, 4>), fgrid, fblk, 0, s, partials, (YT*)Y, ldy, p.m, p.b,  \
-                               p.m_pad, b_pad, slices, span, qm);                                               \
+                               p.m_pad, b_pad, slices, span, qm, dealt);                                               \
         else if (slices <= 8)                                                                                   \
             hipLaunchKernelGGL((reduce_few_kernel<YT, AT, FF, 8>), fgrid, fblk, 0, s, partials, (YT*)Y, ldy, p.m, p.b,  \
-                               p.m_pad, b_pad, slices, span, qm);                                               \
+                               p.m_pad, b_pad, slices, span, qm, dealt);                                               \
         else                                                                                                    \
             hipLaunchKernelGGL((reduce_few_kernel<YT, AT, FF, 16>), fgrid, fblk, 0, s, partials, (YT*)Y, ldy, p.m, p.b, \
-                               p.m_pad, b_pad, slices, span, qm);                                               \
+                               p.m_pad, b_pad, slices, span, qm, dealt);                                               \
     } while (0)
 #define MSGEMM_REDUCE(YT, AT)                                                                                   \
     if (few && f == 8) MSGEMM_REDUCE_FEW(YT, AT, 8);                                                            \
@@ -2015,13 +2035,13 @@ int launch_reduce_second_pass(const Plan& p, const float* partials, void* Y, int
     else if (few) MSGEMM_REDUCE_FEW(YT, AT, 2);                                                                 \
     else if (f == 8)                                                                                            \
         hipLaunchKernelGGL((reduce_kernel<YT, AT, 8>), grid, blk, 0, s, partials, (YT*)Y, ldy, p.m, p.b, p.m_pad, \
-                           b_pad, slices, span, qm);                                                      \
+                           b_pad, slices, span, qm, dealt);                                                      \
     else if (f == 4)                                                                                            \
         hipLaunchKernelGGL((reduce_kernel<YT, AT, 4>), grid, blk, 0, s, partials, (YT*)Y, ldy, p.m, p.b, p.m_pad, \
-                           b_pad, slices, span, qm);                                                      \
+                           b_pad, slices, span, qm, dealt);                                                      \
     else                                                                                                        \
         hipLaunchKernelGGL((reduce_kernel<YT, AT, 2>), grid, blk, 0, s, partials, (YT*)Y, ldy, p.m, p.b, p.m_pad, \
-                           b_pad, slices, span, qm);
+                           b_pad, slices, span, qm, dealt);
     switch (p.y_dtype) {
     case MSGEMM_F32: MSGEMM_REDUCE(float, float) break;
     case MSGEMM_F16: MSGEMM_REDUCE(__half, float) break;

@@ -394,7 +394,7 @@ def test_batched_pipelined_k_tiles_dealt(m, k, b, xd, sg, runs):
     """The pipelined batched kernel with the k-tiles of all row blocks dealt evenly over the workgroups (option
     batched_deal = 2): a workgroup's share may end one row block and begin the next.  Against the oracle, twice on one
     plan, and through the entry point that keeps its partial sums in the shared static array (whose unused slots hold
-    whatever the last call left)."""
+    whatever the last call left: row blocks are cut into different numbers of shares)."""
     options = {"batched_form": 2, "batched_deal": 2}
     codes = inputs.make_codes(m, k, seed=m + 3 * k)
     scales = inputs.make_scales(m, k, sg, seed=9) if sg else None
@@ -414,6 +414,21 @@ def test_batched_pipelined_k_tiles_dealt(m, k, b, xd, sg, runs):
             Y = torch_io.empty_output(b, m, Y_OF_X[xd], ldy=m + 3)
             Y.fill_(-3)
             if rep == 2:
+                # the static array first takes the partial sums of another problem of the same extent (equal segments,
+                # as many as this plan has slots): the slots that a row block of this plan does not use then hold
+                # numbers, and the second launch must not add them
+                k2 = max(sg, 32) * info["split_k"]  # one scale block (or k-tile) per segment
+                codes2 = inputs.make_codes(m, k2, seed=77)
+                scales2 = inputs.make_scales(m, k2, sg, seed=78) if sg else None
+                other = B.msgemm_plan(m, k2, b, xd, Y_OF_X[xd], 2, sg, torch_io.to_device(codes2, "codes"),
+                                      torch_io.to_device(scales2, "scales"), B.VARIANT_FUSED_LDS16,
+                                      options={"batched_form": 2, "batched_deal": 1, "batched_segments": info["split_k"]})
+                try:
+                    assert B.msgemm_plan_get_info(other)["split_k"] == info["split_k"]
+                    B.msgemm_run_static(other, torch_io.to_device(inputs.make_x(k2, b, xd, seed=99), xd), k2, Y, m + 3)
+                finally:
+                    B.msgemm_destroy(other)
+                Y.fill_(-3)
                 B.msgemm_run_static(plan, dX, k, Y, m + 3)
             else:
                 B.msgemm_run(plan, dX, k, Y, m + 3)
