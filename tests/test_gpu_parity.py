@@ -1229,6 +1229,8 @@ CODES8_CASES = [
     (520, 512, 8, "f16", 128, {"batched_form": 2}),                        # the pipelined batched form
     (1000, 1024, 16, "f16", 32, {"batched_form": 2, "rows_per_lane": 4}),
     (300, 384, 5, "bf16", 0, {"batched_form": 2, "batched_segments": 3}),
+    (12288, 1600, 16, "f16", 0, {"batched_form": 2, "batched_deal": 2}),    # k-tiles dealt evenly: shares of 3 cross row blocks
+    (9000, 2048, 60, "bf16", 64, {"batched_form": 2, "batched_deal": 2}),   # ... with scale blocks of 4 k-tiles
 ]
 
 
