@@ -121,7 +121,8 @@ typedef struct {
     int64_t lut_groups;  /* last dimension of L */
     int tile_rows;       /* rows per workgroup (fused variant), else 0 */
     int tile_groups;     /* table groups of a k-tile (one table in LDS), else 0 */
-    int split_k;         /* partial sums reduced per output: k-tiles, or runs of k-tiles (long k, batches) */
+    int split_k;         /* partial sums reduced per output: k-tiles, or runs of k-tiles (long k, batches; with the
+                            k-tiles of a batched plan dealt evenly: the most any output has) */
     int col_chunk;       /* batch columns handled per pass over the codes */
     int64_t workspace_bytes; /* device memory the plan owns besides the codes in its kernels' order */
 } msgemm_plan_info_t;
