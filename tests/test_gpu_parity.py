@@ -1536,3 +1536,42 @@ def test_random_shapes(m, k, b, xd, sg, d, variant, pipe):
     if bnd is not None and info["variant"] == B.VARIANT_GLOBAL_LUT_HALF:
         bnd = 2 * bnd  # an entry of the missing half is c S(j) - L: one more rounding, of magnitude up to the group's sum
     check(out, ref, xd, f"random shape {m}x{k}x{b} {xd} sg={sg} d={d} variant={variant}", bnd)
+
+
+def _random_batched_cases(count, seed):
+    """Larger batched problems with the forms that place or deal their workgroups by the shape of the problem."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        xd = ["f16", "bf16", "i8"][rng.integers(3)]
+        m = int(rng.integers(1500, 30000))
+        sg = 0 if xd == "i8" else int([0, 32, 64, 128, 256][rng.integers(5)])
+        k = 2 * int(rng.integers(300, 4000))
+        if sg:
+            k = max(sg, (k // sg) * sg)
+        b = int(rng.integers(3, 70))
+        if m * k * b > 3e9:
+            continue  # (the oracle stays under a second)
+        which = int(rng.integers(4))
+        options = [{"batched_form": 2, "batched_deal": 2}, {"batched_deal": 2},
+                   {"reduce_mode": 4, "batched_form": int(rng.integers(1, 3)), "panels_per_workgroup": int(rng.integers(1, 9)),
+                    "batched_segments": int(rng.integers(2, 9))},
+                   {"reduce_mode": 4}][which]
+        if sg == 32 and options.get("batched_form") == 1:
+            options["batched_form"] = 2  # (scale blocks of 32 columns: only the pipelined form has k-tiles that small)
+        cases.append((m, k, b, xd, sg, options))
+    return cases
+
+
+@pytest.mark.parametrize("m,k,b,xd,sg,options", _random_batched_cases(24, seed=61782310))
+def test_random_batched_shapes_dealt_and_xcd_local(m, k, b, xd, sg, options):
+    """Seeded random batched problems through the pipelined form with its k-tiles dealt evenly and through the XCD-local
+    reduction, where the shape allows them (elsewhere the request falls back to the library's choice): whatever the
+    plan turns out to be, the result is the oracle's."""
+    codes = inputs.make_codes(m, k, seed=m * 31 + k)
+    X = inputs.make_x(k, b, xd, seed=k * 7 + b)
+    scales = inputs.make_scales(m, k, sg, seed=m + b) if sg else None
+    ref = oracle_y(codes, X, xd, scales, sg)
+    out, info = run_gpu(codes, X, xd, scales, sg, 2, B.VARIANT_FUSED_LDS16, ldx_pad=2, ldy_pad=1, options=options)
+    assert info["variant"] == B.VARIANT_FUSED_LDS16
+    check(out, ref, xd, f"random batched shape {m}x{k}x{b} {xd} sg={sg} {options}", elem_bound(codes, X, xd, scales, sg, table16=True))
