@@ -787,6 +787,12 @@ batched_kernel(BatchedArgs a)
 //   barrier per k-tile (everyone has finished reading the old table and
 //   writing the new one).  The activations of k-tile gen + 2 are fetched during
 //   k-tile gen and handed over through `xs` at that barrier.
+//   A workgroup runs through a segment of its row block's k-tiles, or -- with the
+//   k-tiles dealt evenly (BatchedArgs::dealt, chosen by pipe_form_dealt) -- through
+//   an equal share of the k-tiles of all row blocks of its column pass, which may
+//   end one row block and begin the next: the loop below then goes on with
+//   k-tile 0 of the panels 8 further on, storing and clearing its sums at the
+//   border.
 constexpr int kPG = 16;                   // table groups per k-tile
 constexpr int kPTableBytes = 256 * kPG * 16;
 // kPLB = rows (code bytes) a lane takes per load: 8 (8 wavefronts, 512-row panels) or 4
